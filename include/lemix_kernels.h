@@ -1,0 +1,123 @@
+/*
+ * lemix_kernels.h - kernel-level entry points of the stage library.
+ *
+ * These are the individual steps stage_prefill / stage_decode /
+ * stage_train_fwd / stage_train_bwd are built from, exported so that each can
+ * be checked against the CPU definition and timed on its own.  All pointers
+ * are device memory owned by the caller unless marked [host]; `stream` is a
+ * hipStream_t passed as void*; every call enqueues and returns.
+ * dtype arguments take ls_dtype values (LS_F32 / LS_BF16 / LS_F16).
+ */
+#ifndef LEMIX_KERNELS_H
+#define LEMIX_KERNELS_H
+
+#include "lemix_stage.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/*
+ * The block's linear maps and their gradients (forward Y = X W^T + b, input
+ * gradient dX = dY W, weight gradient dW = dY^T X):
+ *   C[M,N] = (accumulate ? C : 0) + (resid ? resid : 0) + sum_k A(m,k) B(n,k) + bias[n]
+ * A(m,k) is at A[m*lda + k] when a_kmajor, else at A[k*lda + m]; likewise B(n,k).
+ * op_dtype LS_BF16 / LS_F16: MFMA path, fp32 accumulation; the contiguous
+ * extent of each operand, lda and ldb must be multiples of 8 elements and the
+ * bases 16-byte aligned.  op_dtype LS_F32: plain FMA path, no constraints.
+ * c_dtype is LS_F32 or op_dtype; accumulate and resid need... resid is fp32
+ * [M, ldr]; accumulate needs c_dtype LS_F32.  bias has N elements of bias_dtype.
+ */
+ls_status lsk_gemm(int op_dtype, int M, int N, int K, const void* A, long lda, int a_kmajor,
+                   const void* B, long ldb, int b_kmajor, void* C, long ldc, int c_dtype,
+                   const void* bias, int bias_dtype, const float* resid, long ldr,
+                   int accumulate, void* stream);
+
+/* dst[i] = (dst_dtype) src[i], i < n. */
+ls_status lsk_convert(const void* src, int src_dtype, void* dst, int dst_dtype, size_t n,
+                      void* stream);
+
+/*
+ * Row normalisation of the fp32 residual stream x[T,d] -> h[T,d] (h_dtype).
+ * kind 0: LayerNorm (x-mean)*rstd*gamma+beta, biased variance; kind 1:
+ * RMSNorm x*rstd*gamma.  eps is added inside the square root.  mean (kind 0)
+ * and rstd are written as fp32[T] when non-null.  gamma/beta have p_dtype.
+ */
+ls_status lsk_norm_fwd(int kind, const float* x, int T, int d, const void* gamma,
+                       const void* beta, int p_dtype, float eps, void* h, int h_dtype,
+                       float* mean, float* rstd, void* stream);
+
+/*
+ * Backward of lsk_norm_fwd fused with the residual-gradient add:
+ *   dx = dres + norm_bwd(dh)   (fp32 [T,d]; dres may be null = 0)
+ * and optionally a copy of dx in dx16_dtype (the next GEMM's operand).
+ * dgamma (and dbeta for kind 0) = column sums over the T rows, fp32[d],
+ * overwritten or accumulated.  partial: fp32 scratch of
+ * lsk_norm_bwd_partial_floats(T, d) elements.
+ */
+size_t lsk_norm_bwd_partial_floats(int T, int d);
+ls_status lsk_norm_bwd(int kind, const void* dh, int dh_dtype, const float* x,
+                       const float* mean, const float* rstd, const void* gamma, int p_dtype,
+                       int T, int d, const float* dres, float* dx, void* dx16, int dx16_dtype,
+                       float* dgamma, float* dbeta, int accumulate, float* partial,
+                       void* stream);
+
+/*
+ * Half-split rotary embedding in place on the q and k parts of qkv[T, 3d]
+ * (columns [0,d) and [d,2d), heads of head_dim): pair (i, i+head_dim/2) of
+ * row t is rotated by sign * pos[t] * theta^(-2i/head_dim); cos/sin come from
+ * table[pos][i] = {cos, sin} (fp32 pairs, head_dim/2 per position).
+ */
+ls_status lsk_rope(void* qkv, int dtype, int T, int n_heads, int head_dim, const int32_t* pos,
+                   const float* table, float sign, void* stream);
+
+/* GELU forward g = GELU(u) and backward du = dg * GELU'(u); kind = ls_act. */
+ls_status lsk_gelu_fwd(const void* u, void* g, int dtype, size_t n, int kind, void* stream);
+ls_status lsk_gelu_bwd(const void* dg, const void* u, void* du, int dtype, size_t n, int kind,
+                       void* stream);
+/* SwiGLU on gu[T, 2F] (gate columns then up columns): a = SiLU(gate)*up, and
+ * its backward dgu = [da*up*SiLU'(gate) | da*SiLU(gate)]. */
+ls_status lsk_swiglu_fwd(const void* gu, void* a, int dtype, int T, int F, void* stream);
+ls_status lsk_swiglu_bwd(const void* da, const void* gu, void* dgu, int dtype, int T, int F,
+                         void* stream);
+
+/* out[n] (+)= sum_t x[t*ld + n] (bias gradients); partial: fp32 scratch of
+ * lsk_colsum_partial_floats(T, N) elements. */
+size_t lsk_colsum_partial_floats(int T, int N);
+ls_status lsk_colsum(const void* x, int dtype, int T, int N, long ld, float* out,
+                     int accumulate, float* partial, void* stream);
+
+/*
+ * Causal attention over contiguous sequences (training): qkv[B*L, 3d] holds
+ * q | k | v per row; o[B*L, d]; lse[B*L, n_heads] = log-sum-exp of the scaled
+ * scores of each (row, head) (fp32, may be null).  impl 0 = plain kernel,
+ * 1 = MFMA kernel (16-bit only).
+ */
+ls_status lsk_attn_fwd(int impl, const void* qkv, int dtype, int B, int L, int n_heads,
+                       int head_dim, void* o, float* lse, void* stream);
+/* Backward of the above: dqkv[B*L, 3d] from dO[B*L, d], the forward's qkv, o
+ * and lse.  dvec: fp32 scratch [B*L, n_heads]. */
+ls_status lsk_attn_bwd(int impl, const void* qkv, const void* o, const void* dO,
+                       const float* lse, int dtype, int B, int L, int n_heads, int head_dim,
+                       void* dqkv, float* dvec, void* stream);
+
+/*
+ * Serving attention over the paged pool.  Row t of qkv[T, 3d] belongs to
+ * request req[t] and sits at absolute position pos[t]; its K and V are first
+ * written to the request's page, then its query attends to keys 0..pos[t].
+ * k_pool/v_pool point at this layer's [n_pages][n_heads][page][head_dim] slab.
+ */
+ls_status lsk_kv_write(const void* qkv, int dtype, int T, int n_heads, int head_dim,
+                       const int32_t* pos, const int32_t* req, void* k_pool, void* v_pool,
+                       const int32_t* block_table, int max_pages_per_req, int page_size,
+                       void* stream);
+ls_status lsk_attn_paged(int impl, const void* qkv, int dtype, int T, int n_heads, int head_dim,
+                         const int32_t* pos, const int32_t* req, const void* k_pool,
+                         const void* v_pool, const int32_t* block_table, int max_pages_per_req,
+                         int page_size, int max_ctx, void* o, float* scratch, void* stream);
+size_t lsk_attn_paged_scratch_floats(int T, int n_heads, int head_dim, int max_ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

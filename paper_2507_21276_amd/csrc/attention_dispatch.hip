@@ -1,0 +1,38 @@
+// Public attention entry points: choose between the plain kernels and the
+// matrix-core kernels.
+#include "common.h"
+
+extern "C" {
+ls_status lsk_attn_fwd_simple(const void*, int, int, int, int, int, void*, float*, void*);
+ls_status lsk_attn_bwd_simple(const void*, const void*, const void*, const float*, int, int, int, int, int,
+                              void*, float*, void*);
+ls_status lsk_attn_paged_simple(const void*, int, int, int, int, const int32_t*, const int32_t*,
+                                const void*, const void*, const int32_t*, int, int, int, void*, void*);
+
+ls_status lsk_attn_fwd(int impl, const void* qkv, int dtype, int B, int L, int n_heads, int head_dim,
+                       void* o, float* lse, void* stream) {
+  (void)impl;
+  return lsk_attn_fwd_simple(qkv, dtype, B, L, n_heads, head_dim, o, lse, stream);
+}
+
+ls_status lsk_attn_bwd(int impl, const void* qkv, const void* o, const void* dO, const float* lse,
+                       int dtype, int B, int L, int n_heads, int head_dim, void* dqkv, float* dvec,
+                       void* stream) {
+  (void)impl;
+  return lsk_attn_bwd_simple(qkv, o, dO, lse, dtype, B, L, n_heads, head_dim, dqkv, dvec, stream);
+}
+
+size_t lsk_attn_paged_scratch_floats(int T, int n_heads, int head_dim, int max_ctx) {
+  (void)T; (void)n_heads; (void)head_dim; (void)max_ctx;
+  return 0;
+}
+
+ls_status lsk_attn_paged(int impl, const void* qkv, int dtype, int T, int n_heads, int head_dim,
+                         const int32_t* pos, const int32_t* req, const void* k_pool, const void* v_pool,
+                         const int32_t* block_table, int max_pages_per_req, int page_size, int max_ctx,
+                         void* o, float* scratch, void* stream) {
+  (void)impl; (void)scratch;
+  return lsk_attn_paged_simple(qkv, dtype, T, n_heads, head_dim, pos, req, k_pool, v_pool, block_table,
+                               max_pages_per_req, page_size, max_ctx, o, stream);
+}
+}

@@ -1,0 +1,314 @@
+// Bandwidth-bound steps of the block: dtype conversion, LayerNorm / RMSNorm
+// forward and backward (fused with the residual-gradient add), rotary
+// embedding, GELU / SwiGLU forward and backward, column sums for bias
+// gradients.  All statistics and transcendental math are fp32.
+#include "common.h"
+
+namespace {
+
+constexpr float kGeluC = 0.7978845608028654f;  // sqrt(2/pi)
+
+// ------------------------------------------------------------------ convert
+__global__ void convert_kernel(const void* src, int sdt, void* dst, int ddt, size_t n) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x)
+    store_from_f(dst, i, ddt, load_as_f(src, i, sdt));
+}
+
+// ---------------------------------------------------------------- norm fwd
+// one 256-thread workgroup per row
+__global__ __launch_bounds__(256) void norm_fwd_kernel(int kind, const float* x, int d,
+                                                       const void* gamma, const void* beta,
+                                                       int pdt, float eps, void* h, int hdt,
+                                                       float* mean, float* rstd) {
+  __shared__ float red[16];
+  const size_t row = blockIdx.x;
+  const float* xr = x + row * d;
+  float s = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) s += xr[i];
+  float mu = 0.f;
+  if (kind == 0) mu = block_sum(s, red) / d;
+  float q = 0.f;
+  for (int i = threadIdx.x; i < d; i += 256) {
+    const float c = xr[i] - mu;
+    q += c * c;
+  }
+  const float var = block_sum(q, red) / d;
+  const float r = 1.0f / sqrtf(var + eps);
+  for (int i = threadIdx.x; i < d; i += 256) {
+    float v = (xr[i] - mu) * r * load_as_f(gamma, i, pdt);
+    if (kind == 0 && beta) v += load_as_f(beta, i, pdt);
+    store_from_f(h, row * d + i, hdt, v);
+  }
+  if (threadIdx.x == 0) {
+    if (mean && kind == 0) mean[row] = mu;
+    if (rstd) rstd[row] = r;
+  }
+}
+
+// ---------------------------------------------------------------- norm bwd
+// Each workgroup handles ROWS_PER_WG consecutive rows; per row it computes dx,
+// and it accumulates its share of dgamma/dbeta in registers (thread i owns
+// columns i, i+256, ...), written to partial[wg][2][d]; a second kernel sums
+// the partials in a fixed order (deterministic).
+constexpr int NB_ROWS = 32;
+constexpr int NB_MAXCOL = 32;  // d <= 256 * 32
+
+__global__ __launch_bounds__(256) void norm_bwd_kernel(int kind, const void* dh, int dhdt,
+                                                       const float* x, const float* mean,
+                                                       const float* rstd, const void* gamma,
+                                                       int pdt, int T, int d, const float* dres,
+                                                       float* dx, void* dx16, int dx16dt,
+                                                       float* partial) {
+  __shared__ float red[16];
+  float dg[NB_MAXCOL], db[NB_MAXCOL];
+#pragma unroll
+  for (int c = 0; c < NB_MAXCOL; ++c) dg[c] = db[c] = 0.f;
+  const int r0 = blockIdx.x * NB_ROWS;
+  for (int rr = 0; rr < NB_ROWS; ++rr) {
+    const int row = r0 + rr;
+    if (row >= T) break;
+    const size_t off = (size_t)row * d;
+    const float mu = kind == 0 ? mean[row] : 0.f, r = rstd[row];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int c = 0; c < NB_MAXCOL; ++c) {
+      const int i = threadIdx.x + c * 256;
+      if (i < d) {
+        const float g = load_as_f(dh, off + i, dhdt);
+        const float xh = (x[off + i] - mu) * r;
+        const float dxh = g * load_as_f(gamma, i, pdt);
+        s1 += dxh;
+        s2 += dxh * xh;
+        dg[c] += g * xh;
+        db[c] += g;
+      }
+    }
+    const float m2 = block_sum(s2, red) / d;
+    float m1 = 0.f;
+    if (kind == 0) m1 = block_sum(s1, red) / d;
+#pragma unroll
+    for (int c = 0; c < NB_MAXCOL; ++c) {
+      const int i = threadIdx.x + c * 256;
+      if (i < d) {
+        const float g = load_as_f(dh, off + i, dhdt);
+        const float xh = (x[off + i] - mu) * r;
+        const float dxh = g * load_as_f(gamma, i, pdt);
+        float v = r * (dxh - m1 - xh * m2);
+        if (dres) v += dres[off + i];
+        dx[off + i] = v;
+        if (dx16) store_from_f(dx16, off + i, dx16dt, v);
+      }
+    }
+  }
+  float* p = partial + (size_t)blockIdx.x * 2 * d;
+#pragma unroll
+  for (int c = 0; c < NB_MAXCOL; ++c) {
+    const int i = threadIdx.x + c * 256;
+    if (i < d) {
+      p[i] = dg[c];
+      p[d + i] = db[c];
+    }
+  }
+}
+
+__global__ void norm_bwd_finish_kernel(const float* partial, int nwg, int d, float* dgamma,
+                                       float* dbeta, int accumulate) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= d) return;
+  float g = 0.f, b = 0.f;
+  for (int w = 0; w < nwg; ++w) {
+    g += partial[(size_t)w * 2 * d + i];
+    b += partial[(size_t)w * 2 * d + d + i];
+  }
+  if (dgamma) dgamma[i] = accumulate ? dgamma[i] + g : g;
+  if (dbeta) dbeta[i] = accumulate ? dbeta[i] + b : b;
+}
+
+// -------------------------------------------------------------------- rope
+// one thread per (row, head, pair)
+__global__ void rope_kernel(void* qkv, int dt, int T, int h, int dh, const int32_t* pos,
+                            const float* table, float sign) {
+  const int half = dh / 2;
+  const size_t n = (size_t)T * 2 * h * half;
+  const int d = h * dh;
+  for (size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x; idx < n;
+       idx += (size_t)gridDim.x * blockDim.x) {
+    const int i = idx % half;
+    const int hh = (idx / half) % (2 * h);  // q heads then k heads
+    const size_t t = idx / ((size_t)half * 2 * h);
+    const size_t base = t * 3 * d + (size_t)hh * dh + i;
+    const float c = table[((size_t)pos[t] * half + i) * 2];
+    const float s = table[((size_t)pos[t] * half + i) * 2 + 1] * sign;
+    const float a = load_as_f(qkv, base, dt), b = load_as_f(qkv, base + half, dt);
+    store_from_f(qkv, base, dt, a * c - b * s);
+    store_from_f(qkv, base + half, dt, b * c + a * s);
+  }
+}
+
+// ------------------------------------------------------------- activations
+__device__ __forceinline__ float gelu_f(float u, int kind) {
+  if (kind == LS_ACT_GELU_TANH) return 0.5f * u * (1.f + tanhf(kGeluC * (u + 0.044715f * u * u * u)));
+  return 0.5f * u * (1.f + erff(u * 0.70710678118654752f));
+}
+__device__ __forceinline__ float gelu_grad_f(float u, int kind) {
+  if (kind == LS_ACT_GELU_TANH) {
+    const float t = tanhf(kGeluC * (u + 0.044715f * u * u * u));
+    return 0.5f * (1.f + t) + 0.5f * u * (1.f - t * t) * kGeluC * (1.f + 3.f * 0.044715f * u * u);
+  }
+  const float Phi = 0.5f * (1.f + erff(u * 0.70710678118654752f));
+  const float phi = 0.3989422804014327f * expf(-0.5f * u * u);
+  return Phi + u * phi;
+}
+
+__global__ void gelu_fwd_kernel(const void* u, void* g, int dt, size_t n, int kind) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x)
+    store_from_f(g, i, dt, gelu_f(load_as_f(u, i, dt), kind));
+}
+__global__ void gelu_bwd_kernel(const void* dg, const void* u, void* du, int dt, size_t n, int kind) {
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x)
+    store_from_f(du, i, dt, load_as_f(dg, i, dt) * gelu_grad_f(load_as_f(u, i, dt), kind));
+}
+__global__ void swiglu_fwd_kernel(const void* gu, void* a, int dt, size_t T, int F) {
+  const size_t n = T * F;
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x) {
+    const size_t t = i / F, f = i % F;
+    const float gt = load_as_f(gu, t * 2 * F + f, dt), up = load_as_f(gu, t * 2 * F + F + f, dt);
+    const float sg = 1.f / (1.f + expf(-gt));
+    store_from_f(a, i, dt, gt * sg * up);
+  }
+}
+__global__ void swiglu_bwd_kernel(const void* da, const void* gu, void* dgu, int dt, size_t T, int F) {
+  const size_t n = T * F;
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x) {
+    const size_t t = i / F, f = i % F;
+    const float gt = load_as_f(gu, t * 2 * F + f, dt), up = load_as_f(gu, t * 2 * F + F + f, dt);
+    const float g = load_as_f(da, i, dt);
+    const float sg = 1.f / (1.f + expf(-gt));
+    store_from_f(dgu, t * 2 * F + f, dt, g * up * sg * (1.f + gt * (1.f - sg)));
+    store_from_f(dgu, t * 2 * F + F + f, dt, g * gt * sg);
+  }
+}
+
+// ------------------------------------------------------------------ colsum
+constexpr int CS_ROWS = 128;
+__global__ __launch_bounds__(256) void colsum_kernel(const void* x, int dt, int T, int N, long ld,
+                                                     float* partial) {
+  const int n = blockIdx.x * 256 + threadIdx.x;
+  const int r0 = blockIdx.y * CS_ROWS;
+  if (n >= N) return;
+  float s = 0.f;
+  const int r1 = min(T, r0 + CS_ROWS);
+  for (int r = r0; r < r1; ++r) s += load_as_f(x, (size_t)r * ld + n, dt);
+  partial[(size_t)blockIdx.y * N + n] = s;
+}
+__global__ void colsum_finish_kernel(const float* partial, int nchunk, int N, float* out, int accumulate) {
+  const int n = blockIdx.x * blockDim.x + threadIdx.x;
+  if (n >= N) return;
+  float s = 0.f;
+  for (int c = 0; c < nchunk; ++c) s += partial[(size_t)c * N + n];
+  out[n] = accumulate ? out[n] + s : s;
+}
+
+inline int grid_for(size_t n, int block = 256, int cap = 256 * 32) {
+  size_t g = (n + block - 1) / block;
+  return (int)(g < 1 ? 1 : (g > (size_t)cap ? cap : g));
+}
+bool ok_dtype(int dt) { return dt == LS_F32 || dt == LS_BF16 || dt == LS_F16; }
+
+}  // namespace
+
+extern "C" {
+
+ls_status lsk_convert(const void* src, int sdt, void* dst, int ddt, size_t n, void* stream) {
+  LS_REQUIRE(src && dst && ok_dtype(sdt) && ok_dtype(ddt), "convert: bad argument");
+  if (n == 0) return LS_OK;
+  convert_kernel<<<grid_for(n), 256, 0, (hipStream_t)stream>>>(src, sdt, dst, ddt, n);
+  LS_CHECK_LAUNCH();
+  return LS_OK;
+}
+
+ls_status lsk_norm_fwd(int kind, const float* x, int T, int d, const void* gamma, const void* beta,
+                       int pdt, float eps, void* h, int hdt, float* mean, float* rstd, void* stream) {
+  LS_REQUIRE(x && gamma && h && T > 0 && d > 0, "norm_fwd: bad argument");
+  LS_REQUIRE(kind == 0 || kind == 1, "norm_fwd: kind must be 0 (LayerNorm) or 1 (RMSNorm)");
+  norm_fwd_kernel<<<T, 256, 0, (hipStream_t)stream>>>(kind, x, d, gamma, beta, pdt, eps, h, hdt, mean, rstd);
+  LS_CHECK_LAUNCH();
+  return LS_OK;
+}
+
+size_t lsk_norm_bwd_partial_floats(int T, int d) {
+  return (size_t)((T + NB_ROWS - 1) / NB_ROWS) * 2 * d;
+}
+
+ls_status lsk_norm_bwd(int kind, const void* dh, int dhdt, const float* x, const float* mean,
+                       const float* rstd, const void* gamma, int pdt, int T, int d,
+                       const float* dres, float* dx, void* dx16, int dx16dt, float* dgamma,
+                       float* dbeta, int accumulate, float* partial, void* stream) {
+  LS_REQUIRE(dh && x && rstd && gamma && dx && partial && T > 0 && d > 0, "norm_bwd: bad argument");
+  LS_REQUIRE(kind == 1 || mean, "norm_bwd: LayerNorm needs the saved mean");
+  LS_REQUIRE(d <= 256 * NB_MAXCOL, "norm_bwd: d_model %d exceeds %d", d, 256 * NB_MAXCOL);
+  const int nwg = (T + NB_ROWS - 1) / NB_ROWS;
+  norm_bwd_kernel<<<nwg, 256, 0, (hipStream_t)stream>>>(kind, dh, dhdt, x, mean, rstd, gamma, pdt, T, d,
+                                                        dres, dx, dx16, dx16dt, partial);
+  LS_CHECK_LAUNCH();
+  if (dgamma || dbeta) {
+    norm_bwd_finish_kernel<<<(d + 255) / 256, 256, 0, (hipStream_t)stream>>>(
+        partial, nwg, d, dgamma, kind == 0 ? dbeta : nullptr, accumulate);
+    LS_CHECK_LAUNCH();
+  }
+  return LS_OK;
+}
+
+ls_status lsk_rope(void* qkv, int dt, int T, int h, int dh, const int32_t* pos, const float* table,
+                   float sign, void* stream) {
+  LS_REQUIRE(qkv && pos && table && T > 0 && h > 0 && dh > 0 && dh % 2 == 0, "rope: bad argument");
+  const size_t n = (size_t)T * 2 * h * (dh / 2);
+  rope_kernel<<<grid_for(n), 256, 0, (hipStream_t)stream>>>(qkv, dt, T, h, dh, pos, table, sign);
+  LS_CHECK_LAUNCH();
+  return LS_OK;
+}
+
+ls_status lsk_gelu_fwd(const void* u, void* g, int dt, size_t n, int kind, void* stream) {
+  LS_REQUIRE(u && g && n > 0, "gelu_fwd: bad argument");
+  gelu_fwd_kernel<<<grid_for(n), 256, 0, (hipStream_t)stream>>>(u, g, dt, n, kind);
+  LS_CHECK_LAUNCH();
+  return LS_OK;
+}
+ls_status lsk_gelu_bwd(const void* dg, const void* u, void* du, int dt, size_t n, int kind, void* stream) {
+  LS_REQUIRE(dg && u && du && n > 0, "gelu_bwd: bad argument");
+  gelu_bwd_kernel<<<grid_for(n), 256, 0, (hipStream_t)stream>>>(dg, u, du, dt, n, kind);
+  LS_CHECK_LAUNCH();
+  return LS_OK;
+}
+ls_status lsk_swiglu_fwd(const void* gu, void* a, int dt, int T, int F, void* stream) {
+  LS_REQUIRE(gu && a && T > 0 && F > 0, "swiglu_fwd: bad argument");
+  swiglu_fwd_kernel<<<grid_for((size_t)T * F), 256, 0, (hipStream_t)stream>>>(gu, a, dt, T, F);
+  LS_CHECK_LAUNCH();
+  return LS_OK;
+}
+ls_status lsk_swiglu_bwd(const void* da, const void* gu, void* dgu, int dt, int T, int F, void* stream) {
+  LS_REQUIRE(da && gu && dgu && T > 0 && F > 0, "swiglu_bwd: bad argument");
+  swiglu_bwd_kernel<<<grid_for((size_t)T * F), 256, 0, (hipStream_t)stream>>>(da, gu, dgu, dt, T, F);
+  LS_CHECK_LAUNCH();
+  return LS_OK;
+}
+
+size_t lsk_colsum_partial_floats(int T, int N) { return (size_t)((T + CS_ROWS - 1) / CS_ROWS) * N; }
+
+ls_status lsk_colsum(const void* x, int dt, int T, int N, long ld, float* out, int accumulate,
+                     float* partial, void* stream) {
+  LS_REQUIRE(x && out && partial && T > 0 && N > 0, "colsum: bad argument");
+  const int nchunk = (T + CS_ROWS - 1) / CS_ROWS;
+  colsum_kernel<<<dim3((N + 255) / 256, nchunk), 256, 0, (hipStream_t)stream>>>(x, dt, T, N, ld, partial);
+  LS_CHECK_LAUNCH();
+  colsum_finish_kernel<<<(N + 255) / 256, 256, 0, (hipStream_t)stream>>>(partial, nchunk, N, out, accumulate);
+  LS_CHECK_LAUNCH();
+  return LS_OK;
+}
+
+}  // extern "C"

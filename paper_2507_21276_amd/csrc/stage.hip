@@ -1,0 +1,574 @@
+// Stage-level entry points: a run of decoder blocks executed for inference
+// tasks (prefill, KV-cached decode) and training tasks (forward, backward), and
+// the two-stream interference probe.  This file only sequences the kernels
+// (lsk_*) and lays out the workspace / saved-activation buffers.
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "common.h"
+
+// ------------------------------------------------------------ error string
+static thread_local char g_err[512] = "";
+void ls_set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+extern "C" const char* ls_last_error(void) { return g_err; }
+
+// internal kernel-level entry points that are not part of the public kernel header
+extern "C" {
+ls_status lsk_attn_fwd_simple(const void*, int, int, int, int, int, void*, float*, void*);
+ls_status lsk_attn_bwd_simple(const void*, const void*, const void*, const float*, int, int, int, int, int,
+                              void*, float*, void*);
+ls_status lsk_attn_paged_simple(const void*, int, int, int, int, const int32_t*, const int32_t*,
+                                const void*, const void*, const int32_t*, int, int, int, void*, void*);
+}
+
+namespace {
+
+struct LayerOff {  // element offsets into the parameter vector
+  size_t n1_g, n1_b, w_qkv, b_qkv, w_o, b_o, n2_g, n2_b, w_up, b_up, w_dn, b_dn;
+};
+
+}  // namespace
+
+struct ls_stage {
+  ls_config cfg;
+  size_t n_params;
+  std::vector<LayerOff> off;
+  const void* params;   // caller's vector (cfg.dtype), borrowed
+  void* params_op;      // weights in the operand format (owned when it differs from params)
+  bool owns_op;
+  float* rope_table;    // [max_pos][head_dim/2][2]
+  int up_cols;          // F (GPT) or 2F (LLaMA)
+};
+
+namespace {
+
+// bump allocator over a caller buffer, 256-byte aligned pieces
+struct Bump {
+  char* p;
+  size_t used;
+  explicit Bump(void* base) : p((char*)base), used(0) {}
+  void* take(size_t bytes) {
+    void* r = p ? p + used : nullptr;
+    used += align_up(bytes, 256);
+    return r;
+  }
+};
+
+struct Chunks {  // prefill requests passed by value to the index kernel
+  int n;
+  int start[33];
+};
+
+__global__ void token_index_kernel(Chunks ch, const int32_t* ctx_len, int32_t* pos, int32_t* req) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= ch.start[ch.n]) return;
+  int b = 0;
+  while (t >= ch.start[b + 1]) ++b;
+  pos[t] = ctx_len[b] + (t - ch.start[b]);
+  req[t] = b;
+}
+__global__ void decode_index_kernel(int B, const int32_t* ctx_len, int32_t* pos, int32_t* req) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t >= B) return;
+  pos[t] = ctx_len[t];
+  req[t] = t;
+}
+__global__ void train_index_kernel(int T, int L, int32_t* pos) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < T) pos[t] = t % L;
+}
+
+inline const void* pptr(const ls_stage* s, size_t off) {  // gains / biases: caller's dtype
+  return (const char*)s->params + off * dtype_size(s->cfg.dtype);
+}
+inline const void* wptr(const ls_stage* s, size_t off) {  // weights: operand format
+  return (const char*)s->params_op + off * dtype_size(s->cfg.mma_dtype);
+}
+inline size_t osz(const ls_stage* s) { return dtype_size(s->cfg.mma_dtype); }
+
+ls_status check_stage(const ls_stage* s, bool need_params) {
+  LS_REQUIRE(s != nullptr, "null stage");
+  if (need_params && !s->params) {
+    ls_set_error("no parameters bound (call ls_bind_params first)");
+    return LS_ESTATE;
+  }
+  return LS_OK;
+}
+
+// per-layer slices of the saved-activation buffer
+struct Saved {
+  float *x_in, *mean1, *rstd1, *lse, *x1, *mean2, *rstd2;
+  void *h1, *qkv, *o, *h2, *up, *act;
+};
+size_t carve_saved(const ls_stage* s, void* base, int T, std::vector<Saved>* out) {
+  const ls_config& c = s->cfg;
+  const size_t d = c.d_model, e = osz(s);
+  Bump b(base);
+  for (int l = 0; l < c.n_layers; ++l) {
+    Saved v;
+    v.x_in = (float*)b.take(T * d * 4);
+    v.mean1 = (float*)b.take((size_t)T * 4);
+    v.rstd1 = (float*)b.take((size_t)T * 4);
+    v.h1 = b.take(T * d * e);
+    v.qkv = b.take(T * 3 * d * e);
+    v.o = b.take(T * d * e);
+    v.lse = (float*)b.take((size_t)T * c.n_heads * 4);
+    v.x1 = (float*)b.take(T * d * 4);
+    v.mean2 = (float*)b.take((size_t)T * 4);
+    v.rstd2 = (float*)b.take((size_t)T * 4);
+    v.h2 = b.take(T * d * e);
+    v.up = b.take((size_t)T * s->up_cols * e);
+    v.act = b.take((size_t)T * c.d_ff * e);
+    if (out) out->push_back(v);
+  }
+  return b.used;
+}
+
+// forward / serving scratch
+struct FwdWs {
+  int32_t *pos, *req;
+  float *xa, *xb;
+  void *h, *qkv, *o, *up, *act;
+};
+size_t carve_fwd(const ls_stage* s, void* base, int T, FwdWs* w) {
+  const ls_config& c = s->cfg;
+  const size_t d = c.d_model, e = osz(s);
+  Bump b(base);
+  FwdWs v;
+  v.pos = (int32_t*)b.take((size_t)T * 4);
+  v.req = (int32_t*)b.take((size_t)T * 4);
+  v.xa = (float*)b.take(T * d * 4);
+  v.xb = (float*)b.take(T * d * 4);
+  v.h = b.take(T * d * e);
+  v.qkv = b.take(T * 3 * d * e);
+  v.o = b.take(T * d * e);
+  v.up = b.take((size_t)T * s->up_cols * e);
+  v.act = b.take((size_t)T * c.d_ff * e);
+  if (w) *w = v;
+  return b.used;
+}
+
+// backward scratch
+struct BwdWs {
+  int32_t* pos;
+  float *g, *g1, *dvec, *partial;
+  void *g16, *dact, *dup, *dh, *dqkv, *d_o;
+};
+size_t carve_bwd(const ls_stage* s, void* base, int T, BwdWs* w) {
+  const ls_config& c = s->cfg;
+  const size_t d = c.d_model, e = osz(s);
+  Bump b(base);
+  BwdWs v;
+  v.pos = (int32_t*)b.take((size_t)T * 4);
+  v.g = (float*)b.take(T * d * 4);
+  v.g1 = (float*)b.take(T * d * 4);
+  v.g16 = b.take(T * d * e);
+  v.dact = b.take((size_t)T * c.d_ff * e);
+  v.dup = b.take((size_t)T * s->up_cols * e);
+  v.dh = b.take(T * d * e);
+  v.dqkv = b.take(T * 3 * d * e);
+  v.d_o = b.take(T * d * e);
+  v.dvec = (float*)b.take((size_t)T * c.n_heads * 4);
+  size_t pf = lsk_norm_bwd_partial_floats(T, c.d_model);
+  const size_t widest = (size_t)(3 * c.d_model > s->up_cols ? 3 * c.d_model : s->up_cols);
+  const size_t cf = lsk_colsum_partial_floats(T, (int)widest);
+  if (cf > pf) pf = cf;
+  v.partial = (float*)b.take(pf * 4);
+  if (w) *w = v;
+  return b.used;
+}
+
+// one block's forward on the fp32 stream x -> y.  Training keeps everything in
+// `sv`; serving passes its scratch and a KV descriptor.
+struct FwdBufs {
+  const float* x;
+  float *x1, *y, *mean1, *rstd1, *mean2, *rstd2, *lse;
+  void *h1, *qkv, *o, *h2, *up, *act;
+};
+
+ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const int32_t* pos,
+                        const int32_t* req, int B, int L, const ls_kv* kv, int max_ctx,
+                        hipStream_t st) {
+  const ls_config& c = s->cfg;
+  const LayerOff& o = s->off[l];
+  const int d = c.d_model, F = c.d_ff, mt = c.mma_dtype, pt = c.dtype;
+  const bool gpt = c.block == LS_BLOCK_GPT_PRELN;
+  const int nk = gpt ? 0 : 1;
+  LS_TRY(lsk_norm_fwd(nk, f.x, T, d, pptr(s, o.n1_g), gpt ? pptr(s, o.n1_b) : nullptr, pt, c.norm_eps,
+                      f.h1, mt, f.mean1, f.rstd1, st));
+  LS_TRY(lsk_gemm(mt, T, 3 * d, d, f.h1, d, 1, wptr(s, o.w_qkv), d, 1, f.qkv, 3 * d, mt,
+                  gpt ? pptr(s, o.b_qkv) : nullptr, pt, nullptr, 0, 0, st));
+  if (!gpt) LS_TRY(lsk_rope(f.qkv, mt, T, c.n_heads, c.head_dim, pos, s->rope_table, 1.0f, st));
+  if (kv) {
+    const size_t slab = (size_t)kv->n_pages * c.n_heads * c.page_size * c.head_dim * osz(s);
+    void* kp = (char*)kv->k_pool + (size_t)l * slab;
+    void* vp = (char*)kv->v_pool + (size_t)l * slab;
+    LS_TRY(lsk_kv_write(f.qkv, mt, T, c.n_heads, c.head_dim, pos, req, kp, vp, kv->block_table,
+                        kv->max_pages_per_req, c.page_size, st));
+    LS_TRY(lsk_attn_paged_simple(f.qkv, mt, T, c.n_heads, c.head_dim, pos, req, kp, vp, kv->block_table,
+                                 kv->max_pages_per_req, c.page_size, max_ctx, f.o, st));
+  } else {
+    LS_TRY(lsk_attn_fwd(mt == LS_F32 ? 0 : 1, f.qkv, mt, B, L, c.n_heads, c.head_dim, f.o, f.lse, st));
+  }
+  LS_TRY(lsk_gemm(mt, T, d, d, f.o, d, 1, wptr(s, o.w_o), d, 1, f.x1, d, LS_F32,
+                  gpt ? pptr(s, o.b_o) : nullptr, pt, f.x, d, 0, st));
+  LS_TRY(lsk_norm_fwd(nk, f.x1, T, d, pptr(s, o.n2_g), gpt ? pptr(s, o.n2_b) : nullptr, pt, c.norm_eps,
+                      f.h2, mt, f.mean2, f.rstd2, st));
+  LS_TRY(lsk_gemm(mt, T, s->up_cols, d, f.h2, d, 1, wptr(s, o.w_up), d, 1, f.up, s->up_cols, mt,
+                  gpt ? pptr(s, o.b_up) : nullptr, pt, nullptr, 0, 0, st));
+  if (gpt) LS_TRY(lsk_gelu_fwd(f.up, f.act, mt, (size_t)T * F, c.act, st));
+  else LS_TRY(lsk_swiglu_fwd(f.up, f.act, mt, T, F, st));
+  LS_TRY(lsk_gemm(mt, T, d, F, f.act, F, 1, wptr(s, o.w_dn), F, 1, f.y, d, LS_F32,
+                  gpt ? pptr(s, o.b_dn) : nullptr, pt, f.x1, d, 0, st));
+  return LS_OK;
+}
+
+ls_status check_kv(const ls_stage* s, const ls_kv* kv, int B, const int32_t* new_tokens, int* max_ctx) {
+  const ls_config& c = s->cfg;
+  LS_REQUIRE(kv && kv->k_pool && kv->v_pool && kv->block_table && kv->ctx_len, "kv: null field");
+  LS_REQUIRE(kv->n_pages > 0 && kv->max_pages_per_req > 0, "kv: non-positive page counts");
+  int mc = 0;
+  for (int b = 0; b < B; ++b) {
+    const int nt = new_tokens ? new_tokens[b] : 1;
+    LS_REQUIRE(nt > 0, "request %d has %d new tokens", b, nt);
+    if (kv->ctx_len_host) {
+      const long tot = (long)kv->ctx_len_host[b] + nt;
+      LS_REQUIRE(kv->ctx_len_host[b] >= 0, "request %d has negative context length", b);
+      LS_REQUIRE((tot + c.page_size - 1) / c.page_size <= kv->max_pages_per_req,
+                 "request %d needs %ld tokens of KV but the block table holds %d pages of %d", b, tot,
+                 kv->max_pages_per_req, c.page_size);
+      LS_REQUIRE(c.block != LS_BLOCK_LLAMA || tot <= c.max_pos, "request %d reaches position %ld >= max_pos %d",
+                 b, tot, c.max_pos);
+      if (tot > mc) mc = (int)tot;
+    }
+  }
+  if (!kv->ctx_len_host) mc = kv->max_pages_per_req * c.page_size;
+  *max_ctx = mc;
+  return LS_OK;
+}
+
+ls_status serve_forward(ls_stage* s, const void* X, int T, int B, const ls_kv* kv, int max_ctx, void* Y,
+                        const FwdWs& w, hipStream_t st) {
+  const ls_config& c = s->cfg;
+  LS_TRY(lsk_convert(X, c.io_dtype, w.xa, LS_F32, (size_t)T * c.d_model, st));
+  for (int l = 0; l < c.n_layers; ++l) {
+    FwdBufs f{w.xa, w.xb, w.xa, nullptr, nullptr, nullptr, nullptr, nullptr,
+              w.h, w.qkv, w.o, w.h, w.up, w.act};
+    LS_TRY(block_forward(s, l, T, f, w.pos, w.req, B, 0, kv, max_ctx, st));
+  }
+  return lsk_convert(w.xa, LS_F32, Y, c.io_dtype, (size_t)T * c.d_model, st);
+}
+
+}  // namespace
+
+extern "C" {
+
+ls_status ls_create(const ls_config* cfg, ls_stage** out) {
+  LS_REQUIRE(cfg && out, "ls_create: null argument");
+  const ls_config& c = *cfg;
+  LS_REQUIRE(c.block == LS_BLOCK_GPT_PRELN || c.block == LS_BLOCK_LLAMA, "unknown block type %d", c.block);
+  LS_REQUIRE(c.dtype == LS_F32 || c.dtype == LS_BF16, "dtype must be LS_F32 or LS_BF16");
+  LS_REQUIRE(c.io_dtype == LS_F32 || c.io_dtype == LS_BF16, "io_dtype must be LS_F32 or LS_BF16");
+  if (c.dtype == LS_F32)
+    LS_REQUIRE(c.mma_dtype == LS_F32 && c.io_dtype == LS_F32, "an fp32 stage needs fp32 io and operands");
+  else
+    LS_REQUIRE(c.mma_dtype == LS_BF16 || c.mma_dtype == LS_F16, "a bf16 stage needs bf16 or fp16 operands");
+  LS_REQUIRE(c.n_layers > 0 && c.d_model > 0 && c.n_heads > 0 && c.d_ff > 0, "non-positive size");
+  LS_REQUIRE(c.head_dim == 32 || c.head_dim == 64 || c.head_dim == 128, "head_dim must be 32, 64 or 128");
+  LS_REQUIRE(c.d_model == c.n_heads * c.head_dim, "d_model %d != n_heads %d * head_dim %d", c.d_model,
+             c.n_heads, c.head_dim);
+  LS_REQUIRE(c.d_ff % 8 == 0, "d_ff must be a multiple of 8");
+  LS_REQUIRE(c.page_size >= 8 && c.page_size <= 64 && (c.page_size & (c.page_size - 1)) == 0,
+             "page_size must be a power of two in 8..64");
+  if (c.block == LS_BLOCK_GPT_PRELN)
+    LS_REQUIRE(c.act == LS_ACT_GELU_TANH || c.act == LS_ACT_GELU_ERF, "GPT blocks use a GELU activation");
+  else
+    LS_REQUIRE(c.act == LS_ACT_SWIGLU && c.max_pos > 0 && c.rope_theta > 0, "LLaMA blocks use SwiGLU and RoPE");
+  LS_REQUIRE(c.norm_eps > 0, "norm_eps must be positive");
+
+  ls_stage* s = new (std::nothrow) ls_stage();
+  if (!s) { ls_set_error("host allocation failed"); return LS_ENOMEM; }
+  s->cfg = c;
+  s->params = nullptr; s->params_op = nullptr; s->owns_op = false; s->rope_table = nullptr;
+  const bool gpt = c.block == LS_BLOCK_GPT_PRELN;
+  const size_t d = c.d_model, F = c.d_ff;
+  s->up_cols = gpt ? (int)F : (int)(2 * F);
+  size_t off = 0;
+  for (int l = 0; l < c.n_layers; ++l) {
+    LayerOff o{};
+    if (gpt) {
+      o.n1_g = off; off += d; o.n1_b = off; off += d;
+      o.w_qkv = off; off += 3 * d * d; o.b_qkv = off; off += 3 * d;
+      o.w_o = off; off += d * d; o.b_o = off; off += d;
+      o.n2_g = off; off += d; o.n2_b = off; off += d;
+      o.w_up = off; off += F * d; o.b_up = off; off += F;
+      o.w_dn = off; off += d * F; o.b_dn = off; off += d;
+    } else {
+      o.n1_g = off; off += d;
+      o.w_qkv = off; off += 3 * d * d;
+      o.w_o = off; off += d * d;
+      o.n2_g = off; off += d;
+      o.w_up = off; off += 2 * F * d;
+      o.w_dn = off; off += d * F;
+    }
+    s->off.push_back(o);
+  }
+  s->n_params = off;
+  if (c.mma_dtype != c.dtype) {
+    if (hipMalloc(&s->params_op, off * dtype_size(c.mma_dtype)) != hipSuccess) {
+      ls_set_error("device allocation of %zu bytes for the operand-format weights failed",
+                   off * dtype_size(c.mma_dtype));
+      delete s;
+      return LS_ENOMEM;
+    }
+    s->owns_op = true;
+  }
+  if (!gpt) {
+    const int half = c.head_dim / 2;
+    std::vector<float> tab((size_t)c.max_pos * half * 2);
+    for (int p = 0; p < c.max_pos; ++p)
+      for (int i = 0; i < half; ++i) {
+        const double ang = (double)p * pow((double)c.rope_theta, -2.0 * i / c.head_dim);
+        tab[((size_t)p * half + i) * 2] = (float)cos(ang);
+        tab[((size_t)p * half + i) * 2 + 1] = (float)sin(ang);
+      }
+    if (hipMalloc(&s->rope_table, tab.size() * 4) != hipSuccess ||
+        hipMemcpy(s->rope_table, tab.data(), tab.size() * 4, hipMemcpyHostToDevice) != hipSuccess) {
+      ls_set_error("device allocation of the RoPE table failed");
+      ls_destroy(s);
+      return LS_ENOMEM;
+    }
+  }
+  *out = s;
+  return LS_OK;
+}
+
+void ls_destroy(ls_stage* s) {
+  if (!s) return;
+  if (s->owns_op && s->params_op) (void)hipFree(s->params_op);
+  if (s->rope_table) (void)hipFree(s->rope_table);
+  delete s;
+}
+
+size_t ls_param_count(const ls_stage* s) { return s ? s->n_params : 0; }
+
+ls_status ls_bind_params(ls_stage* s, const void* params, void* stream) {
+  LS_TRY(check_stage(s, false));
+  LS_REQUIRE(params != nullptr, "ls_bind_params: null parameter vector");
+  LS_REQUIRE(((uintptr_t)params % 16) == 0, "ls_bind_params: parameter vector must be 16-byte aligned");
+  s->params = params;
+  if (s->owns_op) return lsk_convert(params, s->cfg.dtype, s->params_op, s->cfg.mma_dtype, s->n_params, stream);
+  s->params_op = const_cast<void*>(params);
+  return LS_OK;
+}
+
+size_t ls_workspace_bytes(const ls_stage* s, int max_tokens) {
+  if (!s || max_tokens <= 0) return 0;
+  const size_t a = carve_fwd(s, nullptr, max_tokens, nullptr);
+  const size_t b = carve_bwd(s, nullptr, max_tokens, nullptr);
+  return (a > b ? a : b) + 256;
+}
+
+size_t ls_saved_bytes(const ls_stage* s, int B, int L) {
+  if (!s || B <= 0 || L <= 0) return 0;
+  return carve_saved(s, nullptr, B * L, nullptr) + 256;
+}
+
+ls_status stage_prefill(ls_stage* s, const void* X, const int32_t* chunk_len, int B, const ls_kv* kv,
+                        void* Y, void* workspace, void* stream) {
+  LS_TRY(check_stage(s, true));
+  LS_REQUIRE(X && Y && workspace && chunk_len, "stage_prefill: null argument");
+  LS_REQUIRE(B > 0 && B <= 32, "stage_prefill: B must be in 1..32, got %d", B);
+  int max_ctx = 0;
+  LS_TRY(check_kv(s, kv, B, chunk_len, &max_ctx));
+  Chunks ch;
+  ch.n = B;
+  ch.start[0] = 0;
+  for (int b = 0; b < B; ++b) ch.start[b + 1] = ch.start[b] + chunk_len[b];
+  const int T = ch.start[B];
+  hipStream_t st = (hipStream_t)stream;
+  FwdWs w;
+  carve_fwd(s, workspace, T, &w);
+  token_index_kernel<<<(T + 255) / 256, 256, 0, st>>>(ch, kv->ctx_len, w.pos, w.req);
+  LS_CHECK_LAUNCH();
+  return serve_forward(s, X, T, B, kv, max_ctx, Y, w, st);
+}
+
+ls_status stage_decode(ls_stage* s, const void* X, int B, const ls_kv* kv, void* Y, void* workspace,
+                       void* stream) {
+  LS_TRY(check_stage(s, true));
+  LS_REQUIRE(X && Y && workspace, "stage_decode: null argument");
+  LS_REQUIRE(B > 0, "stage_decode: B must be positive, got %d", B);
+  int max_ctx = 0;
+  LS_TRY(check_kv(s, kv, B, nullptr, &max_ctx));
+  hipStream_t st = (hipStream_t)stream;
+  FwdWs w;
+  carve_fwd(s, workspace, B, &w);
+  decode_index_kernel<<<(B + 255) / 256, 256, 0, st>>>(B, kv->ctx_len, w.pos, w.req);
+  LS_CHECK_LAUNCH();
+  return serve_forward(s, X, B, B, kv, max_ctx, Y, w, st);
+}
+
+ls_status stage_train_fwd(ls_stage* s, const void* X, int B, int L, void* Y, void* saved, void* workspace,
+                          void* stream) {
+  LS_TRY(check_stage(s, true));
+  LS_REQUIRE(X && Y && saved && workspace, "stage_train_fwd: null argument");
+  LS_REQUIRE(B > 0 && L > 0, "stage_train_fwd: B and L must be positive (B=%d L=%d)", B, L);
+  const ls_config& c = s->cfg;
+  LS_REQUIRE(c.block != LS_BLOCK_LLAMA || L <= c.max_pos, "stage_train_fwd: L %d exceeds max_pos %d", L, c.max_pos);
+  const int T = B * L;
+  hipStream_t st = (hipStream_t)stream;
+  std::vector<Saved> sv;
+  carve_saved(s, saved, T, &sv);
+  FwdWs w;
+  carve_fwd(s, workspace, T, &w);
+  train_index_kernel<<<(T + 255) / 256, 256, 0, st>>>(T, L, w.pos);
+  LS_CHECK_LAUNCH();
+  LS_TRY(lsk_convert(X, c.io_dtype, sv[0].x_in, LS_F32, (size_t)T * c.d_model, st));
+  for (int l = 0; l < c.n_layers; ++l) {
+    float* y = l + 1 < c.n_layers ? sv[l + 1].x_in : w.xa;
+    FwdBufs f{sv[l].x_in, sv[l].x1, y, sv[l].mean1, sv[l].rstd1, sv[l].mean2, sv[l].rstd2, sv[l].lse,
+              sv[l].h1, sv[l].qkv, sv[l].o, sv[l].h2, sv[l].up, sv[l].act};
+    LS_TRY(block_forward(s, l, T, f, w.pos, nullptr, B, L, nullptr, 0, st));
+  }
+  return lsk_convert(w.xa, LS_F32, Y, c.io_dtype, (size_t)T * c.d_model, st);
+}
+
+ls_status stage_train_bwd(ls_stage* s, const void* dY, int B, int L, const void* saved, void* dX,
+                          float* dParams, int accumulate, void* workspace, void* stream) {
+  LS_TRY(check_stage(s, true));
+  LS_REQUIRE(dY && saved && dX && dParams && workspace, "stage_train_bwd: null argument");
+  LS_REQUIRE(B > 0 && L > 0, "stage_train_bwd: B and L must be positive (B=%d L=%d)", B, L);
+  const ls_config& c = s->cfg;
+  const int T = B * L, d = c.d_model, F = c.d_ff, mt = c.mma_dtype, pt = c.dtype, U = s->up_cols;
+  const bool gpt = c.block == LS_BLOCK_GPT_PRELN;
+  const int nk = gpt ? 0 : 1, acc = accumulate ? 1 : 0;
+  hipStream_t st = (hipStream_t)stream;
+  std::vector<Saved> sv;
+  carve_saved(s, const_cast<void*>(saved), T, &sv);
+  BwdWs w;
+  carve_bwd(s, workspace, T, &w);
+  train_index_kernel<<<(T + 255) / 256, 256, 0, st>>>(T, L, w.pos);
+  LS_CHECK_LAUNCH();
+  LS_TRY(lsk_convert(dY, c.io_dtype, w.g, LS_F32, (size_t)T * d, st));
+  LS_TRY(lsk_convert(dY, c.io_dtype, w.g16, mt, (size_t)T * d, st));
+  for (int l = c.n_layers - 1; l >= 0; --l) {
+    const LayerOff& o = s->off[l];
+    const Saved& v = sv[l];
+    // y = x1 + act W_dn^T (+ b_dn)
+    LS_TRY(lsk_gemm(mt, T, F, d, w.g16, d, 1, wptr(s, o.w_dn), F, 0, w.dact, F, mt, nullptr, 0, nullptr, 0, 0, st));
+    LS_TRY(lsk_gemm(mt, d, F, T, w.g16, d, 0, v.act, F, 0, dParams + o.w_dn, F, LS_F32, nullptr, 0, nullptr, 0, acc, st));
+    if (gpt) {
+      LS_TRY(lsk_colsum(w.g16, mt, T, d, d, dParams + o.b_dn, acc, w.partial, st));
+      LS_TRY(lsk_gelu_bwd(w.dact, v.up, w.dup, mt, (size_t)T * F, c.act, st));
+    } else {
+      LS_TRY(lsk_swiglu_bwd(w.dact, v.up, w.dup, mt, T, F, st));
+    }
+    // up = h2 W_up^T (+ b_up)
+    LS_TRY(lsk_gemm(mt, T, d, U, w.dup, U, 1, wptr(s, o.w_up), d, 0, w.dh, d, mt, nullptr, 0, nullptr, 0, 0, st));
+    LS_TRY(lsk_gemm(mt, U, d, T, w.dup, U, 0, v.h2, d, 0, dParams + o.w_up, d, LS_F32, nullptr, 0, nullptr, 0, acc, st));
+    if (gpt) LS_TRY(lsk_colsum(w.dup, mt, T, U, U, dParams + o.b_up, acc, w.partial, st));
+    // h2 = norm2(x1);  g1 = g + norm2_bwd(dh)
+    LS_TRY(lsk_norm_bwd(nk, w.dh, mt, v.x1, v.mean2, v.rstd2, pptr(s, o.n2_g), pt, T, d, w.g, w.g1, w.g16, mt,
+                        dParams + o.n2_g, gpt ? dParams + o.n2_b : nullptr, acc, w.partial, st));
+    // x1 = x + o W_o^T (+ b_o)
+    LS_TRY(lsk_gemm(mt, T, d, d, w.g16, d, 1, wptr(s, o.w_o), d, 0, w.d_o, d, mt, nullptr, 0, nullptr, 0, 0, st));
+    LS_TRY(lsk_gemm(mt, d, d, T, w.g16, d, 0, v.o, d, 0, dParams + o.w_o, d, LS_F32, nullptr, 0, nullptr, 0, acc, st));
+    if (gpt) LS_TRY(lsk_colsum(w.g16, mt, T, d, d, dParams + o.b_o, acc, w.partial, st));
+    LS_TRY(lsk_attn_bwd(mt == LS_F32 ? 0 : 1, v.qkv, v.o, w.d_o, v.lse, mt, B, L, c.n_heads, c.head_dim, w.dqkv,
+                        w.dvec, st));
+    if (!gpt) LS_TRY(lsk_rope(w.dqkv, mt, T, c.n_heads, c.head_dim, w.pos, s->rope_table, -1.0f, st));
+    // qkv = h1 W_qkv^T (+ b_qkv)
+    LS_TRY(lsk_gemm(mt, T, d, 3 * d, w.dqkv, 3 * d, 1, wptr(s, o.w_qkv), d, 0, w.dh, d, mt, nullptr, 0, nullptr, 0, 0, st));
+    LS_TRY(lsk_gemm(mt, 3 * d, d, T, w.dqkv, 3 * d, 0, v.h1, d, 0, dParams + o.w_qkv, d, LS_F32, nullptr, 0, nullptr, 0, acc, st));
+    if (gpt) LS_TRY(lsk_colsum(w.dqkv, mt, T, 3 * d, 3 * d, dParams + o.b_qkv, acc, w.partial, st));
+    // h1 = norm1(x);  g = g1 + norm1_bwd(dh)
+    LS_TRY(lsk_norm_bwd(nk, w.dh, mt, v.x_in, v.mean1, v.rstd1, pptr(s, o.n1_g), pt, T, d, w.g1, w.g, w.g16, mt,
+                        dParams + o.n1_g, gpt ? dParams + o.n1_b : nullptr, acc, w.partial, st));
+  }
+  return lsk_convert(w.g, LS_F32, dX, c.io_dtype, (size_t)T * d, st);
+}
+
+ls_status stage_probe_interference(ls_stage* s, const void* dec_X, int dec_B, const ls_kv* kv, void* dec_Y,
+                                   void* ws_a, const void* trn_X, int trn_B, int trn_L, void* trn_Y,
+                                   void* trn_saved, const void* trn_dY, void* trn_dX, float* trn_dParams,
+                                   void* ws_b, void* stream_a, void* stream_b, int iters, float* out_ms) {
+  LS_TRY(check_stage(s, true));
+  LS_REQUIRE(out_ms && iters > 0, "probe: bad iters or null out_ms");
+  LS_REQUIRE(stream_a != stream_b, "probe: the two streams must differ");
+  LS_REQUIRE(ws_a != ws_b, "probe: the two calls need separate workspaces");
+  hipStream_t sa = (hipStream_t)stream_a, sb = (hipStream_t)stream_b;
+  hipEvent_t ea0, ea1, eb0, eb1;
+  LS_CHECK_HIP(hipEventCreate(&ea0));
+  LS_CHECK_HIP(hipEventCreate(&ea1));
+  LS_CHECK_HIP(hipEventCreate(&eb0));
+  LS_CHECK_HIP(hipEventCreate(&eb1));
+  ls_status rc = LS_OK;
+  auto run_a = [&]() { return stage_decode(s, dec_X, dec_B, kv, dec_Y, ws_a, sa); };
+  auto run_b = [&]() {
+    ls_status r = stage_train_fwd(s, trn_X, trn_B, trn_L, trn_Y, trn_saved, ws_b, sb);
+    if (r != LS_OK) return r;
+    return stage_train_bwd(s, trn_dY, trn_B, trn_L, trn_saved, trn_dX, trn_dParams, 0, ws_b, sb);
+  };
+  float ms = 0.f;
+  memset(out_ms, 0, 6 * sizeof(float));
+  do {
+    // warm-up of both paths
+    if ((rc = run_a()) != LS_OK) break;
+    if ((rc = run_b()) != LS_OK) break;
+    if (hipStreamSynchronize(sa) != hipSuccess || hipStreamSynchronize(sb) != hipSuccess) { rc = LS_EHIP; break; }
+    // A alone
+    (void)hipEventRecord(ea0, sa);
+    for (int i = 0; i < iters && rc == LS_OK; ++i) rc = run_a();
+    (void)hipEventRecord(ea1, sa);
+    if (rc != LS_OK) break;
+    if (hipEventSynchronize(ea1) != hipSuccess) { rc = LS_EHIP; break; }
+    (void)hipEventElapsedTime(&ms, ea0, ea1);
+    out_ms[0] = ms / iters;
+    // B alone
+    (void)hipEventRecord(eb0, sb);
+    for (int i = 0; i < iters && rc == LS_OK; ++i) rc = run_b();
+    (void)hipEventRecord(eb1, sb);
+    if (rc != LS_OK) break;
+    if (hipEventSynchronize(eb1) != hipSuccess) { rc = LS_EHIP; break; }
+    (void)hipEventElapsedTime(&ms, eb0, eb1);
+    out_ms[1] = ms / iters;
+    // together: the training stream is enqueued first (it is the long one),
+    // the decode stream keeps issuing steps until it has done `iters` of them
+    (void)hipEventRecord(eb0, sb);
+    (void)hipEventRecord(ea0, sa);
+    for (int i = 0; i < iters && rc == LS_OK; ++i) {
+      rc = run_b();
+      if (rc == LS_OK) rc = run_a();
+    }
+    (void)hipEventRecord(ea1, sa);
+    (void)hipEventRecord(eb1, sb);
+    if (rc != LS_OK) break;
+    if (hipEventSynchronize(ea1) != hipSuccess || hipEventSynchronize(eb1) != hipSuccess) { rc = LS_EHIP; break; }
+    (void)hipEventElapsedTime(&ms, ea0, ea1);
+    out_ms[2] = ms / iters;
+    (void)hipEventElapsedTime(&ms, eb0, eb1);
+    out_ms[3] = ms / iters;
+    float w0 = 0.f;
+    (void)hipEventElapsedTime(&w0, eb0, ea1);
+    out_ms[4] = (ms > w0 ? ms : w0) / iters;
+  } while (0);
+  if (rc == LS_EHIP) ls_set_error("probe: a HIP synchronisation failed");
+  (void)hipStreamSynchronize(sa);
+  (void)hipStreamSynchronize(sb);
+  (void)hipEventDestroy(ea0); (void)hipEventDestroy(ea1);
+  (void)hipEventDestroy(eb0); (void)hipEventDestroy(eb1);
+  return rc;
+}
+
+}  // extern "C"

@@ -1,0 +1,83 @@
+"""CPU-side checks of the C ABI: the library loads, exports every declared
+symbol, and validates arguments on the host (no kernel is launched)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2507_21276_amd import binding as Bd
+from paper_2507_21276_amd import synth_inputs as S
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    names = set()
+    for hdr in ("lemix_stage.h", "lemix_kernels.h"):
+        txt = open(os.path.join(ROOT, "include", hdr)).read()
+        txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+        names |= set(re.findall(r"\b((?:ls|lsk|stage)_[a-z0-9_]+)\s*\(", txt))
+    return names
+
+
+def test_library_exports_every_declared_symbol():
+    lib = Bd.lib()
+    decl = declared_symbols()
+    assert len(decl) >= 25
+    for name in decl:
+        assert hasattr(lib, name), f"{name} is declared in include/ but not exported"
+    assert decl == set(Bd.SIGNATURES), decl ^ set(Bd.SIGNATURES)
+
+
+def test_config_struct_matches_header_field_order():
+    txt = open(os.path.join(ROOT, "include", "lemix_stage.h")).read()
+    body = re.search(r"typedef struct \{([^}]*)\} ls_config;", txt, re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = [f.strip() for decl in body.split(";") for f in re.sub(r"^\s*\w+\s+", "", decl.strip()).split(",") if f.strip()]
+    assert fields == [n for n, _ in Bd.ls_config._fields_]
+
+
+def _create(cfg_over=None, **kw):
+    cfg = dict(S.CONFIGS["tiny_gpt_f32"])
+    cfg.update(cfg_over or {})
+    c = Bd.make_config(cfg, **kw)
+    h = C.c_void_p()
+    st = Bd.lib().ls_create(C.byref(c), C.byref(h))
+    return st, h
+
+
+@pytest.mark.parametrize("over,frag", [
+    (dict(d_model=130), "d_model"),
+    (dict(head_dim=48, d_model=192), "head_dim"),
+    (dict(d_ff=509), "d_ff"),
+    (dict(page_size=12), "page_size"),
+    (dict(act="swiglu"), "GELU"),
+    (dict(n_layers=0), "non-positive"),
+])
+def test_create_rejects_bad_configs_on_the_host(over, frag):
+    st, _ = _create(over)
+    assert st == Bd.LS_EINVAL
+    assert frag in Bd.lib().ls_last_error().decode()
+
+
+def test_create_rejects_mixed_precision_mismatch():
+    st, _ = _create(None, mma_dtype="bf16")
+    assert st == Bd.LS_EINVAL
+    cfg = dict(S.CONFIGS["gpt2s_bf16"])
+    c = Bd.make_config(cfg, mma_dtype="f32")
+    h = C.c_void_p()
+    assert Bd.lib().ls_create(C.byref(c), C.byref(h)) == Bd.LS_EINVAL
+
+
+def test_null_arguments_are_errors_not_crashes():
+    lib = Bd.lib()
+    assert lib.ls_create(None, None) == Bd.LS_EINVAL
+    assert lib.ls_param_count(None) == 0
+    assert lib.ls_workspace_bytes(None, 10) == 0
+    assert lib.stage_decode(None, None, 1, None, None, None, None) == Bd.LS_EINVAL
+    assert lib.stage_train_fwd(None, None, 1, 1, None, None, None, None) == Bd.LS_EINVAL
+    assert lib.lsk_gemm(Bd.LS_BF16, 0, 8, 8, None, 8, 1, None, 8, 1, None, 8, Bd.LS_BF16, None, 0, None, 0,
+                        0, None) == Bd.LS_EINVAL
+    assert b"non-positive" in lib.ls_last_error()
+    lib.ls_destroy(None)

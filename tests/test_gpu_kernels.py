@@ -1,0 +1,261 @@
+"""GPU parity of the individual kernels against the CPU oracle (through the C ABI)."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import stage_oracle as O
+from paper_2507_21276_amd import binding as Bd
+from paper_2507_21276_amd import synth_inputs as S
+from parity_util import TOL, assert_close, dev, host
+
+pytestmark = pytest.mark.gpu
+
+DT = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
+# tolerance by operand type: fp16 operands are held to the bf16 bar too
+KTOL = {"f32": 1e-4, "bf16": 2e-2, "f16": 2e-2}
+
+
+def q(x, name):
+    """Round host data to what the kernel will read."""
+    if name == "f32":
+        return np.asarray(x, np.float32)
+    if name == "bf16":
+        return S.round_bf16(x)
+    return np.asarray(x, np.float32).astype(np.float16).astype(np.float32)
+
+
+@pytest.mark.parametrize("name", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("M,N,K", [(300, 264, 328), (512, 768, 256), (64, 1048, 136), (5, 8, 8), (257, 520, 1000)])
+def test_gemm_forward_layout_with_bias_and_residual(name, M, N, K):
+    A = q(S.normal(1, "A", (M, K)), name)
+    W = q(S.normal(1, "W", (N, K), 0.05), name)
+    bias = q(S.normal(1, "b", (N,)), "f32" if name == "f32" else "bf16")
+    R = S.normal(1, "R", (M, N))
+    ref = A.astype(np.float64) @ W.astype(np.float64).T + bias + R
+    out = torch.empty(M, N, dtype=torch.float32, device="cuda")
+    Bd.lsk_gemm(dev(A, DT[name]), dev(W, DT[name]), out, M=M, N=N, K=K,
+                bias=dev(bias, torch.float32 if name == "f32" else torch.bfloat16), resid=dev(R, torch.float32))
+    assert_close(host(out), ref, KTOL[name] if name == "f32" else 1e-5, f"gemm NT {name}")
+    if name != "f32":   # operand-typed output, no residual
+        out16 = torch.empty(M, N, dtype=DT[name], device="cuda")
+        Bd.lsk_gemm(dev(A, DT[name]), dev(W, DT[name]), out16, M=M, N=N, K=K)
+        assert_close(host(out16), A.astype(np.float64) @ W.astype(np.float64).T, KTOL[name], f"gemm NT16 {name}")
+
+
+@pytest.mark.parametrize("name", ["f32", "bf16", "f16"])
+@pytest.mark.parametrize("T,N,K", [(300, 264, 328), (130, 512, 768), (7, 16, 24)])
+def test_gemm_input_and_weight_gradient_layouts(name, T, N, K):
+    dY = q(S.normal(2, "dY", (T, N)), name)
+    W = q(S.normal(2, "W", (N, K), 0.05), name)
+    X = q(S.normal(2, "X", (T, K)), name)
+    dYd, Wd, Xd = dev(dY, DT[name]), dev(W, DT[name]), dev(X, DT[name])
+    # dX = dY W : contraction over N, B is k-strided
+    dX = torch.empty(T, K, dtype=torch.float32, device="cuda")
+    Bd.lsk_gemm(dYd, Wd, dX, M=T, N=K, K=N, a_kmajor=True, b_kmajor=False, lda=N, ldb=K)
+    assert_close(host(dX), dY.astype(np.float64) @ W.astype(np.float64), 1e-5 if name != "f32" else 1e-4, "dX")
+    # dW = dY^T X : contraction over tokens, both k-strided; accumulate twice
+    dW = torch.zeros(N, K, dtype=torch.float32, device="cuda")
+    for acc in (False, True):
+        Bd.lsk_gemm(dYd, Xd, dW, M=N, N=K, K=T, a_kmajor=False, b_kmajor=False, lda=N, ldb=K, accumulate=acc)
+    assert_close(host(dW), 2.0 * dY.astype(np.float64).T @ X.astype(np.float64), 1e-5 if name != "f32" else 1e-4, "dW")
+
+
+def test_gemm_rejects_unaligned_operands():
+    a = torch.zeros(16, 12, dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros(16, 12, dtype=torch.bfloat16, device="cuda")
+    c = torch.zeros(16, 16, dtype=torch.float32, device="cuda")
+    with pytest.raises(Bd.LsError) as e:
+        Bd.lsk_gemm(a, w, c, M=16, N=16, K=12)
+    assert e.value.status == Bd.LS_EINVAL
+
+
+@pytest.mark.parametrize("kind", [0, 1])
+@pytest.mark.parametrize("hname", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("T,d", [(37, 128), (70, 768), (33, 4096)])
+def test_norm_forward_and_backward(kind, hname, T, d):
+    x = S.normal(3, "x", (T, d)) * 1.7 + 0.3
+    pn = "f32" if hname == "f32" else "bf16"
+    g = q(1.0 + S.normal(3, "g", (d,), 0.1), pn)
+    b = q(S.normal(3, "b", (d,), 0.1), pn)
+    dh = q(S.normal(3, "dh", (T, d)), hname)
+    dres = S.normal(3, "dres", (T, d))
+    x64 = x.astype(np.float64)
+    if kind == 0:
+        ref, xhat, r = O.layer_norm(x64, g.astype(np.float64), b.astype(np.float64), 1e-5)
+        dxr, dgr, dbr = O.layer_norm_bwd(dh.astype(np.float64), xhat, r, g.astype(np.float64))
+    else:
+        ref, xhat, r = O.rms_norm(x64, g.astype(np.float64), 1e-5)
+        dxr, dgr = O.rms_norm_bwd(dh.astype(np.float64), xhat, r, g.astype(np.float64))
+    xd = dev(x, torch.float32)
+    h = torch.empty(T, d, dtype=DT[hname], device="cuda")
+    mean = torch.zeros(T, dtype=torch.float32, device="cuda")
+    rstd = torch.zeros(T, dtype=torch.float32, device="cuda")
+    gd, bd = dev(g, DT[pn]), dev(b, DT[pn])
+    Bd.lsk_norm_fwd(kind, xd, gd, bd if kind == 0 else None, 1e-5, h, mean, rstd)
+    assert_close(host(h), ref, KTOL[hname], "norm fwd")
+    assert_close(host(rstd), r[:, 0], 1e-5, "rstd")
+    dx = torch.empty(T, d, dtype=torch.float32, device="cuda")
+    dx16 = torch.empty(T, d, dtype=DT[hname], device="cuda")
+    dgam = torch.full((d,), 1.0, dtype=torch.float32, device="cuda")
+    dbet = torch.full((d,), 1.0, dtype=torch.float32, device="cuda")
+    Bd.lsk_norm_bwd(kind, dev(dh, DT[hname]), xd, mean, rstd, gd, dev(dres, torch.float32), dx, dx16, dgam,
+                    dbet if kind == 0 else None, True)
+    assert_close(host(dx), dxr + dres, 1e-5, "norm bwd dx")
+    assert_close(host(dx16), dxr + dres, KTOL[hname], "norm bwd dx16")
+    assert_close(host(dgam), dgr + 1.0, 1e-5, "dgamma (accumulated)")
+    if kind == 0:
+        assert_close(host(dbet), dbr + 1.0, 1e-5, "dbeta (accumulated)")
+
+
+def rope_table(max_pos, dh, theta=1e4):
+    i = np.arange(dh // 2, dtype=np.float64)
+    ang = np.arange(max_pos, dtype=np.float64)[:, None] * theta ** (-2.0 * i / dh)[None, :]
+    return np.stack([np.cos(ang), np.sin(ang)], axis=-1).astype(np.float32)
+
+
+@pytest.mark.parametrize("name", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("sign", [1.0, -1.0])
+def test_rope_in_place(name, sign):
+    T, h, dh = 50, 3, 128
+    d = h * dh
+    qkv = q(S.normal(4, "qkv", (T, 3 * d)), name)
+    pos = S.uniform_ints(4, "pos", T, 0, 4095)
+    ref = qkv.astype(np.float64).copy()
+    for part in (0, 1):
+        blk = ref[:, part * d:(part + 1) * d].reshape(T, h, dh)
+        ref[:, part * d:(part + 1) * d] = O.rope(blk, pos, 1e4, sign).reshape(T, d)
+    t = dev(qkv, DT[name])
+    Bd.lsk_rope(t, h, dh, torch.as_tensor(pos, dtype=torch.int32, device="cuda"),
+                dev(rope_table(4096, dh), torch.float32), sign)
+    assert_close(host(t), ref, KTOL[name] if name != "f32" else 1e-5, "rope")
+    assert np.array_equal(host(t)[:, 2 * d:], qkv[:, 2 * d:].astype(np.float64))   # v untouched
+
+
+@pytest.mark.parametrize("name", ["f32", "f16", "bf16"])
+def test_activations(name):
+    T, F = 33, 264
+    u = q(S.normal(5, "u", (T, F)) * 2.0, name)
+    dg = q(S.normal(5, "dg", (T, F)), name)
+    for kind, kname in ((Bd.LS_ACT_GELU_TANH, "gelu_tanh"), (Bd.LS_ACT_GELU_ERF, "gelu_erf")):
+        g = torch.empty(T, F, dtype=DT[name], device="cuda")
+        Bd.lsk_gelu_fwd(dev(u, DT[name]), g, kind)
+        assert_close(host(g), O.gelu(u.astype(np.float64), kname), KTOL[name] if name != "f32" else 1e-6, kname)
+        du = torch.empty(T, F, dtype=DT[name], device="cuda")
+        Bd.lsk_gelu_bwd(dev(dg, DT[name]), dev(u, DT[name]), du, kind)
+        assert_close(host(du), dg * O.gelu_grad(u.astype(np.float64), kname), KTOL[name] if name != "f32" else 1e-6,
+                     kname + " bwd")
+    gu = q(S.normal(5, "gu", (T, 2 * F)) * 2.0, name)
+    gate, up = gu[:, :F].astype(np.float64), gu[:, F:].astype(np.float64)
+    a = torch.empty(T, F, dtype=DT[name], device="cuda")
+    Bd.lsk_swiglu_fwd(dev(gu, DT[name]), a)
+    assert_close(host(a), O.silu(gate) * up, KTOL[name] if name != "f32" else 1e-6, "swiglu")
+    dgu = torch.empty(T, 2 * F, dtype=DT[name], device="cuda")
+    Bd.lsk_swiglu_bwd(dev(dg, DT[name]), dev(gu, DT[name]), dgu)
+    sg = O.sigmoid(gate)
+    ref = np.concatenate([dg * up * sg * (1 + gate * (1 - sg)), dg * gate * sg], axis=1)
+    assert_close(host(dgu), ref, KTOL[name] if name != "f32" else 1e-6, "swiglu bwd")
+
+
+@pytest.mark.parametrize("name", ["f32", "f16"])
+def test_colsum(name):
+    T, N = 333, 520
+    x = q(S.normal(6, "x", (T, N)), name)
+    out = torch.ones(N, dtype=torch.float32, device="cuda")
+    Bd.lsk_colsum(dev(x, DT[name]), out, accumulate=True)
+    assert_close(host(out), x.astype(np.float64).sum(axis=0) + 1.0, 1e-5, "colsum")
+
+
+def attn_ref(qkv, B, L, h, dh):
+    d = h * dh
+    o = np.empty((B * L, d))
+    lse = np.empty((B * L, h))
+    Ps = []
+    for b in range(B):
+        blk = qkv[b * L:(b + 1) * L].astype(np.float64)
+        qq, kk, vv = (blk[:, i * d:(i + 1) * d].reshape(L, h, dh) for i in range(3))
+        ob, P = O.attention(qq, kk, vv, 0)
+        o[b * L:(b + 1) * L] = ob.reshape(L, d)
+        for j in range(h):
+            s = (qq[:, j] @ kk[:, j].T) / math.sqrt(dh)
+            s = np.where(np.tril(np.ones((L, L), bool)), s, -np.inf)
+            m = s.max(1)
+            lse[b * L:(b + 1) * L, j] = m + np.log(np.exp(s - m[:, None]).sum(1))
+        Ps.append((qq, kk, vv, P))
+    return o, lse, Ps
+
+
+@pytest.mark.parametrize("impl", [0, 1])
+@pytest.mark.parametrize("name,B,L,h,dh", [("f32", 2, 64, 4, 32), ("f16", 2, 200, 3, 64), ("bf16", 1, 300, 2, 128),
+                                             ("f16", 3, 129, 2, 128), ("f16", 1, 1, 2, 64)])
+def test_attention_forward_and_backward(impl, name, B, L, h, dh):
+    if impl == 1 and name == "f32":
+        pytest.skip("matrix-core attention is 16-bit only")
+    d = h * dh
+    qkv = q(S.normal(7, "qkv", (B * L, 3 * d)), name)
+    dO = q(S.normal(7, "dO", (B * L, d)), name)
+    o_ref, lse_ref, Ps = attn_ref(qkv, B, L, h, dh)
+    qd = dev(qkv, DT[name])
+    o = torch.empty(B * L, d, dtype=DT[name], device="cuda")
+    lse = torch.empty(B * L, h, dtype=torch.float32, device="cuda")
+    Bd.lsk_attn_fwd(impl, qd, B, L, h, dh, o, lse)
+    tol = KTOL[name]
+    assert_close(host(o), o_ref, tol, "attention o")
+    assert np.abs(host(lse) - lse_ref).max() < (1e-4 if name == "f32" else 2e-2)
+    dqkv_ref = np.empty((B * L, 3 * d))
+    for b, (qq, kk, vv, P) in enumerate(Ps):
+        dq, dk, dv = O.attention_bwd(dO[b * L:(b + 1) * L].astype(np.float64).reshape(L, h, dh), qq, kk, vv, P)
+        dqkv_ref[b * L:(b + 1) * L] = np.concatenate([dq.reshape(L, d), dk.reshape(L, d), dv.reshape(L, d)], 1)
+    dqkv = torch.empty(B * L, 3 * d, dtype=DT[name], device="cuda")
+    # backward consumes the forward's own o and lse
+    Bd.lsk_attn_bwd(impl, qd, o, dev(dO, DT[name]), lse, B, L, h, dh, dqkv)
+    got = host(dqkv)
+    for i, nm in enumerate(("dq", "dk", "dv")):
+        assert_close(got[:, i * d:(i + 1) * d], dqkv_ref[:, i * d:(i + 1) * d], tol, nm)
+
+
+@pytest.mark.parametrize("impl", [0, 1])
+@pytest.mark.parametrize("name,h,dh,P", [("f32", 4, 32, 16), ("f16", 2, 128, 16), ("bf16", 3, 64, 8)])
+def test_paged_attention_ragged(impl, name, h, dh, P):
+    if impl == 1 and name == "f32":
+        pytest.skip("optimised paged attention is 16-bit only")
+    d = h * dh
+    ctx = np.array([0, 5, 16, 100, 333, 47])          # cached tokens per request
+    new = np.array([1, 1, 3, 1, 20, 40])              # decode rows and prefill chunks mixed
+    table, n_pages = S.page_tables(ctx, new, P, seed=3)
+    rng = np.random.default_rng(0)
+    T = int(new.sum())
+    qkv = q(S.normal(8, "qkv", (T, 3 * d)), name)
+    kp = q(rng.normal(0, 1, (n_pages, h, P, dh)), name)   # garbage everywhere, real rows overwritten below
+    vp = q(rng.normal(0, 1, (n_pages, h, P, dh)), name)
+    Kc = [q(S.normal(8, f"K{b}", (int(c), h, dh)), name) for b, c in enumerate(ctx)]
+    Vc = [q(S.normal(8, f"V{b}", (int(c), h, dh)), name) for b, c in enumerate(ctx)]
+    for b in range(len(ctx)):
+        for j in range(int(ctx[b])):
+            kp[table[b, j // P], :, j % P] = Kc[b][j]
+            vp[table[b, j // P], :, j % P] = Vc[b][j]
+    pos = np.concatenate([ctx[b] + np.arange(new[b]) for b in range(len(ctx))]).astype(np.int32)
+    req = np.concatenate([np.full(new[b], b) for b in range(len(ctx))]).astype(np.int32)
+    kd, vd = dev(kp, DT[name]), dev(vp, DT[name])
+    qd = dev(qkv, DT[name])
+    bt = torch.as_tensor(table, dtype=torch.int32, device="cuda")
+    posd, reqd = torch.as_tensor(pos, device="cuda"), torch.as_tensor(req, device="cuda")
+    Bd.lsk_kv_write(qd, h, dh, posd, reqd, kd, vd, bt, P)
+    o = torch.empty(T, d, dtype=DT[name], device="cuda")
+    Bd.lsk_attn_paged(impl, qd, h, dh, posd, reqd, kd, vd, bt, P, int((ctx + new).max()), o)
+    ref = np.empty((T, d))
+    t0 = 0
+    for b in range(len(ctx)):
+        rows = qkv[t0:t0 + new[b]].astype(np.float64)
+        qq, kn, vn = (rows[:, i * d:(i + 1) * d].reshape(-1, h, dh) for i in range(3))
+        K = np.concatenate([Kc[b].astype(np.float64), kn]); V = np.concatenate([Vc[b].astype(np.float64), vn])
+        ob, _ = O.attention(qq, K, V, int(ctx[b]))
+        ref[t0:t0 + new[b]] = ob.reshape(-1, d)
+        # the new rows landed in the right page slots, bit-exactly
+        kh = host(kd)
+        for i in range(new[b]):
+            j = int(ctx[b]) + i
+            assert np.array_equal(kh[table[b, j // P], :, j % P], kn[i])
+        t0 += new[b]
+    assert_close(host(o), ref, KTOL[name], "paged attention")
