@@ -1,0 +1,254 @@
+#!/usr/bin/env python3
+"""Benchmark of the pipeline-stage hot path on one MI355X.
+
+One *step* is one pass of the whole hot path on the LLaMA-7B-shaped 8-block
+stage (bf16 parameters, 16-bit matrix-core operands, fp32 accumulation):
+  1. a training micro-batch of 2 x 2048 tokens, forward + backward
+     (stage_train_fwd + stage_train_bwd),
+  2. one ragged decode step for 64 requests, contexts uniform in [128, 2048],
+     16-token pages in shuffled order (stage_decode),
+  3. two 512-token prefill chunks of one 1024-token prompt (stage_prefill x 2).
+All inputs are seeded, synthetic and resident in HBM before the timed region.
+`value` is tokens processed per second over the whole step; the per-leg rates,
+the GEMM and decode rooflines, the two-stream interference probe and the CPU
+oracle baseline are reported beside it on the same JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--mma f16|bf16]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_TFLOPS = 2500.0   # dense bf16 / fp16 MFMA, MI355X
+PEAK_HBM_GBS = 8000.0       # HBM3E
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_events(torch, fn, iters, warm=1):
+    for _ in range(warm):
+        fn()
+    torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+def cpu_baseline(cfg, S):
+    """The oracle, as it stands, on a bounded sample of the training workload."""
+    from oracle import stage_oracle as O
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    nl, L = 1, 384
+    c = S.scaled(cfg, n_layers=nl)
+    flat = S.make_params(c).astype(np.float64)
+    X = S.make_activations(c, "X", (1, L, c["d_model"])).astype(np.float64)
+    dY = S.make_activations(c, "dY", (1, L, c["d_model"]), std=1e-2).astype(np.float64)
+    t0 = time.perf_counter()
+    _, saved = O.stage_train_fwd(c, flat, X)
+    O.stage_train_bwd(c, flat, saved, dY)
+    dt = time.perf_counter() - t0
+    scale = cfg["n_layers"] / nl
+    return {"value": L / (dt * scale), "unit": "tok/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"train fwd+bwd of {nl} of {cfg['n_layers']} blocks on 1x{L} tokens in float64 numpy "
+                      f"({dt:.1f} s), time scaled x{scale:g} to the full stage"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--mma", default="f16", choices=["f16", "bf16"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-probe", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build measures one GPU only (one pipeline stage on one MI355X); "
+                 "run with --gpus 1")
+
+    import torch
+    from paper_2507_21276_amd import binding as Bd
+    from paper_2507_21276_amd import synth_inputs as S
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    Bd.lib()   # fails loudly when the HIP library has not been built
+    dev = "cuda"
+    cfg = S.CONFIGS["llama7b_bf16"]
+    d, nL, F, h, dh, P = (cfg[k] for k in ("d_model", "n_layers", "d_ff", "n_heads", "head_dim", "page_size"))
+    st = Bd.Stage(cfg, io_dtype="bf16", mma_dtype=args.mma)
+    params = S.make_params_torch(cfg, seed=0, device=dev)
+    st.ls_bind_params(params)
+    io = st.io_torch
+
+    # ---- training micro-batch (BASELINE config 3) --------------------------------------
+    B, L = S.WORKLOADS["cfg3"]["train"]
+    T = B * L
+    X = S.normal_torch(0, "X", (B, L, d), 1.0, dev, io)
+    dY = S.normal_torch(0, "dY", (B, L, d), S.WORKLOADS["cfg3"]["dy_std"], dev, io)
+    Y = torch.empty_like(X)
+    dX = torch.empty_like(X)
+    dP = torch.zeros(st.ls_param_count(), dtype=torch.float32, device=dev)
+    saved = st.new_saved(B, L)
+    ws = st.new_workspace(T)
+
+    def train():
+        st.stage_train_fwd(X, B, L, Y, saved, ws)
+        st.stage_train_bwd(dY, B, L, saved, dX, dP, 0, ws)
+
+    # ---- serving batch (BASELINE config 4) -----------------------------------------------
+    serve = S.WORKLOADS["cfg4"]["serve"]
+    ctx = S.context_lengths(serve, seed=0)
+    Bq = serve["B"]
+    table, n_pages = S.page_tables(ctx, np.ones_like(ctx), P, seed=0)
+    kv = Bd.KV(st, n_pages, table, ctx)
+    kv.k_pool.copy_(S.normal_torch(0, "Kpool", kv.k_pool.shape, 1.0, dev, kv.k_pool.dtype))
+    kv.v_pool.copy_(S.normal_torch(0, "Vpool", kv.v_pool.shape, 1.0, dev, kv.v_pool.dtype))
+    Xd = S.normal_torch(0, "Xdec", (Bq, d), 1.0, dev, io)
+    Yd = torch.empty_like(Xd)
+    ws_a = st.new_workspace(max(Bq, 512))
+    chunks = serve["prefill_chunks"]
+    ptab, pn = S.page_tables(np.zeros(1, np.int64), np.array([sum(chunks)]), P, seed=1)
+    kvp = [Bd.KV(st, pn, ptab, [0])]
+    kvp.append(Bd.KV(st, pn, ptab, [chunks[0]]))
+    kvp[1].k_pool, kvp[1].v_pool = kvp[0].k_pool, kvp[0].v_pool   # same pool, context advanced by chunk 0
+    Xp = S.normal_torch(0, "Xprefill", (sum(chunks), d), 1.0, dev, io)
+    Yp = torch.empty_like(Xp)
+
+    def decode():
+        st.stage_decode(Xd, Bq, kv, Yd, ws_a)
+
+    def prefill():
+        st.stage_prefill(Xp[:chunks[0]], [chunks[0]], kvp[0], Yp[:chunks[0]], ws_a)
+        st.stage_prefill(Xp[chunks[0]:], [chunks[1]], kvp[1], Yp[chunks[0]:], ws_a)
+
+    def step():
+        train()
+        decode()
+        prefill()
+
+    tokens_per_step = T + Bq + sum(chunks)
+
+    # ---- timed region: exactly K steps ------------------------------------------------------
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    log(f"step: {ms_per_step:.2f} ms")
+
+    # ---- per-leg rates --------------------------------------------------------------------
+    it = max(2, min(args.steps, 10))
+    ms_train = time_events(torch, train, it)
+    ms_dec = time_events(torch, decode, it * 2)
+    ms_pre = time_events(torch, prefill, it)
+    log(f"train {ms_train:.2f} ms, decode {ms_dec:.3f} ms, prefill {ms_pre:.2f} ms")
+
+    # ---- GEMM roofline: the 12 GEMM launches of one block, in the stage's own shapes -----------
+    mt = Bd.TORCH_DTYPE[st.c.mma_dtype]
+    U = 2 * F
+    a_d = torch.randn(T, d, device=dev).to(mt)
+    a_3d = torch.randn(T, 3 * d, device=dev).to(mt)
+    a_U = torch.randn(T, U, device=dev).to(mt)
+    a_F = torch.randn(T, F, device=dev).to(mt)
+    w_qkv = (torch.randn(3 * d, d, device=dev) * 0.02).to(mt)
+    w_o = (torch.randn(d, d, device=dev) * 0.02).to(mt)
+    w_gu = (torch.randn(U, d, device=dev) * 0.02).to(mt)
+    w_d = (torch.randn(d, F, device=dev) * 0.02).to(mt)
+    o_3d, o_d, o_U, o_F = (torch.empty(T, n, device=dev, dtype=mt) for n in (3 * d, d, U, F))
+    g_qkv, g_o, g_gu, g_d = (torch.empty_like(w, dtype=torch.float32) for w in (w_qkv, w_o, w_gu, w_d))
+    G = Bd.lsk_gemm
+
+    def gemms():
+        G(a_d, w_qkv, o_3d, M=T, N=3 * d, K=d)
+        G(a_d, w_o, o_d, M=T, N=d, K=d)
+        G(a_d, w_gu, o_U, M=T, N=U, K=d)
+        G(a_F, w_d, o_d, M=T, N=d, K=F)
+        G(a_d, w_d, o_F, M=T, N=F, K=d, b_kmajor=False, ldb=F)
+        G(a_d, a_F, g_d, M=d, N=F, K=T, a_kmajor=False, b_kmajor=False, lda=d, ldb=F)
+        G(a_U, w_gu, o_d, M=T, N=d, K=U, b_kmajor=False, ldb=d)
+        G(a_U, a_d, g_gu, M=U, N=d, K=T, a_kmajor=False, b_kmajor=False, lda=U, ldb=d)
+        G(a_d, w_o, o_d, M=T, N=d, K=d, b_kmajor=False, ldb=d)
+        G(a_d, a_d, g_o, M=d, N=d, K=T, a_kmajor=False, b_kmajor=False, lda=d, ldb=d)
+        G(a_3d, w_qkv, o_d, M=T, N=d, K=3 * d, b_kmajor=False, ldb=d)
+        G(a_3d, a_d, g_qkv, M=3 * d, N=d, K=T, a_kmajor=False, b_kmajor=False, lda=3 * d, ldb=d)
+
+    ms_gemms = time_events(torch, gemms, 5)
+    flop_block = 3.0 * T * (8.0 * d * d + 6.0 * d * F)       # fwd + dX + dW of one block
+    gemm_tflops = flop_block / (ms_gemms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": "gemm_mfma_kernel (12 launches per block: 4 fwd, 4 dX, 4 dW)",
+                "achieved": gemm_tflops, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
+                "frac": gemm_tflops / PEAK_MFMA_TFLOPS, "avg_launch_ms": ms_gemms / 12,
+                "flop_per_launch": flop_block / 12, "traffic": None}
+    log(f"GEMMs of one block: {ms_gemms:.2f} ms -> {gemm_tflops:.0f} TFLOP/s")
+
+    # ---- decode roofline: weights once + the KV of every cached token ---------------------------
+    w_bytes = 2.0 * nL * (4.0 * d * d + 3.0 * d * F)
+    kv_bytes = float((ctx + 1).sum()) * nL * 2 * d * 2
+    dec_gbs = (w_bytes + kv_bytes) / (ms_dec * 1e-3) / 1e9
+    roofline_decode = {"bound": "hbm", "kernel": "stage_decode (whole call)", "achieved": dec_gbs,
+                       "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,
+                       "bytes_per_step": w_bytes + kv_bytes, "traffic": None}
+
+    # ---- interference probe (BASELINE config 4: decode stream + 1 x 2048 training stream) --------
+    probe = None
+    if not args.no_probe:
+        Bt, Lt = S.WORKLOADS["cfg4"]["train"]
+        sa, sb = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        ms = st.stage_probe_interference(Xd, Bq, kv, Yd, ws_a, X[:Bt], Bt, Lt, Y[:Bt], saved, dY[:Bt],
+                                         dX[:Bt], dP, ws, sa, sb, 3)
+        torch.cuda.synchronize()
+        probe = {"decode_alone_ms": ms[0], "train_alone_ms": ms[1], "decode_together_ms": ms[2],
+                 "train_together_ms": ms[3], "wall_together_ms": ms[4],
+                 "decode_tok_s_alone": Bq / ms[0] * 1e3, "decode_tok_s_together": Bq / ms[2] * 1e3,
+                 "train_tok_s_alone": Bt * Lt / ms[1] * 1e3, "train_tok_s_together": Bt * Lt / ms[3] * 1e3}
+
+    out = {
+        "metric": "stage tok/s (train fwd+bwd + ragged decode + prefill chunks), LLaMA-7B-shaped 8-block stage, 1 MI355X",
+        "value": tokens_per_step / (ms_per_step * 1e-3), "unit": "tok/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": f"{args.mma} MFMA operands, bf16 parameters and io, fp32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": "cfg3 train 2x2048 fwd+bwd + cfg4 ragged decode B=64 ctx~U[128,2048] paged(16) "
+                               "+ cfg4 prefill 2x512", "stage": "llama7b_bf16", "n_layers": nL, "d_model": d,
+                   "d_ff": F, "tokens_per_step": tokens_per_step},
+        "breakdown": {"train_fwd_bwd_tok_s": T / ms_train * 1e3, "train_ms": ms_train,
+                      "decode_tok_s": Bq / ms_dec * 1e3, "decode_ms": ms_dec,
+                      "prefill_tok_s": sum(chunks) / ms_pre * 1e3, "prefill_ms": ms_pre,
+                      "train_frac_of_mfma_peak": (3.0 * T * nL * (8.0 * d * d + 6.0 * d * F)
+                                                  + 3.0 * 2.0 * L * L * d * B * nL) / (ms_train * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS},
+        "roofline": roofline, "roofline_decode": roofline_decode, "probe": probe,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, S)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

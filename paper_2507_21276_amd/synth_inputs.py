@@ -282,3 +282,35 @@ def page_tables(ctx_len: np.ndarray, new_tokens: np.ndarray, page_size: int,
         table[b, :k] = perm[p:p + k]
         p += k
     return table, n_pages
+
+
+# --------------------------------------------------------------------------
+# Device-side generation for the full-size workloads (billions of elements):
+# torch's counter-based Philox generator seeded from (seed, tensor name).
+# Values differ from normal() above but are just as reproducible; callers that
+# need them on the host copy them back.
+# --------------------------------------------------------------------------
+
+
+def normal_torch(seed: int, name: str, shape, std: float = 1.0, device="cuda", dtype=None):
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(tensor_key(seed, name) & 0x7FFFFFFFFFFFFFFF)
+    x = torch.empty(tuple(shape), dtype=torch.float32, device=device)
+    x.normal_(0.0, std, generator=g)
+    return x if dtype is None else x.to(dtype)
+
+
+def make_params_torch(cfg: dict, seed: int = 0, w_std: float = 0.02, device="cuda"):
+    """Flat parameter vector on `device` in the stage's parameter dtype (the
+    configs' recipe: weights N(0, w_std), gains 1, biases 0)."""
+    import torch
+    dt = torch.float32 if cfg["dtype"] == "f32" else torch.bfloat16
+    flat = torch.empty(param_count(cfg), dtype=dt, device=device)
+    for name, off, shape, init in param_layout(cfg):
+        n = int(np.prod(shape))
+        if init == "normal":
+            flat[off:off + n] = normal_torch(seed, name, (n,), w_std, device).to(dt)
+        else:
+            flat[off:off + n] = 1.0 if init == "ones" else 0.0
+    return flat
