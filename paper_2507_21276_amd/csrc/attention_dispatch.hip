@@ -9,16 +9,25 @@ ls_status lsk_attn_bwd_simple(const void*, const void*, const void*, const float
 ls_status lsk_attn_paged_simple(const void*, int, int, int, int, const int32_t*, const int32_t*,
                                 const void*, const void*, const int32_t*, int, int, int, void*, void*);
 
+ls_status lsk_attn_fwd_mfma(const void*, int, int, int, int, int, void*, float*, void*);
+ls_status lsk_attn_bwd_mfma(const void*, const void*, const void*, const float*, int, int, int, int, int,
+                            void*, float*, void*);
+
+static bool mfma_ok(int impl, int dtype, int head_dim) {
+  return impl == 1 && (dtype == LS_BF16 || dtype == LS_F16) && (head_dim == 64 || head_dim == 128);
+}
+
 ls_status lsk_attn_fwd(int impl, const void* qkv, int dtype, int B, int L, int n_heads, int head_dim,
                        void* o, float* lse, void* stream) {
-  (void)impl;
+  if (mfma_ok(impl, dtype, head_dim)) return lsk_attn_fwd_mfma(qkv, dtype, B, L, n_heads, head_dim, o, lse, stream);
   return lsk_attn_fwd_simple(qkv, dtype, B, L, n_heads, head_dim, o, lse, stream);
 }
 
 ls_status lsk_attn_bwd(int impl, const void* qkv, const void* o, const void* dO, const float* lse,
                        int dtype, int B, int L, int n_heads, int head_dim, void* dqkv, float* dvec,
                        void* stream) {
-  (void)impl;
+  if (mfma_ok(impl, dtype, head_dim))
+    return lsk_attn_bwd_mfma(qkv, o, dO, lse, dtype, B, L, n_heads, head_dim, dqkv, dvec, stream);
   return lsk_attn_bwd_simple(qkv, o, dO, lse, dtype, B, L, n_heads, head_dim, dqkv, dvec, stream);
 }
 

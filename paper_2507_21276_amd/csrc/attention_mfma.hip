@@ -1,0 +1,693 @@
+// Matrix-core causal attention for training (contiguous sequences), 16-bit
+// operands, fp32 softmax statistics and accumulation.
+//
+// Forward.  A workgroup (4 wavefronts) owns BQ = 4*QT*32 consecutive query rows
+// of one (sequence, head); each wavefront owns QT 32-row query tiles.  K/V are
+// walked in tiles of 64 keys staged in LDS (K as [key][dh], V transposed to
+// [dh][key] on the way in).  Both products are computed *transposed* so that a
+// lane always holds data of one query (its column):
+//     S^T = K Q^T   (A = K rows, B = Q)      lane: query = lane%32, 16 keys/tile
+//     O^T = V^T P^T (A = V^T rows, B = P^T)  lane: query = lane%32, dh rows
+// The online-softmax maximum, sum and rescale factor are therefore per-lane
+// scalars (one exchange with lane^32 for the maximum), and the exponentials of
+// S^T feed the second product straight from registers.  K rows are fetched in
+// the order pi(r) = r with bits 2 and 3 swapped, which makes the 8 values a lane
+// holds per 16-key step consecutive keys, i.e. exactly the B-operand layout.
+//
+// Backward (dQ, dK, dV) follows the same scheme; see flash_bwd_kernel.
+#include "common.h"
+
+namespace {
+
+template <class T> struct Mma;
+template <> struct Mma<bf16_t> {
+  typedef bf16x8 V8;
+  typedef bf16x4 V4;
+  static __device__ __forceinline__ f32x16 run(V8 a, V8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  }
+};
+template <> struct Mma<f16_t> {
+  typedef f16x8 V8;
+  typedef f16x4 V4;
+  static __device__ __forceinline__ f32x16 run(V8 a, V8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+  }
+};
+
+constexpr int KT = 64;  // keys per tile
+
+__device__ __forceinline__ int pi_row(int r) {  // swap bits 2 and 3
+  return (r & ~12) | ((r & 4) << 1) | ((r & 8) >> 1);
+}
+
+// 8x8 transpose of 16-bit elements held as eight 16-byte rows
+__device__ __forceinline__ void transpose8x8(const u32x4 (&in)[8], u32x4 (&out)[8]) {
+#pragma unroll
+  for (int r = 0; r < 8; ++r) {
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+      const uint32_t lo = in[2 * p][r >> 1], hi = in[2 * p + 1][r >> 1];
+      out[r][p] = (r & 1) ? __builtin_amdgcn_perm(hi, lo, 0x07060302u) : __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+    }
+  }
+}
+
+// K tile [KT][DH] (row stride DH+8) and V^T tile [DH][KT] (row stride KT+8)
+template <class T, int DH>
+struct KvStage {
+  static constexpr int KCH = KT * DH / 8 / 256;  // 16-byte chunks of K per thread
+  static constexpr int VBLK = 8 * (DH / 8);      // 8x8 blocks of V (one per thread below VBLK)
+  u32x4 k[KCH];
+  u32x4 v[8];
+  __device__ __forceinline__ void load(const T* kbase, const T* vbase, long ld, int key0, int nkeys) {
+#pragma unroll
+    for (int i = 0; i < KCH; ++i) {
+      const int c = threadIdx.x + i * 256;
+      const int r = c / (DH / 8), col = (c % (DH / 8)) * 8;
+      u32x4 z = {0u, 0u, 0u, 0u};
+      if (key0 + r < nkeys) z = *(const u32x4*)(kbase + (long)(key0 + r) * ld + col);
+      k[i] = z;
+    }
+    if (threadIdx.x < VBLK) {
+      const int kg = threadIdx.x & 7, dg = threadIdx.x >> 3;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int key = key0 + kg * 8 + j;
+        u32x4 z = {0u, 0u, 0u, 0u};
+        if (key < nkeys) z = *(const u32x4*)(vbase + (long)key * ld + dg * 8);
+        v[j] = z;
+      }
+    }
+  }
+  __device__ __forceinline__ void store(T* ks, T* vt) const {
+#pragma unroll
+    for (int i = 0; i < KCH; ++i) {
+      const int c = threadIdx.x + i * 256;
+      const int r = c / (DH / 8), col = (c % (DH / 8)) * 8;
+      *(u32x4*)(ks + r * (DH + 8) + col) = k[i];
+    }
+    if (threadIdx.x < VBLK) {
+      const int kg = threadIdx.x & 7, dg = threadIdx.x >> 3;
+      u32x4 t[8];
+      transpose8x8(v, t);
+#pragma unroll
+      for (int r = 0; r < 8; ++r) *(u32x4*)(vt + (dg * 8 + r) * (KT + 8) + kg * 8) = t[r];
+    }
+  }
+};
+
+template <class T, int DH, int QT>
+__global__ __launch_bounds__(256) void flash_fwd_kernel(const T* __restrict__ qkv, T* __restrict__ o,
+                                                        float* __restrict__ lse, int L, int h,
+                                                        float scale_log2) {
+  typedef typename Mma<T>::V8 V8;
+  typedef typename Mma<T>::V4 V4;
+  constexpr int BQ = 4 * QT * 32;
+  constexpr int KS = DH / 16;   // k steps over the head dimension
+  constexpr int DT = DH / 32;   // 32-row tiles of O^T
+  constexpr int KSTR = DH + 8, VSTR = KT + 8;
+  __shared__ __attribute__((aligned(16))) T ks_lds[2][KT * KSTR];
+  __shared__ __attribute__((aligned(16))) T vt_lds[2][DH * VSTR];
+
+  const int n_qt = (L + BQ - 1) / BQ;
+  const int qtile = n_qt - 1 - blockIdx.x;  // heaviest tiles first
+  const int b = blockIdx.y / h, head = blockIdx.y % h;
+  const int d = h * DH;
+  const long ld = 3L * d;
+  const T* qb = qkv + (long)b * L * ld + (long)head * DH;
+  const T* kb = qb + d;
+  const T* vb = qb + 2 * d;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int col = lane & 31, hf = lane >> 5;
+  const int wq0 = qtile * BQ + wave * QT * 32;  // first query row of this wavefront
+
+  // Q fragments (B operand): column = query, k = head dimension
+  V8 qf[QT][KS];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    const int q = wq0 + t * 32 + col;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      u32x4 z = {0u, 0u, 0u, 0u};
+      if (q < L) z = *(const u32x4*)(qb + (long)q * ld + s * 16 + hf * 8);
+      qf[t][s] = __builtin_bit_cast(V8, z);
+    }
+  }
+
+  f32x16 oacc[QT][DT];
+  float m_run[QT], l_run[QT];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    m_run[t] = -INFINITY;
+    l_run[t] = 0.f;
+#pragma unroll
+    for (int j = 0; j < DT; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[t][j][e] = 0.f;
+  }
+
+  const int q_hi = min(L, qtile * BQ + BQ) - 1;  // last query row of the workgroup
+  const int n_kt = q_hi / KT + 1;
+  KvStage<T, DH> stg;
+  stg.load(kb, vb, ld, 0, L);
+  stg.store(ks_lds[0], vt_lds[0]);
+  __syncthreads();
+
+  for (int kt = 0; kt < n_kt; ++kt) {
+    const int cur = kt & 1;
+    const int key0 = kt * KT;
+    if (kt + 1 < n_kt) stg.load(kb, vb, ld, key0 + KT, L);
+    // this wavefront's rows end at wq0 + QT*32 - 1: skip tiles entirely above its diagonal
+    if (key0 <= wq0 + QT * 32 - 1) {
+      const T* ks = ks_lds[cur];
+      const T* vt = vt_lds[cur];
+      f32x16 sacc[QT][2];
+#pragma unroll
+      for (int t = 0; t < QT; ++t)
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) sacc[t][c][e] = 0.f;
+      // S^T = K Q^T
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          const V8 kf = *(const V8*)(ks + (c * 32 + pi_row(col)) * KSTR + s * 16 + hf * 8);
+#pragma unroll
+          for (int t = 0; t < QT; ++t) sacc[t][c] = Mma<T>::run(kf, qf[t][s], sacc[t][c]);
+        }
+      }
+      // online softmax per query (lane), keys of element e: key0 + c*32 + 16*(e/8) + 8*hf + e%8
+      V8 pf[QT][4];
+#pragma unroll
+      for (int t = 0; t < QT; ++t) {
+        const int q = wq0 + t * 32 + col;
+        const bool diag = key0 + KT - 1 > wq0 + t * 32;  // tile reaches past the first row's diagonal
+        float mx = -INFINITY;
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            float v = sacc[t][c][e] * scale_log2;
+            if (diag) {
+              const int key = key0 + c * 32 + 16 * (e >> 3) + 8 * hf + (e & 7);
+              if (key > q) v = -INFINITY;
+            }
+            sacc[t][c][e] = v;
+            mx = fmaxf(mx, v);
+          }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run[t], mx);
+        // a row with no visible key yet keeps m = -inf; use 0 as the reference then
+        const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+        const float alpha = __builtin_amdgcn_exp2f(m_run[t] - m_ref);
+        float rs = 0.f;
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+          for (int g = 0; g < 2; ++g) {
+            V8 pv;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+              const float p = __builtin_amdgcn_exp2f(sacc[t][c][g * 8 + i] - m_ref);
+              rs += p;
+              pv[i] = from_f<T>(p);
+            }
+            pf[t][c * 2 + g] = pv;
+          }
+        l_run[t] = l_run[t] * alpha + rs;
+        m_run[t] = m_new;
+#pragma unroll
+        for (int j = 0; j < DT; ++j)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) oacc[t][j][e] *= alpha;
+      }
+      // O^T += V^T P^T
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+#pragma unroll
+        for (int j = 0; j < DT; ++j) {
+          const V8 vf = *(const V8*)(vt + (j * 32 + col) * VSTR + kk * 16 + hf * 8);
+#pragma unroll
+          for (int t = 0; t < QT; ++t) oacc[t][j] = Mma<T>::run(vf, pf[t][kk], oacc[t][j]);
+        }
+      }
+    }
+    if (kt + 1 < n_kt) stg.store(ks_lds[cur ^ 1], vt_lds[cur ^ 1]);
+    __syncthreads();
+  }
+
+  // normalise and write O[q][dh]; lane holds dh rows j*32 + 8*(e/4) + 4*hf + e%4 of its query
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    const int q = wq0 + t * 32 + col;
+    const float l = l_run[t] + __shfl_xor(l_run[t], 32, 64);
+    if (q >= L) continue;
+    const float inv = 1.0f / l;
+    T* orow = o + ((long)b * L + q) * d + (long)head * DH;
+#pragma unroll
+    for (int j = 0; j < DT; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        V4 v;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = from_f<T>(oacc[t][j][g * 4 + i] * inv);
+        *(V4*)(orow + j * 32 + 8 * g + 4 * hf) = v;
+      }
+    if (lse && hf == 0)
+      lse[((long)b * L + q) * h + head] = (m_run[t] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+  }
+}
+
+template <class T, int DH>
+ls_status launch_fwd(const void* qkv, int B, int L, int h, void* o, float* lse, hipStream_t st) {
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
+  if (L > 512) {
+    constexpr int QT = 2;
+    dim3 grid((L + 4 * QT * 32 - 1) / (4 * QT * 32), B * h);
+    flash_fwd_kernel<T, DH, QT><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, lse, L, h, scale_log2);
+  } else {
+    constexpr int QT = 1;
+    dim3 grid((L + 4 * QT * 32 - 1) / (4 * QT * 32), B * h);
+    flash_fwd_kernel<T, DH, QT><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, lse, L, h, scale_log2);
+  }
+  LS_CHECK_LAUNCH();
+  return LS_OK;
+}
+
+
+// ---------------------------------------------------------------------------------
+// Backward.  Two kernels, no atomics (deterministic):
+//   flash_bwd_dq_kernel : a workgroup owns 128 query rows, walks key tiles j <= i
+//   flash_bwd_dkv_kernel: a workgroup owns 128 keys, walks query tiles i >= j
+// Both recompute P from the saved log-sum-exp.  An MFMA result has its row index
+// in registers and its column index in lanes, which is the B-operand layout of a
+// following product that contracts over the rows; so each kernel forms its first
+// products with the contraction index of the second products as rows:
+//   dq : S^T, dP^T [key, q]  ->  dQ^T[dh, q]   = K^T[dh, key] dS^T[key, q]
+//   dkv: S,   dP   [q, key]  ->  dV^T[dh, key] = dO^T[dh, q] P[q, key]
+//                                dK^T[dh, key] = Q^T[dh, q]  dS[q, key]
+// The transposed A operands (K^T, Q^T, dO^T) are made in registers on the way
+// into LDS.  D = rowsum(dO * O) comes from a separate bandwidth-bound kernel.
+// ---------------------------------------------------------------------------------
+
+// natural tile [ROWS][DH] -> LDS row stride DH+8
+template <class T, int ROWS, int DH>
+struct NatStage {
+  static constexpr int N = (ROWS * DH / 8 + 255) / 256;
+  u32x4 v[N];
+  __device__ __forceinline__ void load(const T* base, long ld, int row0, int nrows) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int c = threadIdx.x + i * 256;
+      const int r = c / (DH / 8), col = (c % (DH / 8)) * 8;
+      u32x4 z = {0u, 0u, 0u, 0u};
+      if (c < ROWS * DH / 8 && row0 + r < nrows) z = *(const u32x4*)(base + (long)(row0 + r) * ld + col);
+      v[i] = z;
+    }
+  }
+  __device__ __forceinline__ void store(T* lds) const {
+#pragma unroll
+    for (int i = 0; i < N; ++i) {
+      const int c = threadIdx.x + i * 256;
+      const int r = c / (DH / 8), col = (c % (DH / 8)) * 8;
+      if (c < ROWS * DH / 8) *(u32x4*)(lds + r * (DH + 8) + col) = v[i];
+    }
+  }
+};
+
+// transposed tile: global [ROWS][DH] -> LDS [DH][ROWS+8]; one 8x8 block per thread
+// for threads tid0 .. tid0 + (ROWS/8)*(DH/8) - 1
+template <class T, int ROWS, int DH>
+struct TrStage {
+  static constexpr int NBLK = (ROWS / 8) * (DH / 8);
+  u32x4 v[8];
+  __device__ __forceinline__ void load(const T* base, long ld, int row0, int nrows, int tid0) {
+    const int t = (int)threadIdx.x - tid0;
+    if (t >= 0 && t < NBLK) {
+      const int rg = t % (ROWS / 8), dg = t / (ROWS / 8);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const int r = row0 + rg * 8 + j;
+        u32x4 z = {0u, 0u, 0u, 0u};
+        if (r < nrows) z = *(const u32x4*)(base + (long)r * ld + dg * 8);
+        v[j] = z;
+      }
+    }
+  }
+  __device__ __forceinline__ void store(T* lds, int tid0) const {
+    const int t = (int)threadIdx.x - tid0;
+    if (t >= 0 && t < NBLK) {
+      const int rg = t % (ROWS / 8), dg = t / (ROWS / 8);
+      u32x4 o[8];
+      transpose8x8(v, o);
+#pragma unroll
+      for (int r = 0; r < 8; ++r) *(u32x4*)(lds + (dg * 8 + r) * (ROWS + 8) + rg * 8) = o[r];
+    }
+  }
+};
+
+template <class T, int DH>
+__global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const T* __restrict__ qkv,
+                                                           const T* __restrict__ dO,
+                                                           const float* __restrict__ lse,
+                                                           const float* __restrict__ dvec,
+                                                           T* __restrict__ dqkv, int L, int h,
+                                                           float scale) {
+  typedef typename Mma<T>::V8 V8;
+  typedef typename Mma<T>::V4 V4;
+  constexpr int BQ = 128, KS = DH / 16, DT = DH / 32;
+  constexpr int KSTR = DH + 8, TSTR = KT + 8;
+  __shared__ __attribute__((aligned(16))) T k_lds[2][KT * KSTR];
+  __shared__ __attribute__((aligned(16))) T v_lds[2][KT * KSTR];
+  __shared__ __attribute__((aligned(16))) T kt_lds[2][DH * TSTR];
+
+  const int n_qt = (L + BQ - 1) / BQ;
+  const int qtile = n_qt - 1 - blockIdx.x;
+  const int b = blockIdx.y / h, head = blockIdx.y % h;
+  const int d = h * DH;
+  const long ld = 3L * d;
+  const T* qb = qkv + (long)b * L * ld + (long)head * DH;
+  const T* kb = qb + d;
+  const T* vb = qb + 2 * d;
+  const T* dob = dO + (long)b * L * d + (long)head * DH;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int col = lane & 31, hf = lane >> 5;
+  const int wq0 = qtile * BQ + wave * 32;
+  const int q = wq0 + col;
+  const float scale_log2 = scale * 1.4426950408889634f;
+
+  V8 qf[KS], dof[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    u32x4 z0 = {0u, 0u, 0u, 0u}, z1 = {0u, 0u, 0u, 0u};
+    if (q < L) {
+      z0 = *(const u32x4*)(qb + (long)q * ld + s * 16 + hf * 8);
+      z1 = *(const u32x4*)(dob + (long)q * d + s * 16 + hf * 8);
+    }
+    qf[s] = __builtin_bit_cast(V8, z0);
+    dof[s] = __builtin_bit_cast(V8, z1);
+  }
+  float lse2 = INFINITY, dq_ = 0.f;
+  if (q < L) {
+    lse2 = lse[((long)b * L + q) * h + head] * 1.4426950408889634f;
+    dq_ = dvec[((long)b * L + q) * h + head];
+  }
+  f32x16 acc[DT];
+#pragma unroll
+  for (int j = 0; j < DT; ++j)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+
+  const int q_hi = min(L, qtile * BQ + BQ) - 1;
+  const int n_kt = q_hi / KT + 1;
+  NatStage<T, KT, DH> sk, sv;
+  TrStage<T, KT, DH> st;
+  sk.load(kb, ld, 0, L);
+  sv.load(vb, ld, 0, L);
+  st.load(kb, ld, 0, L, 0);
+  sk.store(k_lds[0]);
+  sv.store(v_lds[0]);
+  st.store(kt_lds[0], 0);
+  __syncthreads();
+
+  for (int kt = 0; kt < n_kt; ++kt) {
+    const int cur = kt & 1, key0 = kt * KT;
+    if (kt + 1 < n_kt) {
+      sk.load(kb, ld, key0 + KT, L);
+      sv.load(vb, ld, key0 + KT, L);
+      st.load(kb, ld, key0 + KT, L, 0);
+    }
+    if (key0 <= wq0 + 31) {
+      const T* ks = k_lds[cur];
+      const T* vs = v_lds[cur];
+      const T* kts = kt_lds[cur];
+      f32x16 sacc[2], pacc[2];
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) sacc[c][e] = pacc[c][e] = 0.f;
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          const int row = (c * 32 + pi_row(col)) * KSTR + s * 16 + hf * 8;
+          sacc[c] = Mma<T>::run(*(const V8*)(ks + row), qf[s], sacc[c]);
+          pacc[c] = Mma<T>::run(*(const V8*)(vs + row), dof[s], pacc[c]);
+        }
+      const bool diag = key0 + KT - 1 > wq0;
+      V8 dsf[4];
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+          V8 t;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const int e = g * 8 + i;
+            float p = __builtin_amdgcn_exp2f(sacc[c][e] * scale_log2 - lse2);
+            if (diag && key0 + c * 32 + 16 * g + 8 * hf + i > q) p = 0.f;
+            t[i] = from_f<T>(p * (pacc[c][e] - dq_));
+          }
+          dsf[c * 2 + g] = t;
+        }
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+        for (int j = 0; j < DT; ++j)
+          acc[j] = Mma<T>::run(*(const V8*)(kts + (j * 32 + col) * TSTR + kk * 16 + hf * 8), dsf[kk], acc[j]);
+    }
+    if (kt + 1 < n_kt) {
+      sk.store(k_lds[cur ^ 1]);
+      sv.store(v_lds[cur ^ 1]);
+      st.store(kt_lds[cur ^ 1], 0);
+    }
+    __syncthreads();
+  }
+  if (q < L) {
+    T* row = dqkv + ((long)b * L + q) * ld + (long)head * DH;
+#pragma unroll
+    for (int j = 0; j < DT; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        V4 v;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = from_f<T>(acc[j][g * 4 + i] * scale);
+        *(V4*)(row + j * 32 + 8 * g + 4 * hf) = v;
+      }
+  }
+}
+
+template <class T, int DH>
+__global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const T* __restrict__ qkv,
+                                                            const T* __restrict__ dO,
+                                                            const float* __restrict__ lse,
+                                                            const float* __restrict__ dvec,
+                                                            T* __restrict__ dqkv, int L, int h,
+                                                            float scale) {
+  typedef typename Mma<T>::V8 V8;
+  typedef typename Mma<T>::V4 V4;
+  constexpr int BKEY = 128, QR = 32, KS = DH / 16, DT = DH / 32;
+  constexpr int NSTR = DH + 8, TSTR = QR + 8;
+  __shared__ __attribute__((aligned(16))) T q_lds[2][QR * NSTR];
+  __shared__ __attribute__((aligned(16))) T do_lds[2][QR * NSTR];
+  __shared__ __attribute__((aligned(16))) T qt_lds[2][DH * TSTR];
+  __shared__ __attribute__((aligned(16))) T dot_lds[2][DH * TSTR];
+  __shared__ __attribute__((aligned(16))) float lse_lds[2][QR];
+  __shared__ __attribute__((aligned(16))) float dv_lds[2][QR];
+
+  const int ktile = blockIdx.x;
+  const int b = blockIdx.y / h, head = blockIdx.y % h;
+  const int d = h * DH;
+  const long ld = 3L * d;
+  const T* qb = qkv + (long)b * L * ld + (long)head * DH;
+  const T* kb = qb + d;
+  const T* vb = qb + 2 * d;
+  const T* dob = dO + (long)b * L * d + (long)head * DH;
+  const float* lseb = lse + (long)b * L * h + head;
+  const float* dvb = dvec + (long)b * L * h + head;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int col = lane & 31, hf = lane >> 5;
+  const int wk0 = ktile * BKEY + wave * 32;
+  const int key = wk0 + col;
+  const float scale_log2 = scale * 1.4426950408889634f;
+
+  V8 kf[KS], vf[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    u32x4 z0 = {0u, 0u, 0u, 0u}, z1 = {0u, 0u, 0u, 0u};
+    if (key < L) {
+      z0 = *(const u32x4*)(kb + (long)key * ld + s * 16 + hf * 8);
+      z1 = *(const u32x4*)(vb + (long)key * ld + s * 16 + hf * 8);
+    }
+    kf[s] = __builtin_bit_cast(V8, z0);
+    vf[s] = __builtin_bit_cast(V8, z1);
+  }
+  f32x16 dk[DT], dv[DT];
+#pragma unroll
+  for (int j = 0; j < DT; ++j)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) dk[j][e] = dv[j][e] = 0.f;
+
+  const int qt_first = (ktile * BKEY) / QR;       // first query tile that can see these keys
+  const int n_qt = (L + QR - 1) / QR;
+  NatStage<T, QR, DH> sq, sdo;
+  TrStage<T, QR, DH> tq, tdo;
+  constexpr int TB = TrStage<T, QR, DH>::NBLK;     // threads per transposed tile
+  float st_l = 0.f, st_d = 0.f;
+  auto load_tile = [&](int qt) {
+    const int q0 = qt * QR;
+    sq.load(qb, ld, q0, L);
+    sdo.load(dob, d, q0, L);
+    tq.load(qb, ld, q0, L, 0);
+    tdo.load(dob, d, q0, L, TB);
+    if (threadIdx.x < QR) {
+      const int qq = q0 + threadIdx.x;
+      st_l = qq < L ? lseb[(long)qq * h] * 1.4426950408889634f : INFINITY;
+      st_d = qq < L ? dvb[(long)qq * h] : 0.f;
+    }
+  };
+  auto store_tile = [&](int buf) {
+    sq.store(q_lds[buf]);
+    sdo.store(do_lds[buf]);
+    tq.store(qt_lds[buf], 0);
+    tdo.store(dot_lds[buf], TB);
+    if (threadIdx.x < QR) {
+      lse_lds[buf][threadIdx.x] = st_l;
+      dv_lds[buf][threadIdx.x] = st_d;
+    }
+  };
+  if (qt_first < n_qt) {
+    load_tile(qt_first);
+    store_tile(0);
+  }
+  __syncthreads();
+
+  for (int qt = qt_first; qt < n_qt; ++qt) {
+    const int cur = (qt - qt_first) & 1, q0 = qt * QR;
+    if (qt + 1 < n_qt) load_tile(qt + 1);
+    if (q0 + QR - 1 >= wk0) {   // some query of the tile can see some key of this wavefront
+      const T* qs = q_lds[cur];
+      const T* dos = do_lds[cur];
+      f32x16 sacc, pacc;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sacc[e] = pacc[e] = 0.f;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        const int row = pi_row(col) * NSTR + s * 16 + hf * 8;
+        sacc = Mma<T>::run(*(const V8*)(qs + row), kf[s], sacc);
+        pacc = Mma<T>::run(*(const V8*)(dos + row), vf[s], pacc);
+      }
+      // element e <-> query q0 + 16*(e/8) + 8*hf + e%8, column <-> key
+      const bool diag = q0 < wk0 + 31;
+      V8 pf[2], dsf[2];
+#pragma unroll
+      for (int g = 0; g < 2; ++g) {
+        const f32x4 l0 = *(const f32x4*)&lse_lds[cur][16 * g + 8 * hf];
+        const f32x4 l1 = *(const f32x4*)&lse_lds[cur][16 * g + 8 * hf + 4];
+        const f32x4 d0 = *(const f32x4*)&dv_lds[cur][16 * g + 8 * hf];
+        const f32x4 d1 = *(const f32x4*)&dv_lds[cur][16 * g + 8 * hf + 4];
+        V8 tp, td;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int e = g * 8 + i;
+          const float lq = i < 4 ? l0[i & 3] : l1[i & 3];
+          const float dq = i < 4 ? d0[i & 3] : d1[i & 3];
+          float p = __builtin_amdgcn_exp2f(sacc[e] * scale_log2 - lq);
+          if (diag && key > q0 + 16 * g + 8 * hf + i) p = 0.f;
+          tp[i] = from_f<T>(p);
+          td[i] = from_f<T>(p * (pacc[e] - dq));
+        }
+        pf[g] = tp;
+        dsf[g] = td;
+      }
+      const T* qts = qt_lds[cur];
+      const T* dots = dot_lds[cur];
+#pragma unroll
+      for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+        for (int j = 0; j < DT; ++j) {
+          const int row = (j * 32 + col) * TSTR + kk * 16 + hf * 8;
+          dv[j] = Mma<T>::run(*(const V8*)(dots + row), pf[kk], dv[j]);
+          dk[j] = Mma<T>::run(*(const V8*)(qts + row), dsf[kk], dk[j]);
+        }
+    }
+    if (qt + 1 < n_qt) store_tile(cur ^ 1);
+    __syncthreads();
+  }
+  if (key < L) {
+    T* rk = dqkv + ((long)b * L + key) * ld + d + (long)head * DH;
+    T* rv = rk + d;
+#pragma unroll
+    for (int j = 0; j < DT; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        V4 a, c;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          a[i] = from_f<T>(dk[j][g * 4 + i] * scale);
+          c[i] = from_f<T>(dv[j][g * 4 + i]);
+        }
+        *(V4*)(rk + j * 32 + 8 * g + 4 * hf) = a;
+        *(V4*)(rv + j * 32 + 8 * g + 4 * hf) = c;
+      }
+  }
+}
+
+// D[t, head] = sum_c dO * O, one wavefront per (row, head)
+template <class T>
+__global__ void dvec_kernel(const T* o, const T* dO, long n_items, int dh, float* dvec) {
+  const long item = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (item >= n_items) return;
+  float s = 0.f;
+  for (int c = lane; c < dh; c += 64) s += to_f(o[item * dh + c]) * to_f(dO[item * dh + c]);
+  s = wave_sum(s);
+  if (lane == 0) dvec[item] = s;
+}
+
+template <class T, int DH>
+ls_status launch_bwd(const void* qkv, const void* o, const void* dO, const float* lse, int B, int L, int h,
+                     void* dqkv, float* dvec, hipStream_t st) {
+  const float scale = 1.0f / sqrtf((float)DH);
+  const long items = (long)B * L * h;
+  dvec_kernel<T><<<(unsigned)((items + 3) / 4), 256, 0, st>>>((const T*)o, (const T*)dO, items, DH, dvec);
+  LS_CHECK_LAUNCH();
+  dim3 gq((L + 127) / 128, B * h), gk((L + 127) / 128, B * h);
+  flash_bwd_dq_kernel<T, DH><<<gq, 256, 0, st>>>((const T*)qkv, (const T*)dO, lse, dvec, (T*)dqkv, L, h, scale);
+  LS_CHECK_LAUNCH();
+  flash_bwd_dkv_kernel<T, DH><<<gk, 256, 0, st>>>((const T*)qkv, (const T*)dO, lse, dvec, (T*)dqkv, L, h, scale);
+  LS_CHECK_LAUNCH();
+  return LS_OK;
+}
+
+}  // namespace
+
+extern "C" ls_status lsk_attn_fwd_mfma(const void* qkv, int dt, int B, int L, int h, int dh, void* o,
+                                       float* lse, void* stream) {
+  LS_REQUIRE(qkv && o && B > 0 && L > 0 && h > 0, "attn_fwd: bad argument");
+  LS_REQUIRE(dt == LS_BF16 || dt == LS_F16, "attn_fwd: the matrix-core kernel needs 16-bit operands");
+  LS_REQUIRE(dh == 64 || dh == 128, "attn_fwd: the matrix-core kernel needs head_dim 64 or 128");
+  LS_REQUIRE((long)B * h <= 65535, "attn_fwd: B * n_heads exceeds the grid limit");
+  hipStream_t st = (hipStream_t)stream;
+  if (dt == LS_BF16) return dh == 64 ? launch_fwd<bf16_t, 64>(qkv, B, L, h, o, lse, st)
+                                     : launch_fwd<bf16_t, 128>(qkv, B, L, h, o, lse, st);
+  return dh == 64 ? launch_fwd<f16_t, 64>(qkv, B, L, h, o, lse, st)
+                  : launch_fwd<f16_t, 128>(qkv, B, L, h, o, lse, st);
+}
+
+extern "C" ls_status lsk_attn_bwd_mfma(const void* qkv, const void* o, const void* dO, const float* lse,
+                                       int dt, int B, int L, int h, int dh, void* dqkv, float* dvec,
+                                       void* stream) {
+  LS_REQUIRE(qkv && o && dO && lse && dqkv && dvec && B > 0 && L > 0 && h > 0, "attn_bwd: bad argument");
+  LS_REQUIRE(dt == LS_BF16 || dt == LS_F16, "attn_bwd: the matrix-core kernel needs 16-bit operands");
+  LS_REQUIRE(dh == 64 || dh == 128, "attn_bwd: the matrix-core kernel needs head_dim 64 or 128");
+  LS_REQUIRE((long)B * h <= 65535, "attn_bwd: B * n_heads exceeds the grid limit");
+  hipStream_t st = (hipStream_t)stream;
+  if (dt == LS_BF16) return dh == 64 ? launch_bwd<bf16_t, 64>(qkv, o, dO, lse, B, L, h, dqkv, dvec, st)
+                                     : launch_bwd<bf16_t, 128>(qkv, o, dO, lse, B, L, h, dqkv, dvec, st);
+  return dh == 64 ? launch_bwd<f16_t, 64>(qkv, o, dO, lse, B, L, h, dqkv, dvec, st)
+                  : launch_bwd<f16_t, 128>(qkv, o, dO, lse, B, L, h, dqkv, dvec, st);
+}
