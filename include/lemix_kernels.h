@@ -25,13 +25,25 @@ extern "C" {
  * op_dtype LS_BF16 / LS_F16: MFMA path, fp32 accumulation; the contiguous
  * extent of each operand, lda and ldb must be multiples of 8 elements and the
  * bases 16-byte aligned.  op_dtype LS_F32: plain FMA path, no constraints.
- * c_dtype is LS_F32 or op_dtype; accumulate and resid need... resid is fp32
- * [M, ldr]; accumulate needs c_dtype LS_F32.  bias has N elements of bias_dtype.
+ * c_dtype is LS_F32 or op_dtype; resid is fp32 [M, ldr]; accumulate needs
+ * c_dtype LS_F32.  bias has N elements of bias_dtype.
  */
 ls_status lsk_gemm(int op_dtype, int M, int N, int K, const void* A, long lda, int a_kmajor,
                    const void* B, long ldb, int b_kmajor, void* C, long ldc, int c_dtype,
                    const void* bias, int bias_dtype, const float* resid, long ldr,
                    int accumulate, void* stream);
+
+/*
+ * The same forward map for decode batches (M <= 128 rows, both operands
+ * k-major, 16-bit): weights are streamed once from HBM, the contraction is
+ * split over ksplit slabs of K whose fp32 partial results live in `scratch`
+ * (lsk_gemm_skinny_scratch_floats(M, N, K) floats; null = no split).
+ */
+size_t lsk_gemm_skinny_scratch_floats(int M, int N, int K);
+ls_status lsk_gemm_skinny(int op_dtype, int M, int N, int K, const void* X, long ldx,
+                          const void* W, long ldw, void* C, long ldc, int c_dtype,
+                          const void* bias, int bias_dtype, const float* resid, long ldr,
+                          float* scratch, void* stream);
 
 /* dst[i] = (dst_dtype) src[i], i < n. */
 ls_status lsk_convert(const void* src, int src_dtype, void* dst, int dst_dtype, size_t n,
@@ -115,7 +127,11 @@ ls_status lsk_attn_paged(int impl, const void* qkv, int dtype, int T, int n_head
                          const int32_t* pos, const int32_t* req, const void* k_pool,
                          const void* v_pool, const int32_t* block_table, int max_pages_per_req,
                          int page_size, int max_ctx, void* o, float* scratch, void* stream);
-size_t lsk_attn_paged_scratch_floats(int T, int n_heads, int head_dim, int max_ctx);
+/* impl 0: plain kernel.  impl 1 (16-bit pools): the bandwidth-bound kernel that
+ * reads whole pages with 16-byte-per-lane loads and may split a long context
+ * over several workgroups; `scratch` then holds the per-split partial results
+ * (this many floats; null = never split). */
+size_t lsk_attn_paged_scratch_floats(int T, int n_heads, int head_dim, int max_ctx, int page_size);
 
 #ifdef __cplusplus
 }

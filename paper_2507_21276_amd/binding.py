@@ -83,7 +83,9 @@ SIGNATURES = {
     "lsk_attn_bwd": (_I, [_I, _VP, _VP, _VP, _VP, _I, _I, _I, _I, _I, _VP, _VP, _VP]),
     "lsk_kv_write": (_I, [_VP, _I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP, _I, _I, _VP]),
     "lsk_attn_paged": (_I, [_I, _VP, _I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP, _I, _I, _I, _VP, _VP, _VP]),
-    "lsk_attn_paged_scratch_floats": (_SZ, [_I, _I, _I, _I]),
+    "lsk_attn_paged_scratch_floats": (_SZ, [_I, _I, _I, _I, _I]),
+    "lsk_gemm_skinny_scratch_floats": (_SZ, [_I, _I, _I]),
+    "lsk_gemm_skinny": (_I, [_I, _I, _I, _I, _VP, _L, _VP, _L, _VP, _L, _I, _VP, _I, _VP, _L, _VP, _VP]),
 }
 
 
@@ -241,6 +243,17 @@ def lsk_gemm(A, B, C_out, *, M, N, K, a_kmajor=True, b_kmajor=True, lda=None, ld
                           ldr if ldr is not None else N, int(accumulate), _stream(stream)))
 
 
+def lsk_gemm_skinny(X, W, C_out, *, bias=None, resid=None, split=True, stream=None):
+    M, K = X.shape
+    N = W.shape[0]
+    n = lib().lsk_gemm_skinny_scratch_floats(M, N, K) if split else 0
+    scratch = torch.empty(max(n, 1), dtype=torch.float32, device=X.device) if split else None
+    _check(lib().lsk_gemm_skinny(CODE_OF_TORCH[X.dtype], M, N, K, _p(X), K, _p(W), K, _p(C_out), N,
+                                 CODE_OF_TORCH[C_out.dtype], _p(bias),
+                                 CODE_OF_TORCH[bias.dtype] if bias is not None else 0, _p(resid), N,
+                                 _p(scratch), _stream(stream)))
+
+
 def lsk_convert(src, dst, stream=None):
     _check(lib().lsk_convert(_p(src), CODE_OF_TORCH[src.dtype], _p(dst), CODE_OF_TORCH[dst.dtype],
                              src.numel(), _stream(stream)))
@@ -312,7 +325,7 @@ def lsk_kv_write(qkv, n_heads, head_dim, pos, req, k_pool, v_pool, block_table, 
 def lsk_attn_paged(impl, qkv, n_heads, head_dim, pos, req, k_pool, v_pool, block_table, page_size,
                    max_ctx, o, stream=None):
     T = qkv.shape[0]
-    n = lib().lsk_attn_paged_scratch_floats(T, n_heads, head_dim, max_ctx)
+    n = lib().lsk_attn_paged_scratch_floats(T, n_heads, head_dim, max_ctx, page_size)
     scratch = torch.empty(max(n, 1), dtype=torch.float32, device=qkv.device)
     _check(lib().lsk_attn_paged(impl, _p(qkv), CODE_OF_TORCH[qkv.dtype], T, n_heads, head_dim, _p(pos),
                                 _p(req), _p(k_pool), _p(v_pool), _p(block_table), block_table.shape[1],

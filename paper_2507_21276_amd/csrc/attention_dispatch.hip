@@ -31,16 +31,21 @@ ls_status lsk_attn_bwd(int impl, const void* qkv, const void* o, const void* dO,
   return lsk_attn_bwd_simple(qkv, o, dO, lse, dtype, B, L, n_heads, head_dim, dqkv, dvec, stream);
 }
 
-size_t lsk_attn_paged_scratch_floats(int T, int n_heads, int head_dim, int max_ctx) {
-  (void)T; (void)n_heads; (void)head_dim; (void)max_ctx;
-  return 0;
+size_t lsk_attn_decode_scratch_floats(int, int, int, int, int);
+ls_status lsk_attn_decode(const void*, int, int, int, int, const int32_t*, const int32_t*, const void*,
+                          const void*, const int32_t*, int, int, int, void*, float*, void*);
+
+size_t lsk_attn_paged_scratch_floats(int T, int n_heads, int head_dim, int max_ctx, int page_size) {
+  return lsk_attn_decode_scratch_floats(T, n_heads, head_dim, max_ctx, page_size);
 }
 
 ls_status lsk_attn_paged(int impl, const void* qkv, int dtype, int T, int n_heads, int head_dim,
                          const int32_t* pos, const int32_t* req, const void* k_pool, const void* v_pool,
                          const int32_t* block_table, int max_pages_per_req, int page_size, int max_ctx,
                          void* o, float* scratch, void* stream) {
-  (void)impl; (void)scratch;
+  if (mfma_ok(impl, dtype, head_dim) && (page_size * head_dim) % 512 == 0)
+    return lsk_attn_decode(qkv, dtype, T, n_heads, head_dim, pos, req, k_pool, v_pool, block_table,
+                           max_pages_per_req, page_size, max_ctx, o, scratch, stream);
   return lsk_attn_paged_simple(qkv, dtype, T, n_heads, head_dim, pos, req, k_pool, v_pool, block_table,
                                max_pages_per_req, page_size, max_ctx, o, stream);
 }

@@ -27,8 +27,6 @@ extern "C" {
 ls_status lsk_attn_fwd_simple(const void*, int, int, int, int, int, void*, float*, void*);
 ls_status lsk_attn_bwd_simple(const void*, const void*, const void*, const float*, int, int, int, int, int,
                               void*, float*, void*);
-ls_status lsk_attn_paged_simple(const void*, int, int, int, int, const int32_t*, const int32_t*,
-                                const void*, const void*, const int32_t*, int, int, int, void*, void*);
 }
 
 namespace {
@@ -137,9 +135,18 @@ size_t carve_saved(const ls_stage* s, void* base, int T, std::vector<Saved>* out
 // forward / serving scratch
 struct FwdWs {
   int32_t *pos, *req;
-  float *xa, *xb;
+  float *xa, *xb, *scratch;
   void *h, *qkv, *o, *up, *act;
 };
+// fp32 scratch for split decode attention and split-K decode GEMMs (both are
+// only used for small row counts, where these bounds hold)
+size_t serve_scratch_floats(const ls_stage* s) {
+  const ls_config& c = s->cfg;
+  const size_t attn = (size_t)4096 * (c.head_dim + 2);
+  const size_t widest = (size_t)(3 * c.d_model > s->up_cols ? 3 * c.d_model : s->up_cols);
+  const size_t gemm = (size_t)8 * 128 * widest;
+  return attn > gemm ? attn : gemm;
+}
 size_t carve_fwd(const ls_stage* s, void* base, int T, FwdWs* w) {
   const ls_config& c = s->cfg;
   const size_t d = c.d_model, e = osz(s);
@@ -154,6 +161,7 @@ size_t carve_fwd(const ls_stage* s, void* base, int T, FwdWs* w) {
   v.o = b.take(T * d * e);
   v.up = b.take((size_t)T * s->up_cols * e);
   v.act = b.take((size_t)T * c.d_ff * e);
+  v.scratch = (float*)b.take(serve_scratch_floats(s) * 4);
   if (w) *w = v;
   return b.used;
 }
@@ -194,7 +202,17 @@ struct FwdBufs {
   const float* x;
   float *x1, *y, *mean1, *rstd1, *mean2, *rstd2, *lse;
   void *h1, *qkv, *o, *h2, *up, *act;
+  float* scratch;
 };
+
+// forward linear map: weight-streaming kernel for decode-sized batches, tiled MFMA kernel otherwise
+ls_status linear(const ls_stage* s, int T, int N, int K, const void* X, const void* W, void* C, int c_dtype,
+                 const void* bias, const float* resid, float* scratch, hipStream_t st) {
+  const int mt = s->cfg.mma_dtype;
+  if (mt != LS_F32 && T <= 128 && scratch)
+    return lsk_gemm_skinny(mt, T, N, K, X, K, W, K, C, N, c_dtype, bias, s->cfg.dtype, resid, N, scratch, st);
+  return lsk_gemm(mt, T, N, K, X, K, 1, W, K, 1, C, N, c_dtype, bias, s->cfg.dtype, resid, N, 0, st);
+}
 
 ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const int32_t* pos,
                         const int32_t* req, int B, int L, const ls_kv* kv, int max_ctx,
@@ -206,8 +224,8 @@ ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const
   const int nk = gpt ? 0 : 1;
   LS_TRY(lsk_norm_fwd(nk, f.x, T, d, pptr(s, o.n1_g), gpt ? pptr(s, o.n1_b) : nullptr, pt, c.norm_eps,
                       f.h1, mt, f.mean1, f.rstd1, st));
-  LS_TRY(lsk_gemm(mt, T, 3 * d, d, f.h1, d, 1, wptr(s, o.w_qkv), d, 1, f.qkv, 3 * d, mt,
-                  gpt ? pptr(s, o.b_qkv) : nullptr, pt, nullptr, 0, 0, st));
+  LS_TRY(linear(s, T, 3 * d, d, f.h1, wptr(s, o.w_qkv), f.qkv, mt, gpt ? pptr(s, o.b_qkv) : nullptr, nullptr,
+                f.scratch, st));
   if (!gpt) LS_TRY(lsk_rope(f.qkv, mt, T, c.n_heads, c.head_dim, pos, s->rope_table, 1.0f, st));
   if (kv) {
     const size_t slab = (size_t)kv->n_pages * c.n_heads * c.page_size * c.head_dim * osz(s);
@@ -215,21 +233,20 @@ ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const
     void* vp = (char*)kv->v_pool + (size_t)l * slab;
     LS_TRY(lsk_kv_write(f.qkv, mt, T, c.n_heads, c.head_dim, pos, req, kp, vp, kv->block_table,
                         kv->max_pages_per_req, c.page_size, st));
-    LS_TRY(lsk_attn_paged_simple(f.qkv, mt, T, c.n_heads, c.head_dim, pos, req, kp, vp, kv->block_table,
-                                 kv->max_pages_per_req, c.page_size, max_ctx, f.o, st));
+    LS_TRY(lsk_attn_paged(mt == LS_F32 ? 0 : 1, f.qkv, mt, T, c.n_heads, c.head_dim, pos, req, kp, vp,
+                          kv->block_table, kv->max_pages_per_req, c.page_size, max_ctx, f.o,
+                          (long)T * c.n_heads < 2048 ? f.scratch : nullptr, st));
   } else {
     LS_TRY(lsk_attn_fwd(mt == LS_F32 ? 0 : 1, f.qkv, mt, B, L, c.n_heads, c.head_dim, f.o, f.lse, st));
   }
-  LS_TRY(lsk_gemm(mt, T, d, d, f.o, d, 1, wptr(s, o.w_o), d, 1, f.x1, d, LS_F32,
-                  gpt ? pptr(s, o.b_o) : nullptr, pt, f.x, d, 0, st));
+  LS_TRY(linear(s, T, d, d, f.o, wptr(s, o.w_o), f.x1, LS_F32, gpt ? pptr(s, o.b_o) : nullptr, f.x, f.scratch, st));
   LS_TRY(lsk_norm_fwd(nk, f.x1, T, d, pptr(s, o.n2_g), gpt ? pptr(s, o.n2_b) : nullptr, pt, c.norm_eps,
                       f.h2, mt, f.mean2, f.rstd2, st));
-  LS_TRY(lsk_gemm(mt, T, s->up_cols, d, f.h2, d, 1, wptr(s, o.w_up), d, 1, f.up, s->up_cols, mt,
-                  gpt ? pptr(s, o.b_up) : nullptr, pt, nullptr, 0, 0, st));
+  LS_TRY(linear(s, T, s->up_cols, d, f.h2, wptr(s, o.w_up), f.up, mt, gpt ? pptr(s, o.b_up) : nullptr, nullptr,
+                f.scratch, st));
   if (gpt) LS_TRY(lsk_gelu_fwd(f.up, f.act, mt, (size_t)T * F, c.act, st));
   else LS_TRY(lsk_swiglu_fwd(f.up, f.act, mt, T, F, st));
-  LS_TRY(lsk_gemm(mt, T, d, F, f.act, F, 1, wptr(s, o.w_dn), F, 1, f.y, d, LS_F32,
-                  gpt ? pptr(s, o.b_dn) : nullptr, pt, f.x1, d, 0, st));
+  LS_TRY(linear(s, T, d, F, f.act, wptr(s, o.w_dn), f.y, LS_F32, gpt ? pptr(s, o.b_dn) : nullptr, f.x1, f.scratch, st));
   return LS_OK;
 }
 
@@ -263,7 +280,7 @@ ls_status serve_forward(ls_stage* s, const void* X, int T, int B, const ls_kv* k
   LS_TRY(lsk_convert(X, c.io_dtype, w.xa, LS_F32, (size_t)T * c.d_model, st));
   for (int l = 0; l < c.n_layers; ++l) {
     FwdBufs f{w.xa, w.xb, w.xa, nullptr, nullptr, nullptr, nullptr, nullptr,
-              w.h, w.qkv, w.o, w.h, w.up, w.act};
+              w.h, w.qkv, w.o, w.h, w.up, w.act, w.scratch};
     LS_TRY(block_forward(s, l, T, f, w.pos, w.req, B, 0, kv, max_ctx, st));
   }
   return lsk_convert(w.xa, LS_F32, Y, c.io_dtype, (size_t)T * c.d_model, st);
@@ -438,7 +455,7 @@ ls_status stage_train_fwd(ls_stage* s, const void* X, int B, int L, void* Y, voi
   for (int l = 0; l < c.n_layers; ++l) {
     float* y = l + 1 < c.n_layers ? sv[l + 1].x_in : w.xa;
     FwdBufs f{sv[l].x_in, sv[l].x1, y, sv[l].mean1, sv[l].rstd1, sv[l].mean2, sv[l].rstd2, sv[l].lse,
-              sv[l].h1, sv[l].qkv, sv[l].o, sv[l].h2, sv[l].up, sv[l].act};
+              sv[l].h1, sv[l].qkv, sv[l].o, sv[l].h2, sv[l].up, sv[l].act, w.scratch};
     LS_TRY(block_forward(s, l, T, f, w.pos, nullptr, B, L, nullptr, 0, st));
   }
   return lsk_convert(w.xa, LS_F32, Y, c.io_dtype, (size_t)T * c.d_model, st);

@@ -70,6 +70,24 @@ def test_gemm_input_and_weight_gradient_layouts(name, T, N, K):
     assert_close(host(dW), 2.0 * dY.astype(np.float64).T @ X.astype(np.float64), 1e-5 if name != "f32" else 1e-4, "dW")
 
 
+@pytest.mark.parametrize("name", ["bf16", "f16"])
+@pytest.mark.parametrize("M,N,K", [(64, 1048, 4096), (4, 72, 136), (33, 264, 11008), (128, 520, 768), (1, 64, 32)])
+@pytest.mark.parametrize("split", [True, False])
+def test_gemm_skinny_weight_streaming(name, M, N, K, split):
+    X = q(S.normal(9, "X", (M, K)), name)
+    W = q(S.normal(9, "W", (N, K), 0.05), name)
+    bias = q(S.normal(9, "b", (N,)), "bf16")
+    R = S.normal(9, "R", (M, N))
+    ref = X.astype(np.float64) @ W.astype(np.float64).T
+    out = torch.empty(M, N, dtype=torch.float32, device="cuda")
+    Bd.lsk_gemm_skinny(dev(X, DT[name]), dev(W, DT[name]), out, bias=dev(bias, torch.bfloat16),
+                       resid=dev(R, torch.float32), split=split)
+    assert_close(host(out), ref + bias + R, 1e-5, "skinny gemm fp32 out")
+    out16 = torch.empty(M, N, dtype=DT[name], device="cuda")
+    Bd.lsk_gemm_skinny(dev(X, DT[name]), dev(W, DT[name]), out16, split=split)
+    assert_close(host(out16), ref, otol(name, ref), "skinny gemm 16-bit out")
+
+
 def test_gemm_rejects_unaligned_operands():
     a = torch.zeros(16, 12, dtype=torch.bfloat16, device="cuda")
     w = torch.zeros(16, 12, dtype=torch.bfloat16, device="cuda")
