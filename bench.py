@@ -81,6 +81,9 @@ def main():
     ap.add_argument("--mma", default="f16", choices=["f16", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
+    ap.add_argument("--legs", default="train,decode,prefill",
+                    help="comma list of the legs that make up a step (profiling aid; the default is the full "
+                         "step; 'gemms' = the 12 GEMM launches of one block on their own)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (one pipeline stage on one MI355X); "
@@ -142,32 +145,6 @@ def main():
         st.stage_prefill(Xp[:chunks[0]], [chunks[0]], kvp[0], Yp[:chunks[0]], ws_a)
         st.stage_prefill(Xp[chunks[0]:], [chunks[1]], kvp[1], Yp[chunks[0]:], ws_a)
 
-    def step():
-        train()
-        decode()
-        prefill()
-
-    tokens_per_step = T + Bq + sum(chunks)
-
-    # ---- timed region: exactly K steps ------------------------------------------------------
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    dt = time.perf_counter() - t0
-    ms_per_step = dt * 1e3 / args.steps
-    log(f"step: {ms_per_step:.2f} ms")
-
-    # ---- per-leg rates --------------------------------------------------------------------
-    it = max(2, min(args.steps, 10))
-    ms_train = time_events(torch, train, it)
-    ms_dec = time_events(torch, decode, it * 2)
-    ms_pre = time_events(torch, prefill, it)
-    log(f"train {ms_train:.2f} ms, decode {ms_dec:.3f} ms, prefill {ms_pre:.2f} ms")
-
     # ---- GEMM roofline: the 12 GEMM launches of one block, in the stage's own shapes -----------
     mt = Bd.TORCH_DTYPE[st.c.mma_dtype]
     U = 2 * F
@@ -197,6 +174,41 @@ def main():
         G(a_3d, w_qkv, o_d, M=T, N=d, K=3 * d, b_kmajor=False, ldb=d)
         G(a_3d, a_d, g_qkv, M=3 * d, N=d, K=T, a_kmajor=False, b_kmajor=False, lda=3 * d, ldb=d)
 
+    legs = [l for l in args.legs.split(",") if l]
+    leg_fn = {"train": train, "decode": decode, "prefill": prefill, "gemms": gemms}
+    leg_tok = {"train": T, "decode": Bq, "prefill": sum(chunks), "gemms": T}
+
+    def step():
+        for l in legs:
+            leg_fn[l]()
+
+    tokens_per_step = sum(leg_tok[l] for l in legs)
+
+    # ---- timed region: exactly K steps ------------------------------------------------------
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt * 1e3 / args.steps
+    log(f"step: {ms_per_step:.2f} ms")
+
+    # ---- per-leg rates --------------------------------------------------------------------
+    it = max(2, min(args.steps, 10))
+    partial_run = set(legs) != {"train", "decode", "prefill"}
+    ms_train = time_events(torch, train, it) if "train" in legs else float("nan")
+    ms_dec = time_events(torch, decode, it * 2) if "decode" in legs else float("nan")
+    ms_pre = time_events(torch, prefill, it) if "prefill" in legs else float("nan")
+    if partial_run:
+        print(json.dumps({"legs": legs, "ms_per_step": ms_per_step, "train_ms": ms_train, "decode_ms": ms_dec,
+                          "prefill_ms": ms_pre}), flush=True)
+        return
+    log(f"train {ms_train:.2f} ms, decode {ms_dec:.3f} ms, prefill {ms_pre:.2f} ms")
+
+    # ---- GEMM roofline ---------------------------------------------------------------------
     ms_gemms = time_events(torch, gemms, 5)
     flop_block = 3.0 * T * (8.0 * d * d + 6.0 * d * F)       # fwd + dX + dW of one block
     gemm_tflops = flop_block / (ms_gemms * 1e-3) / 1e12

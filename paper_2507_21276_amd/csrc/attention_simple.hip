@@ -200,6 +200,44 @@ __global__ void kv_write_kernel(const void* qkv, int dt, int T, int h, int dh, c
   }
 }
 
+// serving: rotary embedding of q and k (optional) fused with the K/V page write;
+// one thread per (row, head, pair i < dh/2)
+__global__ void rope_kv_kernel(void* qkv, int dt, int T, int h, int dh, const int32_t* pos,
+                               const int32_t* req, const float* table, void* k_pool, void* v_pool,
+                               const int32_t* block_table, int max_pages, int page) {
+  const int half = dh / 2, d = h * dh;
+  const size_t n = (size_t)T * h * half;
+  for (size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x; idx < n;
+       idx += (size_t)gridDim.x * blockDim.x) {
+    const int i = idx % half, head = (idx / half) % h;
+    const size_t t = idx / ((size_t)half * h);
+    const int p = pos[t];
+    const size_t qi = t * 3 * d + (size_t)head * dh + i;
+    float ka = load_as_f(qkv, qi + d, dt), kb = load_as_f(qkv, qi + d + half, dt);
+    if (table) {
+      const float c = table[((size_t)p * half + i) * 2], s = table[((size_t)p * half + i) * 2 + 1];
+      const float qa = load_as_f(qkv, qi, dt), qb = load_as_f(qkv, qi + half, dt);
+      store_from_f(qkv, qi, dt, qa * c - qb * s);
+      store_from_f(qkv, qi + half, dt, qb * c + qa * s);
+      const float ra = ka * c - kb * s, rb = kb * c + ka * s;
+      ka = ra; kb = rb;
+      store_from_f(qkv, qi + d, dt, ka);
+      store_from_f(qkv, qi + d + half, dt, kb);
+    }
+    const int pg = block_table[(size_t)req[t] * max_pages + p / page];
+    const size_t dst = (((size_t)pg * h + head) * page + p % page) * dh + i;
+    store_from_f(k_pool, dst, dt, ka);
+    store_from_f(k_pool, dst + half, dt, kb);
+    if (dt == LS_F32) {
+      ((float*)v_pool)[dst] = ((const float*)qkv)[qi + 2 * d];
+      ((float*)v_pool)[dst + half] = ((const float*)qkv)[qi + 2 * d + half];
+    } else {
+      ((uint16_t*)v_pool)[dst] = ((const uint16_t*)qkv)[qi + 2 * d];
+      ((uint16_t*)v_pool)[dst + half] = ((const uint16_t*)qkv)[qi + 2 * d + half];
+    }
+  }
+}
+
 ls_status set_lds(const void* fn, size_t bytes) {
   LS_REQUIRE(bytes <= 160 * 1024, "attention: context too long for the plain kernel (%zu bytes of LDS)", bytes);
   if (bytes > 48 * 1024)
@@ -256,6 +294,20 @@ ls_status lsk_kv_write(const void* qkv, int dt, int T, int h, int dh, const int3
   if (g > 8192) g = 8192;
   kv_write_kernel<<<(unsigned)g, 256, 0, (hipStream_t)stream>>>(qkv, dt, T, h, dh, pos, req, k_pool, v_pool,
                                                                 block_table, max_pages, page);
+  LS_CHECK_LAUNCH();
+  return LS_OK;
+}
+
+ls_status lsk_rope_kv_write(void* qkv, int dt, int T, int h, int dh, const int32_t* pos, const int32_t* req,
+                            const float* table, void* k_pool, void* v_pool, const int32_t* block_table,
+                            int max_pages, int page, void* stream) {
+  LS_REQUIRE(qkv && pos && req && k_pool && v_pool && block_table && T > 0 && dh % 2 == 0,
+             "rope_kv_write: bad argument");
+  const size_t n = (size_t)T * h * (dh / 2);
+  size_t g = (n + 255) / 256;
+  if (g > 8192) g = 8192;
+  rope_kv_kernel<<<(unsigned)g, 256, 0, (hipStream_t)stream>>>(qkv, dt, T, h, dh, pos, req, table, k_pool,
+                                                               v_pool, block_table, max_pages, page);
   LS_CHECK_LAUNCH();
   return LS_OK;
 }

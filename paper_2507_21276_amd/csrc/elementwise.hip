@@ -16,7 +16,8 @@ __global__ void convert_kernel(const void* src, int sdt, void* dst, int ddt, siz
 }
 
 // ---------------------------------------------------------------- norm fwd
-// one 256-thread workgroup per row
+// one 256-thread workgroup per row; the row is read once and held in registers
+constexpr int NF_MAXCOL = 32;  // d <= 256 * 32
 __global__ __launch_bounds__(256) void norm_fwd_kernel(int kind, const float* x, int d,
                                                        const void* gamma, const void* beta,
                                                        int pdt, float eps, void* h, int hdt,
@@ -24,21 +25,33 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(int kind, const float* x,
   __shared__ float red[16];
   const size_t row = blockIdx.x;
   const float* xr = x + row * d;
+  float v[NF_MAXCOL];
   float s = 0.f;
-  for (int i = threadIdx.x; i < d; i += 256) s += xr[i];
+#pragma unroll
+  for (int c = 0; c < NF_MAXCOL; ++c) {
+    const int i = threadIdx.x + c * 256;
+    v[c] = i < d ? xr[i] : 0.f;
+    s += v[c];
+  }
   float mu = 0.f;
   if (kind == 0) mu = block_sum(s, red) / d;
   float q = 0.f;
-  for (int i = threadIdx.x; i < d; i += 256) {
-    const float c = xr[i] - mu;
-    q += c * c;
+#pragma unroll
+  for (int c = 0; c < NF_MAXCOL; ++c) {
+    const int i = threadIdx.x + c * 256;
+    const float t = i < d ? v[c] - mu : 0.f;
+    q += t * t;
   }
   const float var = block_sum(q, red) / d;
   const float r = 1.0f / sqrtf(var + eps);
-  for (int i = threadIdx.x; i < d; i += 256) {
-    float v = (xr[i] - mu) * r * load_as_f(gamma, i, pdt);
-    if (kind == 0 && beta) v += load_as_f(beta, i, pdt);
-    store_from_f(h, row * d + i, hdt, v);
+#pragma unroll
+  for (int c = 0; c < NF_MAXCOL; ++c) {
+    const int i = threadIdx.x + c * 256;
+    if (i < d) {
+      float o = (v[c] - mu) * r * load_as_f(gamma, i, pdt);
+      if (kind == 0 && beta) o += load_as_f(beta, i, pdt);
+      store_from_f(h, row * d + i, hdt, o);
+    }
   }
   if (threadIdx.x == 0) {
     if (mean && kind == 0) mean[row] = mu;
@@ -236,6 +249,7 @@ ls_status lsk_norm_fwd(int kind, const float* x, int T, int d, const void* gamma
                        int pdt, float eps, void* h, int hdt, float* mean, float* rstd, void* stream) {
   LS_REQUIRE(x && gamma && h && T > 0 && d > 0, "norm_fwd: bad argument");
   LS_REQUIRE(kind == 0 || kind == 1, "norm_fwd: kind must be 0 (LayerNorm) or 1 (RMSNorm)");
+  LS_REQUIRE(d <= 256 * NF_MAXCOL, "norm_fwd: d_model %d exceeds %d", d, 256 * NF_MAXCOL);
   norm_fwd_kernel<<<T, 256, 0, (hipStream_t)stream>>>(kind, x, d, gamma, beta, pdt, eps, h, hdt, mean, rstd);
   LS_CHECK_LAUNCH();
   return LS_OK;

@@ -16,6 +16,9 @@
 // the way in (8x8 blocks per thread), so the MFMA loop is the same for all
 // three layouts.  Global loads for tile k+1 are in flight while tile k is
 // multiplied; two LDS buffers, one barrier per k step.
+#include <stdlib.h>
+#include <string.h>
+
 #include "common.h"
 
 namespace {
@@ -281,6 +284,19 @@ ls_status dispatch_mfma(const GemmArgs& g, hipStream_t st) {
 
 }  // namespace
 
+ls_status gemm_dma_try(int, int, int, int, const void*, long, int, const void*, long, int, void*, long, int,
+                       const void*, int, const float*, long, int, hipStream_t);
+
+// LS_GEMM_IMPL=staged forces the register-staged kernel (for A/B comparisons)
+static bool use_dma_kernel() {
+  static int v = -1;
+  if (v < 0) {
+    const char* e = getenv("LS_GEMM_IMPL");
+    v = (e && strcmp(e, "staged") == 0) ? 0 : 1;
+  }
+  return v == 1;
+}
+
 extern "C" ls_status lsk_gemm(int op_dtype, int M, int N, int K, const void* A, long lda,
                               int a_kmajor, const void* B, long ldb, int b_kmajor, void* C,
                               long ldc, int c_dtype, const void* bias, int bias_dtype,
@@ -305,6 +321,11 @@ extern "C" ls_status lsk_gemm(int op_dtype, int M, int N, int K, const void* A, 
   LS_REQUIRE(a_kmajor ? (K % 8 == 0) : (M % 8 == 0), "gemm: A contiguous extent must be a multiple of 8");
   LS_REQUIRE(b_kmajor ? (K % 8 == 0) : (N % 8 == 0), "gemm: B contiguous extent must be a multiple of 8");
   LS_REQUIRE(c_dtype == LS_F32 || c_dtype == op_dtype, "gemm: output type must be fp32 or the operand type");
+  if (use_dma_kernel() && (long)((M + 255) / 256) * ((N + 255) / 256) >= 200) {
+    const ls_status r = gemm_dma_try(op_dtype, M, N, K, A, lda, a_kmajor, B, ldb, b_kmajor, C, ldc, c_dtype, bias,
+                                     bias_dtype, resid, ldr, accumulate, st);
+    if (r != LS_ESTATE) return r;
+  }
   if (op_dtype == LS_BF16) return dispatch_mfma<bf16_t>(g, st);
   if (op_dtype == LS_F16) return dispatch_mfma<f16_t>(g, st);
   ls_set_error("gemm: unknown operand dtype %d", op_dtype);

@@ -1,0 +1,282 @@
+// Large-tile MFMA GEMM whose operand tiles go from global memory straight into
+// LDS (16-byte direct-to-LDS loads, no register staging, no LDS store
+// instructions).  256 x 256 x 64 tiles, 4 wavefronts of 128 x 128, 32x32x16 MFMA,
+// two LDS buffers of 64 KB.  Used when the contraction length is a multiple of
+// 64; the register-staged kernel in gemm.hip covers everything else.
+//
+// LDS layouts (a direct-to-LDS wave load writes 1 KB: lane i -> bytes 16 i):
+//   k-major operand  (element (r,k) at r*ld + k): [256 rows][64 k], 128 B per
+//     row, the eight 16-byte chunks of a row XOR-permuted with (row >> 1) & 7,
+//     so that the 16-byte fragment reads of 16 consecutive rows hit 16
+//     different bank groups.  Fragments: one 16-byte LDS read per 8 k.
+//   k-strided operand (element (r,k) at k*ld + r): [64 k][256 rows], 512 B per
+//     k, chunk index XOR-permuted with 4 * (k & 3).  Fragments are read with the
+//     transposing LDS load (4 k x 16 rows per 16 lanes), two per 8 k.
+// The permutations are applied by choosing which global chunk each lane fetches.
+#include "common.h"
+
+namespace {
+
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+template <class T> struct Mf;
+template <> struct Mf<bf16_t> {
+  typedef bf16x8 V8;
+  typedef bf16x4 V4;
+  static __device__ __forceinline__ f32x16 run(V8 a, V8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ V4 tr(const void* p) {
+    return __builtin_bit_cast(V4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p));
+  }
+};
+template <> struct Mf<f16_t> {
+  typedef f16x8 V8;
+  typedef f16x4 V4;
+  static __device__ __forceinline__ f32x16 run(V8 a, V8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+  }
+  static __device__ __forceinline__ V4 tr(const void* p) {
+    return __builtin_bit_cast(V4, __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p));
+  }
+};
+
+struct DmaArgs {
+  int M, N, K;
+  const void* A; long lda; int a_kmajor;
+  const void* B; long ldb; int b_kmajor;
+  void* C; long ldc; int c_dtype;
+  const void* bias; int bias_dtype;
+  const float* resid; long ldr;
+  int accumulate;
+  int tiles_m, tiles_n;
+};
+
+constexpr int TM = 256, TN = 256, TK = 64;
+constexpr int TILE_BYTES = 256 * 64 * 2;  // one operand tile
+
+// Direct-to-LDS loads of one operand tile: 8 wave loads per wavefront.  The
+// per-lane byte offsets inside the tile are fixed for the whole k loop (`off`,
+// computed once); only the uniform tile base moves.
+template <bool KMAJOR>
+__device__ __forceinline__ void tile_offsets(uint32_t (&off)[8], long ld, int row0, int nrows, int wave, int lane) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const int q = wave * 8 + j;  // 1 KB block of the tile
+    if (KMAJOR) {
+      const int row = q * 8 + (lane >> 3);
+      const int kc = (lane & 7) ^ ((row >> 1) & 7);
+      int gr = row0 + row;
+      gr = gr < nrows ? gr : nrows - 1;  // rows past the edge: any valid data, never stored
+      off[j] = (uint32_t)(((long)(gr - row0) * ld + kc * 8) * 2);
+    } else {
+      const int krow = q * 2 + (lane >> 5);
+      const int cl = (lane & 31) ^ (4 * (krow & 3));
+      int gr = row0 + cl * 8;
+      gr = gr + 8 <= nrows ? gr : nrows - 8;
+      off[j] = (uint32_t)(((long)krow * ld + (gr - row0)) * 2);
+    }
+  }
+}
+
+__device__ __forceinline__ void issue_tile(const char* tile_base, const uint32_t (&off)[8], char* lds_tile, int wave) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tile_base + off[j]),
+                                     (__attribute__((address_space(3))) void*)(lds_tile + (wave * 8 + j) * 1024),
+                                     16, 0, 0);
+}
+
+// fragment of 8 k for the 32 rows starting at `r0` of an operand tile
+template <class T, bool KMAJOR>
+__device__ __forceinline__ typename Mf<T>::V8 read_frag(const char* lds_tile, int r0, int ks, int lane) {
+  typedef typename Mf<T>::V8 V8;
+  typedef typename Mf<T>::V4 V4;
+  const int hf = lane >> 5;
+  if (KMAJOR) {
+    const int r = r0 + (lane & 31);
+    const int kc = (ks * 2 + hf) ^ ((r >> 1) & 7);
+    return *(const V8*)(lds_tile + r * 128 + kc * 16);
+  } else {
+    const int i16 = lane & 15, a = i16 >> 2, j4 = i16 & 3;
+    const int nb = r0 + 16 * ((lane >> 4) & 1) + 4 * j4;  // first of the 4 rows this lane addresses
+    const int kb = ks * 16 + 8 * hf;
+    const int phys = (nb >> 3) ^ (4 * a);
+    const char* p0 = lds_tile + (kb + a) * 512 + phys * 16 + ((nb >> 2) & 1) * 8;
+    const V4 lo = Mf<T>::tr(p0);
+    const V4 hi = Mf<T>::tr(p0 + 4 * 512);
+    V8 v;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { v[i] = lo[i]; v[4 + i] = hi[i]; }
+    return v;
+  }
+}
+
+// MODE 0: C (16-bit) = acc + bias;  1: C (fp32) = resid + acc + bias;  2: C (fp32) (+)= acc
+template <class T, bool AK, bool BK, int MODE>
+__global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
+  typedef typename Mf<T>::V8 V8;
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  // buffer b: A tile at smem + 2 b TILE_BYTES, B tile one TILE_BYTES after it
+
+  // workgroups that run at the same time share operand tiles through L2:
+  // walk M fastest inside bands of 8 N tiles
+  // (consecutive workgroup ids are dealt round-robin to the 8 XCDs, each with its
+  // own L2: give every XCD a contiguous run of the tile order instead)
+  const int total = g.tiles_m * g.tiles_n, per_xcd = total / 8;
+  int bid = blockIdx.x;
+  if (bid < per_xcd * 8) bid = (bid % 8) * per_xcd + bid / 8;
+  const int band = 8;
+  const int per_band = band * g.tiles_m;
+  const int b0 = (bid / per_band) * band;
+  const int bw = min(band, g.tiles_n - b0);
+  const int rem = bid % per_band;
+  const int tn = b0 + rem % bw, tm = rem / bw;
+  const int m0 = tm * TM, n0 = tn * TN;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+  // uniform tile bases (bytes) and their advance per k step
+  const char* a_base = (const char*)g.A + (AK ? (long)m0 * g.lda : (long)m0) * 2;
+  const char* b_base = (const char*)g.B + (BK ? (long)n0 * g.ldb : (long)n0) * 2;
+  const long a_step = (AK ? (long)TK : (long)TK * g.lda) * 2;
+  const long b_step = (BK ? (long)TK : (long)TK * g.ldb) * 2;
+  uint32_t a_off[8], b_off[8];
+  tile_offsets<AK>(a_off, g.lda, m0, g.M, wave, lane);
+  tile_offsets<BK>(b_off, g.ldb, n0, g.N, wave, lane);
+
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  const int nk = g.K / TK;
+  issue_tile(a_base, a_off, smem, wave);
+  issue_tile(b_base, b_off, smem + TILE_BYTES, wave);
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
+
+  for (int kt = 0; kt < nk; ++kt) {
+    const int cur = kt & 1;
+    if (kt + 1 < nk) {
+      issue_tile(a_base + (kt + 1) * a_step, a_off, smem + (cur ^ 1) * 2 * TILE_BYTES, wave);
+      issue_tile(b_base + (kt + 1) * b_step, b_off, smem + (cur ^ 1) * 2 * TILE_BYTES + TILE_BYTES, wave);
+    }
+    const char* la = smem + cur * 2 * TILE_BYTES;
+    const char* lb = la + TILE_BYTES;
+    V8 fa[2][4], fb[2][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      fa[0][i] = read_frag<T, AK>(la, wm + i * 32, 0, lane);
+      fb[0][i] = read_frag<T, BK>(lb, wn + i * 32, 0, lane);
+    }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      const int c = ks & 1;
+      if (ks + 1 < 4) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          fa[c ^ 1][i] = read_frag<T, AK>(la, wm + i * 32, ks + 1, lane);
+          fb[c ^ 1][i] = read_frag<T, BK>(lb, wn + i * 32, ks + 1, lane);
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = Mf<T>::run(fa[c][i], fb[c][j], acc[i][j]);
+    }
+    // Instruction order for this k step (the scheduler otherwise serialises each
+    // LDS read with the MFMAs that use it): first fragments, then MFMAs with the
+    // next fragments' LDS reads and the next tile's global loads threaded between.
+    constexpr int RA = AK ? 4 : 8, RB = BK ? 4 : 8;      // LDS reads per k sub-step
+    __builtin_amdgcn_sched_group_barrier(0x100, RA + RB, 0);
+#pragma unroll
+    for (int ks = 0; ks < 3; ++ks) {
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, (RA + RB) / 8, 0);
+        if (ks == 0) __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+      }
+    }
+    __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+  }
+
+  const int col_in = lane & 31, row_in = (lane >> 5) * 4;
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int n = n0 + wn + j * 32 + col_in;
+    if (n >= g.N) continue;
+    float bv = 0.f;
+    if (MODE != 2 && g.bias) bv = load_as_f(g.bias, n, g.bias_dtype);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int m = m0 + wm + i * 32 + 8 * (e >> 2) + row_in + (e & 3);
+        if (m >= g.M) continue;
+        const long ci = (long)m * g.ldc + n;
+        if (MODE == 0) {
+          ((T*)g.C)[ci] = from_f<T>(acc[i][j][e] + bv);
+        } else if (MODE == 1) {
+          ((float*)g.C)[ci] = acc[i][j][e] + bv + g.resid[(long)m * g.ldr + n];
+        } else {
+          float* c = (float*)g.C;
+          c[ci] = g.accumulate ? c[ci] + acc[i][j][e] : acc[i][j][e];
+        }
+      }
+    }
+  }
+}
+
+template <class T, bool AK, bool BK, int MODE>
+ls_status launch(const DmaArgs& g, hipStream_t st) {
+  static bool attr_set = false;
+  const int lds = 4 * TILE_BYTES;
+  if (!attr_set) {
+    LS_CHECK_HIP(hipFuncSetAttribute((const void*)gemm_dma_kernel<T, AK, BK, MODE>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+    attr_set = true;
+  }
+  gemm_dma_kernel<T, AK, BK, MODE><<<g.tiles_m * g.tiles_n, 256, lds, st>>>(g);
+  LS_CHECK_LAUNCH();
+  return LS_OK;
+}
+
+// the combinations a decoder block uses: forward (k-major x k-major, 16-bit or
+// residual output), input gradient (k-major x k-strided, 16-bit output), weight
+// gradient (k-strided x k-strided, fp32 output)
+template <class T>
+ls_status dispatch(const DmaArgs& g, hipStream_t st) {
+  const int mode = g.c_dtype != LS_F32 ? 0 : (g.resid ? 1 : 2);
+  if (mode == 2 && g.bias) return LS_ESTATE;
+  if (mode == 1 && g.accumulate) return LS_ESTATE;
+  if (g.a_kmajor && g.b_kmajor && mode == 0) return launch<T, true, true, 0>(g, st);
+  if (g.a_kmajor && g.b_kmajor && mode == 1) return launch<T, true, true, 1>(g, st);
+  if (g.a_kmajor && g.b_kmajor && mode == 2) return launch<T, true, true, 2>(g, st);
+  if (g.a_kmajor && !g.b_kmajor && mode == 0) return launch<T, true, false, 0>(g, st);
+  if (g.a_kmajor && !g.b_kmajor && mode == 2) return launch<T, true, false, 2>(g, st);
+  if (!g.a_kmajor && !g.b_kmajor && mode == 2) return launch<T, false, false, 2>(g, st);
+  return LS_ESTATE;
+}
+
+}  // namespace
+
+// Returns LS_OK after launching, or LS_ESTATE (without touching the error text)
+// when the shape is outside what this kernel covers.
+ls_status gemm_dma_try(int op_dtype, int M, int N, int K, const void* A, long lda, int a_kmajor,
+                       const void* B, long ldb, int b_kmajor, void* C, long ldc, int c_dtype,
+                       const void* bias, int bias_dtype, const float* resid, long ldr, int accumulate,
+                       hipStream_t st) {
+  if (K % TK != 0 || M < 8 || N < 8) return LS_ESTATE;
+  DmaArgs g{M, N, K, A, lda, a_kmajor, B, ldb, b_kmajor, C, ldc, c_dtype, bias, bias_dtype, resid, ldr,
+            accumulate, (M + TM - 1) / TM, (N + TN - 1) / TN};
+  if (op_dtype == LS_BF16) return dispatch<bf16_t>(g, st);
+  if (op_dtype == LS_F16) return dispatch<f16_t>(g, st);
+  return LS_ESTATE;
+}

@@ -3,6 +3,7 @@
 // from HBM into MFMA operand registers (no LDS: nothing in W is reused inside a
 // workgroup); the few activation rows come through the caches.
 //
+// The activation slab a workgroup needs is staged in LDS in double-buffered chunks.
 // 16x16x32 MFMA with W as the A operand: a lane holds 8 consecutive k of one
 // weight row, four lanes share a row, so one wave-wide load covers 16 rows x
 // 64 contiguous bytes and two successive k steps consume whole 128-byte lines.
@@ -44,9 +45,19 @@ __device__ __forceinline__ void epilogue_store(const SkinnyArgs& g, int m, int n
   else ((T*)g.C)[(long)m * g.ldc + n] = from_f<T>(v);
 }
 
-template <class T, int MT>
+// KC = k extent of one activation chunk staged in LDS (two buffers of
+// [MT*16][KC + 8] elements).  The weight stream is a rolling prefetch: as soon as
+// the MFMAs of k step u have consumed their weight fragment, the same registers
+// receive the load for step u of the next chunk, so every wavefront keeps KC/32
+// 16-byte weight loads per lane in flight at all times.
+template <class T, int MT, int KC>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs g) {
   typedef typename vec8<T>::type V8;
+  constexpr int MP = MT * 16, XSTR = KC + 8;
+  constexpr int NSTEP = KC / 32;                 // MFMA k steps per chunk
+  constexpr int XLD = MP * (KC / 8) / 256;       // 16-byte activation loads per thread per chunk
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+  T* xs = (T*)smem_raw;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int r16 = lane & 15, kc = (lane >> 4) * 8;
   const int n = blockIdx.x * 64 + wave * 16 + r16;
@@ -60,27 +71,55 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs g) {
   for (int t = 0; t < MT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
   const u32x4 zero = {0u, 0u, 0u, 0u};
 
-  constexpr int UN = 4;
-  for (int k0 = k_lo; k0 < k_hi; k0 += 32 * UN) {
-    V8 wf[UN], xf[UN][MT];
+  auto load_w = [&](int k0, int u) -> V8 {
+    const int k = k0 + u * 32 + kc;
+    u32x4 w = zero;
+    if (n_ok && k < k_hi) w = __builtin_nontemporal_load((const u32x4*)(wrow + k));
+    return __builtin_bit_cast(V8, w);
+  };
+  u32x4 xr[XLD];
+  auto load_x = [&](int k0) {
 #pragma unroll
-    for (int u = 0; u < UN; ++u) {
-      const int k = k0 + u * 32 + kc;
-      u32x4 w = zero;
-      if (n_ok && k < k_hi) w = __builtin_nontemporal_load((const u32x4*)(wrow + k));
-      wf[u] = __builtin_bit_cast(V8, w);
+    for (int i = 0; i < XLD; ++i) {
+      const int c = threadIdx.x + i * 256;
+      const int m = c / (KC / 8), k = k0 + (c % (KC / 8)) * 8;
+      u32x4 x = zero;
+      if (m < g.M && k < k_hi) x = *(const u32x4*)(X + (long)m * g.ldx + k);
+      xr[i] = x;
+    }
+  };
+  auto store_x = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < XLD; ++i) {
+      const int c = threadIdx.x + i * 256;
+      const int m = c / (KC / 8), kk = (c % (KC / 8)) * 8;
+      *(u32x4*)(xs + buf * (MP * XSTR) + m * XSTR + kk) = xr[i];
+    }
+  };
+
+  V8 wf[NSTEP];
+#pragma unroll
+  for (int u = 0; u < NSTEP; ++u) wf[u] = load_w(k_lo, u);
+  load_x(k_lo);
+  store_x(0);
+  __syncthreads();
+  int buf = 0;
+  for (int k0 = k_lo; k0 < k_hi; k0 += KC, buf ^= 1) {
+    const bool more = k0 + KC < k_hi;
+    if (more) load_x(k0 + KC);
+    const T* xb = xs + buf * (MP * XSTR);
+#pragma unroll
+    for (int u = 0; u < NSTEP; ++u) {
+      const V8 w = wf[u];
+      if (more) wf[u] = load_w(k0 + KC, u);
 #pragma unroll
       for (int t = 0; t < MT; ++t) {
-        const int m = t * 16 + r16;
-        u32x4 x = zero;
-        if (m < g.M && k < k_hi) x = *(const u32x4*)(X + (long)m * g.ldx + k);
-        xf[u][t] = __builtin_bit_cast(V8, x);
+        const V8 xf = *(const V8*)(xb + (t * 16 + r16) * XSTR + u * 32 + kc);
+        acc[t] = Mfma16<T>::run(w, xf, acc[t]);
       }
     }
-#pragma unroll
-    for (int u = 0; u < UN; ++u)
-#pragma unroll
-      for (int t = 0; t < MT; ++t) acc[t] = Mfma16<T>::run(wf[u], xf[u][t], acc[t]);
+    if (more) store_x(buf ^ 1);   // the other buffer was last read one iteration ago
+    __syncthreads();
   }
   // accumulator: column (lane % 16) = batch row m, rows 4 * (lane / 16) + e = weight row
   const int nb = blockIdx.x * 64 + wave * 16 + (lane >> 4) * 4;
@@ -114,20 +153,33 @@ void plan(int N, int K, int* ksplit, int* kslab) {
   if (ks > 8) ks = 8;
   while (ks > 1 && K / ks < 512) --ks;
   if (ks < 1) ks = 1;
-  int slab = ((K + ks - 1) / ks + 31) / 32 * 32;
+  int slab = ((K + ks - 1) / ks + 511) / 512 * 512;   // whole LDS chunks
   *ksplit = (K + slab - 1) / slab;
   *kslab = slab;
+}
+
+template <class T, int MT, int KC>
+ls_status launch_one(const SkinnyArgs& g, dim3 grid, hipStream_t st) {
+  const size_t lds = 2 * (size_t)MT * 16 * (KC + 8) * sizeof(T);
+  static bool attr_set = false;   // per instantiation; the attribute is idempotent
+  if (lds > 48 * 1024 && !attr_set) {
+    LS_CHECK_HIP(hipFuncSetAttribute((const void*)gemm_skinny_kernel<T, MT, KC>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
+    attr_set = true;
+  }
+  gemm_skinny_kernel<T, MT, KC><<<grid, 256, lds, st>>>(g);
+  LS_CHECK_LAUNCH();
+  return LS_OK;
 }
 
 template <class T>
 ls_status run(SkinnyArgs g, hipStream_t st) {
   dim3 grid((g.N + 63) / 64, g.ksplit);
   const int mt = (g.M + 15) / 16;
-  if (mt <= 1) gemm_skinny_kernel<T, 1><<<grid, 256, 0, st>>>(g);
-  else if (mt <= 2) gemm_skinny_kernel<T, 2><<<grid, 256, 0, st>>>(g);
-  else if (mt <= 4) gemm_skinny_kernel<T, 4><<<grid, 256, 0, st>>>(g);
-  else gemm_skinny_kernel<T, 8><<<grid, 256, 0, st>>>(g);
-  LS_CHECK_LAUNCH();
+  if (mt <= 1) LS_TRY((launch_one<T, 1, 512>(g, grid, st)));
+  else if (mt <= 2) LS_TRY((launch_one<T, 2, 512>(g, grid, st)));
+  else if (mt <= 4) LS_TRY((launch_one<T, 4, 256>(g, grid, st)));
+  else LS_TRY((launch_one<T, 8, 128>(g, grid, st)));
   if (g.ksplit > 1) {
     const long total = (long)g.M * g.N;
     skinny_reduce_kernel<T><<<(unsigned)((total + 255) / 256), 256, 0, st>>>(g);
@@ -157,7 +209,7 @@ ls_status lsk_gemm_skinny(int op_dtype, int M, int N, int K, const void* X, long
   LS_REQUIRE(c_dtype == LS_F32 || c_dtype == op_dtype, "gemm_skinny: output type must be fp32 or the operand type");
   SkinnyArgs g{M, N, K, K, 1, X, ldx, W, ldw, C, ldc, c_dtype, bias, bias_dtype, resid, ldr, scratch};
   if (scratch) plan(N, K, &g.ksplit, &g.kslab);
-  else g.kslab = (K + 31) / 32 * 32;
+  else g.kslab = (K + 511) / 512 * 512;
   hipStream_t st = (hipStream_t)stream;
   return op_dtype == LS_BF16 ? run<bf16_t>(g, st) : run<f16_t>(g, st);
 }

@@ -27,6 +27,8 @@ extern "C" {
 ls_status lsk_attn_fwd_simple(const void*, int, int, int, int, int, void*, float*, void*);
 ls_status lsk_attn_bwd_simple(const void*, const void*, const void*, const float*, int, int, int, int, int,
                               void*, float*, void*);
+ls_status lsk_rope_kv_write(void*, int, int, int, int, const int32_t*, const int32_t*, const float*, void*, void*,
+                            const int32_t*, int, int, void*);
 }
 
 namespace {
@@ -226,13 +228,13 @@ ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const
                       f.h1, mt, f.mean1, f.rstd1, st));
   LS_TRY(linear(s, T, 3 * d, d, f.h1, wptr(s, o.w_qkv), f.qkv, mt, gpt ? pptr(s, o.b_qkv) : nullptr, nullptr,
                 f.scratch, st));
-  if (!gpt) LS_TRY(lsk_rope(f.qkv, mt, T, c.n_heads, c.head_dim, pos, s->rope_table, 1.0f, st));
+  if (!gpt && !kv) LS_TRY(lsk_rope(f.qkv, mt, T, c.n_heads, c.head_dim, pos, s->rope_table, 1.0f, st));
   if (kv) {
     const size_t slab = (size_t)kv->n_pages * c.n_heads * c.page_size * c.head_dim * osz(s);
     void* kp = (char*)kv->k_pool + (size_t)l * slab;
     void* vp = (char*)kv->v_pool + (size_t)l * slab;
-    LS_TRY(lsk_kv_write(f.qkv, mt, T, c.n_heads, c.head_dim, pos, req, kp, vp, kv->block_table,
-                        kv->max_pages_per_req, c.page_size, st));
+    LS_TRY(lsk_rope_kv_write(f.qkv, mt, T, c.n_heads, c.head_dim, pos, req, gpt ? nullptr : s->rope_table, kp, vp,
+                             kv->block_table, kv->max_pages_per_req, c.page_size, st));
     LS_TRY(lsk_attn_paged(mt == LS_F32 ? 0 : 1, f.qkv, mt, T, c.n_heads, c.head_dim, pos, req, kp, vp,
                           kv->block_table, kv->max_pages_per_req, c.page_size, max_ctx, f.o,
                           (long)T * c.n_heads < 2048 ? f.scratch : nullptr, st));

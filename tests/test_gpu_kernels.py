@@ -88,6 +88,41 @@ def test_gemm_skinny_weight_streaming(name, M, N, K, split):
     assert_close(host(out16), ref, otol(name, ref), "skinny gemm 16-bit out")
 
 
+@pytest.mark.parametrize("name", ["f16", "bf16"])
+def test_gemm_full_size_launch_configuration_on_sampled_outputs(name):
+    """The LLaMA-7B-shaped projections at the training micro-batch size (the
+    256 x 256 tile kernel with direct-to-LDS loads and all three operand
+    layouts): sampled rows of each result against float64 dot products."""
+    T, d, F = 4096, 4096, 11008
+    rows = [0, 1, 255, 256, 2047, 3000, 4095]
+    dt = DT[name]
+    X = S.normal_torch(11, "X", (T, d), 1.0, "cuda", dt)
+    dY = S.normal_torch(11, "dY", (T, 2 * F), 1.0, "cuda", dt)
+    W = S.normal_torch(11, "W", (2 * F, d), 0.02, "cuda", dt)
+    R = S.normal_torch(11, "R", (T, 2 * F), 1.0, "cuda")
+    Xh, dYh, Wh = (host(t) for t in (X, dY, W))
+    # forward, 16-bit output
+    Y = torch.empty(T, 2 * F, dtype=dt, device="cuda")
+    Bd.lsk_gemm(X, W, Y, M=T, N=2 * F, K=d)
+    ref = Xh[rows] @ Wh.T
+    assert_close(host(Y[rows]), ref, otol(name, ref), "fwd rows")
+    # forward, fp32 output with residual
+    Yf = torch.empty(T, 2 * F, dtype=torch.float32, device="cuda")
+    Bd.lsk_gemm(X, W, Yf, M=T, N=2 * F, K=d, resid=R)
+    assert_close(host(Yf[rows]), ref + host(R[rows]), 1e-5, "fwd+resid rows")
+    # input gradient dX = dY W
+    dX = torch.empty(T, d, dtype=dt, device="cuda")
+    Bd.lsk_gemm(dY, W, dX, M=T, N=d, K=2 * F, a_kmajor=True, b_kmajor=False, lda=2 * F, ldb=d)
+    ref = dYh[rows] @ Wh
+    assert_close(host(dX[rows]), ref, otol(name, ref), "dX rows")
+    # weight gradient dW = dY^T X, sampled rows of dW (= columns of dY)
+    dW = torch.empty(2 * F, d, dtype=torch.float32, device="cuda")
+    Bd.lsk_gemm(dY, X, dW, M=2 * F, N=d, K=T, a_kmajor=False, b_kmajor=False, lda=2 * F, ldb=d)
+    wrows = [0, 7, 256, 11007, 11008, 22015]
+    ref = dYh[:, wrows].T @ Xh
+    assert_close(host(dW[wrows]), ref, 1e-5, "dW rows")
+
+
 def test_gemm_rejects_unaligned_operands():
     a = torch.zeros(16, 12, dtype=torch.bfloat16, device="cuda")
     w = torch.zeros(16, 12, dtype=torch.bfloat16, device="cuda")
