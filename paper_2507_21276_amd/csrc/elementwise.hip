@@ -60,69 +60,106 @@ __global__ __launch_bounds__(256) void norm_fwd_kernel(int kind, const float* x,
 }
 
 // ---------------------------------------------------------------- norm bwd
-// Each workgroup handles ROWS_PER_WG consecutive rows; per row it computes dx,
-// and it accumulates its share of dgamma/dbeta in registers (thread i owns
-// columns i, i+256, ...), written to partial[wg][2][d]; a second kernel sums
-// the partials in a fixed order (deterministic).
-constexpr int NB_ROWS = 32;
-constexpr int NB_MAXCOL = 32;  // d <= 256 * 32
+// Two kernels.  (1) per-row statistics m1 = mean(dh*gamma), m2 = mean(dh*gamma*xhat),
+// one wavefront per row.  (2) dx and the column partial sums: a thread owns 8
+// consecutive columns (16-byte loads) and walks NB_ROWS rows, so a workgroup
+// covers a 2048-column x NB_ROWS-row patch; its dgamma/dbeta partials go to
+// partial[row chunk][2][d] and a last kernel sums them in a fixed order.
+constexpr int NB_ROWS = 16;
 
-__global__ __launch_bounds__(256) void norm_bwd_kernel(int kind, const void* dh, int dhdt,
-                                                       const float* x, const float* mean,
-                                                       const float* rstd, const void* gamma,
-                                                       int pdt, int T, int d, const float* dres,
-                                                       float* dx, void* dx16, int dx16dt,
-                                                       float* partial) {
-  __shared__ float red[16];
-  float dg[NB_MAXCOL], db[NB_MAXCOL];
+template <class TD> struct Ld8 {
+  static __device__ __forceinline__ void load(const TD* p, float (&v)[8]) {
+    typedef typename vec8<TD>::type V8;
+    const V8 t = *(const V8*)p;
 #pragma unroll
-  for (int c = 0; c < NB_MAXCOL; ++c) dg[c] = db[c] = 0.f;
-  const int r0 = blockIdx.x * NB_ROWS;
-  for (int rr = 0; rr < NB_ROWS; ++rr) {
-    const int row = r0 + rr;
-    if (row >= T) break;
-    const size_t off = (size_t)row * d;
+    for (int i = 0; i < 8; ++i) v[i] = to_f(t[i]);
+  }
+  static __device__ __forceinline__ void store(TD* p, const float (&v)[8]) {
+    typedef typename vec8<TD>::type V8;
+    V8 t;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) t[i] = from_f<TD>(v[i]);
+    *(V8*)p = t;
+  }
+};
+template <> struct Ld8<float> {
+  static __device__ __forceinline__ void load(const float* p, float (&v)[8]) {
+    const f32x4 a = *(const f32x4*)p, b = *(const f32x4*)(p + 4);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { v[i] = a[i]; v[4 + i] = b[i]; }
+  }
+  static __device__ __forceinline__ void store(float* p, const float (&v)[8]) {
+    *(f32x4*)p = f32x4{v[0], v[1], v[2], v[3]};
+    *(f32x4*)(p + 4) = f32x4{v[4], v[5], v[6], v[7]};
+  }
+};
+
+template <class TD>
+__global__ __launch_bounds__(256) void norm_bwd_stats_kernel(int kind, const TD* dh, const float* x,
+                                                             const float* mean, const float* rstd,
+                                                             const void* gamma, int pdt, int T, int d,
+                                                             float* stats) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= T) return;
+  const size_t off = (size_t)row * d;
+  const float mu = kind == 0 ? mean[row] : 0.f, r = rstd[row];
+  float s1 = 0.f, s2 = 0.f;
+  for (int c = lane * 8; c < d; c += 512) {
+    float g[8], xv[8];
+    Ld8<TD>::load(dh + off + c, g);
+    Ld8<float>::load(x + off + c, xv);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float dxh = g[i] * load_as_f(gamma, c + i, pdt);
+      s1 += dxh;
+      s2 += dxh * (xv[i] - mu) * r;
+    }
+  }
+  s1 = wave_sum(s1);
+  s2 = wave_sum(s2);
+  if (lane == 0) {
+    stats[2 * row] = s1 / d;
+    stats[2 * row + 1] = s2 / d;
+  }
+}
+
+template <class TD>
+__global__ __launch_bounds__(256) void norm_bwd_apply_kernel(int kind, const TD* dh, const float* x,
+                                                             const float* mean, const float* rstd,
+                                                             const void* gamma, int pdt, int T, int d,
+                                                             const float* stats, const float* dres,
+                                                             float* dx, TD* dx16, float* partial) {
+  const int c = (blockIdx.x * 256 + threadIdx.x) * 8;
+  if (c >= d) return;
+  float gam[8], dg[8], db[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    gam[i] = load_as_f(gamma, c + i, pdt);
+    dg[i] = db[i] = 0.f;
+  }
+  const int r0 = blockIdx.y * NB_ROWS, r1 = min(T, r0 + NB_ROWS);
+  for (int row = r0; row < r1; ++row) {
+    const size_t off = (size_t)row * d + c;
     const float mu = kind == 0 ? mean[row] : 0.f, r = rstd[row];
-    float s1 = 0.f, s2 = 0.f;
+    const float m1 = kind == 0 ? stats[2 * row] : 0.f, m2 = stats[2 * row + 1];
+    float g[8], xv[8], o[8];
+    Ld8<TD>::load(dh + off, g);
+    Ld8<float>::load(x + off, xv);
+    if (dres) Ld8<float>::load(dres + off, o);
 #pragma unroll
-    for (int c = 0; c < NB_MAXCOL; ++c) {
-      const int i = threadIdx.x + c * 256;
-      if (i < d) {
-        const float g = load_as_f(dh, off + i, dhdt);
-        const float xh = (x[off + i] - mu) * r;
-        const float dxh = g * load_as_f(gamma, i, pdt);
-        s1 += dxh;
-        s2 += dxh * xh;
-        dg[c] += g * xh;
-        db[c] += g;
-      }
+    for (int i = 0; i < 8; ++i) {
+      const float xh = (xv[i] - mu) * r;
+      const float v = r * (g[i] * gam[i] - m1 - xh * m2);
+      o[i] = dres ? o[i] + v : v;
+      dg[i] += g[i] * xh;
+      db[i] += g[i];
     }
-    const float m2 = block_sum(s2, red) / d;
-    float m1 = 0.f;
-    if (kind == 0) m1 = block_sum(s1, red) / d;
-#pragma unroll
-    for (int c = 0; c < NB_MAXCOL; ++c) {
-      const int i = threadIdx.x + c * 256;
-      if (i < d) {
-        const float g = load_as_f(dh, off + i, dhdt);
-        const float xh = (x[off + i] - mu) * r;
-        const float dxh = g * load_as_f(gamma, i, pdt);
-        float v = r * (dxh - m1 - xh * m2);
-        if (dres) v += dres[off + i];
-        dx[off + i] = v;
-        if (dx16) store_from_f(dx16, off + i, dx16dt, v);
-      }
-    }
+    Ld8<float>::store(dx + off, o);
+    if (dx16) Ld8<TD>::store(dx16 + off, o);
   }
-  float* p = partial + (size_t)blockIdx.x * 2 * d;
-#pragma unroll
-  for (int c = 0; c < NB_MAXCOL; ++c) {
-    const int i = threadIdx.x + c * 256;
-    if (i < d) {
-      p[i] = dg[c];
-      p[d + i] = db[c];
-    }
-  }
+  float* p = partial + (size_t)blockIdx.y * 2 * d + c;
+  Ld8<float>::store(p, dg);
+  Ld8<float>::store(p + d, db);
 }
 
 __global__ void norm_bwd_finish_kernel(const float* partial, int nwg, int d, float* dgamma,
@@ -136,6 +173,17 @@ __global__ void norm_bwd_finish_kernel(const float* partial, int nwg, int d, flo
   }
   if (dgamma) dgamma[i] = accumulate ? dgamma[i] + g : g;
   if (dbeta) dbeta[i] = accumulate ? dbeta[i] + b : b;
+}
+
+template <class TD>
+void launch_norm_bwd(int kind, const void* dh, const float* x, const float* mean, const float* rstd,
+                     const void* gamma, int pdt, int T, int d, const float* dres, float* dx, void* dx16,
+                     float* partial, hipStream_t st) {
+  const int nchunk = (T + NB_ROWS - 1) / NB_ROWS;
+  float* stats = partial + (size_t)nchunk * 2 * d;
+  norm_bwd_stats_kernel<TD><<<(T + 3) / 4, 256, 0, st>>>(kind, (const TD*)dh, x, mean, rstd, gamma, pdt, T, d, stats);
+  norm_bwd_apply_kernel<TD><<<dim3((d + 2047) / 2048, nchunk), 256, 0, st>>>(
+      kind, (const TD*)dh, x, mean, rstd, gamma, pdt, T, d, stats, dres, dx, (TD*)dx16, partial);
 }
 
 // -------------------------------------------------------------------- rope
@@ -184,26 +232,39 @@ __global__ void gelu_bwd_kernel(const void* dg, const void* u, void* du, int dt,
        i += (size_t)gridDim.x * blockDim.x)
     store_from_f(du, i, dt, load_as_f(dg, i, dt) * gelu_grad_f(load_as_f(u, i, dt), kind));
 }
-__global__ void swiglu_fwd_kernel(const void* gu, void* a, int dt, size_t T, int F) {
-  const size_t n = T * F;
-  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n;
+// SwiGLU: a thread owns 8 consecutive hidden units (16-byte loads of gate, up)
+template <class TD>
+__global__ void swiglu_fwd_kernel(const TD* gu, TD* a, size_t T, int F) {
+  const size_t n8 = T * (size_t)(F / 8);
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n8;
        i += (size_t)gridDim.x * blockDim.x) {
-    const size_t t = i / F, f = i % F;
-    const float gt = load_as_f(gu, t * 2 * F + f, dt), up = load_as_f(gu, t * 2 * F + F + f, dt);
-    const float sg = 1.f / (1.f + expf(-gt));
-    store_from_f(a, i, dt, gt * sg * up);
+    const size_t t = i / (F / 8), f = (i % (F / 8)) * 8;
+    float gt[8], up[8], o[8];
+    Ld8<TD>::load(gu + t * 2 * F + f, gt);
+    Ld8<TD>::load(gu + t * 2 * F + F + f, up);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) o[k] = gt[k] / (1.f + __expf(-gt[k])) * up[k];
+    Ld8<TD>::store(a + t * F + f, o);
   }
 }
-__global__ void swiglu_bwd_kernel(const void* da, const void* gu, void* dgu, int dt, size_t T, int F) {
-  const size_t n = T * F;
-  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n;
+template <class TD>
+__global__ void swiglu_bwd_kernel(const TD* da, const TD* gu, TD* dgu, size_t T, int F) {
+  const size_t n8 = T * (size_t)(F / 8);
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n8;
        i += (size_t)gridDim.x * blockDim.x) {
-    const size_t t = i / F, f = i % F;
-    const float gt = load_as_f(gu, t * 2 * F + f, dt), up = load_as_f(gu, t * 2 * F + F + f, dt);
-    const float g = load_as_f(da, i, dt);
-    const float sg = 1.f / (1.f + expf(-gt));
-    store_from_f(dgu, t * 2 * F + f, dt, g * up * sg * (1.f + gt * (1.f - sg)));
-    store_from_f(dgu, t * 2 * F + F + f, dt, g * gt * sg);
+    const size_t t = i / (F / 8), f = (i % (F / 8)) * 8;
+    float gt[8], up[8], g[8], og[8], ou[8];
+    Ld8<TD>::load(gu + t * 2 * F + f, gt);
+    Ld8<TD>::load(gu + t * 2 * F + F + f, up);
+    Ld8<TD>::load(da + t * F + f, g);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+      const float sg = 1.f / (1.f + __expf(-gt[k]));
+      og[k] = g[k] * up[k] * sg * (1.f + gt[k] * (1.f - sg));
+      ou[k] = g[k] * gt[k] * sg;
+    }
+    Ld8<TD>::store(dgu + t * 2 * F + f, og);
+    Ld8<TD>::store(dgu + t * 2 * F + F + f, ou);
   }
 }
 
@@ -256,7 +317,7 @@ ls_status lsk_norm_fwd(int kind, const float* x, int T, int d, const void* gamma
 }
 
 size_t lsk_norm_bwd_partial_floats(int T, int d) {
-  return (size_t)((T + NB_ROWS - 1) / NB_ROWS) * 2 * d;
+  return (size_t)((T + NB_ROWS - 1) / NB_ROWS) * 2 * d + 2 * (size_t)T;
 }
 
 ls_status lsk_norm_bwd(int kind, const void* dh, int dhdt, const float* x, const float* mean,
@@ -265,14 +326,17 @@ ls_status lsk_norm_bwd(int kind, const void* dh, int dhdt, const float* x, const
                        float* dbeta, int accumulate, float* partial, void* stream) {
   LS_REQUIRE(dh && x && rstd && gamma && dx && partial && T > 0 && d > 0, "norm_bwd: bad argument");
   LS_REQUIRE(kind == 1 || mean, "norm_bwd: LayerNorm needs the saved mean");
-  LS_REQUIRE(d <= 256 * NB_MAXCOL, "norm_bwd: d_model %d exceeds %d", d, 256 * NB_MAXCOL);
-  const int nwg = (T + NB_ROWS - 1) / NB_ROWS;
-  norm_bwd_kernel<<<nwg, 256, 0, (hipStream_t)stream>>>(kind, dh, dhdt, x, mean, rstd, gamma, pdt, T, d,
-                                                        dres, dx, dx16, dx16dt, partial);
+  LS_REQUIRE(d % 8 == 0, "norm_bwd: d_model must be a multiple of 8");
+  LS_REQUIRE(!dx16 || dx16dt == dhdt, "norm_bwd: the 16-bit copy of dx must have the type of dh");
+  hipStream_t st = (hipStream_t)stream;
+  if (dhdt == LS_F32) launch_norm_bwd<float>(kind, dh, x, mean, rstd, gamma, pdt, T, d, dres, dx, dx16, partial, st);
+  else if (dhdt == LS_BF16) launch_norm_bwd<bf16_t>(kind, dh, x, mean, rstd, gamma, pdt, T, d, dres, dx, dx16, partial, st);
+  else launch_norm_bwd<f16_t>(kind, dh, x, mean, rstd, gamma, pdt, T, d, dres, dx, dx16, partial, st);
   LS_CHECK_LAUNCH();
   if (dgamma || dbeta) {
-    norm_bwd_finish_kernel<<<(d + 255) / 256, 256, 0, (hipStream_t)stream>>>(
-        partial, nwg, d, dgamma, kind == 0 ? dbeta : nullptr, accumulate);
+    const int nchunk = (T + NB_ROWS - 1) / NB_ROWS;
+    norm_bwd_finish_kernel<<<(d + 255) / 256, 256, 0, st>>>(partial, nchunk, d, dgamma,
+                                                            kind == 0 ? dbeta : nullptr, accumulate);
     LS_CHECK_LAUNCH();
   }
   return LS_OK;
@@ -301,13 +365,23 @@ ls_status lsk_gelu_bwd(const void* dg, const void* u, void* du, int dt, size_t n
 }
 ls_status lsk_swiglu_fwd(const void* gu, void* a, int dt, int T, int F, void* stream) {
   LS_REQUIRE(gu && a && T > 0 && F > 0, "swiglu_fwd: bad argument");
-  swiglu_fwd_kernel<<<grid_for((size_t)T * F), 256, 0, (hipStream_t)stream>>>(gu, a, dt, T, F);
+  LS_REQUIRE(F % 8 == 0, "swiglu_fwd: d_ff must be a multiple of 8");
+  const int gr = grid_for((size_t)T * F / 8);
+  hipStream_t st = (hipStream_t)stream;
+  if (dt == LS_F32) swiglu_fwd_kernel<float><<<gr, 256, 0, st>>>((const float*)gu, (float*)a, T, F);
+  else if (dt == LS_BF16) swiglu_fwd_kernel<bf16_t><<<gr, 256, 0, st>>>((const bf16_t*)gu, (bf16_t*)a, T, F);
+  else swiglu_fwd_kernel<f16_t><<<gr, 256, 0, st>>>((const f16_t*)gu, (f16_t*)a, T, F);
   LS_CHECK_LAUNCH();
   return LS_OK;
 }
 ls_status lsk_swiglu_bwd(const void* da, const void* gu, void* dgu, int dt, int T, int F, void* stream) {
   LS_REQUIRE(da && gu && dgu && T > 0 && F > 0, "swiglu_bwd: bad argument");
-  swiglu_bwd_kernel<<<grid_for((size_t)T * F), 256, 0, (hipStream_t)stream>>>(da, gu, dgu, dt, T, F);
+  LS_REQUIRE(F % 8 == 0, "swiglu_bwd: d_ff must be a multiple of 8");
+  const int gr = grid_for((size_t)T * F / 8);
+  hipStream_t st = (hipStream_t)stream;
+  if (dt == LS_F32) swiglu_bwd_kernel<float><<<gr, 256, 0, st>>>((const float*)da, (const float*)gu, (float*)dgu, T, F);
+  else if (dt == LS_BF16) swiglu_bwd_kernel<bf16_t><<<gr, 256, 0, st>>>((const bf16_t*)da, (const bf16_t*)gu, (bf16_t*)dgu, T, F);
+  else swiglu_bwd_kernel<f16_t><<<gr, 256, 0, st>>>((const f16_t*)da, (const f16_t*)gu, (f16_t*)dgu, T, F);
   LS_CHECK_LAUNCH();
   return LS_OK;
 }
