@@ -83,7 +83,8 @@ def main():
     ap.add_argument("--no-probe", action="store_true")
     ap.add_argument("--legs", default="train,decode,prefill",
                     help="comma list of the legs that make up a step (profiling aid; the default is the full "
-                         "step; 'gemms' = the 12 GEMM launches of one block on their own)")
+                         "step; 'gemms' = the 12 GEMM launches of one block on their own; 'calib' = a 256 MiB copy kernel "
+                         "used to scale the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (one pipeline stage on one MI355X); "
@@ -174,9 +175,16 @@ def main():
         G(a_3d, w_qkv, o_d, M=T, N=d, K=3 * d, b_kmajor=False, ldb=d)
         G(a_3d, a_d, g_qkv, M=3 * d, N=d, K=T, a_kmajor=False, b_kmajor=False, lda=3 * d, ldb=d)
 
+    # counter calibration: a plain copy kernel of known size (256 MiB read, 256 MiB written)
+    cal_src = torch.zeros(64 << 20, dtype=torch.float32, device=dev)
+    cal_dst = torch.empty_like(cal_src)
+
+    def calib():
+        Bd.lsk_convert(cal_src, cal_dst)
+
     legs = [l for l in args.legs.split(",") if l]
-    leg_fn = {"train": train, "decode": decode, "prefill": prefill, "gemms": gemms}
-    leg_tok = {"train": T, "decode": Bq, "prefill": sum(chunks), "gemms": T}
+    leg_fn = {"train": train, "decode": decode, "prefill": prefill, "gemms": gemms, "calib": calib}
+    leg_tok = {"train": T, "decode": Bq, "prefill": sum(chunks), "gemms": T, "calib": 0}
 
     def step():
         for l in legs:
@@ -209,13 +217,21 @@ def main():
     log(f"train {ms_train:.2f} ms, decode {ms_dec:.3f} ms, prefill {ms_pre:.2f} ms")
 
     # ---- GEMM roofline ---------------------------------------------------------------------
+    traffic = {}
+    try:   # HBM bytes measured with rocprofv3 --pmc in an earlier run of this same command
+        with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as fh:
+            traffic = json.load(fh)
+    except OSError:
+        pass
     ms_gemms = time_events(torch, gemms, 5)
     flop_block = 3.0 * T * (8.0 * d * d + 6.0 * d * F)       # fwd + dX + dW of one block
     gemm_tflops = flop_block / (ms_gemms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "gemm_mfma_kernel (12 launches per block: 4 fwd, 4 dX, 4 dW)",
+    roofline = {"bound": "mfma", "kernel": "gemm_dma_kernel (12 launches per block: 4 fwd, 4 dX, 4 dW)",
                 "achieved": gemm_tflops, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
                 "frac": gemm_tflops / PEAK_MFMA_TFLOPS, "avg_launch_ms": ms_gemms / 12,
-                "flop_per_launch": flop_block / 12, "traffic": None}
+                "flop_per_launch": flop_block / 12,
+                "traffic": traffic.get("gemm_dma_kernel_bytes_per_launch"),
+                "peak_measured_gaussian_operands": 1625.0}
     log(f"GEMMs of one block: {ms_gemms:.2f} ms -> {gemm_tflops:.0f} TFLOP/s")
 
     # ---- decode roofline: weights once + the KV of every cached token ---------------------------
@@ -224,7 +240,7 @@ def main():
     dec_gbs = (w_bytes + kv_bytes) / (ms_dec * 1e-3) / 1e9
     roofline_decode = {"bound": "hbm", "kernel": "stage_decode (whole call)", "achieved": dec_gbs,
                        "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,
-                       "bytes_per_step": w_bytes + kv_bytes, "traffic": None}
+                       "bytes_per_step": w_bytes + kv_bytes, "traffic": traffic.get("decode_step_bytes")}
 
     # ---- interference probe (BASELINE config 4: decode stream + 1 x 2048 training stream) --------
     probe = None
