@@ -58,7 +58,7 @@ def cpu_baseline(cfg, S):
         cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
     except Exception:
         cores = os.cpu_count() or 1
-    nl, L = 1, 384
+    nl, L = 2, 2048
     c = S.scaled(cfg, n_layers=nl)
     flat = S.make_params(c).astype(np.float64)
     X = S.make_activations(c, "X", (1, L, c["d_model"])).astype(np.float64)

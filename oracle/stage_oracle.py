@@ -338,11 +338,86 @@ def stage_prefill(cfg, flat_params, chunks, cache):
     return outs
 
 
+def block_decode(cfg, p, X, cache_l):
+    """One block on one new token per request.  The row-wise steps (norms,
+    linear maps, activation) are applied to all B rows at once - they do not mix
+    rows - and attention runs per request over its own cache, which receives
+    the new K (after RoPE) and V row first."""
+    d, h, dh, F = cfg["d_model"], cfg["n_heads"], cfg["head_dim"], cfg["d_ff"]
+    gpt = cfg["block"] == "gpt"
+    B = X.shape[0]
+    h1, _, _ = _norm1(cfg, p, X)
+    qkv = h1 @ p["W_qkv"].T
+    if gpt:
+        qkv = qkv + p["b_qkv"]
+    o = np.empty((B, d), X.dtype)
+    for b in range(B):
+        K, V = cache_l[b]
+        pos = np.array([K.shape[0]])
+        q = qkv[b:b + 1, :d].reshape(1, h, dh)
+        k = qkv[b:b + 1, d:2 * d].reshape(1, h, dh)
+        v = qkv[b:b + 1, 2 * d:].reshape(1, h, dh)
+        if not gpt:
+            q = rope(q, pos, cfg["rope_theta"])
+            k = rope(k, pos, cfg["rope_theta"])
+        K = np.concatenate([K, k], axis=0)
+        V = np.concatenate([V, v], axis=0)
+        cache_l[b] = [K, V]
+        ob, _ = attention(q, K, V, K.shape[0] - 1)
+        o[b] = ob.reshape(d)
+    x1 = X + o @ p["W_o"].T
+    if gpt:
+        x1 = x1 + p["b_o"]
+    h2, _, _ = _norm2(cfg, p, x1)
+    if gpt:
+        a = gelu(h2 @ p["W_1"].T + p["b_1"], cfg["act"])
+        return x1 + a @ p["W_2"].T + p["b_2"]
+    gu = h2 @ p["W_gu"].T
+    return x1 + (silu(gu[:, :F]) * gu[:, F:]) @ p["W_d"].T
+
+
 def stage_decode(cfg, flat_params, X, cache):
     """One new token per request: X[B, d] -> Y[B, d]; request b's token sits at
     position ctx_b = len(cache) and attends over ctx_b + 1 keys."""
-    ys = stage_prefill(cfg, flat_params, [X[b:b + 1] for b in range(X.shape[0])], cache)
-    return np.concatenate(ys, axis=0)
+    x = X
+    for l, p in enumerate(split_params(cfg, flat_params)):
+        x = block_decode(cfg, p, x, cache[l])
+    return x
+
+
+def block_forward_rows(cfg, p, x, rows):
+    """Rows `rows` of block_forward(cfg, p, x, arange(L))[0] for one sequence
+    from position 0, without forming the other output rows: K and V are needed
+    for every position, the query side only for the sampled ones."""
+    d, h, dh, F = cfg["d_model"], cfg["n_heads"], cfg["head_dim"], cfg["d_ff"]
+    gpt = cfg["block"] == "gpt"
+    L = x.shape[0]
+    rows = np.asarray(rows)
+    h1, _, _ = _norm1(cfg, p, x)
+    kv = h1 @ p["W_qkv"][d:].T
+    q = h1[rows] @ p["W_qkv"][:d].T
+    if gpt:
+        kv = kv + p["b_qkv"][d:]
+        q = q + p["b_qkv"][:d]
+    k = kv[:, :d].reshape(L, h, dh)
+    v = kv[:, d:].reshape(L, h, dh)
+    q = q.reshape(len(rows), h, dh)
+    if not gpt:
+        k = rope(k, np.arange(L), cfg["rope_theta"])
+        q = rope(q, rows, cfg["rope_theta"])
+    o = np.empty((len(rows), d), x.dtype)
+    for i, t in enumerate(rows):
+        ob, _ = attention(q[i:i + 1], k[: t + 1], v[: t + 1], int(t))
+        o[i] = ob.reshape(d)
+    x1 = x[rows] + o @ p["W_o"].T
+    if gpt:
+        x1 = x1 + p["b_o"]
+    h2, _, _ = _norm2(cfg, p, x1)
+    if gpt:
+        a = gelu(h2 @ p["W_1"].T + p["b_1"], cfg["act"])
+        return x1 + a @ p["W_2"].T + p["b_2"]
+    gu = h2 @ p["W_gu"].T
+    return x1 + (silu(gu[:, :F]) * gu[:, F:]) @ p["W_d"].T
 
 
 def stage_train_fwd(cfg, flat_params, X):

@@ -419,3 +419,16 @@ def test_matmul_step_against_compensated_loops():
     a, w = rng.normal(0, 1, (5, 37)), rng.normal(0, 1, (4, 37))
     ref = [[math.fsum(a[i, k] * w[j, k] for k in range(37)) for j in range(4)] for i in range(5)]
     np.testing.assert_allclose(a @ w.T, np.array(ref), rtol=0, atol=1e-13)
+
+
+@pytest.mark.parametrize("block,act", BLOCKS)
+def test_sampled_rows_equal_the_full_block(block, act):
+    # block_forward_rows is what the full-size GPU tests compare against
+    cfg = small_cfg(block, act)
+    rng = np.random.default_rng(24)
+    flat = rand_params(cfg)
+    p = O.split_params(cfg, flat)[1]
+    x = rng.normal(0, 1, (11, cfg["d_model"]))
+    full, _, _, _ = O.block_forward(cfg, p, x, np.arange(11))
+    rows = [0, 3, 10]
+    np.testing.assert_allclose(O.block_forward_rows(cfg, p, x, rows), full[rows], rtol=0, atol=1e-12)
