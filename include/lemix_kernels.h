@@ -108,7 +108,8 @@ ls_status lsk_colsum(const void* x, int dtype, int T, int N, long ld, float* out
 ls_status lsk_attn_fwd(int impl, const void* qkv, int dtype, int B, int L, int n_heads,
                        int head_dim, void* o, float* lse, void* stream);
 /* Backward of the above: dqkv[B*L, 3d] from dO[B*L, d], the forward's qkv, o
- * and lse.  dvec: fp32 scratch [B*L, n_heads]. */
+ * and lse.  dvec: fp32 scratch of B*L*n_heads + 1 floats (rowsum(dO*O) per
+ * (row, head), then max|dO|). */
 ls_status lsk_attn_bwd(int impl, const void* qkv, const void* o, const void* dO,
                        const float* lse, int dtype, int B, int L, int n_heads, int head_dim,
                        void* dqkv, float* dvec, void* stream);
@@ -132,6 +133,30 @@ ls_status lsk_attn_paged(int impl, const void* qkv, int dtype, int T, int n_head
  * over several workgroups; `scratch` then holds the per-split partial results
  * (this many floats; null = never split). */
 size_t lsk_attn_paged_scratch_floats(int T, int n_heads, int head_dim, int max_ctx, int page_size);
+
+/*
+ * Backward-pass gradient scaling.  stage_train_bwd runs the whole backward on
+ * dY * 2^e so that 16-bit gradient operands stay in the fp16 normal range (the
+ * matrix cores flush fp16 subnormal inputs), and multiplies every fp32 result by
+ * 2^-e, which is exact.  lsk_grad_scale writes out3 = {2^e, 2^-e, max|x|} with
+ * max|x| * 2^e in (8, 16].  The *_scaled variants take a device scalar that
+ * multiplies the accumulator / sum / element before it is added or stored
+ * (null = 1); the unscaled entry points above are these with null.
+ */
+ls_status lsk_grad_scale(const void* x, int dtype, size_t n, float* out3, void* stream);
+ls_status lsk_gemm_scaled(int op_dtype, int M, int N, int K, const void* A, long lda, int a_kmajor,
+                          const void* B, long ldb, int b_kmajor, void* C, long ldc, int c_dtype,
+                          const void* bias, int bias_dtype, const float* resid, long ldr,
+                          int accumulate, const float* alpha_dev, void* stream);
+ls_status lsk_convert_scaled(const void* src, int src_dtype, void* dst, int dst_dtype, size_t n,
+                             const float* scale_dev, void* stream);
+ls_status lsk_norm_bwd_scaled(int kind, const void* dh, int dh_dtype, const float* x,
+                              const float* mean, const float* rstd, const void* gamma, int p_dtype,
+                              int T, int d, const float* dres, float* dx, void* dx16,
+                              int dx16_dtype, float* dgamma, float* dbeta, int accumulate,
+                              float* partial, const float* alpha_dev, void* stream);
+ls_status lsk_colsum_scaled(const void* x, int dtype, int T, int N, long ld, float* out,
+                            int accumulate, float* partial, const float* alpha_dev, void* stream);
 
 #ifdef __cplusplus
 }

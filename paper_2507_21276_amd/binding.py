@@ -68,6 +68,12 @@ SIGNATURES = {
     "ls_last_error": (C.c_char_p, []),
     "lsk_gemm": (_I, [_I, _I, _I, _I, _VP, _L, _I, _VP, _L, _I, _VP, _L, _I, _VP, _I, _VP, _L, _I, _VP]),
     "lsk_convert": (_I, [_VP, _I, _VP, _I, _SZ, _VP]),
+    "lsk_grad_scale": (_I, [_VP, _I, _SZ, _VP, _VP]),
+    "lsk_gemm_scaled": (_I, [_I, _I, _I, _I, _VP, _L, _I, _VP, _L, _I, _VP, _L, _I, _VP, _I, _VP, _L, _I, _VP, _VP]),
+    "lsk_convert_scaled": (_I, [_VP, _I, _VP, _I, _SZ, _VP, _VP]),
+    "lsk_norm_bwd_scaled": (_I, [_I, _VP, _I, _VP, _VP, _VP, _VP, _I, _I, _I, _VP, _VP, _VP, _I, _VP, _VP, _I,
+                                 _VP, _VP, _VP]),
+    "lsk_colsum_scaled": (_I, [_VP, _I, _I, _I, _L, _VP, _I, _VP, _VP, _VP]),
     "lsk_norm_fwd": (_I, [_I, _VP, _I, _I, _VP, _VP, _I, _F, _VP, _I, _VP, _VP, _VP]),
     "lsk_norm_bwd_partial_floats": (_SZ, [_I, _I]),
     "lsk_norm_bwd": (_I, [_I, _VP, _I, _VP, _VP, _VP, _VP, _I, _I, _I, _VP, _VP, _VP, _I, _VP, _VP, _I,
@@ -254,6 +260,10 @@ def lsk_gemm_skinny(X, W, C_out, *, bias=None, resid=None, split=True, stream=No
                                  _p(scratch), _stream(stream)))
 
 
+def lsk_grad_scale(x, out3, stream=None):
+    _check(lib().lsk_grad_scale(_p(x), CODE_OF_TORCH[x.dtype], x.numel(), _p(out3), _stream(stream)))
+
+
 def lsk_convert(src, dst, stream=None):
     _check(lib().lsk_convert(_p(src), CODE_OF_TORCH[src.dtype], _p(dst), CODE_OF_TORCH[dst.dtype],
                              src.numel(), _stream(stream)))
@@ -311,7 +321,7 @@ def lsk_attn_fwd(impl, qkv, B, L, n_heads, head_dim, o, lse, stream=None):
 
 
 def lsk_attn_bwd(impl, qkv, o, dO, lse, B, L, n_heads, head_dim, dqkv, stream=None):
-    dvec = torch.empty(B * L * n_heads, dtype=torch.float32, device=qkv.device)
+    dvec = torch.empty(B * L * n_heads + 1, dtype=torch.float32, device=qkv.device)
     _check(lib().lsk_attn_bwd(impl, _p(qkv), _p(o), _p(dO), _p(lse), CODE_OF_TORCH[qkv.dtype], B, L,
                               n_heads, head_dim, _p(dqkv), _p(dvec), _stream(stream)))
 

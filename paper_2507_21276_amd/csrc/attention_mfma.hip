@@ -293,6 +293,28 @@ ls_status launch_fwd(const void* qkv, int B, int L, int h, void* o, float* lse, 
 // into LDS.  D = rowsum(dO * O) comes from a separate bandwidth-bound kernel.
 // ---------------------------------------------------------------------------------
 
+// multiply the eight 16-bit elements of a raw 16-byte chunk by a power of two (exact)
+template <class T>
+__device__ __forceinline__ u32x4 scale_chunk(u32x4 raw, float sc) {
+  typedef typename Mma<T>::V8 V8;
+  V8 v = __builtin_bit_cast(V8, raw);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) v[i] = from_f<T>(to_f(v[i]) * sc);
+  return __builtin_bit_cast(u32x4, v);
+}
+
+// Power-of-two factor that brings the largest |dO| element into (16, 32].  dS = P (dP - D)
+// is linear in dO and carries the softmax probabilities (~1/context), so without it
+// dS sits in the fp16 subnormal range for small upstream gradients.  dP <= 32 * sum|v|
+// stays far below the fp16 maximum.
+__device__ __forceinline__ float do_scale(const float* amax_ptr) {
+  const float a = *amax_ptr;
+  if (!(a > 0.f) || a > 3.0e38f) return 1.f;
+  float e = floorf(__builtin_amdgcn_logf(32.f / a));   // log2
+  e = fminf(fmaxf(e, -14.f), 24.f);
+  return __builtin_amdgcn_exp2f(e);
+}
+
 // natural tile [ROWS][DH] -> LDS row stride DH+8
 template <class T, int ROWS, int DH>
 struct NatStage {
@@ -307,6 +329,10 @@ struct NatStage {
       if (c < ROWS * DH / 8 && row0 + r < nrows) z = *(const u32x4*)(base + (long)(row0 + r) * ld + col);
       v[i] = z;
     }
+  }
+  __device__ __forceinline__ void scale(float sc) {
+#pragma unroll
+    for (int i = 0; i < N; ++i) v[i] = scale_chunk<T>(v[i], sc);
   }
   __device__ __forceinline__ void store(T* lds) const {
 #pragma unroll
@@ -336,6 +362,10 @@ struct TrStage {
         v[j] = z;
       }
     }
+  }
+  __device__ __forceinline__ void scale(float sc) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = scale_chunk<T>(v[j], sc);
   }
   __device__ __forceinline__ void store(T* lds, int tid0) const {
     const int t = (int)threadIdx.x - tid0;
@@ -378,6 +408,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const T* __restrict__
   const int wq0 = qtile * BQ + wave * 32;
   const int q = wq0 + col;
   const float scale_log2 = scale * 1.4426950408889634f;
+  const float gsc = do_scale(dvec + (long)gridDim.y * L);   // one float after the [B*L, h] array
 
   V8 qf[KS], dof[KS];
 #pragma unroll
@@ -388,12 +419,12 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const T* __restrict__
       z1 = *(const u32x4*)(dob + (long)q * d + s * 16 + hf * 8);
     }
     qf[s] = __builtin_bit_cast(V8, z0);
-    dof[s] = __builtin_bit_cast(V8, z1);
+    dof[s] = __builtin_bit_cast(V8, scale_chunk<T>(z1, gsc));
   }
   float lse2 = INFINITY, dq_ = 0.f;
   if (q < L) {
     lse2 = lse[((long)b * L + q) * h + head] * 1.4426950408889634f;
-    dq_ = dvec[((long)b * L + q) * h + head];
+    dq_ = dvec[((long)b * L + q) * h + head] * gsc;
   }
   f32x16 acc[DT];
 #pragma unroll
@@ -474,7 +505,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const T* __restrict__
       for (int g = 0; g < 4; ++g) {
         V4 v;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = from_f<T>(acc[j][g * 4 + i] * scale);
+        for (int i = 0; i < 4; ++i) v[i] = from_f<T>(acc[j][g * 4 + i] * (scale / gsc));
         *(V4*)(row + j * 32 + 8 * g + 4 * hf) = v;
       }
   }
@@ -513,6 +544,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const T* __restrict_
   const int wk0 = ktile * BKEY + wave * 32;
   const int key = wk0 + col;
   const float scale_log2 = scale * 1.4426950408889634f;
+  const float gsc = do_scale(dvec + (long)gridDim.y * L);
 
   V8 kf[KS], vf[KS];
 #pragma unroll
@@ -541,12 +573,14 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const T* __restrict_
     const int q0 = qt * QR;
     sq.load(qb, ld, q0, L);
     sdo.load(dob, d, q0, L);
+    sdo.scale(gsc);
     tq.load(qb, ld, q0, L, 0);
     tdo.load(dob, d, q0, L, TB);
+    if ((int)threadIdx.x >= TB && (int)threadIdx.x < 2 * TB) tdo.scale(gsc);
     if (threadIdx.x < QR) {
       const int qq = q0 + threadIdx.x;
       st_l = qq < L ? lseb[(long)qq * h] * 1.4426950408889634f : INFINITY;
-      st_d = qq < L ? dvb[(long)qq * h] : 0.f;
+      st_d = qq < L ? dvb[(long)qq * h] * gsc : 0.f;
     }
   };
   auto store_tile = [&](int buf) {
@@ -627,8 +661,8 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const T* __restrict_
         V4 a, c;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          a[i] = from_f<T>(dk[j][g * 4 + i] * scale);
-          c[i] = from_f<T>(dv[j][g * 4 + i]);
+          a[i] = from_f<T>(dk[j][g * 4 + i] * (scale / gsc));
+          c[i] = from_f<T>(dv[j][g * 4 + i] * (1.0f / gsc));
         }
         *(V4*)(rk + j * 32 + 8 * g + 4 * hf) = a;
         *(V4*)(rv + j * 32 + 8 * g + 4 * hf) = c;
@@ -637,22 +671,36 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const T* __restrict_
 }
 
 // D[t, head] = sum_c dO * O, one wavefront per (row, head)
+// also tracks max|dO| in dvec[n_items] (zeroed by amax_reset_kernel before the launch)
 template <class T>
 __global__ void dvec_kernel(const T* o, const T* dO, long n_items, int dh, float* dvec) {
   const long item = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
   if (item >= n_items) return;
-  float s = 0.f;
-  for (int c = lane; c < dh; c += 64) s += to_f(o[item * dh + c]) * to_f(dO[item * dh + c]);
+  float s = 0.f, m = 0.f;
+  for (int c = lane; c < dh; c += 64) {
+    const float g = to_f(dO[item * dh + c]);
+    s += to_f(o[item * dh + c]) * g;
+    m = fmaxf(m, fabsf(g));
+  }
   s = wave_sum(s);
-  if (lane == 0) dvec[item] = s;
+  m = wave_max(m);
+  if (lane == 0) {
+    dvec[item] = s;
+    // non-negative floats order like their bit patterns; skip the atomic when it cannot raise the maximum
+    unsigned* am = (unsigned*)(dvec + n_items);
+    if (m <= 3.0e38f && __float_as_uint(m) > __hip_atomic_load(am, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+      atomicMax(am, __float_as_uint(m));
+  }
 }
+__global__ void amax_reset_kernel(float* p) { *p = 0.f; }
 
 template <class T, int DH>
 ls_status launch_bwd(const void* qkv, const void* o, const void* dO, const float* lse, int B, int L, int h,
                      void* dqkv, float* dvec, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)DH);
   const long items = (long)B * L * h;
+  amax_reset_kernel<<<1, 1, 0, st>>>(dvec + items);
   dvec_kernel<T><<<(unsigned)((items + 3) / 4), 256, 0, st>>>((const T*)o, (const T*)dO, items, DH, dvec);
   LS_CHECK_LAUNCH();
   dim3 gq((L + 127) / 128, B * h), gk((L + 127) / 128, B * h);

@@ -9,10 +9,34 @@ namespace {
 constexpr float kGeluC = 0.7978845608028654f;  // sqrt(2/pi)
 
 // ------------------------------------------------------------------ convert
-__global__ void convert_kernel(const void* src, int sdt, void* dst, int ddt, size_t n) {
+__global__ void convert_kernel(const void* src, int sdt, void* dst, int ddt, size_t n, const float* scale) {
+  const float sc = scale ? *scale : 1.f;
   for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n;
        i += (size_t)gridDim.x * blockDim.x)
-    store_from_f(dst, i, ddt, load_as_f(src, i, sdt));
+    store_from_f(dst, i, ddt, load_as_f(src, i, sdt) * sc);
+}
+
+// ------------------------------------------------------------ gradient scale
+// out[0] = 2^e with max|x| * 2^e in (8, 16], out[1] = 2^-e.  Multiplying the
+// upstream gradient by out[0] keeps every 16-bit gradient operand of the
+// backward pass well inside the fp16 normal range (the matrix cores flush
+// fp16 subnormal inputs); results are multiplied by out[1], which is exact.
+__global__ void amax_kernel(const void* x, int dt, size_t n, unsigned* amax_bits) {
+  float m = 0.f;
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n;
+       i += (size_t)gridDim.x * blockDim.x)
+    m = fmaxf(m, fabsf(load_as_f(x, i, dt)));
+  m = wave_max(m);
+  if ((threadIdx.x & 63) == 0 && m <= 3.0e38f && __float_as_uint(m) > __hip_atomic_load(amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+    atomicMax(amax_bits, __float_as_uint(m));
+}
+__global__ void scale_reset_kernel(float* out) { out[2] = 0.f; }
+__global__ void scale_finish_kernel(float* out) {
+  const float a = out[2];
+  float e = 0.f;
+  if (a > 0.f && a <= 3.0e38f) e = fminf(fmaxf(floorf(log2f(16.f / a)), -24.f), 40.f);
+  out[0] = exp2f(e);
+  out[1] = exp2f(-e);
 }
 
 // ---------------------------------------------------------------- norm fwd
@@ -163,7 +187,7 @@ __global__ __launch_bounds__(256) void norm_bwd_apply_kernel(int kind, const TD*
 }
 
 __global__ void norm_bwd_finish_kernel(const float* partial, int nwg, int d, float* dgamma,
-                                       float* dbeta, int accumulate) {
+                                       float* dbeta, int accumulate, const float* alpha) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= d) return;
   float g = 0.f, b = 0.f;
@@ -171,6 +195,7 @@ __global__ void norm_bwd_finish_kernel(const float* partial, int nwg, int d, flo
     g += partial[(size_t)w * 2 * d + i];
     b += partial[(size_t)w * 2 * d + d + i];
   }
+  if (alpha) { g *= *alpha; b *= *alpha; }
   if (dgamma) dgamma[i] = accumulate ? dgamma[i] + g : g;
   if (dbeta) dbeta[i] = accumulate ? dbeta[i] + b : b;
 }
@@ -280,11 +305,13 @@ __global__ __launch_bounds__(256) void colsum_kernel(const void* x, int dt, int 
   for (int r = r0; r < r1; ++r) s += load_as_f(x, (size_t)r * ld + n, dt);
   partial[(size_t)blockIdx.y * N + n] = s;
 }
-__global__ void colsum_finish_kernel(const float* partial, int nchunk, int N, float* out, int accumulate) {
+__global__ void colsum_finish_kernel(const float* partial, int nchunk, int N, float* out, int accumulate,
+                                     const float* alpha) {
   const int n = blockIdx.x * blockDim.x + threadIdx.x;
   if (n >= N) return;
   float s = 0.f;
   for (int c = 0; c < nchunk; ++c) s += partial[(size_t)c * N + n];
+  if (alpha) s *= *alpha;
   out[n] = accumulate ? out[n] + s : s;
 }
 
@@ -298,10 +325,24 @@ bool ok_dtype(int dt) { return dt == LS_F32 || dt == LS_BF16 || dt == LS_F16; }
 
 extern "C" {
 
-ls_status lsk_convert(const void* src, int sdt, void* dst, int ddt, size_t n, void* stream) {
+ls_status lsk_convert_scaled(const void* src, int sdt, void* dst, int ddt, size_t n, const float* scale_dev,
+                             void* stream) {
   LS_REQUIRE(src && dst && ok_dtype(sdt) && ok_dtype(ddt), "convert: bad argument");
   if (n == 0) return LS_OK;
-  convert_kernel<<<grid_for(n), 256, 0, (hipStream_t)stream>>>(src, sdt, dst, ddt, n);
+  convert_kernel<<<grid_for(n), 256, 0, (hipStream_t)stream>>>(src, sdt, dst, ddt, n, scale_dev);
+  LS_CHECK_LAUNCH();
+  return LS_OK;
+}
+ls_status lsk_convert(const void* src, int sdt, void* dst, int ddt, size_t n, void* stream) {
+  return lsk_convert_scaled(src, sdt, dst, ddt, n, nullptr, stream);
+}
+
+ls_status lsk_grad_scale(const void* x, int dt, size_t n, float* out3, void* stream) {
+  LS_REQUIRE(x && out3 && ok_dtype(dt) && n > 0, "grad_scale: bad argument");
+  hipStream_t st = (hipStream_t)stream;
+  scale_reset_kernel<<<1, 1, 0, st>>>(out3);
+  amax_kernel<<<grid_for(n, 256, 2048), 256, 0, st>>>(x, dt, n, (unsigned*)(out3 + 2));
+  scale_finish_kernel<<<1, 1, 0, st>>>(out3);
   LS_CHECK_LAUNCH();
   return LS_OK;
 }
@@ -320,10 +361,11 @@ size_t lsk_norm_bwd_partial_floats(int T, int d) {
   return (size_t)((T + NB_ROWS - 1) / NB_ROWS) * 2 * d + 2 * (size_t)T;
 }
 
-ls_status lsk_norm_bwd(int kind, const void* dh, int dhdt, const float* x, const float* mean,
-                       const float* rstd, const void* gamma, int pdt, int T, int d,
-                       const float* dres, float* dx, void* dx16, int dx16dt, float* dgamma,
-                       float* dbeta, int accumulate, float* partial, void* stream) {
+ls_status lsk_norm_bwd_scaled(int kind, const void* dh, int dhdt, const float* x, const float* mean,
+                              const float* rstd, const void* gamma, int pdt, int T, int d,
+                              const float* dres, float* dx, void* dx16, int dx16dt, float* dgamma,
+                              float* dbeta, int accumulate, float* partial, const float* alpha_dev,
+                              void* stream) {
   LS_REQUIRE(dh && x && rstd && gamma && dx && partial && T > 0 && d > 0, "norm_bwd: bad argument");
   LS_REQUIRE(kind == 1 || mean, "norm_bwd: LayerNorm needs the saved mean");
   LS_REQUIRE(d % 8 == 0, "norm_bwd: d_model must be a multiple of 8");
@@ -336,10 +378,17 @@ ls_status lsk_norm_bwd(int kind, const void* dh, int dhdt, const float* x, const
   if (dgamma || dbeta) {
     const int nchunk = (T + NB_ROWS - 1) / NB_ROWS;
     norm_bwd_finish_kernel<<<(d + 255) / 256, 256, 0, st>>>(partial, nchunk, d, dgamma,
-                                                            kind == 0 ? dbeta : nullptr, accumulate);
+                                                            kind == 0 ? dbeta : nullptr, accumulate, alpha_dev);
     LS_CHECK_LAUNCH();
   }
   return LS_OK;
+}
+ls_status lsk_norm_bwd(int kind, const void* dh, int dhdt, const float* x, const float* mean,
+                       const float* rstd, const void* gamma, int pdt, int T, int d,
+                       const float* dres, float* dx, void* dx16, int dx16dt, float* dgamma,
+                       float* dbeta, int accumulate, float* partial, void* stream) {
+  return lsk_norm_bwd_scaled(kind, dh, dhdt, x, mean, rstd, gamma, pdt, T, d, dres, dx, dx16, dx16dt, dgamma,
+                             dbeta, accumulate, partial, nullptr, stream);
 }
 
 ls_status lsk_rope(void* qkv, int dt, int T, int h, int dh, const int32_t* pos, const float* table,
@@ -388,15 +437,20 @@ ls_status lsk_swiglu_bwd(const void* da, const void* gu, void* dgu, int dt, int 
 
 size_t lsk_colsum_partial_floats(int T, int N) { return (size_t)((T + CS_ROWS - 1) / CS_ROWS) * N; }
 
-ls_status lsk_colsum(const void* x, int dt, int T, int N, long ld, float* out, int accumulate,
-                     float* partial, void* stream) {
+ls_status lsk_colsum_scaled(const void* x, int dt, int T, int N, long ld, float* out, int accumulate,
+                            float* partial, const float* alpha_dev, void* stream) {
   LS_REQUIRE(x && out && partial && T > 0 && N > 0, "colsum: bad argument");
   const int nchunk = (T + CS_ROWS - 1) / CS_ROWS;
   colsum_kernel<<<dim3((N + 255) / 256, nchunk), 256, 0, (hipStream_t)stream>>>(x, dt, T, N, ld, partial);
   LS_CHECK_LAUNCH();
-  colsum_finish_kernel<<<(N + 255) / 256, 256, 0, (hipStream_t)stream>>>(partial, nchunk, N, out, accumulate);
+  colsum_finish_kernel<<<(N + 255) / 256, 256, 0, (hipStream_t)stream>>>(partial, nchunk, N, out, accumulate,
+                                                                         alpha_dev);
   LS_CHECK_LAUNCH();
   return LS_OK;
+}
+ls_status lsk_colsum(const void* x, int dt, int T, int N, long ld, float* out, int accumulate,
+                     float* partial, void* stream) {
+  return lsk_colsum_scaled(x, dt, T, N, ld, out, accumulate, partial, nullptr, stream);
 }
 
 }  // extern "C"

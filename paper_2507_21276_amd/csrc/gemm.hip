@@ -43,6 +43,7 @@ struct GemmArgs {
   const void* bias; int bias_dtype;
   const float* resid; long ldr;
   int accumulate;
+  const float* alpha;   // device scalar multiplying the accumulator (null = 1)
 };
 
 constexpr int BK = 64;
@@ -191,6 +192,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
   // epilogue: 32x32 accumulator tile: column = lane % 32,
   // row = 8 * (e / 4) + 4 * (lane / 32) + e % 4
   const int col_in = lane & 31, row_in = (lane >> 5) * 4;
+  const float alpha = g.alpha ? *g.alpha : 1.f;
 #pragma unroll
   for (int j = 0; j < TN; ++j) {
     const int n = n0 + wn + j * 32 + col_in;
@@ -202,7 +204,7 @@ __global__ __launch_bounds__(256) void gemm_mfma_kernel(GemmArgs g) {
       for (int e = 0; e < 16; ++e) {
         const int m = m0 + wm + i * 32 + 8 * (e >> 2) + row_in + (e & 3);
         if (m >= g.M) continue;
-        float v = acc[i][j][e] + bv;
+        float v = acc[i][j][e] * alpha + bv;
         if (g.resid) v += g.resid[(long)m * g.ldr + n];
         const long ci = (long)m * g.ldc + n;
         if (g.c_dtype == LS_F32) {
@@ -253,7 +255,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(GemmArgs g) {
     for (int j = 0; j < 4; ++j) {
       const int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
       if (m >= g.M || n >= g.N) continue;
-      float v = acc[i][j];
+      float v = acc[i][j] * (g.alpha ? *g.alpha : 1.f);
       if (g.bias) v += load_as_f(g.bias, n, g.bias_dtype);
       if (g.resid) v += g.resid[(long)m * g.ldr + n];
       float* c = (float*)g.C;
@@ -285,7 +287,7 @@ ls_status dispatch_mfma(const GemmArgs& g, hipStream_t st) {
 }  // namespace
 
 ls_status gemm_dma_try(int, int, int, int, const void*, long, int, const void*, long, int, void*, long, int,
-                       const void*, int, const float*, long, int, hipStream_t);
+                       const void*, int, const float*, long, int, const float*, hipStream_t);
 
 // LS_GEMM_IMPL=staged forces the register-staged kernel (for A/B comparisons)
 static bool use_dma_kernel() {
@@ -297,15 +299,16 @@ static bool use_dma_kernel() {
   return v == 1;
 }
 
-extern "C" ls_status lsk_gemm(int op_dtype, int M, int N, int K, const void* A, long lda,
-                              int a_kmajor, const void* B, long ldb, int b_kmajor, void* C,
-                              long ldc, int c_dtype, const void* bias, int bias_dtype,
-                              const float* resid, long ldr, int accumulate, void* stream) {
+extern "C" ls_status lsk_gemm_scaled(int op_dtype, int M, int N, int K, const void* A, long lda,
+                                     int a_kmajor, const void* B, long ldb, int b_kmajor, void* C,
+                                     long ldc, int c_dtype, const void* bias, int bias_dtype,
+                                     const float* resid, long ldr, int accumulate,
+                                     const float* alpha_dev, void* stream) {
   LS_REQUIRE(M > 0 && N > 0 && K > 0, "gemm: non-positive size M=%d N=%d K=%d", M, N, K);
   LS_REQUIRE(A && B && C, "gemm: null operand");
   LS_REQUIRE(!accumulate || c_dtype == LS_F32, "gemm: accumulate needs an fp32 output");
   GemmArgs g{M, N, K, A, lda, a_kmajor, B, ldb, b_kmajor, C, ldc, c_dtype,
-             bias, bias_dtype, resid, ldr, accumulate};
+             bias, bias_dtype, resid, ldr, accumulate, alpha_dev};
   hipStream_t st = (hipStream_t)stream;
   if (op_dtype == LS_F32) {
     LS_REQUIRE(c_dtype == LS_F32, "gemm: fp32 operands need an fp32 output");
@@ -323,11 +326,19 @@ extern "C" ls_status lsk_gemm(int op_dtype, int M, int N, int K, const void* A, 
   LS_REQUIRE(c_dtype == LS_F32 || c_dtype == op_dtype, "gemm: output type must be fp32 or the operand type");
   if (use_dma_kernel() && (long)((M + 255) / 256) * ((N + 255) / 256) >= 200) {
     const ls_status r = gemm_dma_try(op_dtype, M, N, K, A, lda, a_kmajor, B, ldb, b_kmajor, C, ldc, c_dtype, bias,
-                                     bias_dtype, resid, ldr, accumulate, st);
+                                     bias_dtype, resid, ldr, accumulate, alpha_dev, st);
     if (r != LS_ESTATE) return r;
   }
   if (op_dtype == LS_BF16) return dispatch_mfma<bf16_t>(g, st);
   if (op_dtype == LS_F16) return dispatch_mfma<f16_t>(g, st);
   ls_set_error("gemm: unknown operand dtype %d", op_dtype);
   return LS_EINVAL;
+}
+
+extern "C" ls_status lsk_gemm(int op_dtype, int M, int N, int K, const void* A, long lda, int a_kmajor,
+                              const void* B, long ldb, int b_kmajor, void* C, long ldc, int c_dtype,
+                              const void* bias, int bias_dtype, const float* resid, long ldr,
+                              int accumulate, void* stream) {
+  return lsk_gemm_scaled(op_dtype, M, N, K, A, lda, a_kmajor, B, ldb, b_kmajor, C, ldc, c_dtype, bias,
+                         bias_dtype, resid, ldr, accumulate, nullptr, stream);
 }

@@ -50,6 +50,7 @@ struct DmaArgs {
   const void* bias; int bias_dtype;
   const float* resid; long ldr;
   int accumulate;
+  const float* alpha;
   int tiles_m, tiles_n;
 };
 
@@ -208,6 +209,7 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
   }
 
   const int col_in = lane & 31, row_in = (lane >> 5) * 4;
+  const float alpha = g.alpha ? *g.alpha : 1.f;
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
     const int n = n0 + wn + j * 32 + col_in;
@@ -222,12 +224,12 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
         if (m >= g.M) continue;
         const long ci = (long)m * g.ldc + n;
         if (MODE == 0) {
-          ((T*)g.C)[ci] = from_f<T>(acc[i][j][e] + bv);
+          ((T*)g.C)[ci] = from_f<T>(acc[i][j][e] * alpha + bv);
         } else if (MODE == 1) {
-          ((float*)g.C)[ci] = acc[i][j][e] + bv + g.resid[(long)m * g.ldr + n];
+          ((float*)g.C)[ci] = acc[i][j][e] * alpha + bv + g.resid[(long)m * g.ldr + n];
         } else {
           float* c = (float*)g.C;
-          c[ci] = g.accumulate ? c[ci] + acc[i][j][e] : acc[i][j][e];
+          c[ci] = g.accumulate ? c[ci] + acc[i][j][e] * alpha : acc[i][j][e] * alpha;
         }
       }
     }
@@ -272,10 +274,10 @@ ls_status dispatch(const DmaArgs& g, hipStream_t st) {
 ls_status gemm_dma_try(int op_dtype, int M, int N, int K, const void* A, long lda, int a_kmajor,
                        const void* B, long ldb, int b_kmajor, void* C, long ldc, int c_dtype,
                        const void* bias, int bias_dtype, const float* resid, long ldr, int accumulate,
-                       hipStream_t st) {
+                       const float* alpha, hipStream_t st) {
   if (K % TK != 0 || M < 8 || N < 8) return LS_ESTATE;
   DmaArgs g{M, N, K, A, lda, a_kmajor, B, ldb, b_kmajor, C, ldc, c_dtype, bias, bias_dtype, resid, ldr,
-            accumulate, (M + TM - 1) / TM, (N + TN - 1) / TN};
+            accumulate, alpha, (M + TM - 1) / TM, (N + TN - 1) / TN};
   if (op_dtype == LS_BF16) return dispatch<bf16_t>(g, st);
   if (op_dtype == LS_F16) return dispatch<f16_t>(g, st);
   return LS_ESTATE;

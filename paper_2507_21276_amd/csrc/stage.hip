@@ -27,6 +27,14 @@ extern "C" {
 ls_status lsk_attn_fwd_simple(const void*, int, int, int, int, int, void*, float*, void*);
 ls_status lsk_attn_bwd_simple(const void*, const void*, const void*, const float*, int, int, int, int, int,
                               void*, float*, void*);
+ls_status lsk_gemm_scaled(int, int, int, int, const void*, long, int, const void*, long, int, void*, long, int,
+                          const void*, int, const float*, long, int, const float*, void*);
+ls_status lsk_convert_scaled(const void*, int, void*, int, size_t, const float*, void*);
+ls_status lsk_grad_scale(const void*, int, size_t, float*, void*);
+ls_status lsk_norm_bwd_scaled(int, const void*, int, const float*, const float*, const float*, const void*, int,
+                              int, int, const float*, float*, void*, int, float*, float*, int, float*,
+                              const float*, void*);
+ls_status lsk_colsum_scaled(const void*, int, int, int, long, float*, int, float*, const float*, void*);
 ls_status lsk_rope_kv_write(void*, int, int, int, int, const int32_t*, const int32_t*, const float*, void*, void*,
                             const int32_t*, int, int, void*);
 }
@@ -171,7 +179,7 @@ size_t carve_fwd(const ls_stage* s, void* base, int T, FwdWs* w) {
 // backward scratch
 struct BwdWs {
   int32_t* pos;
-  float *g, *g1, *dvec, *partial;
+  float *g, *g1, *dvec, *partial, *gscale;
   void *g16, *dact, *dup, *dh, *dqkv, *d_o;
 };
 size_t carve_bwd(const ls_stage* s, void* base, int T, BwdWs* w) {
@@ -180,6 +188,7 @@ size_t carve_bwd(const ls_stage* s, void* base, int T, BwdWs* w) {
   Bump b(base);
   BwdWs v;
   v.pos = (int32_t*)b.take((size_t)T * 4);
+  v.gscale = (float*)b.take(4 * 4);
   v.g = (float*)b.take(T * d * 4);
   v.g1 = (float*)b.take(T * d * 4);
   v.g16 = b.take(T * d * e);
@@ -188,7 +197,7 @@ size_t carve_bwd(const ls_stage* s, void* base, int T, BwdWs* w) {
   v.dh = b.take(T * d * e);
   v.dqkv = b.take(T * 3 * d * e);
   v.d_o = b.take(T * d * e);
-  v.dvec = (float*)b.take((size_t)T * c.n_heads * 4);
+  v.dvec = (float*)b.take(((size_t)T * c.n_heads + 1) * 4);
   size_t pf = lsk_norm_bwd_partial_floats(T, c.d_model);
   const size_t widest = (size_t)(3 * c.d_model > s->up_cols ? 3 * c.d_model : s->up_cols);
   const size_t cf = lsk_colsum_partial_floats(T, (int)widest);
@@ -479,43 +488,46 @@ ls_status stage_train_bwd(ls_stage* s, const void* dY, int B, int L, const void*
   carve_bwd(s, workspace, T, &w);
   train_index_kernel<<<(T + 255) / 256, 256, 0, st>>>(T, L, w.pos);
   LS_CHECK_LAUNCH();
-  LS_TRY(lsk_convert(dY, c.io_dtype, w.g, LS_F32, (size_t)T * d, st));
-  LS_TRY(lsk_convert(dY, c.io_dtype, w.g16, mt, (size_t)T * d, st));
+  // the whole backward runs on dY * 2^e (gscale[0]); every fp32 result is multiplied by 2^-e (gscale[1])
+  LS_TRY(lsk_grad_scale(dY, c.io_dtype, (size_t)T * d, w.gscale, st));
+  const float* inv = w.gscale + 1;
+  LS_TRY(lsk_convert_scaled(dY, c.io_dtype, w.g, LS_F32, (size_t)T * d, w.gscale, st));
+  LS_TRY(lsk_convert_scaled(dY, c.io_dtype, w.g16, mt, (size_t)T * d, w.gscale, st));
   for (int l = c.n_layers - 1; l >= 0; --l) {
     const LayerOff& o = s->off[l];
     const Saved& v = sv[l];
     // y = x1 + act W_dn^T (+ b_dn)
     LS_TRY(lsk_gemm(mt, T, F, d, w.g16, d, 1, wptr(s, o.w_dn), F, 0, w.dact, F, mt, nullptr, 0, nullptr, 0, 0, st));
-    LS_TRY(lsk_gemm(mt, d, F, T, w.g16, d, 0, v.act, F, 0, dParams + o.w_dn, F, LS_F32, nullptr, 0, nullptr, 0, acc, st));
+    LS_TRY(lsk_gemm_scaled(mt, d, F, T, w.g16, d, 0, v.act, F, 0, dParams + o.w_dn, F, LS_F32, nullptr, 0, nullptr, 0, acc, inv, st));
     if (gpt) {
-      LS_TRY(lsk_colsum(w.g16, mt, T, d, d, dParams + o.b_dn, acc, w.partial, st));
+      LS_TRY(lsk_colsum_scaled(w.g16, mt, T, d, d, dParams + o.b_dn, acc, w.partial, inv, st));
       LS_TRY(lsk_gelu_bwd(w.dact, v.up, w.dup, mt, (size_t)T * F, c.act, st));
     } else {
       LS_TRY(lsk_swiglu_bwd(w.dact, v.up, w.dup, mt, T, F, st));
     }
     // up = h2 W_up^T (+ b_up)
     LS_TRY(lsk_gemm(mt, T, d, U, w.dup, U, 1, wptr(s, o.w_up), d, 0, w.dh, d, mt, nullptr, 0, nullptr, 0, 0, st));
-    LS_TRY(lsk_gemm(mt, U, d, T, w.dup, U, 0, v.h2, d, 0, dParams + o.w_up, d, LS_F32, nullptr, 0, nullptr, 0, acc, st));
-    if (gpt) LS_TRY(lsk_colsum(w.dup, mt, T, U, U, dParams + o.b_up, acc, w.partial, st));
+    LS_TRY(lsk_gemm_scaled(mt, U, d, T, w.dup, U, 0, v.h2, d, 0, dParams + o.w_up, d, LS_F32, nullptr, 0, nullptr, 0, acc, inv, st));
+    if (gpt) LS_TRY(lsk_colsum_scaled(w.dup, mt, T, U, U, dParams + o.b_up, acc, w.partial, inv, st));
     // h2 = norm2(x1);  g1 = g + norm2_bwd(dh)
-    LS_TRY(lsk_norm_bwd(nk, w.dh, mt, v.x1, v.mean2, v.rstd2, pptr(s, o.n2_g), pt, T, d, w.g, w.g1, w.g16, mt,
-                        dParams + o.n2_g, gpt ? dParams + o.n2_b : nullptr, acc, w.partial, st));
+    LS_TRY(lsk_norm_bwd_scaled(nk, w.dh, mt, v.x1, v.mean2, v.rstd2, pptr(s, o.n2_g), pt, T, d, w.g, w.g1, w.g16, mt,
+                        dParams + o.n2_g, gpt ? dParams + o.n2_b : nullptr, acc, w.partial, inv, st));
     // x1 = x + o W_o^T (+ b_o)
     LS_TRY(lsk_gemm(mt, T, d, d, w.g16, d, 1, wptr(s, o.w_o), d, 0, w.d_o, d, mt, nullptr, 0, nullptr, 0, 0, st));
-    LS_TRY(lsk_gemm(mt, d, d, T, w.g16, d, 0, v.o, d, 0, dParams + o.w_o, d, LS_F32, nullptr, 0, nullptr, 0, acc, st));
-    if (gpt) LS_TRY(lsk_colsum(w.g16, mt, T, d, d, dParams + o.b_o, acc, w.partial, st));
+    LS_TRY(lsk_gemm_scaled(mt, d, d, T, w.g16, d, 0, v.o, d, 0, dParams + o.w_o, d, LS_F32, nullptr, 0, nullptr, 0, acc, inv, st));
+    if (gpt) LS_TRY(lsk_colsum_scaled(w.g16, mt, T, d, d, dParams + o.b_o, acc, w.partial, inv, st));
     LS_TRY(lsk_attn_bwd(mt == LS_F32 ? 0 : 1, v.qkv, v.o, w.d_o, v.lse, mt, B, L, c.n_heads, c.head_dim, w.dqkv,
                         w.dvec, st));
     if (!gpt) LS_TRY(lsk_rope(w.dqkv, mt, T, c.n_heads, c.head_dim, w.pos, s->rope_table, -1.0f, st));
     // qkv = h1 W_qkv^T (+ b_qkv)
     LS_TRY(lsk_gemm(mt, T, d, 3 * d, w.dqkv, 3 * d, 1, wptr(s, o.w_qkv), d, 0, w.dh, d, mt, nullptr, 0, nullptr, 0, 0, st));
-    LS_TRY(lsk_gemm(mt, 3 * d, d, T, w.dqkv, 3 * d, 0, v.h1, d, 0, dParams + o.w_qkv, d, LS_F32, nullptr, 0, nullptr, 0, acc, st));
-    if (gpt) LS_TRY(lsk_colsum(w.dqkv, mt, T, 3 * d, 3 * d, dParams + o.b_qkv, acc, w.partial, st));
+    LS_TRY(lsk_gemm_scaled(mt, 3 * d, d, T, w.dqkv, 3 * d, 0, v.h1, d, 0, dParams + o.w_qkv, d, LS_F32, nullptr, 0, nullptr, 0, acc, inv, st));
+    if (gpt) LS_TRY(lsk_colsum_scaled(w.dqkv, mt, T, 3 * d, 3 * d, dParams + o.b_qkv, acc, w.partial, inv, st));
     // h1 = norm1(x);  g = g1 + norm1_bwd(dh)
-    LS_TRY(lsk_norm_bwd(nk, w.dh, mt, v.x_in, v.mean1, v.rstd1, pptr(s, o.n1_g), pt, T, d, w.g1, w.g, w.g16, mt,
-                        dParams + o.n1_g, gpt ? dParams + o.n1_b : nullptr, acc, w.partial, st));
+    LS_TRY(lsk_norm_bwd_scaled(nk, w.dh, mt, v.x_in, v.mean1, v.rstd1, pptr(s, o.n1_g), pt, T, d, w.g1, w.g, w.g16, mt,
+                        dParams + o.n1_g, gpt ? dParams + o.n1_b : nullptr, acc, w.partial, inv, st));
   }
-  return lsk_convert(w.g, LS_F32, dX, c.io_dtype, (size_t)T * d, st);
+  return lsk_convert_scaled(w.g, LS_F32, dX, c.io_dtype, (size_t)T * d, inv, st);
 }
 
 ls_status stage_probe_interference(ls_stage* s, const void* dec_X, int dec_B, const ls_kv* kv, void* dec_Y,

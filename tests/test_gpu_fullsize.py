@@ -165,9 +165,12 @@ def test_cfg3_full_stage_properties_at_bench_size():
     Y2, _, _ = train_on_gpu(st, cfg, X2, dYd, B, L)
     assert torch.equal(Y2[0, : t + 1], Y[0, : t + 1]) and torch.equal(Y2[1], Y[1])
     assert not torch.equal(Y2[0, t + 1:], Y[0, t + 1:])
-    # (b) backward is linear in dY: doubling dY doubles every gradient exactly
+    # (b) backward is linear in dY, and exactly so under a power of two: the stage scales the
+    #     upstream gradient to a fixed binade before any 16-bit rounding happens
     _, dXb, dPb = train_on_gpu(st, cfg, Xd, 2.0 * dYd, B, L)
     assert torch.equal(dXb, 2.0 * dX) and torch.equal(dPb, 2.0 * dP)
+    _, dXc, _ = train_on_gpu(st, cfg, Xd, 2.0 ** -10 * dYd, B, L)
+    assert torch.equal(dXc, 2.0 ** -10 * dX)
     say("cfg3 full stage: causal invariance and linearity hold")
     # (c) a training forward is an inference forward: prefill of the same tokens gives the same Y
     ctx0 = np.zeros(B, np.int64)

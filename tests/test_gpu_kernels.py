@@ -220,6 +220,21 @@ def test_activations(name):
     assert_close(host(dgu), ref, otol(name, ref), "swiglu bwd")
 
 
+def test_grad_scale_is_a_power_of_two_that_brings_the_maximum_to_8_16():
+    for amax in (3.7e-6, 1e-2, 1.0, 15.9, 16.0, 4.0e4):
+        x = torch.zeros(10000, dtype=torch.float32, device="cuda")
+        x[1234] = -amax
+        out = torch.zeros(3, dtype=torch.float32, device="cuda")
+        Bd.lsk_grad_scale(x, out)
+        sc, inv, m = out.cpu().tolist()
+        assert m == np.float32(amax) and sc * inv == 1.0 and np.log2(sc) == round(np.log2(sc))
+        assert 8.0 < np.float32(amax) * sc <= 16.0
+    x = torch.zeros(100, dtype=torch.float16, device="cuda")
+    out = torch.zeros(3, dtype=torch.float32, device="cuda")
+    Bd.lsk_grad_scale(x, out)
+    assert out.cpu().tolist()[:2] == [1.0, 1.0]          # all-zero gradient: no scaling
+
+
 @pytest.mark.parametrize("name", ["f32", "f16"])
 def test_colsum(name):
     T, N = 333, 520
