@@ -87,6 +87,7 @@ SIGNATURES = {
     "lsk_colsum": (_I, [_VP, _I, _I, _I, _L, _VP, _I, _VP, _VP]),
     "lsk_attn_fwd": (_I, [_I, _VP, _I, _I, _I, _I, _I, _VP, _VP, _VP]),
     "lsk_attn_bwd": (_I, [_I, _VP, _VP, _VP, _VP, _I, _I, _I, _I, _I, _VP, _VP, _VP]),
+    "lsk_attn_bwd_scratch_floats": (_SZ, [_I, _I, _I]),
     "lsk_kv_write": (_I, [_VP, _I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP, _I, _I, _VP]),
     "lsk_attn_paged": (_I, [_I, _VP, _I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP, _I, _I, _I, _VP, _VP, _VP]),
     "lsk_attn_paged_scratch_floats": (_SZ, [_I, _I, _I, _I, _I]),
@@ -321,7 +322,7 @@ def lsk_attn_fwd(impl, qkv, B, L, n_heads, head_dim, o, lse, stream=None):
 
 
 def lsk_attn_bwd(impl, qkv, o, dO, lse, B, L, n_heads, head_dim, dqkv, stream=None):
-    dvec = torch.empty(B * L * n_heads + 1, dtype=torch.float32, device=qkv.device)
+    dvec = torch.empty(lib().lsk_attn_bwd_scratch_floats(B, L, n_heads), dtype=torch.float32, device=qkv.device)
     _check(lib().lsk_attn_bwd(impl, _p(qkv), _p(o), _p(dO), _p(lse), CODE_OF_TORCH[qkv.dtype], B, L,
                               n_heads, head_dim, _p(dqkv), _p(dvec), _stream(stream)))
 

@@ -31,6 +31,11 @@ ls_status lsk_attn_bwd(int impl, const void* qkv, const void* o, const void* dO,
   return lsk_attn_bwd_simple(qkv, o, dO, lse, dtype, B, L, n_heads, head_dim, dqkv, dvec, stream);
 }
 
+size_t lsk_attn_bwd_scratch_floats(int B, int L, int n_heads) {
+  const size_t items = (size_t)B * L * n_heads;
+  return items + (items + 3) / 4 + 1;
+}
+
 size_t lsk_attn_decode_scratch_floats(int, int, int, int, int);
 ls_status lsk_attn_decode(const void*, int, int, int, int, const int32_t*, const int32_t*, const void*,
                           const void*, const int32_t*, int, int, int, void*, float*, void*);

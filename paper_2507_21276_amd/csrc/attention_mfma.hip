@@ -53,6 +53,24 @@ __device__ __forceinline__ void transpose8x8(const u32x4 (&in)[8], u32x4 (&out)[
   }
 }
 
+// Where the keys of one (sequence, head) live: rows of the training qkv buffer,
+// or pages of the serving pool found through the request's block table.
+template <class T>
+struct KvContig {
+  const T* k; const T* v; long ld;
+  __device__ __forceinline__ const T* krow(int key) const { return k + (long)key * ld; }
+  __device__ __forceinline__ const T* vrow(int key) const { return v + (long)key * ld; }
+};
+template <class T>
+struct KvPaged {
+  const T* k; const T* v; const int32_t* bt; int page, h, head, dh;
+  __device__ __forceinline__ long off(int key) const {
+    return (((long)bt[key / page] * h + head) * page + key % page) * dh;
+  }
+  __device__ __forceinline__ const T* krow(int key) const { return k + off(key); }
+  __device__ __forceinline__ const T* vrow(int key) const { return v + off(key); }
+};
+
 // K tile [KT][DH] (row stride DH+8) and V^T tile [DH][KT] (row stride KT+8)
 template <class T, int DH>
 struct KvStage {
@@ -60,13 +78,14 @@ struct KvStage {
   static constexpr int VBLK = 8 * (DH / 8);      // 8x8 blocks of V (one per thread below VBLK)
   u32x4 k[KCH];
   u32x4 v[8];
-  __device__ __forceinline__ void load(const T* kbase, const T* vbase, long ld, int key0, int nkeys) {
+  template <class SRC>
+  __device__ __forceinline__ void load(const SRC& src, int key0, int nkeys) {
 #pragma unroll
     for (int i = 0; i < KCH; ++i) {
       const int c = threadIdx.x + i * 256;
       const int r = c / (DH / 8), col = (c % (DH / 8)) * 8;
       u32x4 z = {0u, 0u, 0u, 0u};
-      if (key0 + r < nkeys) z = *(const u32x4*)(kbase + (long)(key0 + r) * ld + col);
+      if (key0 + r < nkeys) z = *(const u32x4*)(src.krow(key0 + r) + col);
       k[i] = z;
     }
     if (threadIdx.x < VBLK) {
@@ -75,7 +94,7 @@ struct KvStage {
       for (int j = 0; j < 8; ++j) {
         const int key = key0 + kg * 8 + j;
         u32x4 z = {0u, 0u, 0u, 0u};
-        if (key < nkeys) z = *(const u32x4*)(vbase + (long)key * ld + dg * 8);
+        if (key < nkeys) z = *(const u32x4*)(src.vrow(key) + dg * 8);
         v[j] = z;
       }
     }
@@ -97,10 +116,18 @@ struct KvStage {
   }
 };
 
-template <class T, int DH, int QT>
+// Serving geometry: request r owns rows start[r] .. start[r+1]-1 of qkv / o, its queries sit at
+// absolute positions ctx_len[r] + i and its keys 0 .. ctx_len[r] + chunk - 1 are in the pool.
+struct PagedGeom {
+  const void* k_pool; const void* v_pool; const int32_t* block_table; const int32_t* ctx_len;
+  int max_pages, page, n_req;
+  int start[33];
+};
+
+template <class T, int DH, int QT, bool PAGED>
 __global__ __launch_bounds__(256) void flash_fwd_kernel(const T* __restrict__ qkv, T* __restrict__ o,
                                                         float* __restrict__ lse, int L, int h,
-                                                        float scale_log2) {
+                                                        float scale_log2, PagedGeom pg) {
   typedef typename Mma<T>::V8 V8;
   typedef typename Mma<T>::V4 V4;
   constexpr int BQ = 4 * QT * 32;
@@ -110,17 +137,24 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const T* __restrict__ qk
   __shared__ __attribute__((aligned(16))) T ks_lds[2][KT * KSTR];
   __shared__ __attribute__((aligned(16))) T vt_lds[2][DH * VSTR];
 
-  const int n_qt = (L + BQ - 1) / BQ;
-  const int qtile = n_qt - 1 - blockIdx.x;  // heaviest tiles first
   const int b = blockIdx.y / h, head = blockIdx.y % h;
   const int d = h * DH;
   const long ld = 3L * d;
-  const T* qb = qkv + (long)b * L * ld + (long)head * DH;
-  const T* kb = qb + d;
-  const T* vb = qb + 2 * d;
+  // rows of this sequence / request chunk, number of cached tokens before it
+  const long row0 = PAGED ? pg.start[b] : (long)b * L;
+  const int Lq = PAGED ? pg.start[b + 1] - pg.start[b] : L;
+  const int past = PAGED ? pg.ctx_len[b] : 0;
+  const int n_qt = (Lq + BQ - 1) / BQ;
+  if ((int)blockIdx.x >= n_qt) return;
+  const int qtile = n_qt - 1 - blockIdx.x;  // heaviest tiles first
+  const T* qb = qkv + row0 * ld + (long)head * DH;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int col = lane & 31, hf = lane >> 5;
   const int wq0 = qtile * BQ + wave * QT * 32;  // first query row of this wavefront
+  const int nkeys = past + Lq;
+  const KvContig<T> src_c{qb + d, qb + 2 * d, ld};
+  const KvPaged<T> src_p{(const T*)pg.k_pool, (const T*)pg.v_pool,
+                         pg.block_table + (PAGED ? (long)b * pg.max_pages : 0), pg.page, h, head, DH};
 
   // Q fragments (B operand): column = query, k = head dimension
   V8 qf[QT][KS];
@@ -130,7 +164,7 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const T* __restrict__ qk
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       u32x4 z = {0u, 0u, 0u, 0u};
-      if (q < L) z = *(const u32x4*)(qb + (long)q * ld + s * 16 + hf * 8);
+      if (q < Lq) z = *(const u32x4*)(qb + (long)q * ld + s * 16 + hf * 8);
       qf[t][s] = __builtin_bit_cast(V8, z);
     }
   }
@@ -147,19 +181,23 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const T* __restrict__ qk
       for (int e = 0; e < 16; ++e) oacc[t][j][e] = 0.f;
   }
 
-  const int q_hi = min(L, qtile * BQ + BQ) - 1;  // last query row of the workgroup
-  const int n_kt = q_hi / KT + 1;
+  const int q_hi = min(Lq, qtile * BQ + BQ) - 1;  // last query row of the workgroup
+  const int n_kt = (past + q_hi) / KT + 1;
   KvStage<T, DH> stg;
-  stg.load(kb, vb, ld, 0, L);
+  auto load_tile = [&](int key0) {
+    if (PAGED) stg.load(src_p, key0, nkeys);
+    else stg.load(src_c, key0, nkeys);
+  };
+  load_tile(0);
   stg.store(ks_lds[0], vt_lds[0]);
   __syncthreads();
 
   for (int kt = 0; kt < n_kt; ++kt) {
     const int cur = kt & 1;
     const int key0 = kt * KT;
-    if (kt + 1 < n_kt) stg.load(kb, vb, ld, key0 + KT, L);
+    if (kt + 1 < n_kt) load_tile(key0 + KT);
     // this wavefront's rows end at wq0 + QT*32 - 1: skip tiles entirely above its diagonal
-    if (key0 <= wq0 + QT * 32 - 1) {
+    if (key0 <= past + wq0 + QT * 32 - 1) {
       const T* ks = ks_lds[cur];
       const T* vt = vt_lds[cur];
       f32x16 sacc[QT][2];
@@ -183,8 +221,8 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const T* __restrict__ qk
       V8 pf[QT][4];
 #pragma unroll
       for (int t = 0; t < QT; ++t) {
-        const int q = wq0 + t * 32 + col;
-        const bool diag = key0 + KT - 1 > wq0 + t * 32;  // tile reaches past the first row's diagonal
+        const int q = past + wq0 + t * 32 + col;           // absolute position of this lane's query
+        const bool diag = key0 + KT - 1 > past + wq0 + t * 32;  // tile reaches past the first row's diagonal
         float mx = -INFINITY;
 #pragma unroll
         for (int c = 0; c < 2; ++c)
@@ -244,9 +282,9 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const T* __restrict__ qk
   for (int t = 0; t < QT; ++t) {
     const int q = wq0 + t * 32 + col;
     const float l = l_run[t] + __shfl_xor(l_run[t], 32, 64);
-    if (q >= L) continue;
+    if (q >= Lq) continue;
     const float inv = 1.0f / l;
-    T* orow = o + ((long)b * L + q) * d + (long)head * DH;
+    T* orow = o + (row0 + q) * d + (long)head * DH;
 #pragma unroll
     for (int j = 0; j < DT; ++j)
 #pragma unroll
@@ -257,26 +295,36 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const T* __restrict__ qk
         *(V4*)(orow + j * 32 + 8 * g + 4 * hf) = v;
       }
     if (lse && hf == 0)
-      lse[((long)b * L + q) * h + head] = (m_run[t] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+      lse[(row0 + q) * h + head] = (m_run[t] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
   }
 }
 
 template <class T, int DH>
 ls_status launch_fwd(const void* qkv, int B, int L, int h, void* o, float* lse, hipStream_t st) {
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
+  PagedGeom pg{};
   if (L > 512) {
     constexpr int QT = 2;
     dim3 grid((L + 4 * QT * 32 - 1) / (4 * QT * 32), B * h);
-    flash_fwd_kernel<T, DH, QT><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, lse, L, h, scale_log2);
+    flash_fwd_kernel<T, DH, QT, false><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, lse, L, h, scale_log2, pg);
   } else {
     constexpr int QT = 1;
     dim3 grid((L + 4 * QT * 32 - 1) / (4 * QT * 32), B * h);
-    flash_fwd_kernel<T, DH, QT><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, lse, L, h, scale_log2);
+    flash_fwd_kernel<T, DH, QT, false><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, lse, L, h, scale_log2, pg);
   }
   LS_CHECK_LAUNCH();
   return LS_OK;
 }
 
+template <class T, int DH>
+ls_status launch_prefill(const void* qkv, int h, void* o, const PagedGeom& pg, int max_chunk, hipStream_t st) {
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
+  constexpr int QT = 1;
+  dim3 grid((max_chunk + 4 * QT * 32 - 1) / (4 * QT * 32), pg.n_req * h);
+  flash_fwd_kernel<T, DH, QT, true><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, nullptr, 0, h, scale_log2, pg);
+  LS_CHECK_LAUNCH();
+  return LS_OK;
+}
 
 // ---------------------------------------------------------------------------------
 // Backward.  Two kernels, no atomics (deterministic):
@@ -408,7 +456,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const T* __restrict__
   const int wq0 = qtile * BQ + wave * 32;
   const int q = wq0 + col;
   const float scale_log2 = scale * 1.4426950408889634f;
-  const float gsc = do_scale(dvec + (long)gridDim.y * L);   // one float after the [B*L, h] array
+  const float gsc = do_scale(dvec + (long)gridDim.y * L + ((long)gridDim.y * L + 3) / 4);   // after D and the per-workgroup maxima
 
   V8 qf[KS], dof[KS];
 #pragma unroll
@@ -544,7 +592,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const T* __restrict_
   const int wk0 = ktile * BKEY + wave * 32;
   const int key = wk0 + col;
   const float scale_log2 = scale * 1.4426950408889634f;
-  const float gsc = do_scale(dvec + (long)gridDim.y * L);
+  const float gsc = do_scale(dvec + (long)gridDim.y * L + ((long)gridDim.y * L + 3) / 4);
 
   V8 kf[KS], vf[KS];
 #pragma unroll
@@ -671,37 +719,48 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const T* __restrict_
 }
 
 // D[t, head] = sum_c dO * O, one wavefront per (row, head)
-// also tracks max|dO| in dvec[n_items] (zeroed by amax_reset_kernel before the launch)
+// also records max|dO| per workgroup in dvec[n_items + blockIdx.x]; amax_finish_kernel
+// folds those into dvec[n_items + gridDim.x] (no atomics: deterministic and contention-free)
 template <class T>
-__global__ void dvec_kernel(const T* o, const T* dO, long n_items, int dh, float* dvec) {
+__global__ __launch_bounds__(256) void dvec_kernel(const T* o, const T* dO, long n_items, int dh, float* dvec) {
+  __shared__ float wmax[4];
   const long item = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
-  if (item >= n_items) return;
   float s = 0.f, m = 0.f;
-  for (int c = lane; c < dh; c += 64) {
-    const float g = to_f(dO[item * dh + c]);
-    s += to_f(o[item * dh + c]) * g;
-    m = fmaxf(m, fabsf(g));
+  if (item < n_items) {
+    for (int c = lane; c < dh; c += 64) {
+      const float g = to_f(dO[item * dh + c]);
+      s += to_f(o[item * dh + c]) * g;
+      m = fmaxf(m, fabsf(g));
+    }
   }
   s = wave_sum(s);
   m = wave_max(m);
   if (lane == 0) {
-    dvec[item] = s;
-    // non-negative floats order like their bit patterns; skip the atomic when it cannot raise the maximum
-    unsigned* am = (unsigned*)(dvec + n_items);
-    if (m <= 3.0e38f && __float_as_uint(m) > __hip_atomic_load(am, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
-      atomicMax(am, __float_as_uint(m));
+    if (item < n_items) dvec[item] = s;
+    wmax[threadIdx.x >> 6] = m;
   }
+  __syncthreads();
+  if (threadIdx.x == 0) dvec[n_items + blockIdx.x] = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
 }
-__global__ void amax_reset_kernel(float* p) { *p = 0.f; }
+__global__ __launch_bounds__(256) void amax_finish_kernel(float* blockmax, long nb) {
+  __shared__ float red[4];
+  float m = 0.f;
+  for (long i = threadIdx.x; i < nb; i += 256) m = fmaxf(m, blockmax[i]);
+  m = wave_max(m);
+  if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) blockmax[nb] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+}
 
 template <class T, int DH>
 ls_status launch_bwd(const void* qkv, const void* o, const void* dO, const float* lse, int B, int L, int h,
                      void* dqkv, float* dvec, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)DH);
   const long items = (long)B * L * h;
-  amax_reset_kernel<<<1, 1, 0, st>>>(dvec + items);
-  dvec_kernel<T><<<(unsigned)((items + 3) / 4), 256, 0, st>>>((const T*)o, (const T*)dO, items, DH, dvec);
+  const long nb = (items + 3) / 4;
+  dvec_kernel<T><<<(unsigned)nb, 256, 0, st>>>((const T*)o, (const T*)dO, items, DH, dvec);
+  amax_finish_kernel<<<1, 256, 0, st>>>(dvec + items, nb);
   LS_CHECK_LAUNCH();
   dim3 gq((L + 127) / 128, B * h), gk((L + 127) / 128, B * h);
   flash_bwd_dq_kernel<T, DH><<<gq, 256, 0, st>>>((const T*)qkv, (const T*)dO, lse, dvec, (T*)dqkv, L, h, scale);
@@ -724,6 +783,28 @@ extern "C" ls_status lsk_attn_fwd_mfma(const void* qkv, int dt, int B, int L, in
                                      : launch_fwd<bf16_t, 128>(qkv, B, L, h, o, lse, st);
   return dh == 64 ? launch_fwd<f16_t, 64>(qkv, B, L, h, o, lse, st)
                   : launch_fwd<f16_t, 128>(qkv, B, L, h, o, lse, st);
+}
+
+// Prefill attention over the paged pool: request r owns rows start[r] .. start[r+1]-1 of qkv
+// (start on the host, n_req + 1 entries, n_req <= 32); its K/V rows are already in the pool.
+extern "C" ls_status lsk_attn_prefill_mfma(const void* qkv, int dt, int n_req, const int32_t* start_host, int h,
+                                           int dh, const void* k_pool, const void* v_pool,
+                                           const int32_t* block_table, const int32_t* ctx_len, int max_pages,
+                                           int page, void* o, void* stream) {
+  LS_REQUIRE(qkv && o && start_host && k_pool && v_pool && block_table && ctx_len, "attn_prefill: null argument");
+  LS_REQUIRE(n_req > 0 && n_req <= 32, "attn_prefill: 1..32 requests per call");
+  LS_REQUIRE(dt == LS_BF16 || dt == LS_F16, "attn_prefill: 16-bit operands only");
+  LS_REQUIRE(dh == 64 || dh == 128, "attn_prefill: head_dim must be 64 or 128");
+  PagedGeom pg{k_pool, v_pool, block_table, ctx_len, max_pages, page, n_req, {0}};
+  int max_chunk = 0;
+  for (int r = 0; r <= n_req; ++r) pg.start[r] = start_host[r];
+  for (int r = 0; r < n_req; ++r) max_chunk = max_chunk > pg.start[r + 1] - pg.start[r] ? max_chunk : pg.start[r + 1] - pg.start[r];
+  LS_REQUIRE(max_chunk > 0, "attn_prefill: empty chunks");
+  hipStream_t st = (hipStream_t)stream;
+  if (dt == LS_BF16) return dh == 64 ? launch_prefill<bf16_t, 64>(qkv, h, o, pg, max_chunk, st)
+                                     : launch_prefill<bf16_t, 128>(qkv, h, o, pg, max_chunk, st);
+  return dh == 64 ? launch_prefill<f16_t, 64>(qkv, h, o, pg, max_chunk, st)
+                  : launch_prefill<f16_t, 128>(qkv, h, o, pg, max_chunk, st);
 }
 
 extern "C" ls_status lsk_attn_bwd_mfma(const void* qkv, const void* o, const void* dO, const float* lse,

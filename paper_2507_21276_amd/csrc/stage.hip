@@ -35,6 +35,8 @@ ls_status lsk_norm_bwd_scaled(int, const void*, int, const float*, const float*,
                               int, int, const float*, float*, void*, int, float*, float*, int, float*,
                               const float*, void*);
 ls_status lsk_colsum_scaled(const void*, int, int, int, long, float*, int, float*, const float*, void*);
+ls_status lsk_attn_prefill_mfma(const void*, int, int, const int32_t*, int, int, const void*, const void*,
+                                const int32_t*, const int32_t*, int, int, void*, void*);
 ls_status lsk_rope_kv_write(void*, int, int, int, int, const int32_t*, const int32_t*, const float*, void*, void*,
                             const int32_t*, int, int, void*);
 }
@@ -197,7 +199,7 @@ size_t carve_bwd(const ls_stage* s, void* base, int T, BwdWs* w) {
   v.dh = b.take(T * d * e);
   v.dqkv = b.take(T * 3 * d * e);
   v.d_o = b.take(T * d * e);
-  v.dvec = (float*)b.take(((size_t)T * c.n_heads + 1) * 4);
+  v.dvec = (float*)b.take(lsk_attn_bwd_scratch_floats(1, T, c.n_heads) * 4);
   size_t pf = lsk_norm_bwd_partial_floats(T, c.d_model);
   const size_t widest = (size_t)(3 * c.d_model > s->up_cols ? 3 * c.d_model : s->up_cols);
   const size_t cf = lsk_colsum_partial_floats(T, (int)widest);
@@ -227,7 +229,7 @@ ls_status linear(const ls_stage* s, int T, int N, int K, const void* X, const vo
 
 ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const int32_t* pos,
                         const int32_t* req, int B, int L, const ls_kv* kv, int max_ctx,
-                        hipStream_t st) {
+                        const int32_t* chunk_start, hipStream_t st) {
   const ls_config& c = s->cfg;
   const LayerOff& o = s->off[l];
   const int d = c.d_model, F = c.d_ff, mt = c.mma_dtype, pt = c.dtype;
@@ -244,9 +246,15 @@ ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const
     void* vp = (char*)kv->v_pool + (size_t)l * slab;
     LS_TRY(lsk_rope_kv_write(f.qkv, mt, T, c.n_heads, c.head_dim, pos, req, gpt ? nullptr : s->rope_table, kp, vp,
                              kv->block_table, kv->max_pages_per_req, c.page_size, st));
-    LS_TRY(lsk_attn_paged(mt == LS_F32 ? 0 : 1, f.qkv, mt, T, c.n_heads, c.head_dim, pos, req, kp, vp,
-                          kv->block_table, kv->max_pages_per_req, c.page_size, max_ctx, f.o,
-                          (long)T * c.n_heads < 2048 ? f.scratch : nullptr, st));
+    if (chunk_start && mt != LS_F32 && c.head_dim >= 64) {
+      // prompt chunks: matrix-core attention over the pages (queries of a chunk share the K/V tiles)
+      LS_TRY(lsk_attn_prefill_mfma(f.qkv, mt, B, chunk_start, c.n_heads, c.head_dim, kp, vp, kv->block_table,
+                                   kv->ctx_len, kv->max_pages_per_req, c.page_size, f.o, st));
+    } else {
+      LS_TRY(lsk_attn_paged(mt == LS_F32 ? 0 : 1, f.qkv, mt, T, c.n_heads, c.head_dim, pos, req, kp, vp,
+                            kv->block_table, kv->max_pages_per_req, c.page_size, max_ctx, f.o,
+                            (long)T * c.n_heads < 2048 ? f.scratch : nullptr, st));
+    }
   } else {
     LS_TRY(lsk_attn_fwd(mt == LS_F32 ? 0 : 1, f.qkv, mt, B, L, c.n_heads, c.head_dim, f.o, f.lse, st));
   }
@@ -286,13 +294,13 @@ ls_status check_kv(const ls_stage* s, const ls_kv* kv, int B, const int32_t* new
 }
 
 ls_status serve_forward(ls_stage* s, const void* X, int T, int B, const ls_kv* kv, int max_ctx, void* Y,
-                        const FwdWs& w, hipStream_t st) {
+                        const FwdWs& w, const int32_t* chunk_start, hipStream_t st) {
   const ls_config& c = s->cfg;
   LS_TRY(lsk_convert(X, c.io_dtype, w.xa, LS_F32, (size_t)T * c.d_model, st));
   for (int l = 0; l < c.n_layers; ++l) {
     FwdBufs f{w.xa, w.xb, w.xa, nullptr, nullptr, nullptr, nullptr, nullptr,
               w.h, w.qkv, w.o, w.h, w.up, w.act, w.scratch};
-    LS_TRY(block_forward(s, l, T, f, w.pos, w.req, B, 0, kv, max_ctx, st));
+    LS_TRY(block_forward(s, l, T, f, w.pos, w.req, B, 0, kv, max_ctx, chunk_start, st));
   }
   return lsk_convert(w.xa, LS_F32, Y, c.io_dtype, (size_t)T * c.d_model, st);
 }
@@ -429,7 +437,7 @@ ls_status stage_prefill(ls_stage* s, const void* X, const int32_t* chunk_len, in
   carve_fwd(s, workspace, T, &w);
   token_index_kernel<<<(T + 255) / 256, 256, 0, st>>>(ch, kv->ctx_len, w.pos, w.req);
   LS_CHECK_LAUNCH();
-  return serve_forward(s, X, T, B, kv, max_ctx, Y, w, st);
+  return serve_forward(s, X, T, B, kv, max_ctx, Y, w, ch.start, st);
 }
 
 ls_status stage_decode(ls_stage* s, const void* X, int B, const ls_kv* kv, void* Y, void* workspace,
@@ -444,7 +452,7 @@ ls_status stage_decode(ls_stage* s, const void* X, int B, const ls_kv* kv, void*
   carve_fwd(s, workspace, B, &w);
   decode_index_kernel<<<(B + 255) / 256, 256, 0, st>>>(B, kv->ctx_len, w.pos, w.req);
   LS_CHECK_LAUNCH();
-  return serve_forward(s, X, B, B, kv, max_ctx, Y, w, st);
+  return serve_forward(s, X, B, B, kv, max_ctx, Y, w, nullptr, st);
 }
 
 ls_status stage_train_fwd(ls_stage* s, const void* X, int B, int L, void* Y, void* saved, void* workspace,
@@ -467,7 +475,7 @@ ls_status stage_train_fwd(ls_stage* s, const void* X, int B, int L, void* Y, voi
     float* y = l + 1 < c.n_layers ? sv[l + 1].x_in : w.xa;
     FwdBufs f{sv[l].x_in, sv[l].x1, y, sv[l].mean1, sv[l].rstd1, sv[l].mean2, sv[l].rstd2, sv[l].lse,
               sv[l].h1, sv[l].qkv, sv[l].o, sv[l].h2, sv[l].up, sv[l].act, w.scratch};
-    LS_TRY(block_forward(s, l, T, f, w.pos, nullptr, B, L, nullptr, 0, st));
+    LS_TRY(block_forward(s, l, T, f, w.pos, nullptr, B, L, nullptr, 0, nullptr, st));
   }
   return lsk_convert(w.xa, LS_F32, Y, c.io_dtype, (size_t)T * c.d_model, st);
 }
