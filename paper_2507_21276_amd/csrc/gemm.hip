@@ -324,7 +324,7 @@ extern "C" ls_status lsk_gemm_scaled(int op_dtype, int M, int N, int K, const vo
   LS_REQUIRE(a_kmajor ? (K % 8 == 0) : (M % 8 == 0), "gemm: A contiguous extent must be a multiple of 8");
   LS_REQUIRE(b_kmajor ? (K % 8 == 0) : (N % 8 == 0), "gemm: B contiguous extent must be a multiple of 8");
   LS_REQUIRE(c_dtype == LS_F32 || c_dtype == op_dtype, "gemm: output type must be fp32 or the operand type");
-  if (use_dma_kernel() && (long)((M + 255) / 256) * ((N + 255) / 256) >= 200) {
+  if (use_dma_kernel() && M >= 256) {
     const ls_status r = gemm_dma_try(op_dtype, M, N, K, A, lda, a_kmajor, B, ldb, b_kmajor, C, ldc, c_dtype, bias,
                                      bias_dtype, resid, ldr, accumulate, alpha_dev, st);
     if (r != LS_ESTATE) return r;

@@ -1,7 +1,7 @@
 // Large-tile MFMA GEMM whose operand tiles go from global memory straight into
 // LDS (16-byte direct-to-LDS loads, no register staging, no LDS store
-// instructions).  256 x 256 x 64 tiles, 4 wavefronts of 128 x 128, 32x32x16 MFMA,
-// two LDS buffers of 64 KB.  Used when the contraction length is a multiple of
+// instructions).  256 x 256 x 64 tiles (4 wavefronts of 128 x 128) or 128 x 128 x 64 tiles
+// (4 wavefronts of 64 x 64) for problems with few tiles, 32x32x16 MFMA, two LDS buffers.  Used when the contraction length is a multiple of
 // 64; the register-staged kernel in gemm.hip covers everything else.
 //
 // LDS layouts (a direct-to-LDS wave load writes 1 KB: lane i -> bytes 16 i):
@@ -54,17 +54,19 @@ struct DmaArgs {
   int tiles_m, tiles_n;
 };
 
-constexpr int TM = 256, TN = 256, TK = 64;
-constexpr int TILE_BYTES = 256 * 64 * 2;  // one operand tile
+constexpr int TK = 64;  // k extent of a tile; a tile of ROWS rows is ROWS * 128 bytes = ROWS / 8 wave loads
 
-// Direct-to-LDS loads of one operand tile: 8 wave loads per wavefront.  The
-// per-lane byte offsets inside the tile are fixed for the whole k loop (`off`,
-// computed once); only the uniform tile base moves.
-template <bool KMAJOR>
-__device__ __forceinline__ void tile_offsets(uint32_t (&off)[8], long ld, int row0, int nrows, int wave, int lane) {
+// Direct-to-LDS loads of one operand tile of ROWS rows (256 or 128): ROWS / 32
+// wave loads per wavefront.  The per-lane byte offsets inside the tile are fixed
+// for the whole k loop (`off`, computed once); only the uniform tile base moves.
+template <bool KMAJOR, int ROWS>
+__device__ __forceinline__ void tile_offsets(uint32_t (&off)[ROWS / 32], long ld, int row0, int nrows, int wave,
+                                             int lane) {
+  constexpr int NL = ROWS / 32;         // wave loads per wavefront
+  constexpr int LPR = ROWS / 8;         // lanes (16-byte chunks) per k row of a k-strided tile
 #pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const int q = wave * 8 + j;  // 1 KB block of the tile
+  for (int j = 0; j < NL; ++j) {
+    const int q = wave * NL + j;  // 1 KB block of the tile
     if (KMAJOR) {
       const int row = q * 8 + (lane >> 3);
       const int kc = (lane & 7) ^ ((row >> 1) & 7);
@@ -72,8 +74,8 @@ __device__ __forceinline__ void tile_offsets(uint32_t (&off)[8], long ld, int ro
       gr = gr < nrows ? gr : nrows - 1;  // rows past the edge: any valid data, never stored
       off[j] = (uint32_t)(((long)(gr - row0) * ld + kc * 8) * 2);
     } else {
-      const int krow = q * 2 + (lane >> 5);
-      const int cl = (lane & 31) ^ (4 * (krow & 3));
+      const int krow = q * (64 / LPR) + lane / LPR;
+      const int cl = (lane % LPR) ^ (4 * (krow & 3));
       int gr = row0 + cl * 8;
       gr = gr + 8 <= nrows ? gr : nrows - 8;
       off[j] = (uint32_t)(((long)krow * ld + (gr - row0)) * 2);
@@ -81,16 +83,19 @@ __device__ __forceinline__ void tile_offsets(uint32_t (&off)[8], long ld, int ro
   }
 }
 
-__device__ __forceinline__ void issue_tile(const char* tile_base, const uint32_t (&off)[8], char* lds_tile, int wave) {
+template <int ROWS>
+__device__ __forceinline__ void issue_tile(const char* tile_base, const uint32_t (&off)[ROWS / 32], char* lds_tile,
+                                           int wave) {
+  constexpr int NL = ROWS / 32;
 #pragma unroll
-  for (int j = 0; j < 8; ++j)
+  for (int j = 0; j < NL; ++j)
     __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tile_base + off[j]),
-                                     (__attribute__((address_space(3))) void*)(lds_tile + (wave * 8 + j) * 1024),
+                                     (__attribute__((address_space(3))) void*)(lds_tile + (wave * NL + j) * 1024),
                                      16, 0, 0);
 }
 
-// fragment of 8 k for the 32 rows starting at `r0` of an operand tile
-template <class T, bool KMAJOR>
+// fragment of 8 k for the 32 rows starting at `r0` of an operand tile of ROWS rows
+template <class T, bool KMAJOR, int ROWS>
 __device__ __forceinline__ typename Mf<T>::V8 read_frag(const char* lds_tile, int r0, int ks, int lane) {
   typedef typename Mf<T>::V8 V8;
   typedef typename Mf<T>::V4 V4;
@@ -100,13 +105,14 @@ __device__ __forceinline__ typename Mf<T>::V8 read_frag(const char* lds_tile, in
     const int kc = (ks * 2 + hf) ^ ((r >> 1) & 7);
     return *(const V8*)(lds_tile + r * 128 + kc * 16);
   } else {
+    constexpr int KROW = ROWS * 2;  // bytes per k row
     const int i16 = lane & 15, a = i16 >> 2, j4 = i16 & 3;
     const int nb = r0 + 16 * ((lane >> 4) & 1) + 4 * j4;  // first of the 4 rows this lane addresses
     const int kb = ks * 16 + 8 * hf;
     const int phys = (nb >> 3) ^ (4 * a);
-    const char* p0 = lds_tile + (kb + a) * 512 + phys * 16 + ((nb >> 2) & 1) * 8;
+    const char* p0 = lds_tile + (kb + a) * KROW + phys * 16 + ((nb >> 2) & 1) * 8;
     const V4 lo = Mf<T>::tr(p0);
-    const V4 hi = Mf<T>::tr(p0 + 4 * 512);
+    const V4 hi = Mf<T>::tr(p0 + 4 * KROW);
     V8 v;
 #pragma unroll
     for (int i = 0; i < 4; ++i) { v[i] = lo[i]; v[4 + i] = hi[i]; }
@@ -115,11 +121,15 @@ __device__ __forceinline__ typename Mf<T>::V8 read_frag(const char* lds_tile, in
 }
 
 // MODE 0: C (16-bit) = acc + bias;  1: C (fp32) = resid + acc + bias;  2: C (fp32) (+)= acc
-template <class T, bool AK, bool BK, int MODE>
+template <class T, int BM, int BN, bool AK, bool BK, int MODE>
 __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
   typedef typename Mf<T>::V8 V8;
+  constexpr int TM = BM, TN = BN;
+  constexpr int WM = BM / 2, WN = BN / 2;       // wavefront tile
+  constexpr int TI = WM / 32, TJ = WN / 32;     // 32x32 MFMA tiles per wavefront
+  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, BUF_BYTES = A_BYTES + B_BYTES;
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  // buffer b: A tile at smem + 2 b TILE_BYTES, B tile one TILE_BYTES after it
+  // buffer b: A tile at smem + b BUF_BYTES, B tile A_BYTES after it
 
   // workgroups that run at the same time share operand tiles through L2:
   // walk M fastest inside bands of 8 N tiles
@@ -136,74 +146,74 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
   const int tn = b0 + rem % bw, tm = rem / bw;
   const int m0 = tm * TM, n0 = tn * TN;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int wm = (wave >> 1) * 128, wn = (wave & 1) * 128;
+  const int wm = (wave >> 1) * WM, wn = (wave & 1) * WN;
   // uniform tile bases (bytes) and their advance per k step
   const char* a_base = (const char*)g.A + (AK ? (long)m0 * g.lda : (long)m0) * 2;
   const char* b_base = (const char*)g.B + (BK ? (long)n0 * g.ldb : (long)n0) * 2;
   const long a_step = (AK ? (long)TK : (long)TK * g.lda) * 2;
   const long b_step = (BK ? (long)TK : (long)TK * g.ldb) * 2;
-  uint32_t a_off[8], b_off[8];
-  tile_offsets<AK>(a_off, g.lda, m0, g.M, wave, lane);
-  tile_offsets<BK>(b_off, g.ldb, n0, g.N, wave, lane);
+  uint32_t a_off[BM / 32], b_off[BN / 32];
+  tile_offsets<AK, BM>(a_off, g.lda, m0, g.M, wave, lane);
+  tile_offsets<BK, BN>(b_off, g.ldb, n0, g.N, wave, lane);
 
-  f32x16 acc[4][4];
+  f32x16 acc[TI][TJ];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < TI; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < TJ; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   const int nk = g.K / TK;
-  issue_tile(a_base, a_off, smem, wave);
-  issue_tile(b_base, b_off, smem + TILE_BYTES, wave);
+  issue_tile<BM>(a_base, a_off, smem, wave);
+  issue_tile<BN>(b_base, b_off, smem + A_BYTES, wave);
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1;
     if (kt + 1 < nk) {
-      issue_tile(a_base + (kt + 1) * a_step, a_off, smem + (cur ^ 1) * 2 * TILE_BYTES, wave);
-      issue_tile(b_base + (kt + 1) * b_step, b_off, smem + (cur ^ 1) * 2 * TILE_BYTES + TILE_BYTES, wave);
+      issue_tile<BM>(a_base + (kt + 1) * a_step, a_off, smem + (cur ^ 1) * BUF_BYTES, wave);
+      issue_tile<BN>(b_base + (kt + 1) * b_step, b_off, smem + (cur ^ 1) * BUF_BYTES + A_BYTES, wave);
     }
-    const char* la = smem + cur * 2 * TILE_BYTES;
-    const char* lb = la + TILE_BYTES;
-    V8 fa[2][4], fb[2][4];
+    const char* la = smem + cur * BUF_BYTES;
+    const char* lb = la + A_BYTES;
+    V8 fa[2][TI], fb[2][TJ];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      fa[0][i] = read_frag<T, AK>(la, wm + i * 32, 0, lane);
-      fb[0][i] = read_frag<T, BK>(lb, wn + i * 32, 0, lane);
-    }
+    for (int i = 0; i < TI; ++i) fa[0][i] = read_frag<T, AK, BM>(la, wm + i * 32, 0, lane);
+#pragma unroll
+    for (int j = 0; j < TJ; ++j) fb[0][j] = read_frag<T, BK, BN>(lb, wn + j * 32, 0, lane);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const int c = ks & 1;
       if (ks + 1 < 4) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          fa[c ^ 1][i] = read_frag<T, AK>(la, wm + i * 32, ks + 1, lane);
-          fb[c ^ 1][i] = read_frag<T, BK>(lb, wn + i * 32, ks + 1, lane);
-        }
+        for (int i = 0; i < TI; ++i) fa[c ^ 1][i] = read_frag<T, AK, BM>(la, wm + i * 32, ks + 1, lane);
+#pragma unroll
+        for (int j = 0; j < TJ; ++j) fb[c ^ 1][j] = read_frag<T, BK, BN>(lb, wn + j * 32, ks + 1, lane);
       }
 #pragma unroll
-      for (int i = 0; i < 4; ++i)
+      for (int i = 0; i < TI; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = Mf<T>::run(fa[c][i], fb[c][j], acc[i][j]);
+        for (int j = 0; j < TJ; ++j) acc[i][j] = Mf<T>::run(fa[c][i], fb[c][j], acc[i][j]);
     }
     // Instruction order for this k step (the scheduler otherwise serialises each
     // LDS read with the MFMAs that use it): first fragments, then MFMAs with the
     // next fragments' LDS reads and the next tile's global loads threaded between.
-    constexpr int RA = AK ? 4 : 8, RB = BK ? 4 : 8;      // LDS reads per k sub-step
-    __builtin_amdgcn_sched_group_barrier(0x100, RA + RB, 0);
+    constexpr int RD = TI * (AK ? 1 : 2) + TJ * (BK ? 1 : 2);   // LDS reads per k sub-step
+    constexpr int NM = TI * TJ;                                   // MFMAs per k sub-step
+    constexpr int GRP = NM / 2;                                   // (2 MFMA + reads) groups
+    __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);
 #pragma unroll
     for (int ks = 0; ks < 3; ++ks) {
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
+      for (int u = 0; u < GRP; ++u) {
         __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, (RA + RB) / 8, 0);
-        if (ks == 0) __builtin_amdgcn_sched_group_barrier(0x020, 2, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, (RD + GRP - 1) / GRP, 0);
+        if (ks == 0) __builtin_amdgcn_sched_group_barrier(0x020, (BM + BN) / 32 / GRP, 0);
       }
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, 16, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, NM, 0);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
   }
@@ -211,13 +221,13 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
   const int col_in = lane & 31, row_in = (lane >> 5) * 4;
   const float alpha = g.alpha ? *g.alpha : 1.f;
 #pragma unroll
-  for (int j = 0; j < 4; ++j) {
+  for (int j = 0; j < TJ; ++j) {
     const int n = n0 + wn + j * 32 + col_in;
     if (n >= g.N) continue;
     float bv = 0.f;
     if (MODE != 2 && g.bias) bv = load_as_f(g.bias, n, g.bias_dtype);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < TI; ++i) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int m = m0 + wm + i * 32 + 8 * (e >> 2) + row_in + (e & 3);
@@ -236,16 +246,18 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
   }
 }
 
-template <class T, bool AK, bool BK, int MODE>
-ls_status launch(const DmaArgs& g, hipStream_t st) {
+template <class T, int BM, int BN, bool AK, bool BK, int MODE>
+ls_status launch(DmaArgs g, hipStream_t st) {
   static bool attr_set = false;
-  const int lds = 4 * TILE_BYTES;
+  const int lds = 2 * (BM + BN) * 128;
   if (!attr_set) {
-    LS_CHECK_HIP(hipFuncSetAttribute((const void*)gemm_dma_kernel<T, AK, BK, MODE>,
+    LS_CHECK_HIP(hipFuncSetAttribute((const void*)gemm_dma_kernel<T, BM, BN, AK, BK, MODE>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds));
     attr_set = true;
   }
-  gemm_dma_kernel<T, AK, BK, MODE><<<g.tiles_m * g.tiles_n, 256, lds, st>>>(g);
+  g.tiles_m = (g.M + BM - 1) / BM;
+  g.tiles_n = (g.N + BN - 1) / BN;
+  gemm_dma_kernel<T, BM, BN, AK, BK, MODE><<<g.tiles_m * g.tiles_n, 256, lds, st>>>(g);
   LS_CHECK_LAUNCH();
   return LS_OK;
 }
@@ -253,18 +265,26 @@ ls_status launch(const DmaArgs& g, hipStream_t st) {
 // the combinations a decoder block uses: forward (k-major x k-major, 16-bit or
 // residual output), input gradient (k-major x k-strided, 16-bit output), weight
 // gradient (k-strided x k-strided, fp32 output)
-template <class T>
-ls_status dispatch(const DmaArgs& g, hipStream_t st) {
+template <class T, int BM, int BN>
+ls_status dispatch_layout(const DmaArgs& g, hipStream_t st) {
   const int mode = g.c_dtype != LS_F32 ? 0 : (g.resid ? 1 : 2);
   if (mode == 2 && g.bias) return LS_ESTATE;
   if (mode == 1 && g.accumulate) return LS_ESTATE;
-  if (g.a_kmajor && g.b_kmajor && mode == 0) return launch<T, true, true, 0>(g, st);
-  if (g.a_kmajor && g.b_kmajor && mode == 1) return launch<T, true, true, 1>(g, st);
-  if (g.a_kmajor && g.b_kmajor && mode == 2) return launch<T, true, true, 2>(g, st);
-  if (g.a_kmajor && !g.b_kmajor && mode == 0) return launch<T, true, false, 0>(g, st);
-  if (g.a_kmajor && !g.b_kmajor && mode == 2) return launch<T, true, false, 2>(g, st);
-  if (!g.a_kmajor && !g.b_kmajor && mode == 2) return launch<T, false, false, 2>(g, st);
+  if (g.a_kmajor && g.b_kmajor && mode == 0) return launch<T, BM, BN, true, true, 0>(g, st);
+  if (g.a_kmajor && g.b_kmajor && mode == 1) return launch<T, BM, BN, true, true, 1>(g, st);
+  if (g.a_kmajor && g.b_kmajor && mode == 2) return launch<T, BM, BN, true, true, 2>(g, st);
+  if (g.a_kmajor && !g.b_kmajor && mode == 0) return launch<T, BM, BN, true, false, 0>(g, st);
+  if (g.a_kmajor && !g.b_kmajor && mode == 2) return launch<T, BM, BN, true, false, 2>(g, st);
+  if (!g.a_kmajor && !g.b_kmajor && mode == 2) return launch<T, BM, BN, false, false, 2>(g, st);
   return LS_ESTATE;
+}
+
+// 256 x 256 tiles when they still give most compute units a workgroup, else 128 x 128
+template <class T>
+ls_status dispatch(const DmaArgs& g, hipStream_t st) {
+  const long big = (long)((g.M + 255) / 256) * ((g.N + 255) / 256);
+  if (big >= 160) return dispatch_layout<T, 256, 256>(g, st);
+  return dispatch_layout<T, 128, 128>(g, st);
 }
 
 }  // namespace
@@ -275,9 +295,9 @@ ls_status gemm_dma_try(int op_dtype, int M, int N, int K, const void* A, long ld
                        const void* B, long ldb, int b_kmajor, void* C, long ldc, int c_dtype,
                        const void* bias, int bias_dtype, const float* resid, long ldr, int accumulate,
                        const float* alpha, hipStream_t st) {
-  if (K % TK != 0 || M < 8 || N < 8) return LS_ESTATE;
+  if (K % TK != 0 || M < 64 || N < 64) return LS_ESTATE;
   DmaArgs g{M, N, K, A, lda, a_kmajor, B, ldb, b_kmajor, C, ldc, c_dtype, bias, bias_dtype, resid, ldr,
-            accumulate, alpha, (M + TM - 1) / TM, (N + TN - 1) / TN};
+            accumulate, alpha, 0, 0};
   if (op_dtype == LS_BF16) return dispatch<bf16_t>(g, st);
   if (op_dtype == LS_F16) return dispatch<f16_t>(g, st);
   return LS_ESTATE;
