@@ -116,6 +116,36 @@ ls_status lsk_attn_bwd(int impl, const void* qkv, const void* o, const void* dO,
                        void* dqkv, float* dvec, void* stream);
 
 /*
+ * lsk_attn_bwd followed by the backward of the rotary embedding on the dq and
+ * dk parts of dqkv (each pair rotated by minus its position's angle: the
+ * rotation is orthogonal, so its transpose is the inverse rotation; RoFormer
+ * section 3.4.2 as used by the LLaMA block of Model Architecture).  pos[t]
+ * (device, int32[B*L]) must equal t mod L; table is the device
+ * [max_pos][head_dim/2][cos, sin] fp32 table, max_pos >= L.  The matrix-core
+ * kernels rotate in their stores; otherwise lsk_rope runs afterwards.
+ */
+ls_status lsk_attn_bwd_rope(int impl, const void* qkv, const void* o, const void* dO,
+                            const float* lse, int dtype, int B, int L, int n_heads,
+                            int head_dim, void* dqkv, float* dvec, const int32_t* pos,
+                            const float* table, void* stream);
+
+/*
+ * The LLaMA block's QKV projection with its rotary embedding (Model
+ * Architecture: attention sub-layer with rotary positions): qkv[T, 3d] =
+ * H[T, d] Wqkv[3d, d]^T in op_dtype (LS_F16 / LS_BF16; fp32 accumulation),
+ * then the pairs (i, i + head_dim/2) of every q and k head of row t rotated
+ * by pos[t].  All pointers are device memory; qkv is written in op_dtype.
+ * The rotation runs in the GEMM's epilogue on its fp32 accumulators when
+ * head_dim == 128 and the problem fills the chip with 256x256 tiles; otherwise
+ * the GEMM stores 16-bit values and lsk_rope rotates those in place (one more
+ * rounding; both are within the 16-bit tolerance).  LS_EINVAL on null
+ * pointers or d != n_heads * head_dim.
+ */
+ls_status lsk_gemm_qkv_rope(int op_dtype, int T, int d, const void* H, const void* Wqkv,
+                            void* qkv, int n_heads, int head_dim, const int32_t* pos,
+                            const float* table, void* stream);
+
+/*
  * Serving attention over the paged pool.  Row t of qkv[T, 3d] belongs to
  * request req[t] and sits at absolute position pos[t]; its K and V are first
  * written to the request's page, then its query attends to keys 0..pos[t].

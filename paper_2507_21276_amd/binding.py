@@ -88,6 +88,8 @@ SIGNATURES = {
     "lsk_attn_fwd": (_I, [_I, _VP, _I, _I, _I, _I, _I, _VP, _VP, _VP]),
     "lsk_attn_bwd": (_I, [_I, _VP, _VP, _VP, _VP, _I, _I, _I, _I, _I, _VP, _VP, _VP]),
     "lsk_attn_bwd_scratch_floats": (_SZ, [_I, _I, _I]),
+    "lsk_attn_bwd_rope": (_I, [_I, _VP, _VP, _VP, _VP, _I, _I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP]),
+    "lsk_gemm_qkv_rope": (_I, [_I, _I, _I, _VP, _VP, _VP, _I, _I, _VP, _VP, _VP]),
     "lsk_kv_write": (_I, [_VP, _I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP, _I, _I, _VP]),
     "lsk_attn_paged": (_I, [_I, _VP, _I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP, _I, _I, _I, _VP, _VP, _VP]),
     "lsk_attn_paged_scratch_floats": (_SZ, [_I, _I, _I, _I, _I]),
@@ -325,6 +327,17 @@ def lsk_attn_bwd(impl, qkv, o, dO, lse, B, L, n_heads, head_dim, dqkv, stream=No
     dvec = torch.empty(lib().lsk_attn_bwd_scratch_floats(B, L, n_heads), dtype=torch.float32, device=qkv.device)
     _check(lib().lsk_attn_bwd(impl, _p(qkv), _p(o), _p(dO), _p(lse), CODE_OF_TORCH[qkv.dtype], B, L,
                               n_heads, head_dim, _p(dqkv), _p(dvec), _stream(stream)))
+
+
+def lsk_attn_bwd_rope(impl, qkv, o, dO, lse, B, L, n_heads, head_dim, dqkv, pos, table, stream=None):
+    dvec = torch.empty(lib().lsk_attn_bwd_scratch_floats(B, L, n_heads), dtype=torch.float32, device=qkv.device)
+    _check(lib().lsk_attn_bwd_rope(impl, _p(qkv), _p(o), _p(dO), _p(lse), CODE_OF_TORCH[qkv.dtype], B, L,
+                                   n_heads, head_dim, _p(dqkv), _p(dvec), _p(pos), _p(table), _stream(stream)))
+
+
+def lsk_gemm_qkv_rope(h, w, qkv, n_heads, head_dim, pos, table, stream=None):
+    _check(lib().lsk_gemm_qkv_rope(CODE_OF_TORCH[h.dtype], h.shape[0], h.shape[1], _p(h), _p(w), _p(qkv),
+                                   n_heads, head_dim, _p(pos), _p(table), _stream(stream)))
 
 
 def lsk_kv_write(qkv, n_heads, head_dim, pos, req, k_pool, v_pool, block_table, page_size, stream=None):

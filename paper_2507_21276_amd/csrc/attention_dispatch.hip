@@ -11,7 +11,7 @@ ls_status lsk_attn_paged_simple(const void*, int, int, int, int, const int32_t*,
 
 ls_status lsk_attn_fwd_mfma(const void*, int, int, int, int, int, void*, float*, void*);
 ls_status lsk_attn_bwd_mfma(const void*, const void*, const void*, const float*, int, int, int, int, int,
-                            void*, float*, void*);
+                            void*, float*, const float*, void*);
 
 static bool mfma_ok(int impl, int dtype, int head_dim) {
   return impl == 1 && (dtype == LS_BF16 || dtype == LS_F16) && (head_dim == 64 || head_dim == 128);
@@ -27,8 +27,21 @@ ls_status lsk_attn_bwd(int impl, const void* qkv, const void* o, const void* dO,
                        int dtype, int B, int L, int n_heads, int head_dim, void* dqkv, float* dvec,
                        void* stream) {
   if (mfma_ok(impl, dtype, head_dim))
-    return lsk_attn_bwd_mfma(qkv, o, dO, lse, dtype, B, L, n_heads, head_dim, dqkv, dvec, stream);
+    return lsk_attn_bwd_mfma(qkv, o, dO, lse, dtype, B, L, n_heads, head_dim, dqkv, dvec, nullptr, stream);
   return lsk_attn_bwd_simple(qkv, o, dO, lse, dtype, B, L, n_heads, head_dim, dqkv, dvec, stream);
+}
+
+// Attention backward followed by the backward of the rotary embedding on dq and dk
+// (rotation by -pos[t]); pos[t] must be t mod L.  Fused into the matrix-core kernels' stores
+// when they apply, otherwise the in-place rotary kernel runs afterwards.
+ls_status lsk_attn_bwd_rope(int impl, const void* qkv, const void* o, const void* dO, const float* lse,
+                            int dtype, int B, int L, int n_heads, int head_dim, void* dqkv, float* dvec,
+                            const int32_t* pos, const float* table, void* stream) {
+  LS_REQUIRE(pos && table, "attn_bwd_rope: null rotary arguments");
+  if (mfma_ok(impl, dtype, head_dim))
+    return lsk_attn_bwd_mfma(qkv, o, dO, lse, dtype, B, L, n_heads, head_dim, dqkv, dvec, table, stream);
+  LS_TRY(lsk_attn_bwd_simple(qkv, o, dO, lse, dtype, B, L, n_heads, head_dim, dqkv, dvec, stream));
+  return lsk_rope(dqkv, dtype, B * L, n_heads, head_dim, pos, table, -1.0f, stream);
 }
 
 size_t lsk_attn_bwd_scratch_floats(int B, int L, int n_heads) {

@@ -427,13 +427,53 @@ struct TrStage {
   }
 };
 
+// Store one gradient row held as O^T-style accumulators (lane = row, registers = head
+// dimension j*32 + 8g + 4hf + i), multiplied by `mul`.  With a rotary table the row is first
+// rotated back by its position (the transpose of the forward rotation): the pair
+// (i, i + DH/2) lives in tiles j and j + DT/2 of the same lane.
+template <class T, int DH>
+__device__ __forceinline__ void store_grad_row(T* row, const f32x16 (&acc)[DH / 32], float mul, int hf,
+                                               const float* tab) {
+  typedef typename Mma<T>::V4 V4;
+  constexpr int DT = DH / 32;
+  if (tab == nullptr) {
+#pragma unroll
+    for (int j = 0; j < DT; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        V4 v;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = from_f<T>(acc[j][g * 4 + i] * mul);
+        *(V4*)(row + j * 32 + 8 * g + 4 * hf) = v;
+      }
+    return;
+  }
+#pragma unroll
+  for (int j = 0; j < DT / 2; ++j)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      const int i0 = j * 32 + 8 * g + 4 * hf;
+      const f32x4 cs0 = *(const f32x4*)(tab + i0 * 2), cs1 = *(const f32x4*)(tab + i0 * 2 + 4);
+      V4 lo, hi;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float c = i < 2 ? cs0[2 * i] : cs1[2 * (i - 2)], sn = i < 2 ? cs0[2 * i + 1] : cs1[2 * (i - 2) + 1];
+        const float a = acc[j][g * 4 + i] * mul, b = acc[j + DT / 2][g * 4 + i] * mul;
+        lo[i] = from_f<T>(a * c + b * sn);
+        hi[i] = from_f<T>(b * c - a * sn);
+      }
+      *(V4*)(row + i0) = lo;
+      *(V4*)(row + i0 + DH / 2) = hi;
+    }
+}
+
 template <class T, int DH>
 __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const T* __restrict__ qkv,
                                                            const T* __restrict__ dO,
                                                            const float* __restrict__ lse,
                                                            const float* __restrict__ dvec,
                                                            T* __restrict__ dqkv, int L, int h,
-                                                           float scale) {
+                                                           float scale, const float* __restrict__ rope) {
   typedef typename Mma<T>::V8 V8;
   typedef typename Mma<T>::V4 V4;
   constexpr int BQ = 128, KS = DH / 16, DT = DH / 32;
@@ -547,15 +587,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const T* __restrict__
   }
   if (q < L) {
     T* row = dqkv + ((long)b * L + q) * ld + (long)head * DH;
-#pragma unroll
-    for (int j = 0; j < DT; ++j)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        V4 v;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = from_f<T>(acc[j][g * 4 + i] * (scale / gsc));
-        *(V4*)(row + j * 32 + 8 * g + 4 * hf) = v;
-      }
+    store_grad_row<T, DH>(row, acc, scale / gsc, hf, rope ? rope + (long)q * DH : nullptr);
   }
 }
 
@@ -565,7 +597,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const T* __restrict_
                                                             const float* __restrict__ lse,
                                                             const float* __restrict__ dvec,
                                                             T* __restrict__ dqkv, int L, int h,
-                                                            float scale) {
+                                                            float scale, const float* __restrict__ rope) {
   typedef typename Mma<T>::V8 V8;
   typedef typename Mma<T>::V4 V4;
   constexpr int BKEY = 128, QR = 32, KS = DH / 16, DT = DH / 32;
@@ -701,24 +733,11 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const T* __restrict_
   }
   if (key < L) {
     T* rk = dqkv + ((long)b * L + key) * ld + d + (long)head * DH;
-    T* rv = rk + d;
-#pragma unroll
-    for (int j = 0; j < DT; ++j)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        V4 a, c;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          a[i] = from_f<T>(dk[j][g * 4 + i] * (scale / gsc));
-          c[i] = from_f<T>(dv[j][g * 4 + i] * (1.0f / gsc));
-        }
-        *(V4*)(rk + j * 32 + 8 * g + 4 * hf) = a;
-        *(V4*)(rv + j * 32 + 8 * g + 4 * hf) = c;
-      }
+    store_grad_row<T, DH>(rk, dk, scale / gsc, hf, rope ? rope + (long)key * DH : nullptr);
+    store_grad_row<T, DH>(rk + d, dv, 1.0f / gsc, hf, nullptr);
   }
 }
 
-// D[t, head] = sum_c dO * O, one wavefront per (row, head)
 // also records max|dO| per workgroup in dvec[n_items + blockIdx.x]; amax_finish_kernel
 // folds those into dvec[n_items + gridDim.x] (no atomics: deterministic and contention-free)
 template <class T>
@@ -755,7 +774,7 @@ __global__ __launch_bounds__(256) void amax_finish_kernel(float* blockmax, long 
 
 template <class T, int DH>
 ls_status launch_bwd(const void* qkv, const void* o, const void* dO, const float* lse, int B, int L, int h,
-                     void* dqkv, float* dvec, hipStream_t st) {
+                     void* dqkv, float* dvec, const float* rope, hipStream_t st) {
   const float scale = 1.0f / sqrtf((float)DH);
   const long items = (long)B * L * h;
   const long nb = (items + 3) / 4;
@@ -763,9 +782,9 @@ ls_status launch_bwd(const void* qkv, const void* o, const void* dO, const float
   amax_finish_kernel<<<1, 256, 0, st>>>(dvec + items, nb);
   LS_CHECK_LAUNCH();
   dim3 gq((L + 127) / 128, B * h), gk((L + 127) / 128, B * h);
-  flash_bwd_dq_kernel<T, DH><<<gq, 256, 0, st>>>((const T*)qkv, (const T*)dO, lse, dvec, (T*)dqkv, L, h, scale);
+  flash_bwd_dq_kernel<T, DH><<<gq, 256, 0, st>>>((const T*)qkv, (const T*)dO, lse, dvec, (T*)dqkv, L, h, scale, rope);
   LS_CHECK_LAUNCH();
-  flash_bwd_dkv_kernel<T, DH><<<gk, 256, 0, st>>>((const T*)qkv, (const T*)dO, lse, dvec, (T*)dqkv, L, h, scale);
+  flash_bwd_dkv_kernel<T, DH><<<gk, 256, 0, st>>>((const T*)qkv, (const T*)dO, lse, dvec, (T*)dqkv, L, h, scale, rope);
   LS_CHECK_LAUNCH();
   return LS_OK;
 }
@@ -807,16 +826,18 @@ extern "C" ls_status lsk_attn_prefill_mfma(const void* qkv, int dt, int n_req, c
                   : launch_prefill<f16_t, 128>(qkv, h, o, pg, max_chunk, st);
 }
 
+// rope_table (nullable): [position][head_dim/2][cos, sin]; when given, dq and dk are rotated back
+// by their positions before they are stored (the backward of the rotary embedding, fused)
 extern "C" ls_status lsk_attn_bwd_mfma(const void* qkv, const void* o, const void* dO, const float* lse,
                                        int dt, int B, int L, int h, int dh, void* dqkv, float* dvec,
-                                       void* stream) {
+                                       const float* rope_table, void* stream) {
   LS_REQUIRE(qkv && o && dO && lse && dqkv && dvec && B > 0 && L > 0 && h > 0, "attn_bwd: bad argument");
   LS_REQUIRE(dt == LS_BF16 || dt == LS_F16, "attn_bwd: the matrix-core kernel needs 16-bit operands");
   LS_REQUIRE(dh == 64 || dh == 128, "attn_bwd: the matrix-core kernel needs head_dim 64 or 128");
   LS_REQUIRE((long)B * h <= 65535, "attn_bwd: B * n_heads exceeds the grid limit");
   hipStream_t st = (hipStream_t)stream;
-  if (dt == LS_BF16) return dh == 64 ? launch_bwd<bf16_t, 64>(qkv, o, dO, lse, B, L, h, dqkv, dvec, st)
-                                     : launch_bwd<bf16_t, 128>(qkv, o, dO, lse, B, L, h, dqkv, dvec, st);
-  return dh == 64 ? launch_bwd<f16_t, 64>(qkv, o, dO, lse, B, L, h, dqkv, dvec, st)
-                  : launch_bwd<f16_t, 128>(qkv, o, dO, lse, B, L, h, dqkv, dvec, st);
+  if (dt == LS_BF16) return dh == 64 ? launch_bwd<bf16_t, 64>(qkv, o, dO, lse, B, L, h, dqkv, dvec, rope_table, st)
+                                     : launch_bwd<bf16_t, 128>(qkv, o, dO, lse, B, L, h, dqkv, dvec, rope_table, st);
+  return dh == 64 ? launch_bwd<f16_t, 64>(qkv, o, dO, lse, B, L, h, dqkv, dvec, rope_table, st)
+                  : launch_bwd<f16_t, 128>(qkv, o, dO, lse, B, L, h, dqkv, dvec, rope_table, st);
 }

@@ -186,15 +186,25 @@ __global__ __launch_bounds__(256) void norm_bwd_apply_kernel(int kind, const TD*
   Ld8<float>::store(p + d, db);
 }
 
-__global__ void norm_bwd_finish_kernel(const float* partial, int nwg, int d, float* dgamma,
-                                       float* dbeta, int accumulate, const float* alpha) {
-  const int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i >= d) return;
+// 64 columns x 4 row groups per workgroup; the four partial sums of a column are combined in
+// a fixed order through LDS
+__global__ __launch_bounds__(256) void norm_bwd_finish_kernel(const float* partial, int nwg, int d, float* dgamma,
+                                                              float* dbeta, int accumulate, const float* alpha) {
+  __shared__ float sg[4][64], sb[4][64];
+  const int cl = threadIdx.x & 63, rg = threadIdx.x >> 6;
+  const int i = blockIdx.x * 64 + cl;
   float g = 0.f, b = 0.f;
-  for (int w = 0; w < nwg; ++w) {
-    g += partial[(size_t)w * 2 * d + i];
-    b += partial[(size_t)w * 2 * d + d + i];
-  }
+  if (i < d)
+    for (int w = rg; w < nwg; w += 4) {
+      g += partial[(size_t)w * 2 * d + i];
+      b += partial[(size_t)w * 2 * d + d + i];
+    }
+  sg[rg][cl] = g;
+  sb[rg][cl] = b;
+  __syncthreads();
+  if (rg != 0 || i >= d) return;
+  g = (sg[0][cl] + sg[1][cl]) + (sg[2][cl] + sg[3][cl]);
+  b = (sb[0][cl] + sb[1][cl]) + (sb[2][cl] + sb[3][cl]);
   if (alpha) { g *= *alpha; b *= *alpha; }
   if (dgamma) dgamma[i] = accumulate ? dgamma[i] + g : g;
   if (dbeta) dbeta[i] = accumulate ? dbeta[i] + b : b;
@@ -377,7 +387,7 @@ ls_status lsk_norm_bwd_scaled(int kind, const void* dh, int dhdt, const float* x
   LS_CHECK_LAUNCH();
   if (dgamma || dbeta) {
     const int nchunk = (T + NB_ROWS - 1) / NB_ROWS;
-    norm_bwd_finish_kernel<<<(d + 255) / 256, 256, 0, st>>>(partial, nchunk, d, dgamma,
+    norm_bwd_finish_kernel<<<(d + 63) / 64, 256, 0, st>>>(partial, nchunk, d, dgamma,
                                                             kind == 0 ? dbeta : nullptr, accumulate, alpha_dev);
     LS_CHECK_LAUNCH();
   }

@@ -287,7 +287,8 @@ ls_status dispatch_mfma(const GemmArgs& g, hipStream_t st) {
 }  // namespace
 
 ls_status gemm_dma_try(int, int, int, int, const void*, long, int, const void*, long, int, void*, long, int,
-                       const void*, int, const float*, long, int, const float*, hipStream_t);
+                       const void*, int, const float*, long, int, const float*, const int32_t*, const float*, int,
+                       hipStream_t);
 
 // LS_GEMM_IMPL=staged forces the register-staged kernel (for A/B comparisons)
 static bool use_dma_kernel() {
@@ -326,7 +327,7 @@ extern "C" ls_status lsk_gemm_scaled(int op_dtype, int M, int N, int K, const vo
   LS_REQUIRE(c_dtype == LS_F32 || c_dtype == op_dtype, "gemm: output type must be fp32 or the operand type");
   if (use_dma_kernel() && M >= 256) {
     const ls_status r = gemm_dma_try(op_dtype, M, N, K, A, lda, a_kmajor, B, ldb, b_kmajor, C, ldc, c_dtype, bias,
-                                     bias_dtype, resid, ldr, accumulate, alpha_dev, st);
+                                     bias_dtype, resid, ldr, accumulate, alpha_dev, nullptr, nullptr, 0, st);
     if (r != LS_ESTATE) return r;
   }
   if (op_dtype == LS_BF16) return dispatch_mfma<bf16_t>(g, st);
@@ -341,4 +342,24 @@ extern "C" ls_status lsk_gemm(int op_dtype, int M, int N, int K, const void* A, 
                               int accumulate, void* stream) {
   return lsk_gemm_scaled(op_dtype, M, N, K, A, lda, a_kmajor, B, ldb, b_kmajor, C, ldc, c_dtype, bias,
                          bias_dtype, resid, ldr, accumulate, nullptr, stream);
+}
+
+// QKV projection with the rotary embedding of q and k fused into the epilogue
+// (head_dim 128, no bias): qkv[T, 3d] = h1 Wqkv^T, then the pairs (i, i + 64) of
+// every q and k head of row t rotated by pos[t] * theta^(-2i/128).  Falls back to
+// the plain GEMM followed by the in-place rotary kernel for shapes the fused
+// epilogue does not cover.
+extern "C" ls_status lsk_gemm_qkv_rope(int op_dtype, int T, int d, const void* H, const void* Wqkv, void* qkv,
+                                       int n_heads, int head_dim, const int32_t* pos, const float* table,
+                                       void* stream) {
+  LS_REQUIRE(H && Wqkv && qkv && pos && table && T > 0 && d == n_heads * head_dim, "gemm_qkv_rope: bad argument");
+  hipStream_t st = (hipStream_t)stream;
+  if (use_dma_kernel() && head_dim == 128 && T >= 256 && (long)((T + 255) / 256) * ((3 * d + 255) / 256) >= 160 &&
+      (op_dtype == LS_BF16 || op_dtype == LS_F16)) {
+    const ls_status r = gemm_dma_try(op_dtype, T, 3 * d, d, H, d, 1, Wqkv, d, 1, qkv, 3 * d, op_dtype, nullptr, 0,
+                                     nullptr, 0, 0, nullptr, pos, table, 2 * d, st);
+    if (r != LS_ESTATE) return r;
+  }
+  LS_TRY(lsk_gemm(op_dtype, T, 3 * d, d, H, d, 1, Wqkv, d, 1, qkv, 3 * d, op_dtype, nullptr, 0, nullptr, 0, 0, stream));
+  return lsk_rope(qkv, op_dtype, T, n_heads, head_dim, pos, table, 1.0f, stream);
 }

@@ -52,6 +52,8 @@ struct DmaArgs {
   int accumulate;
   const float* alpha;
   int tiles_m, tiles_n;
+  // MODE 3 only: rotary embedding of the columns below rope_cols (heads of 128)
+  const int32_t* rope_pos; const float* rope_table; int rope_cols;
 };
 
 constexpr int TK = 64;  // k extent of a tile; a tile of ROWS rows is ROWS * 128 bytes = ROWS / 8 wave loads
@@ -120,7 +122,10 @@ __device__ __forceinline__ typename Mf<T>::V8 read_frag(const char* lds_tile, in
   }
 }
 
-// MODE 0: C (16-bit) = acc + bias;  1: C (fp32) = resid + acc + bias;  2: C (fp32) (+)= acc
+// MODE 0: C (16-bit) = acc + bias;  1: C (fp32) = resid + acc + bias;  2: C (fp32) (+)= acc;
+// MODE 3: as 0 without bias, and the half-split rotary embedding (head_dim 128) applied to the
+//         columns below rope_cols: a wavefront's 128 columns are one head, so the pair
+//         (c, c + 64) sits in accumulator tiles j and j + 2 of the same lane
 template <class T, int BM, int BN, bool AK, bool BK, int MODE>
 __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
   typedef typename Mf<T>::V8 V8;
@@ -220,6 +225,33 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
 
   const int col_in = lane & 31, row_in = (lane >> 5) * 4;
   const float alpha = g.alpha ? *g.alpha : 1.f;
+  if (MODE == 3) {
+    if constexpr (TJ == 4) {
+      const bool rot = n0 + wn < g.rope_cols;   // q or k section: uniform over the wavefront
+#pragma unroll
+      for (int i = 0; i < TI; ++i) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          const int m = m0 + wm + i * 32 + 8 * (e >> 2) + row_in + (e & 3);
+          if (m >= g.M) continue;
+          const float* tab = g.rope_table + (long)g.rope_pos[m] * 128;   // 64 (cos, sin) pairs
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            const int n = n0 + wn + j * 32 + col_in;
+            float a = acc[i][j][e], b = acc[i][j + 2][e];
+            if (rot) {
+              const float c = tab[(j * 32 + col_in) * 2], sn = tab[(j * 32 + col_in) * 2 + 1];
+              const float ra = a * c - b * sn, rb = b * c + a * sn;
+              a = ra; b = rb;
+            }
+            if (n < g.N) ((T*)g.C)[(long)m * g.ldc + n] = from_f<T>(a);
+            if (n + 64 < g.N) ((T*)g.C)[(long)m * g.ldc + n + 64] = from_f<T>(b);
+          }
+        }
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int j = 0; j < TJ; ++j) {
     const int n = n0 + wn + j * 32 + col_in;
@@ -267,6 +299,11 @@ ls_status launch(DmaArgs g, hipStream_t st) {
 // gradient (k-strided x k-strided, fp32 output)
 template <class T, int BM, int BN>
 ls_status dispatch_layout(const DmaArgs& g, hipStream_t st) {
+  if (g.rope_table) {
+    if (BM == 256 && g.a_kmajor && g.b_kmajor && g.c_dtype != LS_F32 && !g.bias)
+      return launch<T, 256, 256, true, true, 3>(g, st);
+    return LS_ESTATE;
+  }
   const int mode = g.c_dtype != LS_F32 ? 0 : (g.resid ? 1 : 2);
   if (mode == 2 && g.bias) return LS_ESTATE;
   if (mode == 1 && g.accumulate) return LS_ESTATE;
@@ -294,10 +331,11 @@ ls_status dispatch(const DmaArgs& g, hipStream_t st) {
 ls_status gemm_dma_try(int op_dtype, int M, int N, int K, const void* A, long lda, int a_kmajor,
                        const void* B, long ldb, int b_kmajor, void* C, long ldc, int c_dtype,
                        const void* bias, int bias_dtype, const float* resid, long ldr, int accumulate,
-                       const float* alpha, hipStream_t st) {
+                       const float* alpha, const int32_t* rope_pos, const float* rope_table, int rope_cols,
+                       hipStream_t st) {
   if (K % TK != 0 || M < 64 || N < 64) return LS_ESTATE;
   DmaArgs g{M, N, K, A, lda, a_kmajor, B, ldb, b_kmajor, C, ldc, c_dtype, bias, bias_dtype, resid, ldr,
-            accumulate, alpha, 0, 0};
+            accumulate, alpha, 0, 0, rope_pos, rope_table, rope_cols};
   if (op_dtype == LS_BF16) return dispatch<bf16_t>(g, st);
   if (op_dtype == LS_F16) return dispatch<f16_t>(g, st);
   return LS_ESTATE;

@@ -97,29 +97,39 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs g) {
     }
   };
 
-  V8 wf[NSTEP];
+  // weight fragments of two chunks are always in flight (rolling prefetch, distance 2 chunks)
+  V8 wf[2][NSTEP];
 #pragma unroll
-  for (int u = 0; u < NSTEP; ++u) wf[u] = load_w(k_lo, u);
+  for (int u = 0; u < NSTEP; ++u) wf[0][u] = load_w(k_lo, u);
+#pragma unroll
+  for (int u = 0; u < NSTEP; ++u) wf[1][u] = load_w(k_lo + KC, u);
   load_x(k_lo);
   store_x(0);
   __syncthreads();
   int buf = 0;
-  for (int k0 = k_lo; k0 < k_hi; k0 += KC, buf ^= 1) {
-    const bool more = k0 + KC < k_hi;
-    if (more) load_x(k0 + KC);
-    const T* xb = xs + buf * (MP * XSTR);
+  for (int k0 = k_lo; k0 < k_hi; k0 += 2 * KC) {
 #pragma unroll
-    for (int u = 0; u < NSTEP; ++u) {
-      const V8 w = wf[u];
-      if (more) wf[u] = load_w(k0 + KC, u);
+    for (int half = 0; half < 2; ++half) {
+      const int kc0 = k0 + half * KC;
+      if (kc0 < k_hi) {     // uniform across the workgroup
+        const bool more = kc0 + KC < k_hi;
+        if (more) load_x(kc0 + KC);
+        const T* xb = xs + buf * (MP * XSTR);
 #pragma unroll
-      for (int t = 0; t < MT; ++t) {
-        const V8 xf = *(const V8*)(xb + (t * 16 + r16) * XSTR + u * 32 + kc);
-        acc[t] = Mfma16<T>::run(w, xf, acc[t]);
+        for (int u = 0; u < NSTEP; ++u) {
+          const V8 w = wf[half][u];
+          wf[half][u] = load_w(kc0 + 2 * KC, u);   // zero-filled past the slab
+#pragma unroll
+          for (int t = 0; t < MT; ++t) {
+            const V8 xf = *(const V8*)(xb + (t * 16 + r16) * XSTR + u * 32 + kc);
+            acc[t] = Mfma16<T>::run(w, xf, acc[t]);
+          }
+        }
+        if (more) store_x(buf ^ 1);   // the other buffer was last read one chunk ago
+        __syncthreads();
+        buf ^= 1;
       }
     }
-    if (more) store_x(buf ^ 1);   // the other buffer was last read one iteration ago
-    __syncthreads();
   }
   // accumulator: column (lane % 16) = batch row m, rows 4 * (lane / 16) + e = weight row
   const int nb = blockIdx.x * 64 + wave * 16 + (lane >> 4) * 4;

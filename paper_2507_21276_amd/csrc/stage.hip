@@ -37,6 +37,10 @@ ls_status lsk_norm_bwd_scaled(int, const void*, int, const float*, const float*,
 ls_status lsk_colsum_scaled(const void*, int, int, int, long, float*, int, float*, const float*, void*);
 ls_status lsk_attn_prefill_mfma(const void*, int, int, const int32_t*, int, int, const void*, const void*,
                                 const int32_t*, const int32_t*, int, int, void*, void*);
+ls_status lsk_gemm_qkv_rope(int, int, int, const void*, const void*, void*, int, int, const int32_t*, const float*,
+                            void*);
+ls_status lsk_attn_bwd_rope(int, const void*, const void*, const void*, const float*, int, int, int, int, int,
+                            void*, float*, const int32_t*, const float*, void*);
 ls_status lsk_rope_kv_write(void*, int, int, int, int, const int32_t*, const int32_t*, const float*, void*, void*,
                             const int32_t*, int, int, void*);
 }
@@ -237,14 +241,21 @@ ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const
   const int nk = gpt ? 0 : 1;
   LS_TRY(lsk_norm_fwd(nk, f.x, T, d, pptr(s, o.n1_g), gpt ? pptr(s, o.n1_b) : nullptr, pt, c.norm_eps,
                       f.h1, mt, f.mean1, f.rstd1, st));
-  LS_TRY(linear(s, T, 3 * d, d, f.h1, wptr(s, o.w_qkv), f.qkv, mt, gpt ? pptr(s, o.b_qkv) : nullptr, nullptr,
-                f.scratch, st));
-  if (!gpt && !kv) LS_TRY(lsk_rope(f.qkv, mt, T, c.n_heads, c.head_dim, pos, s->rope_table, 1.0f, st));
+  const bool roped = !gpt && mt != LS_F32 && (!kv || T >= 256);
+  if (roped) {
+    // training and prompt chunks: rotary embedding fused into the projection's epilogue where the
+    // tile shape allows
+    LS_TRY(lsk_gemm_qkv_rope(mt, T, d, f.h1, wptr(s, o.w_qkv), f.qkv, c.n_heads, c.head_dim, pos, s->rope_table, st));
+  } else {
+    LS_TRY(linear(s, T, 3 * d, d, f.h1, wptr(s, o.w_qkv), f.qkv, mt, gpt ? pptr(s, o.b_qkv) : nullptr, nullptr,
+                  f.scratch, st));
+    if (!gpt && !kv) LS_TRY(lsk_rope(f.qkv, mt, T, c.n_heads, c.head_dim, pos, s->rope_table, 1.0f, st));
+  }
   if (kv) {
     const size_t slab = (size_t)kv->n_pages * c.n_heads * c.page_size * c.head_dim * osz(s);
     void* kp = (char*)kv->k_pool + (size_t)l * slab;
     void* vp = (char*)kv->v_pool + (size_t)l * slab;
-    LS_TRY(lsk_rope_kv_write(f.qkv, mt, T, c.n_heads, c.head_dim, pos, req, gpt ? nullptr : s->rope_table, kp, vp,
+    LS_TRY(lsk_rope_kv_write(f.qkv, mt, T, c.n_heads, c.head_dim, pos, req, gpt || roped ? nullptr : s->rope_table, kp, vp,
                              kv->block_table, kv->max_pages_per_req, c.page_size, st));
     if (chunk_start && mt != LS_F32 && c.head_dim >= 64) {
       // prompt chunks: matrix-core attention over the pages (queries of a chunk share the K/V tiles)
@@ -524,9 +535,12 @@ ls_status stage_train_bwd(ls_stage* s, const void* dY, int B, int L, const void*
     LS_TRY(lsk_gemm(mt, T, d, d, w.g16, d, 1, wptr(s, o.w_o), d, 0, w.d_o, d, mt, nullptr, 0, nullptr, 0, 0, st));
     LS_TRY(lsk_gemm_scaled(mt, d, d, T, w.g16, d, 0, v.o, d, 0, dParams + o.w_o, d, LS_F32, nullptr, 0, nullptr, 0, acc, inv, st));
     if (gpt) LS_TRY(lsk_colsum_scaled(w.g16, mt, T, d, d, dParams + o.b_o, acc, w.partial, inv, st));
-    LS_TRY(lsk_attn_bwd(mt == LS_F32 ? 0 : 1, v.qkv, v.o, w.d_o, v.lse, mt, B, L, c.n_heads, c.head_dim, w.dqkv,
-                        w.dvec, st));
-    if (!gpt) LS_TRY(lsk_rope(w.dqkv, mt, T, c.n_heads, c.head_dim, w.pos, s->rope_table, -1.0f, st));
+    if (gpt)
+      LS_TRY(lsk_attn_bwd(mt == LS_F32 ? 0 : 1, v.qkv, v.o, w.d_o, v.lse, mt, B, L, c.n_heads, c.head_dim, w.dqkv,
+                          w.dvec, st));
+    else
+      LS_TRY(lsk_attn_bwd_rope(mt == LS_F32 ? 0 : 1, v.qkv, v.o, w.d_o, v.lse, mt, B, L, c.n_heads, c.head_dim,
+                               w.dqkv, w.dvec, w.pos, s->rope_table, st));
     // qkv = h1 W_qkv^T (+ b_qkv)
     LS_TRY(lsk_gemm(mt, T, d, 3 * d, w.dqkv, 3 * d, 1, wptr(s, o.w_qkv), d, 0, w.dh, d, mt, nullptr, 0, nullptr, 0, 0, st));
     LS_TRY(lsk_gemm_scaled(mt, 3 * d, d, T, w.dqkv, 3 * d, 0, v.h1, d, 0, dParams + o.w_qkv, d, LS_F32, nullptr, 0, nullptr, 0, acc, inv, st));

@@ -294,6 +294,65 @@ def test_attention_forward_and_backward(impl, name, B, L, h, dh):
 
 
 @pytest.mark.parametrize("impl", [0, 1])
+@pytest.mark.parametrize("name,B,L,h,dh", [("f32", 2, 40, 2, 32), ("f16", 2, 200, 3, 64), ("bf16", 1, 300, 2, 128),
+                                             ("f16", 3, 129, 2, 128)])
+def test_attention_backward_with_rotary_backward(impl, name, B, L, h, dh):
+    """dq and dk leave the kernel rotated back by their positions (rotation transposed)."""
+    if impl == 1 and name == "f32":
+        pytest.skip("matrix-core attention is 16-bit only")
+    d = h * dh
+    qkv = q(S.normal(17, "qkv", (B * L, 3 * d)), name)
+    dO = q(S.normal(17, "dO", (B * L, d)), name)
+    _, _, Ps = attn_ref(qkv, B, L, h, dh)
+    pos = np.tile(np.arange(L), B)
+    ref = np.empty((B * L, 3 * d))
+    for b, (qq, kk, vv, P) in enumerate(Ps):
+        dq, dk, dv = O.attention_bwd(dO[b * L:(b + 1) * L].astype(np.float64).reshape(L, h, dh), qq, kk, vv, P)
+        dq, dk = (O.rope(g, np.arange(L), 1e4, -1.0) for g in (dq, dk))
+        ref[b * L:(b + 1) * L] = np.concatenate([dq.reshape(L, d), dk.reshape(L, d), dv.reshape(L, d)], 1)
+    qd = dev(qkv, DT[name])
+    o = torch.empty(B * L, d, dtype=DT[name], device="cuda")
+    lse = torch.empty(B * L, h, dtype=torch.float32, device="cuda")
+    Bd.lsk_attn_fwd(impl, qd, B, L, h, dh, o, lse)
+    dqkv = torch.empty(B * L, 3 * d, dtype=DT[name], device="cuda")
+    Bd.lsk_attn_bwd_rope(impl, qd, o, dev(dO, DT[name]), lse, B, L, h, dh, dqkv,
+                         torch.as_tensor(pos, dtype=torch.int32, device="cuda"),
+                         dev(rope_table(L + 3, dh), torch.float32))
+    got = host(dqkv)
+    for i, nm in enumerate(("dq", "dk", "dv")):
+        r_ = ref[:, i * d:(i + 1) * d]
+        assert_close(got[:, i * d:(i + 1) * d], r_, otol(name, r_, 1e-4), nm + " (rotary backward)")
+
+
+@pytest.mark.parametrize("name", ["f16", "bf16"])
+@pytest.mark.parametrize("T,h,dh", [(70, 2, 64), (300, 3, 128), (4096, 32, 128), (2304, 16, 128)])
+def test_qkv_projection_with_fused_rotary_embedding(name, T, h, dh):
+    """(4096, 32, 128) is the training launch configuration with the rotation in the GEMM epilogue
+    (checked on sampled rows); the small shapes take the GEMM + in-place rotation route."""
+    d = h * dh
+    dt = DT[name]
+    hd = S.normal_torch(21, "h", (T, d), 1.0, dtype=dt)
+    wd = S.normal_torch(21, "w", (3 * d, d), d ** -0.5, dtype=dt)
+    pos = S.uniform_ints(21, "pos", T, 0, 2047).astype(np.int32)
+    qkv = torch.empty(T, 3 * d, dtype=dt, device="cuda")
+    Bd.lsk_gemm_qkv_rope(hd, wd, qkv, h, dh, torch.as_tensor(pos, device="cuda"),
+                         dev(rope_table(2048, dh), torch.float32))
+    rows = np.arange(T) if T <= 300 else np.unique(np.concatenate(
+        [[0, 1, 127, 128, 255, 256, T - 1], S.uniform_ints(22, "rows", 40, 0, T - 1)]))
+    W = host(wd)
+    ref = host(hd[torch.as_tensor(rows, device="cuda")]) @ W.T
+    for part in (0, 1):
+        blk = ref[:, part * d:(part + 1) * d].reshape(len(rows), h, dh)
+        ref[:, part * d:(part + 1) * d] = O.rope(blk, pos[rows], 1e4, 1.0).reshape(len(rows), d)
+    got = host(qkv[torch.as_tensor(rows, device="cuda")])
+    # two 16-bit roundings on the unfused route (GEMM output, then the rotated value)
+    tol = otol(name, ref) + out_rounding_bound(ref, name)
+    for part, nm in enumerate(("q", "k", "v")):
+        sl = slice(part * d, (part + 1) * d)
+        assert_close(got[:, sl], ref[:, sl], tol, "qkv+rope " + nm)
+
+
+@pytest.mark.parametrize("impl", [0, 1])
 @pytest.mark.parametrize("name,h,dh,P", [("f32", 4, 32, 16), ("f16", 2, 128, 16), ("bf16", 3, 64, 8)])
 def test_paged_attention_ragged(impl, name, h, dh, P):
     if impl == 1 and name == "f32":
