@@ -1,8 +1,9 @@
 // Large-tile MFMA GEMM whose operand tiles go from global memory straight into
 // LDS (16-byte direct-to-LDS loads, no register staging, no LDS store
-// instructions).  256 x 256 x 64 tiles (4 wavefronts of 128 x 128) or 128 x 128 x 64 tiles
-// (4 wavefronts of 64 x 64) for problems with few tiles, 32x32x16 MFMA, two LDS buffers.  Used when the contraction length is a multiple of
-// 64; the register-staged kernel in gemm.hip covers everything else.
+// instructions).  256 x 256 x 64 tiles (4 wavefronts of 128 x 128) or 128 x 128 x 64
+// tiles (4 wavefronts of 64 x 64) for problems with few tiles, 32x32x16 MFMA, two
+// LDS buffers.  Used when the contraction length is a multiple of 64; the
+// register-staged kernel in gemm.hip covers everything else.
 //
 // LDS layouts (a direct-to-LDS wave load writes 1 KB: lane i -> bytes 16 i):
 //   k-major operand  (element (r,k) at r*ld + k): [256 rows][64 k], 128 B per
@@ -13,6 +14,13 @@
 //     k, chunk index XOR-permuted with 4 * (k & 3).  Fragments are read with the
 //     transposing LDS load (4 k x 16 rows per 16 lanes), two per 8 k.
 // The permutations are applied by choosing which global chunk each lane fetches.
+//
+// With one wavefront per SIMD nothing hides a stalled wavefront, so the k loop is
+// software-pipelined by hand: the next tile's loads are issued a few at a time
+// between the MFMAs of the first half of a tile (a burst of 16 loads blocks the
+// wavefront on the address path for about as long as the tile's MFMAs take), the
+// LDS reads of the next fragments run under the current MFMAs, and the single
+// workgroup barrier per tile sits before the last quarter of the MFMAs.
 #include "common.h"
 
 namespace {
@@ -96,16 +104,41 @@ __device__ __forceinline__ void issue_tile(const char* tile_base, const uint32_t
                                      16, 0, 0);
 }
 
-// fragment of 8 k for the 32 rows starting at `r0` of an operand tile of ROWS rows
+// load `l` (0 .. (BM + BN) / 32 - 1) of a wavefront's share of the A and B tiles
+template <int BM, int BN>
+__device__ __forceinline__ void issue_one(int l, const char* a_tile, const uint32_t (&a_off)[BM / 32],
+                                          const char* b_tile, const uint32_t (&b_off)[BN / 32], char* lds_a,
+                                          char* lds_b, int wave) {
+  constexpr int NA = BM / 32, NB = BN / 32;
+  if (l < NA)
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a_tile + a_off[l]),
+                                     (__attribute__((address_space(3))) void*)(lds_a + (wave * NA + l) * 1024),
+                                     16, 0, 0);
+  else
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(b_tile + b_off[l - NA]),
+                                     (__attribute__((address_space(3))) void*)(lds_b + (wave * NB + l - NA) * 1024),
+                                     16, 0, 0);
+}
+
+// One operand fragment: 8 k for 32 rows of an operand tile.
+//  - k-major tiles: one ordinary 16-byte LDS load, tracked by the compiler.
+//  - k-strided tiles: two transposing LDS loads.  These are issued from inline assembly: before
+//    the builtin form the compiler waits for every direct-to-LDS load in flight (it cannot tell
+//    that the tile being filled is another one), which serialises loads and arithmetic.  The
+//    assembly form is invisible to the compiler's wait-count bookkeeping, so wait_frags() must
+//    run between the reads and the first use; it redefines the registers, which pins the order.
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+template <class T, bool KMAJOR> struct Frag { typename Mf<T>::V8 v; };
+template <class T> struct Frag<T, false> { s16x4 lo, hi; };
+
 template <class T, bool KMAJOR, int ROWS>
-__device__ __forceinline__ typename Mf<T>::V8 read_frag(const char* lds_tile, int r0, int ks, int lane) {
+__device__ __forceinline__ void read_frag(Frag<T, KMAJOR>& f, const char* lds_tile, int r0, int ks, int lane) {
   typedef typename Mf<T>::V8 V8;
-  typedef typename Mf<T>::V4 V4;
   const int hf = lane >> 5;
-  if (KMAJOR) {
+  if constexpr (KMAJOR) {
     const int r = r0 + (lane & 31);
     const int kc = (ks * 2 + hf) ^ ((r >> 1) & 7);
-    return *(const V8*)(lds_tile + r * 128 + kc * 16);
+    f.v = *(const V8*)(lds_tile + r * 128 + kc * 16);
   } else {
     constexpr int KROW = ROWS * 2;  // bytes per k row
     const int i16 = lane & 15, a = i16 >> 2, j4 = i16 & 3;
@@ -113,12 +146,32 @@ __device__ __forceinline__ typename Mf<T>::V8 read_frag(const char* lds_tile, in
     const int kb = ks * 16 + 8 * hf;
     const int phys = (nb >> 3) ^ (4 * a);
     const char* p0 = lds_tile + (kb + a) * KROW + phys * 16 + ((nb >> 2) & 1) * 8;
-    const V4 lo = Mf<T>::tr(p0);
-    const V4 hi = Mf<T>::tr(p0 + 4 * KROW);
-    V8 v;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) { v[i] = lo[i]; v[4 + i] = hi[i]; }
-    return v;
+    const uint32_t addr = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p0;
+    asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(f.lo) : "v"(addr) : "memory");
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(f.hi) : "v"(addr), "n"(4 * KROW) : "memory");
+  }
+}
+
+template <class T, bool KMAJOR, int N>
+__device__ __forceinline__ void wait_frags(Frag<T, KMAJOR> (&f)[N]) {
+  static_assert(N == 2 || N == 4, "fragment count");
+  if constexpr (!KMAJOR) {
+    if constexpr (N == 4)
+      asm volatile("s_waitcnt lgkmcnt(0)"
+                   : "+v"(f[0].lo), "+v"(f[0].hi), "+v"(f[1].lo), "+v"(f[1].hi), "+v"(f[2].lo), "+v"(f[2].hi),
+                     "+v"(f[3].lo), "+v"(f[3].hi));
+    else
+      asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0].lo), "+v"(f[0].hi), "+v"(f[1].lo), "+v"(f[1].hi));
+  }
+}
+
+template <class T, bool KMAJOR>
+__device__ __forceinline__ typename Mf<T>::V8 frag_value(const Frag<T, KMAJOR>& f) {
+  if constexpr (KMAJOR) {
+    return f.v;
+  } else {
+    const s16x8 w = __builtin_shufflevector(f.lo, f.hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(typename Mf<T>::V8, w);
   }
 }
 
@@ -150,7 +203,7 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
   const int rem = bid % per_band;
   const int tn = b0 + rem % bw, tm = rem / bw;
   const int m0 = tm * TM, n0 = tn * TN;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int wm = (wave >> 1) * WM, wn = (wave & 1) * WN;
   // uniform tile bases (bytes) and their advance per k step
   const char* a_base = (const char*)g.A + (AK ? (long)m0 * g.lda : (long)m0) * 2;
@@ -175,53 +228,76 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
   __builtin_amdgcn_s_waitcnt(0);
   __syncthreads();
 
+  // Software pipeline of one k tile (4 sub-steps of 16 k): while the MFMAs of a sub-step run, the
+  // fragments of the next one are read from LDS, and during the first LDKS sub-steps the next
+  // tile's direct-to-LDS loads are issued, a few per chunk of two MFMAs (a burst would stall the
+  // wavefront, and with it the matrix pipe, on the address path).  The workgroup barrier sits
+  // before the last sub-step: by then every wavefront holds its last fragments of the current
+  // tile in registers, so the fragments read during the last sub-step come from the next tile.
+  // Chunks are fenced with scheduling barriers: the source order below is the issue order.
+  constexpr int NM = TI * TJ;            // MFMAs per k sub-step
+  constexpr int GRP = NM / 2;            // chunks of two MFMAs
+  constexpr int NF = TI + TJ;            // fragments per k sub-step
+  constexpr int RCH = GRP > 2 ? GRP * 3 / 4 : 1;  // chunks that carry fragment reads (the rest cover their latency)
+  constexpr int NLD = (BM + BN) / 32;    // direct-to-LDS loads per tile and wavefront
+  constexpr int LDKS = 2;                // k sub-steps over which they are issued
+  Frag<T, AK> fa[2][TI];
+  Frag<T, BK> fb[2][TJ];
+#pragma unroll
+  for (int i = 0; i < TI; ++i) read_frag<T, AK, BM>(fa[0][i], smem, wm + i * 32, 0, lane);
+#pragma unroll
+  for (int j = 0; j < TJ; ++j) read_frag<T, BK, BN>(fb[0][j], smem + A_BYTES, wn + j * 32, 0, lane);
+
   for (int kt = 0; kt < nk; ++kt) {
     const int cur = kt & 1;
-    if (kt + 1 < nk) {
-      issue_tile<BM>(a_base + (kt + 1) * a_step, a_off, smem + (cur ^ 1) * BUF_BYTES, wave);
-      issue_tile<BN>(b_base + (kt + 1) * b_step, b_off, smem + (cur ^ 1) * BUF_BYTES + A_BYTES, wave);
-    }
     const char* la = smem + cur * BUF_BYTES;
     const char* lb = la + A_BYTES;
-    V8 fa[2][TI], fb[2][TJ];
-#pragma unroll
-    for (int i = 0; i < TI; ++i) fa[0][i] = read_frag<T, AK, BM>(la, wm + i * 32, 0, lane);
-#pragma unroll
-    for (int j = 0; j < TJ; ++j) fb[0][j] = read_frag<T, BK, BN>(lb, wn + j * 32, 0, lane);
+    char* na = smem + (cur ^ 1) * BUF_BYTES;
+    char* nb = na + A_BYTES;
+    // the tile after the last is the last again: fetched, never multiplied
+    const int tn = kt + 1 < nk ? kt + 1 : kt;
+    const char* ga = a_base + tn * a_step;
+    const char* gb = b_base + tn * b_step;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const int c = ks & 1;
-      if (ks + 1 < 4) {
-#pragma unroll
-        for (int i = 0; i < TI; ++i) fa[c ^ 1][i] = read_frag<T, AK, BM>(la, wm + i * 32, ks + 1, lane);
-#pragma unroll
-        for (int j = 0; j < TJ; ++j) fb[c ^ 1][j] = read_frag<T, BK, BN>(lb, wn + j * 32, ks + 1, lane);
+      wait_frags<T, AK, TI>(fa[c]);
+      wait_frags<T, BK, TJ>(fb[c]);
+      if (ks == 3) {
+        __builtin_amdgcn_s_waitcnt(0);   // this wavefront's share of the next tile has landed
+        __syncthreads();
       }
+      V8 va[TI], vb[TJ];
 #pragma unroll
-      for (int i = 0; i < TI; ++i)
+      for (int i = 0; i < TI; ++i) va[i] = frag_value<T, AK>(fa[c][i]);
 #pragma unroll
-        for (int j = 0; j < TJ; ++j) acc[i][j] = Mf<T>::run(fa[c][i], fb[c][j], acc[i][j]);
-    }
-    // Instruction order for this k step (the scheduler otherwise serialises each
-    // LDS read with the MFMAs that use it): first fragments, then MFMAs with the
-    // next fragments' LDS reads and the next tile's global loads threaded between.
-    constexpr int RD = TI * (AK ? 1 : 2) + TJ * (BK ? 1 : 2);   // LDS reads per k sub-step
-    constexpr int NM = TI * TJ;                                   // MFMAs per k sub-step
-    constexpr int GRP = NM / 2;                                   // (2 MFMA + reads) groups
-    __builtin_amdgcn_sched_group_barrier(0x100, RD, 0);
-#pragma unroll
-    for (int ks = 0; ks < 3; ++ks) {
+      for (int j = 0; j < TJ; ++j) vb[j] = frag_value<T, BK>(fb[c][j]);
+      const char* ra = ks < 3 ? la : na;
+      const char* rb = ks < 3 ? lb : nb;
+      const int kn = (ks + 1) & 3;
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int u = 0; u < GRP; ++u) {
-        __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, (RD + GRP - 1) / GRP, 0);
-        if (ks == 0) __builtin_amdgcn_sched_group_barrier(0x020, (BM + BN) / 32 / GRP, 0);
+#pragma unroll
+        for (int m = 2 * u; m < 2 * u + 2; ++m) acc[m / TJ][m % TJ] = Mf<T>::run(va[m / TJ], vb[m % TJ], acc[m / TJ][m % TJ]);
+        __builtin_amdgcn_sched_barrier(0);   // MFMAs first: the memory operations issue in their shadow
+#pragma unroll
+        for (int r = 0; r < NF; ++r) {
+          if (r * RCH / NF != u) continue;
+          if (r < TI) read_frag<T, AK, BM>(fa[c ^ 1][r], ra, wm + r * 32, kn, lane);
+          else read_frag<T, BK, BN>(fb[c ^ 1][r - TI], rb, wn + (r - TI) * 32, kn, lane);
+        }
+        if (ks < LDKS) {
+          const int sl = ks * GRP + u;
+#pragma unroll
+          for (int l = sl * NLD / (LDKS * GRP); l < (sl + 1) * NLD / (LDKS * GRP); ++l)
+            issue_one<BM, BN>(l, ga, a_off, gb, b_off, na, nb, wave);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, NM, 0);
-    __builtin_amdgcn_s_waitcnt(0);
-    __syncthreads();
   }
+  __builtin_amdgcn_s_waitcnt(0);
 
   const int col_in = lane & 31, row_in = (lane >> 5) * 4;
   const float alpha = g.alpha ? *g.alpha : 1.f;
