@@ -279,7 +279,7 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
 #pragma unroll
       for (int u = 0; u < GRP; ++u) {
 #pragma unroll
-        for (int m = 2 * u; m < 2 * u + 2; ++m) acc[m / TJ][m % TJ] = Mf<T>::run(va[m / TJ], vb[m % TJ], acc[m / TJ][m % TJ]);
+        for (int m = 2 * u; m < 2 * u + 2; ++m) acc[m / TJ][m % TJ] = Mf<T>::run(vb[m % TJ], va[m / TJ], acc[m / TJ][m % TJ]);
         __builtin_amdgcn_sched_barrier(0);   // MFMAs first: the memory operations issue in their shadow
 #pragma unroll
         for (int r = 0; r < NF; ++r) {
@@ -299,56 +299,106 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
   }
   __builtin_amdgcn_s_waitcnt(0);
 
-  const int col_in = lane & 31, row_in = (lane >> 5) * 4;
+  // Epilogue.  The MFMAs ran with the operands swapped, so the accumulators hold C^T tiles:
+  // lane -> row m (lane & 31), register 4 q + e -> column 8 q + 4 (lane >> 5) + e.  Storing
+  // from that layout touches 32 rows per instruction, 16 bytes in each, which the memory
+  // pipeline takes far longer over than over the same bytes as whole cache lines.  So each
+  // wavefront stages its tile in its quarter of the (now idle) LDS, row-major with the 16-byte
+  // chunks of a row XOR-permuted by the row number, and writes it out as full rows; residual
+  // and accumulation operands are read with the same coalesced pattern.
+  typedef typename Mf<T>::V4 V4;
+  constexpr int ESZ = (MODE == 0 || MODE == 3) ? 2 : 4;
+  constexpr int REGION = (BM + BN) * 128 * 2 / 4;   // bytes of LDS per wavefront
+  constexpr int ROWB = WN * ESZ;                    // bytes of a staged row
+  constexpr int CPR = ROWB / 16;                    // 16-byte chunks per row
+  constexpr int NPASS = (WM * ROWB + REGION - 1) / REGION;
+  constexpr int TIP = TI / NPASS;                   // 32-row MFMA tiles per pass
+  constexpr int ROWS_P = TIP * 32;
+  const int row_in = lane & 31, hf = lane >> 5;
   const float alpha = g.alpha ? *g.alpha : 1.f;
-  if (MODE == 3) {
-    if constexpr (TJ == 4) {
-      const bool rot = n0 + wn < g.rope_cols;   // q or k section: uniform over the wavefront
+  __syncthreads();   // every wavefront is done with the operand tiles
+  char* stg = smem + wave * REGION;
 #pragma unroll
-      for (int i = 0; i < TI; ++i) {
+  for (int pass = 0; pass < NPASS; ++pass) {
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int m = m0 + wm + i * 32 + 8 * (e >> 2) + row_in + (e & 3);
-          if (m >= g.M) continue;
-          const float* tab = g.rope_table + (long)g.rope_pos[m] * 128;   // 64 (cos, sin) pairs
+    for (int ii = 0; ii < TIP; ++ii) {
+      const int i = pass * TIP + ii;
+      const int r = ii * 32 + row_in;
+      char* srow = stg + r * ROWB;
+      const int sw = r & (CPR - 1);
+      if constexpr (MODE == 3) {
+        if constexpr (TJ == 4) {
+          const int m = min(m0 + wm + i * 32 + row_in, g.M - 1);   // rows past the edge are staged, never stored
+          const bool rot = n0 + wn < g.rope_cols;   // q or k section: uniform over the wavefront
+          const float* tab = g.rope_table + (long)g.rope_pos[m] * 128 + 8 * hf;   // 64 (cos, sin) pairs
 #pragma unroll
-          for (int j = 0; j < 2; ++j) {
-            const int n = n0 + wn + j * 32 + col_in;
-            float a = acc[i][j][e], b = acc[i][j + 2][e];
-            if (rot) {
-              const float c = tab[(j * 32 + col_in) * 2], sn = tab[(j * 32 + col_in) * 2 + 1];
-              const float ra = a * c - b * sn, rb = b * c + a * sn;
-              a = ra; b = rb;
+          for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              V4 lo, hi;
+              if (rot) {
+                const f32x4 cs0 = *(const f32x4*)(tab + (j * 32 + 8 * q) * 2);
+                const f32x4 cs1 = *(const f32x4*)(tab + (j * 32 + 8 * q) * 2 + 4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  const float c = e < 2 ? cs0[2 * e] : cs1[2 * (e - 2)];
+                  const float sn = e < 2 ? cs0[2 * e + 1] : cs1[2 * (e - 2) + 1];
+                  const float a = acc[i][j][4 * q + e], bb = acc[i][j + 2][4 * q + e];
+                  lo[e] = from_f<T>(a * c - bb * sn);
+                  hi[e] = from_f<T>(bb * c + a * sn);
+                }
+              } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                  lo[e] = from_f<T>(acc[i][j][4 * q + e]);
+                  hi[e] = from_f<T>(acc[i][j + 2][4 * q + e]);
+                }
+              }
+              *(V4*)(srow + (((j * 4 + q) ^ sw) * 16) + hf * 8) = lo;
+              *(V4*)(srow + (((j * 4 + q + 8) ^ sw) * 16) + hf * 8) = hi;
             }
-            if (n < g.N) ((T*)g.C)[(long)m * g.ldc + n] = from_f<T>(a);
-            if (n + 64 < g.N) ((T*)g.C)[(long)m * g.ldc + n + 64] = from_f<T>(b);
-          }
         }
+      } else {
+#pragma unroll
+        for (int j = 0; j < TJ; ++j)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            f32x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e] * alpha;
+            if (MODE != 2 && g.bias) {
+              const int n = n0 + wn + j * 32 + 8 * q + 4 * hf;
+#pragma unroll
+              for (int e = 0; e < 4; ++e)
+                if (n + e < g.N) v[e] += load_as_f(g.bias, n + e, g.bias_dtype);
+            }
+            if constexpr (ESZ == 2) {
+              V4 o;
+#pragma unroll
+              for (int e = 0; e < 4; ++e) o[e] = from_f<T>(v[e]);
+              *(V4*)(srow + (((j * 4 + q) ^ sw) * 16) + hf * 8) = o;
+            } else {
+              *(f32x4*)(srow + (((j * 8 + 2 * q + hf) ^ sw) * 16)) = v;
+            }
+          }
       }
     }
-    return;
-  }
+    // full rows out: 64 / CPR rows per instruction, 16 bytes per lane
 #pragma unroll
-  for (int j = 0; j < TJ; ++j) {
-    const int n = n0 + wn + j * 32 + col_in;
-    if (n >= g.N) continue;
-    float bv = 0.f;
-    if (MODE != 2 && g.bias) bv = load_as_f(g.bias, n, g.bias_dtype);
-#pragma unroll
-    for (int i = 0; i < TI; ++i) {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int m = m0 + wm + i * 32 + 8 * (e >> 2) + row_in + (e & 3);
-        if (m >= g.M) continue;
-        const long ci = (long)m * g.ldc + n;
-        if (MODE == 0) {
-          ((T*)g.C)[ci] = from_f<T>(acc[i][j][e] * alpha + bv);
-        } else if (MODE == 1) {
-          ((float*)g.C)[ci] = acc[i][j][e] * alpha + bv + g.resid[(long)m * g.ldr + n];
-        } else {
-          float* c = (float*)g.C;
-          c[ci] = g.accumulate ? c[ci] + acc[i][j][e] * alpha : acc[i][j][e] * alpha;
-        }
+    for (int it = 0; it < ROWS_P * CPR / 64; ++it) {
+      const int idx = it * 64 + lane;
+      const int r = idx / CPR, c = idx % CPR;
+      const int m = m0 + wm + pass * ROWS_P + r;
+      const int n = n0 + wn + c * (16 / ESZ);
+      if (m >= g.M || n >= g.N) continue;
+      const f32x4 v = *(const f32x4*)(stg + r * ROWB + ((c ^ (r & (CPR - 1))) * 16));
+      if constexpr (ESZ == 2) {
+        *(f32x4*)((T*)g.C + (long)m * g.ldc + n) = v;
+      } else if constexpr (MODE == 1) {
+        *(f32x4*)((float*)g.C + (long)m * g.ldc + n) = v + *(const f32x4*)(g.resid + (long)m * g.ldr + n);
+      } else {
+        f32x4* cp = (f32x4*)((float*)g.C + (long)m * g.ldc + n);
+        *cp = g.accumulate ? *cp + v : v;
       }
     }
   }
@@ -410,6 +460,10 @@ ls_status gemm_dma_try(int op_dtype, int M, int N, int K, const void* A, long ld
                        const float* alpha, const int32_t* rope_pos, const float* rope_table, int rope_cols,
                        hipStream_t st) {
   if (K % TK != 0 || M < 64 || N < 64) return LS_ESTATE;
+  // the epilogue stores 16-byte pieces of rows
+  const int per16 = c_dtype == LS_F32 ? 4 : 8;
+  if (N % per16 != 0 || ldc % per16 != 0 || (uintptr_t)C % 16 != 0) return LS_ESTATE;
+  if (resid && (ldr % 4 != 0 || (uintptr_t)resid % 16 != 0)) return LS_ESTATE;
   DmaArgs g{M, N, K, A, lda, a_kmajor, B, ldb, b_kmajor, C, ldc, c_dtype, bias, bias_dtype, resid, ldr,
             accumulate, alpha, 0, 0, rope_pos, rope_table, rope_cols};
   if (op_dtype == LS_BF16) return dispatch<bf16_t>(g, st);
