@@ -591,6 +591,83 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const T* __restrict__
   }
 }
 
+// ---- tiles brought in by direct-to-LDS loads ------------------------------------------------
+// A tile is ROWS rows of DH 16-bit elements, row-major in LDS, the 16-byte chunks of a row
+// XOR-permuted by the row number so that both kinds of fragment read are conflict-free:
+//   - 16-byte reads of 8 consecutive head-dimension elements (operand rows = tile rows), and
+//   - transposing reads (operand rows = head dimension, contraction over the tile rows).
+// A wave load writes 1 KB (lane i -> bytes 16 i), i.e. 1024 / (2 DH) whole rows.
+typedef short s16x4_t __attribute__((ext_vector_type(4)));
+typedef short s16x8_t __attribute__((ext_vector_type(8)));
+
+// Chunk permutation of a tile row.  16 consecutive rows (one phase of a 16-byte fragment read)
+// must get 16 different bank groups, and 4 consecutive rows (one phase of a transposing read,
+// which takes a pair of adjacent chunks from each) 4 different chunk pairs.
+template <int DH> __device__ __forceinline__ int tile_swz(int row) {
+  return DH == 128 ? (((row & 7) << 1) | ((row >> 3) & 1)) : ((((row >> 1) & 3) << 1) | ((row >> 3) & 1));
+}
+
+// wave load `l` of a tile whose first row is global row `row0` (rows past `nrows` re-read the last row)
+template <class T, int DH>
+__device__ __forceinline__ void dma_rows(const T* base, long ld, int row0, int nrows, char* lds_tile, int l,
+                                         int lane) {
+  constexpr int CPR = DH / 8, RPL = 64 / CPR;
+  const int row = l * RPL + lane / CPR;
+  const int gch = (lane % CPR) ^ tile_swz<DH>(row);
+  const int gr = min(row0 + row, nrows - 1);
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + (long)gr * ld + gch * 8),
+                                   (__attribute__((address_space(3))) void*)(lds_tile + l * 1024), 16, 0, 0);
+}
+
+// 64 floats, one per lane: element i of a strided vector (stride in floats) -> LDS float i
+__device__ __forceinline__ void dma_floats(const float* base, long stride, int i0, int n, char* lds, int lane) {
+  const int i = min(i0 + lane, n - 1);
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + (long)i * stride),
+                                   (__attribute__((address_space(3))) void*)lds, 4, 0, 0);
+}
+
+// fragment for operand rows = tile rows: row (of the tile) and the 8 head-dimension elements 8 c .. 8 c + 7
+template <class T, int DH>
+__device__ __forceinline__ typename Mma<T>::V8 frag_rows(const char* tile, int row, int c) {
+  return *(const typename Mma<T>::V8*)(tile + row * (DH * 2) + ((c ^ tile_swz<DH>(row)) * 16));
+}
+
+// Fragment for operand rows = head dimension d0 .. d0 + 31, contraction over tile rows
+// k0 + 8 (lane >> 5) .. + 7: two transposing LDS reads.  They are issued from inline assembly
+// (the builtin form makes the compiler wait for all direct-to-LDS loads in flight), so the
+// registers are only valid after tr_wait() has been applied to them.
+struct TrFrag { s16x4_t lo, hi; };
+template <int DH>
+__device__ __forceinline__ void tr_read(TrFrag& f, const char* tile, int d0, int k0, int lane) {
+  const int i16 = lane & 15, a = i16 >> 2, j4 = i16 & 3;
+  const int nb = d0 + 16 * ((lane >> 4) & 1) + 4 * j4;   // first of the 4 head-dimension elements of this lane
+  const int k = k0 + 8 * (lane >> 5) + a;
+  const char* p0 = tile + k * (DH * 2) + (((nb >> 3) ^ tile_swz<DH>(k)) * 16) + ((nb >> 2) & 1) * 8;
+  const char* p1 = tile + (k + 4) * (DH * 2) + (((nb >> 3) ^ tile_swz<DH>(k + 4)) * 16) + ((nb >> 2) & 1) * 8;
+  const uint32_t a0 = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p0;
+  const uint32_t a1 = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p1;
+  asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(f.lo) : "v"(a0) : "memory");
+  asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(f.hi) : "v"(a1) : "memory");
+}
+__device__ __forceinline__ void tr_wait(TrFrag (&f)[4]) {
+  asm volatile("s_waitcnt lgkmcnt(0)"
+               : "+v"(f[0].lo), "+v"(f[0].hi), "+v"(f[1].lo), "+v"(f[1].hi), "+v"(f[2].lo), "+v"(f[2].hi),
+                 "+v"(f[3].lo), "+v"(f[3].hi));
+}
+__device__ __forceinline__ void tr_wait(TrFrag (&f)[2]) {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(f[0].lo), "+v"(f[0].hi), "+v"(f[1].lo), "+v"(f[1].hi));
+}
+template <class T>
+__device__ __forceinline__ typename Mma<T>::V8 tr_value(const TrFrag& f) {
+  const s16x8_t w = __builtin_shufflevector(f.lo, f.hi, 0, 1, 2, 3, 4, 5, 6, 7);
+  return __builtin_bit_cast(typename Mma<T>::V8, w);
+}
+
+// dK, dV.  A workgroup owns 128 keys (32 per wavefront, K and V fragments in registers) and walks
+// the query tiles of 64 rows that can see them.  Q, dO, the log-sum-exp and D of a tile arrive by
+// direct-to-LDS loads through a ring of NS stages (three tiles in flight); the transposed
+// operands dO^T and Q^T of the second pair of products are read from the same tiles with the
+// transposing LDS load.  dS is scaled by a power of two before it is rounded to 16 bits.
 template <class T, int DH>
 __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const T* __restrict__ qkv,
                                                             const T* __restrict__ dO,
@@ -599,18 +676,16 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const T* __restrict_
                                                             T* __restrict__ dqkv, int L, int h,
                                                             float scale, const float* __restrict__ rope) {
   typedef typename Mma<T>::V8 V8;
-  typedef typename Mma<T>::V4 V4;
-  constexpr int BKEY = 128, QR = 32, KS = DH / 16, DT = DH / 32;
-  constexpr int NSTR = DH + 8, TSTR = QR + 8;
-  __shared__ __attribute__((aligned(16))) T q_lds[2][QR * NSTR];
-  __shared__ __attribute__((aligned(16))) T do_lds[2][QR * NSTR];
-  __shared__ __attribute__((aligned(16))) T qt_lds[2][DH * TSTR];
-  __shared__ __attribute__((aligned(16))) T dot_lds[2][DH * TSTR];
-  __shared__ __attribute__((aligned(16))) float lse_lds[2][QR];
-  __shared__ __attribute__((aligned(16))) float dv_lds[2][QR];
+  constexpr int BKEY = 128, QR = 64, NS = 4, KS = DH / 16, DT = DH / 32;
+  constexpr int TILE_B = QR * DH * 2;            // bytes of a Q or dO tile
+  constexpr int STAGE_B = 2 * TILE_B + 512;      // Q, dO, 64 log-sum-exp, 64 D
+  constexpr int NLT = TILE_B / 1024 / 4;         // wave loads per wavefront and tile
+  constexpr int NLD = 2 * NLT + 2;               // loads per wavefront and stage
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
 
-  const int ktile = blockIdx.x;
-  const int b = blockIdx.y / h, head = blockIdx.y % h;
+  // key tiles in grid.y (dispatched slowest): the long workgroups of all heads start first
+  const int ktile = blockIdx.y;
+  const int b = blockIdx.x / h, head = blockIdx.x % h;
   const int d = h * DH;
   const long ld = 3L * d;
   const T* qb = qkv + (long)b * L * ld + (long)head * DH;
@@ -619,12 +694,12 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const T* __restrict_
   const T* dob = dO + (long)b * L * d + (long)head * DH;
   const float* lseb = lse + (long)b * L * h + head;
   const float* dvb = dvec + (long)b * L * h + head;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int col = lane & 31, hf = lane >> 5;
   const int wk0 = ktile * BKEY + wave * 32;
   const int key = wk0 + col;
   const float scale_log2 = scale * 1.4426950408889634f;
-  const float gsc = do_scale(dvec + (long)gridDim.y * L + ((long)gridDim.y * L + 3) / 4);
+  const float gsc = do_scale(dvec + (long)gridDim.x * L + ((long)gridDim.x * L + 3) / 4);
 
   V8 kf[KS], vf[KS];
 #pragma unroll
@@ -642,99 +717,106 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const T* __restrict_
   for (int j = 0; j < DT; ++j)
 #pragma unroll
     for (int e = 0; e < 16; ++e) dk[j][e] = dv[j][e] = 0.f;
+  const unsigned vis = (unsigned)max(L - key, 0);   // queries key .. L - 1 see this lane's key
 
-  const int qt_first = (ktile * BKEY) / QR;       // first query tile that can see these keys
-  const int n_qt = (L + QR - 1) / QR;
-  NatStage<T, QR, DH> sq, sdo;
-  TrStage<T, QR, DH> tq, tdo;
-  constexpr int TB = TrStage<T, QR, DH>::NBLK;     // threads per transposed tile
-  float st_l = 0.f, st_d = 0.f;
-  auto load_tile = [&](int qt) {
-    const int q0 = qt * QR;
-    sq.load(qb, ld, q0, L);
-    sdo.load(dob, d, q0, L);
-    sdo.scale(gsc);
-    tq.load(qb, ld, q0, L, 0);
-    tdo.load(dob, d, q0, L, TB);
-    if ((int)threadIdx.x >= TB && (int)threadIdx.x < 2 * TB) tdo.scale(gsc);
-    if (threadIdx.x < QR) {
-      const int qq = q0 + threadIdx.x;
-      st_l = qq < L ? lseb[(long)qq * h] * 1.4426950408889634f : INFINITY;
-      st_d = qq < L ? dvb[(long)qq * h] * gsc : 0.f;
+  // the wait counts below assume that only direct-to-LDS loads are in flight
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  const int qt_first = (ktile * BKEY) / QR;   // first query tile that can see these keys
+  const int nt = (L + QR - 1) / QR - qt_first;
+  // tile t of this workgroup -> stage t % NS; tiles past the end re-fetch the last one (never
+  // used), so that every wavefront always has the same number of loads in flight
+  auto issue = [&](int t) {
+    const int q0 = (qt_first + min(t, nt - 1)) * QR;
+    char* st = smem + (t % NS) * STAGE_B;
+#pragma unroll
+    for (int j = 0; j < NLT; ++j) {
+      dma_rows<T, DH>(qb, ld, q0, L, st, wave * NLT + j, lane);
+      dma_rows<T, DH>(dob, d, q0, L, st + TILE_B, wave * NLT + j, lane);
     }
+    dma_floats(lseb, h, q0, L, st + 2 * TILE_B, lane);          // every wavefront writes the same values
+    dma_floats(dvb, h, q0, L, st + 2 * TILE_B + 256, lane);
   };
-  auto store_tile = [&](int buf) {
-    sq.store(q_lds[buf]);
-    sdo.store(do_lds[buf]);
-    tq.store(qt_lds[buf], 0);
-    tdo.store(dot_lds[buf], TB);
-    if (threadIdx.x < QR) {
-      lse_lds[buf][threadIdx.x] = st_l;
-      dv_lds[buf][threadIdx.x] = st_d;
-    }
-  };
-  if (qt_first < n_qt) {
-    load_tile(qt_first);
-    store_tile(0);
-  }
+#pragma unroll
+  for (int t = 0; t < NS; ++t) issue(t);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 1) * NLD) : "memory");
   __syncthreads();
 
-  for (int qt = qt_first; qt < n_qt; ++qt) {
-    const int cur = (qt - qt_first) & 1, q0 = qt * QR;
-    if (qt + 1 < n_qt) load_tile(qt + 1);
-    if (q0 + QR - 1 >= wk0) {   // some query of the tile can see some key of this wavefront
-      const T* qs = q_lds[cur];
-      const T* dos = do_lds[cur];
-      f32x16 sacc, pacc;
+  for (int t = 0; t < nt; ++t) {
+    const int q0 = (qt_first + t) * QR;
+    const char* qs = smem + (t % NS) * STAGE_B;
+    const char* dos = qs + TILE_B;
+    const float* lses = (const float*)(qs + 2 * TILE_B);
+    const float* ds_ = lses + 64;
+    {
+      // the tile's 64 queries in two blocks of 32 (keeps the live registers within one wavefront's share)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) sacc[e] = pacc[e] = 0.f;
+      for (int c = 0; c < 2; ++c) {
+        // S = Q K^T and dP = dO V^T for 32 queries x 32 keys; MFMA row r is query pi(r), which
+        // makes a lane's 8 values per 16-query step consecutive queries
+        f32x16 sacc, pacc;
 #pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        const int row = pi_row(col) * NSTR + s * 16 + hf * 8;
-        sacc = Mma<T>::run(*(const V8*)(qs + row), kf[s], sacc);
-        pacc = Mma<T>::run(*(const V8*)(dos + row), vf[s], pacc);
-      }
-      // element e <-> query q0 + 16*(e/8) + 8*hf + e%8, column <-> key
-      const bool diag = q0 < wk0 + 31;
-      V8 pf[2], dsf[2];
+        for (int e = 0; e < 16; ++e) sacc[e] = pacc[e] = 0.f;
+        const int row = c * 32 + pi_row(col);
 #pragma unroll
-      for (int g = 0; g < 2; ++g) {
-        const f32x4 l0 = *(const f32x4*)&lse_lds[cur][16 * g + 8 * hf];
-        const f32x4 l1 = *(const f32x4*)&lse_lds[cur][16 * g + 8 * hf + 4];
-        const f32x4 d0 = *(const f32x4*)&dv_lds[cur][16 * g + 8 * hf];
-        const f32x4 d1 = *(const f32x4*)&dv_lds[cur][16 * g + 8 * hf + 4];
-        V8 tp, td;
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const int e = g * 8 + i;
-          const float lq = i < 4 ? l0[i & 3] : l1[i & 3];
-          const float dq = i < 4 ? d0[i & 3] : d1[i & 3];
-          float p = __builtin_amdgcn_exp2f(sacc[e] * scale_log2 - lq);
-          if (diag && key > q0 + 16 * g + 8 * hf + i) p = 0.f;
-          tp[i] = from_f<T>(p);
-          td[i] = from_f<T>(p * (pacc[e] - dq));
+        for (int s = 0; s < KS; ++s) {
+          sacc = Mma<T>::run(frag_rows<T, DH>(qs, row, 2 * s + hf), kf[s], sacc);
+          pacc = Mma<T>::run(frag_rows<T, DH>(dos, row, 2 * s + hf), vf[s], pacc);
         }
-        pf[g] = tp;
-        dsf[g] = td;
-      }
-      const T* qts = qt_lds[cur];
-      const T* dots = dot_lds[cur];
+        // first transposed fragments of this block: their latency hides behind the exponentials
+        TrFrag fr[2][DT];
 #pragma unroll
-      for (int kk = 0; kk < 2; ++kk)
+        for (int j = 0; j < DT; ++j) tr_read<DH>(fr[0][j], dos, j * 32, c * 32, lane);
+        // element e <-> query q0 + 32 c + 16 (e / 8) + 8 hf + e % 8, lane column <-> key
+        V8 pf[2], dsf[2];
 #pragma unroll
-        for (int j = 0; j < DT; ++j) {
-          const int row = (j * 32 + col) * TSTR + kk * 16 + hf * 8;
-          dv[j] = Mma<T>::run(*(const V8*)(dots + row), pf[kk], dv[j]);
-          dk[j] = Mma<T>::run(*(const V8*)(qts + row), dsf[kk], dk[j]);
+        for (int g = 0; g < 2; ++g) {
+          const int r0 = 32 * c + 16 * g + 8 * hf;
+          const f32x4 l0 = *(const f32x4*)&lses[r0], l1 = *(const f32x4*)&lses[r0 + 4];
+          const f32x4 d0 = *(const f32x4*)&ds_[r0], d1 = *(const f32x4*)&ds_[r0 + 4];
+          V8 tp, td;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const int e = g * 8 + i;
+            const float lq = (i < 4 ? l0[i & 3] : l1[i & 3]) * 1.4426950408889634f;
+            const float dq = i < 4 ? d0[i & 3] : d1[i & 3];
+            float p = __builtin_amdgcn_exp2f(sacc[e] * scale_log2 - lq);
+            if ((unsigned)(q0 + r0 - key + i) >= vis) p = 0.f;   // key <= query < L, as one unsigned compare
+            tp[i] = from_f<T>(p);
+            td[i] = from_f<T>(p * (pacc[e] - dq) * gsc);
+          }
+          pf[g] = tp;
+          dsf[g] = td;
         }
+        // dV^T += dO^T P and dK^T += Q^T dS over these 32 queries: 4 steps (dO^T, Q^T) x (16, 16)
+#pragma unroll
+        for (int st4 = 0; st4 < 4; ++st4) {
+          const int g = st4 >> 1, which = st4 & 1;   // which: 0 = dO^T P, 1 = Q^T dS
+          tr_wait(fr[st4 & 1]);
+          if (st4 + 1 < 4) {
+            const int g1 = (st4 + 1) >> 1;
+            const char* src = ((st4 + 1) & 1) ? qs : dos;
+#pragma unroll
+            for (int j = 0; j < DT; ++j) tr_read<DH>(fr[(st4 + 1) & 1][j], src, j * 32, c * 32 + g1 * 16, lane);
+          }
+#pragma unroll
+          for (int j = 0; j < DT; ++j) {
+            if (which == 0) dv[j] = Mma<T>::run(tr_value<T>(fr[st4 & 1][j]), pf[g], dv[j]);
+            else dk[j] = Mma<T>::run(tr_value<T>(fr[st4 & 1][j]), dsf[g], dk[j]);
+          }
+        }
+      }
     }
-    if (qt + 1 < n_qt) store_tile(cur ^ 1);
+    // tile t + 1 has landed when only the loads of tiles t + 2 .. t + NS - 1 are outstanding;
+    // after the barrier nobody reads tile t any more and its stage is refilled
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((NS - 2) * NLD) : "memory");
     __syncthreads();
+    issue(t + NS);
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no direct-to-LDS write may outlive the workgroup
   if (key < L) {
     T* rk = dqkv + ((long)b * L + key) * ld + d + (long)head * DH;
     store_grad_row<T, DH>(rk, dk, scale / gsc, hf, rope ? rope + (long)key * DH : nullptr);
-    store_grad_row<T, DH>(rk + d, dv, 1.0f / gsc, hf, nullptr);
+    store_grad_row<T, DH>(rk + d, dv, 1.0f, hf, nullptr);
   }
 }
 
@@ -784,7 +866,14 @@ ls_status launch_bwd(const void* qkv, const void* o, const void* dO, const float
   dim3 gq((L + 127) / 128, B * h), gk((L + 127) / 128, B * h);
   flash_bwd_dq_kernel<T, DH><<<gq, 256, 0, st>>>((const T*)qkv, (const T*)dO, lse, dvec, (T*)dqkv, L, h, scale, rope);
   LS_CHECK_LAUNCH();
-  flash_bwd_dkv_kernel<T, DH><<<gk, 256, 0, st>>>((const T*)qkv, (const T*)dO, lse, dvec, (T*)dqkv, L, h, scale, rope);
+  constexpr int dkv_lds = 4 * (2 * 64 * DH * 2 + 512);
+  static bool dkv_attr = false;
+  if (!dkv_attr) {
+    LS_CHECK_HIP(hipFuncSetAttribute((const void*)flash_bwd_dkv_kernel<T, DH>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, dkv_lds));
+    dkv_attr = true;
+  }
+  flash_bwd_dkv_kernel<T, DH><<<dim3(gk.y, gk.x), 256, dkv_lds, st>>>((const T*)qkv, (const T*)dO, lse, dvec, (T*)dqkv, L, h, scale, rope);
   LS_CHECK_LAUNCH();
   return LS_OK;
 }
