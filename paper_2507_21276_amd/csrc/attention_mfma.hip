@@ -137,7 +137,8 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const T* __restrict__ qk
   __shared__ __attribute__((aligned(16))) T ks_lds[2][KT * KSTR];
   __shared__ __attribute__((aligned(16))) T vt_lds[2][DH * VSTR];
 
-  const int b = blockIdx.y / h, head = blockIdx.y % h;
+  // query tiles in grid.y (dispatched slowest): the long workgroups of all heads start first
+  const int b = blockIdx.x / h, head = blockIdx.x % h;
   const int d = h * DH;
   const long ld = 3L * d;
   // rows of this sequence / request chunk, number of cached tokens before it
@@ -145,8 +146,8 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const T* __restrict__ qk
   const int Lq = PAGED ? pg.start[b + 1] - pg.start[b] : L;
   const int past = PAGED ? pg.ctx_len[b] : 0;
   const int n_qt = (Lq + BQ - 1) / BQ;
-  if ((int)blockIdx.x >= n_qt) return;
-  const int qtile = n_qt - 1 - blockIdx.x;  // heaviest tiles first
+  if ((int)blockIdx.y >= n_qt) return;
+  const int qtile = n_qt - 1 - blockIdx.y;  // heaviest tiles first
   const T* qb = qkv + row0 * ld + (long)head * DH;
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
   const int col = lane & 31, hf = lane >> 5;
@@ -305,11 +306,11 @@ ls_status launch_fwd(const void* qkv, int B, int L, int h, void* o, float* lse, 
   PagedGeom pg{};
   if (L > 512) {
     constexpr int QT = 2;
-    dim3 grid((L + 4 * QT * 32 - 1) / (4 * QT * 32), B * h);
+    dim3 grid(B * h, (L + 4 * QT * 32 - 1) / (4 * QT * 32));
     flash_fwd_kernel<T, DH, QT, false><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, lse, L, h, scale_log2, pg);
   } else {
     constexpr int QT = 1;
-    dim3 grid((L + 4 * QT * 32 - 1) / (4 * QT * 32), B * h);
+    dim3 grid(B * h, (L + 4 * QT * 32 - 1) / (4 * QT * 32));
     flash_fwd_kernel<T, DH, QT, false><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, lse, L, h, scale_log2, pg);
   }
   LS_CHECK_LAUNCH();
@@ -320,7 +321,7 @@ template <class T, int DH>
 ls_status launch_prefill(const void* qkv, int h, void* o, const PagedGeom& pg, int max_chunk, hipStream_t st) {
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
   constexpr int QT = 1;
-  dim3 grid((max_chunk + 4 * QT * 32 - 1) / (4 * QT * 32), pg.n_req * h);
+  dim3 grid(pg.n_req * h, (max_chunk + 4 * QT * 32 - 1) / (4 * QT * 32));
   flash_fwd_kernel<T, DH, QT, true><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, nullptr, 0, h, scale_log2, pg);
   LS_CHECK_LAUNCH();
   return LS_OK;
@@ -483,8 +484,8 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const T* __restrict__
   __shared__ __attribute__((aligned(16))) T kt_lds[2][DH * TSTR];
 
   const int n_qt = (L + BQ - 1) / BQ;
-  const int qtile = n_qt - 1 - blockIdx.x;
-  const int b = blockIdx.y / h, head = blockIdx.y % h;
+  const int qtile = n_qt - 1 - blockIdx.y;   // heaviest tiles of all heads first
+  const int b = blockIdx.x / h, head = blockIdx.x % h;
   const int d = h * DH;
   const long ld = 3L * d;
   const T* qb = qkv + (long)b * L * ld + (long)head * DH;
@@ -496,7 +497,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const T* __restrict__
   const int wq0 = qtile * BQ + wave * 32;
   const int q = wq0 + col;
   const float scale_log2 = scale * 1.4426950408889634f;
-  const float gsc = do_scale(dvec + (long)gridDim.y * L + ((long)gridDim.y * L + 3) / 4);   // after D and the per-workgroup maxima
+  const float gsc = do_scale(dvec + (long)gridDim.x * L + ((long)gridDim.x * L + 3) / 4);   // after D and the per-workgroup maxima
 
   V8 qf[KS], dof[KS];
 #pragma unroll
@@ -863,7 +864,7 @@ ls_status launch_bwd(const void* qkv, const void* o, const void* dO, const float
   dvec_kernel<T><<<(unsigned)nb, 256, 0, st>>>((const T*)o, (const T*)dO, items, DH, dvec);
   amax_finish_kernel<<<1, 256, 0, st>>>(dvec + items, nb);
   LS_CHECK_LAUNCH();
-  dim3 gq((L + 127) / 128, B * h), gk((L + 127) / 128, B * h);
+  dim3 gq(B * h, (L + 127) / 128), gk(B * h, (L + 127) / 128);
   flash_bwd_dq_kernel<T, DH><<<gq, 256, 0, st>>>((const T*)qkv, (const T*)dO, lse, dvec, (T*)dqkv, L, h, scale, rope);
   LS_CHECK_LAUNCH();
   constexpr int dkv_lds = 4 * (2 * 64 * DH * 2 + 512);
@@ -873,7 +874,7 @@ ls_status launch_bwd(const void* qkv, const void* o, const void* dO, const float
                                      hipFuncAttributeMaxDynamicSharedMemorySize, dkv_lds));
     dkv_attr = true;
   }
-  flash_bwd_dkv_kernel<T, DH><<<dim3(gk.y, gk.x), 256, dkv_lds, st>>>((const T*)qkv, (const T*)dO, lse, dvec, (T*)dqkv, L, h, scale, rope);
+  flash_bwd_dkv_kernel<T, DH><<<gk, 256, dkv_lds, st>>>((const T*)qkv, (const T*)dO, lse, dvec, (T*)dqkv, L, h, scale, rope);
   LS_CHECK_LAUNCH();
   return LS_OK;
 }
