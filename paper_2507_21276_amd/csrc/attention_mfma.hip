@@ -468,130 +468,6 @@ __device__ __forceinline__ void store_grad_row(T* row, const f32x16 (&acc)[DH / 
     }
 }
 
-template <class T, int DH>
-__global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const T* __restrict__ qkv,
-                                                           const T* __restrict__ dO,
-                                                           const float* __restrict__ lse,
-                                                           const float* __restrict__ dvec,
-                                                           T* __restrict__ dqkv, int L, int h,
-                                                           float scale, const float* __restrict__ rope) {
-  typedef typename Mma<T>::V8 V8;
-  typedef typename Mma<T>::V4 V4;
-  constexpr int BQ = 128, KS = DH / 16, DT = DH / 32;
-  constexpr int KSTR = DH + 8, TSTR = KT + 8;
-  __shared__ __attribute__((aligned(16))) T k_lds[2][KT * KSTR];
-  __shared__ __attribute__((aligned(16))) T v_lds[2][KT * KSTR];
-  __shared__ __attribute__((aligned(16))) T kt_lds[2][DH * TSTR];
-
-  const int n_qt = (L + BQ - 1) / BQ;
-  const int qtile = n_qt - 1 - blockIdx.y;   // heaviest tiles of all heads first
-  const int b = blockIdx.x / h, head = blockIdx.x % h;
-  const int d = h * DH;
-  const long ld = 3L * d;
-  const T* qb = qkv + (long)b * L * ld + (long)head * DH;
-  const T* kb = qb + d;
-  const T* vb = qb + 2 * d;
-  const T* dob = dO + (long)b * L * d + (long)head * DH;
-  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-  const int col = lane & 31, hf = lane >> 5;
-  const int wq0 = qtile * BQ + wave * 32;
-  const int q = wq0 + col;
-  const float scale_log2 = scale * 1.4426950408889634f;
-  const float gsc = do_scale(dvec + (long)gridDim.x * L + ((long)gridDim.x * L + 3) / 4);   // after D and the per-workgroup maxima
-
-  V8 qf[KS], dof[KS];
-#pragma unroll
-  for (int s = 0; s < KS; ++s) {
-    u32x4 z0 = {0u, 0u, 0u, 0u}, z1 = {0u, 0u, 0u, 0u};
-    if (q < L) {
-      z0 = *(const u32x4*)(qb + (long)q * ld + s * 16 + hf * 8);
-      z1 = *(const u32x4*)(dob + (long)q * d + s * 16 + hf * 8);
-    }
-    qf[s] = __builtin_bit_cast(V8, z0);
-    dof[s] = __builtin_bit_cast(V8, scale_chunk<T>(z1, gsc));
-  }
-  float lse2 = INFINITY, dq_ = 0.f;
-  if (q < L) {
-    lse2 = lse[((long)b * L + q) * h + head] * 1.4426950408889634f;
-    dq_ = dvec[((long)b * L + q) * h + head] * gsc;
-  }
-  f32x16 acc[DT];
-#pragma unroll
-  for (int j = 0; j < DT; ++j)
-#pragma unroll
-    for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
-
-  const int q_hi = min(L, qtile * BQ + BQ) - 1;
-  const int n_kt = q_hi / KT + 1;
-  NatStage<T, KT, DH> sk, sv;
-  TrStage<T, KT, DH> st;
-  sk.load(kb, ld, 0, L);
-  sv.load(vb, ld, 0, L);
-  st.load(kb, ld, 0, L, 0);
-  sk.store(k_lds[0]);
-  sv.store(v_lds[0]);
-  st.store(kt_lds[0], 0);
-  __syncthreads();
-
-  for (int kt = 0; kt < n_kt; ++kt) {
-    const int cur = kt & 1, key0 = kt * KT;
-    if (kt + 1 < n_kt) {
-      sk.load(kb, ld, key0 + KT, L);
-      sv.load(vb, ld, key0 + KT, L);
-      st.load(kb, ld, key0 + KT, L, 0);
-    }
-    if (key0 <= wq0 + 31) {
-      const T* ks = k_lds[cur];
-      const T* vs = v_lds[cur];
-      const T* kts = kt_lds[cur];
-      f32x16 sacc[2], pacc[2];
-#pragma unroll
-      for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) sacc[c][e] = pacc[c][e] = 0.f;
-#pragma unroll
-      for (int s = 0; s < KS; ++s)
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-          const int row = (c * 32 + pi_row(col)) * KSTR + s * 16 + hf * 8;
-          sacc[c] = Mma<T>::run(*(const V8*)(ks + row), qf[s], sacc[c]);
-          pacc[c] = Mma<T>::run(*(const V8*)(vs + row), dof[s], pacc[c]);
-        }
-      const bool diag = key0 + KT - 1 > wq0;
-      V8 dsf[4];
-#pragma unroll
-      for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int g = 0; g < 2; ++g) {
-          V8 t;
-#pragma unroll
-          for (int i = 0; i < 8; ++i) {
-            const int e = g * 8 + i;
-            float p = __builtin_amdgcn_exp2f(sacc[c][e] * scale_log2 - lse2);
-            if (diag && key0 + c * 32 + 16 * g + 8 * hf + i > q) p = 0.f;
-            t[i] = from_f<T>(p * (pacc[c][e] - dq_));
-          }
-          dsf[c * 2 + g] = t;
-        }
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-        for (int j = 0; j < DT; ++j)
-          acc[j] = Mma<T>::run(*(const V8*)(kts + (j * 32 + col) * TSTR + kk * 16 + hf * 8), dsf[kk], acc[j]);
-    }
-    if (kt + 1 < n_kt) {
-      sk.store(k_lds[cur ^ 1]);
-      sv.store(v_lds[cur ^ 1]);
-      st.store(kt_lds[cur ^ 1], 0);
-    }
-    __syncthreads();
-  }
-  if (q < L) {
-    T* row = dqkv + ((long)b * L + q) * ld + (long)head * DH;
-    store_grad_row<T, DH>(row, acc, scale / gsc, hf, rope ? rope + (long)q * DH : nullptr);
-  }
-}
-
 // ---- tiles brought in by direct-to-LDS loads ------------------------------------------------
 // A tile is ROWS rows of DH 16-bit elements, row-major in LDS, the 16-byte chunks of a row
 // XOR-permuted by the row number so that both kinds of fragment read are conflict-free:
@@ -662,6 +538,143 @@ template <class T>
 __device__ __forceinline__ typename Mma<T>::V8 tr_value(const TrFrag& f) {
   const s16x8_t w = __builtin_shufflevector(f.lo, f.hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(typename Mma<T>::V8, w);
+}
+
+// dQ.  A workgroup owns 128 queries (32 per wavefront, Q and dO fragments in registers) and
+// walks the key tiles of 64 keys below its diagonal.  K and V tiles arrive by direct-to-LDS
+// loads through a ring of NS stages; K^T for the second product is read from the K tile with
+// the transposing LDS load.  Both first products are formed transposed (S^T, dP^T: rows =
+// keys, lane column = query), so the softmax statistics are per-lane scalars.
+template <class T, int DH>
+__global__ __launch_bounds__(256) void flash_bwd_dq_kernel(const T* __restrict__ qkv,
+                                                           const T* __restrict__ dO,
+                                                           const float* __restrict__ lse,
+                                                           const float* __restrict__ dvec,
+                                                           T* __restrict__ dqkv, int L, int h,
+                                                           float scale, const float* __restrict__ rope) {
+  typedef typename Mma<T>::V8 V8;
+  constexpr int BQ = 128, NS = 4, KS = DH / 16, DT = DH / 32;
+  constexpr int TILE_B = KT * DH * 2;            // bytes of a K or V tile
+  constexpr int STAGE_B = 2 * TILE_B;
+  constexpr int NLT = TILE_B / 1024 / 4;         // wave loads per wavefront and tile
+  constexpr int NLD = 2 * NLT;                   // loads per wavefront and stage
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+  const int n_qt = (L + BQ - 1) / BQ;
+  const int qtile = n_qt - 1 - blockIdx.y;   // heaviest tiles of all heads first
+  const int b = blockIdx.x / h, head = blockIdx.x % h;
+  const int d = h * DH;
+  const long ld = 3L * d;
+  const T* qb = qkv + (long)b * L * ld + (long)head * DH;
+  const T* kb = qb + d;
+  const T* vb = qb + 2 * d;
+  const T* dob = dO + (long)b * L * d + (long)head * DH;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int col = lane & 31, hf = lane >> 5;
+  const int wq0 = qtile * BQ + wave * 32;
+  const int q = wq0 + col;
+  const float scale_log2 = scale * 1.4426950408889634f;
+  const float gsc = do_scale(dvec + (long)gridDim.x * L + ((long)gridDim.x * L + 3) / 4);   // after D and the per-workgroup maxima
+
+  V8 qf[KS], dof[KS];
+#pragma unroll
+  for (int s = 0; s < KS; ++s) {
+    u32x4 z0 = {0u, 0u, 0u, 0u}, z1 = {0u, 0u, 0u, 0u};
+    if (q < L) {
+      z0 = *(const u32x4*)(qb + (long)q * ld + s * 16 + hf * 8);
+      z1 = *(const u32x4*)(dob + (long)q * d + s * 16 + hf * 8);
+    }
+    qf[s] = __builtin_bit_cast(V8, z0);
+    dof[s] = __builtin_bit_cast(V8, z1);
+  }
+  float lse2 = INFINITY, dq_ = 0.f;
+  if (q < L) {
+    lse2 = lse[((long)b * L + q) * h + head] * 1.4426950408889634f;
+    dq_ = dvec[((long)b * L + q) * h + head];
+  }
+  f32x16 acc[DT];
+#pragma unroll
+  for (int j = 0; j < DT; ++j)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+  // the wait counts below assume that only direct-to-LDS loads are in flight
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+  const int q_hi = min(L, qtile * BQ + BQ) - 1;
+  const int nt = q_hi / KT + 1;
+  // tile t -> stage t % NS; tiles past the end re-fetch the last one (never used), so that
+  // every wavefront always has the same number of loads in flight
+  auto issue = [&](int t) {
+    const int key0 = min(t, nt - 1) * KT;
+    char* st = smem + (t % NS) * STAGE_B;
+#pragma unroll
+    for (int j = 0; j < NLT; ++j) {
+      dma_rows<T, DH>(kb, ld, key0, L, st, wave * NLT + j, lane);
+      dma_rows<T, DH>(vb, ld, key0, L, st + TILE_B, wave * NLT + j, lane);
+    }
+  };
+#pragma unroll
+  for (int t = 0; t < NS; ++t) issue(t);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 1) * NLD) : "memory");
+  __syncthreads();
+
+  for (int t = 0; t < nt; ++t) {
+    const int key0 = t * KT;
+    const char* ks = smem + (t % NS) * STAGE_B;
+    const char* vs = ks + TILE_B;
+    // the tile's 64 keys in two blocks of 32
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+      f32x16 sacc, pacc;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) sacc[e] = pacc[e] = 0.f;
+      const int row = c * 32 + pi_row(col);   // MFMA row r is key pi(r): a lane's 8 values per 16-key step are consecutive keys
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        sacc = Mma<T>::run(frag_rows<T, DH>(ks, row, 2 * s + hf), qf[s], sacc);
+        pacc = Mma<T>::run(frag_rows<T, DH>(vs, row, 2 * s + hf), dof[s], pacc);
+      }
+      TrFrag fr[2][DT];
+#pragma unroll
+      for (int j = 0; j < DT; ++j) tr_read<DH>(fr[0][j], ks, j * 32, c * 32, lane);
+      // element e <-> key key0 + 32 c + 16 (e / 8) + 8 hf + e % 8, lane column <-> query
+      V8 dsf[2];
+#pragma unroll
+      for (int g = 0; g < 2; ++g) {
+        const int kbase = key0 + 32 * c + 16 * g + 8 * hf;
+        V8 td;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int e = g * 8 + i;
+          float p = __builtin_amdgcn_exp2f(sacc[e] * scale_log2 - lse2);
+          if (kbase + i > q) p = 0.f;
+          td[i] = from_f<T>(p * (pacc[e] - dq_) * gsc);
+        }
+        dsf[g] = td;
+      }
+      // dQ^T += K^T dS^T over these 32 keys in 2 steps of 16
+#pragma unroll
+      for (int g = 0; g < 2; ++g) {
+        tr_wait(fr[g]);
+        if (g == 0) {
+#pragma unroll
+          for (int j = 0; j < DT; ++j) tr_read<DH>(fr[1][j], ks, j * 32, c * 32 + 16, lane);
+        }
+#pragma unroll
+        for (int j = 0; j < DT; ++j) acc[j] = Mma<T>::run(tr_value<T>(fr[g][j]), dsf[g], acc[j]);
+      }
+    }
+    // tile t + 1 has landed when only the loads of tiles t + 2 .. t + NS - 1 are outstanding;
+    // after the barrier nobody reads tile t any more and its stage is refilled
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((NS - 2) * NLD) : "memory");
+    __syncthreads();
+    issue(t + NS);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no direct-to-LDS write may outlive the workgroup
+  if (q < L) {
+    T* row = dqkv + ((long)b * L + q) * ld + (long)head * DH;
+    store_grad_row<T, DH>(row, acc, scale / gsc, hf, rope ? rope + (long)q * DH : nullptr);
+  }
 }
 
 // dK, dV.  A workgroup owns 128 keys (32 per wavefront, K and V fragments in registers) and walks
@@ -845,14 +858,25 @@ __global__ __launch_bounds__(256) void dvec_kernel(const T* o, const T* dO, long
   __syncthreads();
   if (threadIdx.x == 0) dvec[n_items + blockIdx.x] = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
 }
-__global__ __launch_bounds__(256) void amax_finish_kernel(float* blockmax, long nb) {
-  __shared__ float red[4];
-  float m = 0.f;
-  for (long i = threadIdx.x; i < nb; i += 256) m = fmaxf(m, blockmax[i]);
-  m = wave_max(m);
+__global__ __launch_bounds__(1024) void amax_finish_kernel(float* blockmax, long nb) {
+  __shared__ float red[16];
+  // independent partial maxima per thread: the loads of one thread do not wait for each other
+  float m0 = 0.f, m1 = 0.f, m2 = 0.f, m3 = 0.f;
+  long i = threadIdx.x;
+  for (; i + 3 * 1024 < nb; i += 4 * 1024) {
+    m0 = fmaxf(m0, blockmax[i]);
+    m1 = fmaxf(m1, blockmax[i + 1024]);
+    m2 = fmaxf(m2, blockmax[i + 2 * 1024]);
+    m3 = fmaxf(m3, blockmax[i + 3 * 1024]);
+  }
+  for (; i < nb; i += 1024) m0 = fmaxf(m0, blockmax[i]);
+  float m = wave_max(fmaxf(fmaxf(m0, m1), fmaxf(m2, m3)));
   if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
   __syncthreads();
-  if (threadIdx.x == 0) blockmax[nb] = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  if (threadIdx.x < 64) {
+    m = wave_max(threadIdx.x < 16 ? red[threadIdx.x] : 0.f);
+    if (threadIdx.x == 0) blockmax[nb] = m;
+  }
 }
 
 template <class T, int DH>
@@ -862,10 +886,17 @@ ls_status launch_bwd(const void* qkv, const void* o, const void* dO, const float
   const long items = (long)B * L * h;
   const long nb = (items + 3) / 4;
   dvec_kernel<T><<<(unsigned)nb, 256, 0, st>>>((const T*)o, (const T*)dO, items, DH, dvec);
-  amax_finish_kernel<<<1, 256, 0, st>>>(dvec + items, nb);
+  amax_finish_kernel<<<1, 1024, 0, st>>>(dvec + items, nb);
   LS_CHECK_LAUNCH();
   dim3 gq(B * h, (L + 127) / 128), gk(B * h, (L + 127) / 128);
-  flash_bwd_dq_kernel<T, DH><<<gq, 256, 0, st>>>((const T*)qkv, (const T*)dO, lse, dvec, (T*)dqkv, L, h, scale, rope);
+  constexpr int dq_lds = 4 * (2 * KT * DH * 2);
+  static bool dq_attr = false;
+  if (!dq_attr) {
+    LS_CHECK_HIP(hipFuncSetAttribute((const void*)flash_bwd_dq_kernel<T, DH>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, dq_lds));
+    dq_attr = true;
+  }
+  flash_bwd_dq_kernel<T, DH><<<gq, 256, dq_lds, st>>>((const T*)qkv, (const T*)dO, lse, dvec, (T*)dqkv, L, h, scale, rope);
   LS_CHECK_LAUNCH();
   constexpr int dkv_lds = 4 * (2 * 64 * DH * 2 + 512);
   static bool dkv_attr = false;
