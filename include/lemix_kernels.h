@@ -130,6 +130,22 @@ ls_status lsk_attn_bwd_rope(int impl, const void* qkv, const void* o, const void
                             const float* table, void* stream);
 
 /*
+ * The forward-layout product of a decoder block's linear maps (Model
+ * Architecture): C[M, N] = X[M, K] W[N, K]^T + bias + resid, as lsk_gemm with
+ * both operands k-major, plus a caller workspace `scratch` (device, fp32,
+ * scratch_floats elements, may be null).  When M x N gives fewer than about
+ * 200 tiles of 128 x 128 (prompt chunks of a few hundred tokens) the
+ * contraction is split over up to 8 workgroups per tile; their fp32 partial
+ * results go through `scratch` and are added in a fixed order, so the result
+ * is deterministic.  Shapes that do not need it, or a workspace smaller than
+ * 2 * M * N floats, take the lsk_gemm path.  Errors as lsk_gemm.
+ */
+ls_status lsk_gemm_ws(int op_dtype, int M, int N, int K, const void* X, long ldx, const void* W,
+                      long ldw, void* C, long ldc, int c_dtype, const void* bias,
+                      int bias_dtype, const float* resid, long ldr, float* scratch,
+                      size_t scratch_floats, void* stream);
+
+/*
  * The LLaMA block's QKV projection with its rotary embedding (Model
  * Architecture: attention sub-layer with rotary positions): qkv[T, 3d] =
  * H[T, d] Wqkv[3d, d]^T in op_dtype (LS_F16 / LS_BF16; fp32 accumulation),

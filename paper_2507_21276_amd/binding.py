@@ -67,6 +67,7 @@ SIGNATURES = {
                                       _VP, _VP, _VP, _VP, _VP, _VP, _I, C.POINTER(C.c_float)]),
     "ls_last_error": (C.c_char_p, []),
     "lsk_gemm": (_I, [_I, _I, _I, _I, _VP, _L, _I, _VP, _L, _I, _VP, _L, _I, _VP, _I, _VP, _L, _I, _VP]),
+    "lsk_gemm_ws": (_I, [_I, _I, _I, _I, _VP, _L, _VP, _L, _VP, _L, _I, _VP, _I, _VP, _L, _VP, _SZ, _VP]),
     "lsk_convert": (_I, [_VP, _I, _VP, _I, _SZ, _VP]),
     "lsk_grad_scale": (_I, [_VP, _I, _SZ, _VP, _VP]),
     "lsk_gemm_scaled": (_I, [_I, _I, _I, _I, _VP, _L, _I, _VP, _L, _I, _VP, _L, _I, _VP, _I, _VP, _L, _I, _VP, _VP]),
@@ -327,6 +328,18 @@ def lsk_attn_bwd(impl, qkv, o, dO, lse, B, L, n_heads, head_dim, dqkv, stream=No
     dvec = torch.empty(lib().lsk_attn_bwd_scratch_floats(B, L, n_heads), dtype=torch.float32, device=qkv.device)
     _check(lib().lsk_attn_bwd(impl, _p(qkv), _p(o), _p(dO), _p(lse), CODE_OF_TORCH[qkv.dtype], B, L,
                               n_heads, head_dim, _p(dqkv), _p(dvec), _stream(stream)))
+
+
+def lsk_gemm_ws(x, w, c, scratch, bias=None, resid=None, stream=None):
+    """C[M, N] = X[M, K] W[N, K]^T (+ bias + resid) with an fp32 workspace for the split-K path."""
+    M, K = x.shape
+    N = w.shape[0]
+    _check(lib().lsk_gemm_ws(CODE_OF_TORCH[x.dtype], M, N, K, _p(x), x.stride(0), _p(w), w.stride(0), _p(c),
+                             c.stride(0), CODE_OF_TORCH[c.dtype], _p(bias) if bias is not None else None,
+                             CODE_OF_TORCH[bias.dtype] if bias is not None else 0,
+                             _p(resid) if resid is not None else None,
+                             resid.stride(0) if resid is not None else 0, _p(scratch), scratch.numel(),
+                             _stream(stream)))
 
 
 def lsk_attn_bwd_rope(impl, qkv, o, dO, lse, B, L, n_heads, head_dim, dqkv, pos, table, stream=None):

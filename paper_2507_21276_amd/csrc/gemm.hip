@@ -290,6 +290,9 @@ ls_status gemm_dma_try(int, int, int, int, const void*, long, int, const void*, 
                        const void*, int, const float*, long, int, const float*, const int32_t*, const float*, int,
                        hipStream_t);
 
+ls_status gemm_dma_splitk_try(int, int, int, int, const void*, long, const void*, long, void*, long, int, const void*,
+                              int, const float*, long, float*, size_t, hipStream_t);
+
 // LS_GEMM_IMPL=staged forces the register-staged kernel (for A/B comparisons)
 static bool use_dma_kernel() {
   static int v = -1;
@@ -342,6 +345,25 @@ extern "C" ls_status lsk_gemm(int op_dtype, int M, int N, int K, const void* A, 
                               int accumulate, void* stream) {
   return lsk_gemm_scaled(op_dtype, M, N, K, A, lda, a_kmajor, B, ldb, b_kmajor, C, ldc, c_dtype, bias,
                          bias_dtype, resid, ldr, accumulate, nullptr, stream);
+}
+
+// Forward-layout product C[M, N] = X[M, K] W[N, K]^T (+ bias, + residual) with a caller workspace:
+// shapes that give the chip too few output tiles are computed split along K through `scratch`
+// (deterministic: partial sums are added in a fixed order); everything else goes to lsk_gemm.
+extern "C" ls_status lsk_gemm_ws(int op_dtype, int M, int N, int K, const void* X, long ldx, const void* W,
+                                 long ldw, void* C, long ldc, int c_dtype, const void* bias, int bias_dtype,
+                                 const float* resid, long ldr, float* scratch, size_t scratch_floats,
+                                 void* stream) {
+  LS_REQUIRE(M > 0 && N > 0 && K > 0, "gemm_ws: non-positive size M=%d N=%d K=%d", M, N, K);
+  LS_REQUIRE(X && W && C, "gemm_ws: null operand");
+  if (use_dma_kernel() && scratch && (op_dtype == LS_BF16 || op_dtype == LS_F16) && M >= 256 && K % 8 == 0 &&
+      ldx % 8 == 0 && ldw % 8 == 0 && (uintptr_t)X % 16 == 0 && (uintptr_t)W % 16 == 0 &&
+      (c_dtype == LS_F32 || c_dtype == op_dtype)) {
+    const ls_status r = gemm_dma_splitk_try(op_dtype, M, N, K, X, ldx, W, ldw, C, ldc, c_dtype, bias, bias_dtype, resid,
+                                            ldr, scratch, scratch_floats, (hipStream_t)stream);
+    if (r != LS_ESTATE) return r;
+  }
+  return lsk_gemm(op_dtype, M, N, K, X, ldx, 1, W, ldw, 1, C, ldc, c_dtype, bias, bias_dtype, resid, ldr, 0, stream);
 }
 
 // QKV projection with the rotary embedding of q and k fused into the epilogue

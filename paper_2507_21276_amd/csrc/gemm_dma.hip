@@ -60,6 +60,7 @@ struct DmaArgs {
   int accumulate;
   const float* alpha;
   int tiles_m, tiles_n;
+  long split_stride;   // split-K launches (gridDim.y > 1, MODE 2): elements between the partial results
   // MODE 3 only: rotary embedding of the columns below rope_cols (heads of 128)
   const int32_t* rope_pos; const float* rope_table; int rope_cols;
 };
@@ -222,7 +223,12 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  const int nk = g.K / TK;
+  // gridDim.y > 1: split-K, this workgroup contracts over its share of the k tiles
+  const int nk_all = g.K / TK;
+  const int kt0 = (int)((long)blockIdx.y * nk_all / gridDim.y);
+  const int nk = (int)((long)(blockIdx.y + 1) * nk_all / gridDim.y) - kt0;
+  a_base += kt0 * a_step;
+  b_base += kt0 * b_step;
   issue_tile<BM>(a_base, a_off, smem, wave);
   issue_tile<BN>(b_base, b_off, smem + A_BYTES, wave);
   __builtin_amdgcn_s_waitcnt(0);
@@ -397,7 +403,7 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
       } else if constexpr (MODE == 1) {
         *(f32x4*)((float*)g.C + (long)m * g.ldc + n) = v + *(const f32x4*)(g.resid + (long)m * g.ldr + n);
       } else {
-        f32x4* cp = (f32x4*)((float*)g.C + (long)m * g.ldc + n);
+        f32x4* cp = (f32x4*)((float*)g.C + blockIdx.y * g.split_stride + (long)m * g.ldc + n);
         *cp = g.accumulate ? *cp + v : v;
       }
     }
@@ -405,7 +411,7 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
 }
 
 template <class T, int BM, int BN, bool AK, bool BK, int MODE>
-ls_status launch(DmaArgs g, hipStream_t st) {
+ls_status launch(DmaArgs g, hipStream_t st, int splits = 1) {
   static bool attr_set = false;
   const int lds = 2 * (BM + BN) * 128;
   if (!attr_set) {
@@ -415,7 +421,7 @@ ls_status launch(DmaArgs g, hipStream_t st) {
   }
   g.tiles_m = (g.M + BM - 1) / BM;
   g.tiles_n = (g.N + BN - 1) / BN;
-  gemm_dma_kernel<T, BM, BN, AK, BK, MODE><<<g.tiles_m * g.tiles_n, 256, lds, st>>>(g);
+  gemm_dma_kernel<T, BM, BN, AK, BK, MODE><<<dim3(g.tiles_m * g.tiles_n, splits), 256, lds, st>>>(g);
   LS_CHECK_LAUNCH();
   return LS_OK;
 }
@@ -452,6 +458,78 @@ ls_status dispatch(const DmaArgs& g, hipStream_t st) {
 
 }  // namespace
 
+namespace {
+
+// C = sum over the splits (in order) of the fp32 partial results, + bias + residual
+template <class T>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* partial, int splits, long MN, int N,
+                                                            void* C, long ldc, int c_dtype, const void* bias,
+                                                            int bias_dtype, const float* resid, long ldr) {
+  const long i4 = ((long)blockIdx.x * 256 + threadIdx.x) * 4;
+  if (i4 >= MN) return;
+  f32x4 v = *(const f32x4*)(partial + i4);
+  for (int s = 1; s < splits; ++s) v += *(const f32x4*)(partial + s * MN + i4);
+  const long m = i4 / N;
+  const int n = (int)(i4 % N);
+  if (bias) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) v[e] += load_as_f(bias, n + e, bias_dtype);
+  }
+  if (resid) v += *(const f32x4*)(resid + m * ldr + n);
+  if (c_dtype == LS_F32) {
+    *(f32x4*)((float*)C + m * ldc + n) = v;
+  } else {
+    typename Mf<T>::V4 o;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) o[e] = from_f<T>(v[e]);
+    *(typename Mf<T>::V4*)((T*)C + m * ldc + n) = o;
+  }
+}
+
+template <class T>
+ls_status run_splitk(DmaArgs g, int splits, float* scratch, void* C, long ldc, int c_dtype, const void* bias,
+                     int bias_dtype, const float* resid, long ldr, hipStream_t st) {
+  const long MN = (long)g.M * g.N;
+  g.C = scratch; g.ldc = g.N; g.c_dtype = LS_F32; g.bias = nullptr; g.resid = nullptr; g.accumulate = 0;
+  g.split_stride = MN;
+  LS_TRY((launch<T, 128, 128, true, true, 2>(g, st, splits)));
+  splitk_reduce_kernel<T><<<(unsigned)((MN / 4 + 255) / 256), 256, 0, st>>>(scratch, splits, MN, g.N, C, ldc, c_dtype,
+                                                                          bias, bias_dtype, resid, ldr);
+  LS_CHECK_LAUNCH();
+  return LS_OK;
+}
+
+}  // namespace
+
+// Forward-layout GEMM (both operands k-major) for problems with too few output tiles to fill
+// the chip: the contraction is split over `splits` workgroups per tile, partial results go to
+// `scratch` (fp32, splits * M * N) and are summed in a fixed order (deterministic).  Returns
+// LS_ESTATE when the shape does not call for it or the scratch is too small.
+ls_status gemm_dma_splitk_try(int op_dtype, int M, int N, int K, const void* A, long lda, const void* B, long ldb,
+                              void* C, long ldc, int c_dtype, const void* bias, int bias_dtype,
+                              const float* resid, long ldr, float* scratch, size_t scratch_floats,
+                              hipStream_t st) {
+  if (!scratch || K % TK != 0 || M < 64 || N < 64 || N % 4 != 0) return LS_ESTATE;
+  const int per16 = c_dtype == LS_F32 ? 4 : 8;
+  if (ldc % per16 != 0 || (uintptr_t)C % 16 != 0 || (uintptr_t)scratch % 16 != 0) return LS_ESTATE;
+  if (resid && (ldr % 4 != 0 || (uintptr_t)resid % 16 != 0)) return LS_ESTATE;
+  const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
+  const int nk = K / TK;
+  if (tiles >= 200 || nk < 32) return LS_ESTATE;
+  int splits = (int)(512 / tiles);
+  if (splits > 8) splits = 8;
+  while (splits > 1 && nk / splits < 8) --splits;
+  while (splits > 1 && (size_t)splits * M * N > scratch_floats) --splits;
+  if (splits < 2) return LS_ESTATE;
+  DmaArgs g{M, N, K, A, lda, 1, B, ldb, 1, nullptr, 0, LS_F32, nullptr, 0, nullptr, 0, 0, nullptr, 0, 0, 0, nullptr,
+            nullptr, 0};
+  if (op_dtype == LS_BF16)
+    return run_splitk<bf16_t>(g, splits, scratch, C, ldc, c_dtype, bias, bias_dtype, resid, ldr, st);
+  if (op_dtype == LS_F16)
+    return run_splitk<f16_t>(g, splits, scratch, C, ldc, c_dtype, bias, bias_dtype, resid, ldr, st);
+  return LS_ESTATE;
+}
+
 // Returns LS_OK after launching, or LS_ESTATE (without touching the error text)
 // when the shape is outside what this kernel covers.
 ls_status gemm_dma_try(int op_dtype, int M, int N, int K, const void* A, long lda, int a_kmajor,
@@ -465,7 +543,7 @@ ls_status gemm_dma_try(int op_dtype, int M, int N, int K, const void* A, long ld
   if (N % per16 != 0 || ldc % per16 != 0 || (uintptr_t)C % 16 != 0) return LS_ESTATE;
   if (resid && (ldr % 4 != 0 || (uintptr_t)resid % 16 != 0)) return LS_ESTATE;
   DmaArgs g{M, N, K, A, lda, a_kmajor, B, ldb, b_kmajor, C, ldc, c_dtype, bias, bias_dtype, resid, ldr,
-            accumulate, alpha, 0, 0, rope_pos, rope_table, rope_cols};
+            accumulate, alpha, 0, 0, 0, rope_pos, rope_table, rope_cols};
   if (op_dtype == LS_BF16) return dispatch<bf16_t>(g, st);
   if (op_dtype == LS_F16) return dispatch<f16_t>(g, st);
   return LS_ESTATE;

@@ -39,6 +39,8 @@ ls_status lsk_attn_prefill_mfma(const void*, int, int, const int32_t*, int, int,
                                 const int32_t*, const int32_t*, int, int, void*, void*);
 ls_status lsk_gemm_qkv_rope(int, int, int, const void*, const void*, void*, int, int, const int32_t*, const float*,
                             void*);
+ls_status lsk_gemm_ws(int, int, int, int, const void*, long, const void*, long, void*, long, int, const void*, int,
+                      const float*, long, float*, size_t, void*);
 ls_status lsk_attn_bwd_rope(int, const void*, const void*, const void*, const float*, int, int, int, int, int,
                             void*, float*, const int32_t*, const float*, void*);
 ls_status lsk_rope_kv_write(void*, int, int, int, int, const int32_t*, const int32_t*, const float*, void*, void*,
@@ -228,7 +230,8 @@ ls_status linear(const ls_stage* s, int T, int N, int K, const void* X, const vo
   const int mt = s->cfg.mma_dtype;
   if (mt != LS_F32 && T <= 128 && scratch)
     return lsk_gemm_skinny(mt, T, N, K, X, K, W, K, C, N, c_dtype, bias, s->cfg.dtype, resid, N, scratch, st);
-  return lsk_gemm(mt, T, N, K, X, K, 1, W, K, 1, C, N, c_dtype, bias, s->cfg.dtype, resid, N, 0, st);
+  return lsk_gemm_ws(mt, T, N, K, X, K, W, K, C, N, c_dtype, bias, s->cfg.dtype, resid, N, scratch,
+                     scratch ? serve_scratch_floats(s) : 0, st);
 }
 
 ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const int32_t* pos,
