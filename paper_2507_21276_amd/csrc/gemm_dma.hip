@@ -303,6 +303,12 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
       }
     }
   }
+  // The last iteration read the fragments of a tile that does not exist.  Their registers must
+  // stay allocated until the reads have returned: the compiler does not know that the
+  // transposing reads issued from assembly are still in flight and would hand the registers to
+  // the epilogue, where the late LDS data would overwrite live values.
+  wait_frags<T, AK, TI>(fa[0]);
+  wait_frags<T, BK, TJ>(fb[0]);
   __builtin_amdgcn_s_waitcnt(0);
 
   // Epilogue.  The MFMAs ran with the operands swapped, so the accumulators hold C^T tiles:

@@ -81,3 +81,24 @@ def test_null_arguments_are_errors_not_crashes():
                         0, None) == Bd.LS_EINVAL
     assert b"non-positive" in lib.ls_last_error()
     lib.ls_destroy(None)
+
+
+def test_no_instruction_touches_a_register_with_an_assembly_issued_lds_read_in_flight(tmp_path):
+    """Compiles the two sources that use transposing LDS reads to ISA and lints them."""
+    import shutil
+    import subprocess
+    import isa_lint
+    if shutil.which("hipcc") is None:
+        pytest.skip("hipcc not available")
+    csrc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "paper_2507_21276_amd", "csrc")
+    # a planted hazard is found (the checker itself works)
+    planted = "_Zk:\n\tds_read_b64_tr_b16 v[4:5], v9\n\tv_mov_b32_e32 v4, 0\n\ts_waitcnt lgkmcnt(0)\n\ts_endpgm\n"
+    assert isa_lint.scan(planted) == {"_Zk": [(2, "v_mov_b32_e32 v4, 0")]}
+    for src in ("gemm_dma.hip", "attention_mfma.hip"):
+        out = tmp_path / (src + ".s")
+        subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+                        "-packed-fp32-ops", "-S", "--cuda-device-only", os.path.join(csrc, src), "-o", str(out)],
+                       check=True, capture_output=True)
+        text = out.read_text()
+        assert "ds_read_b64_tr_b16" in text
+        assert isa_lint.scan(text) == {}, src
