@@ -176,6 +176,10 @@ __device__ __forceinline__ typename Mf<T>::V8 frag_value(const Frag<T, KMAJOR>& 
   }
 }
 
+typedef f32x4 __attribute__((may_alias)) f32x4_a;
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef u32x2_t __attribute__((may_alias)) u32x2_a;
+
 // MODE 0: C (16-bit) = acc + bias;  1: C (fp32) = resid + acc + bias;  2: C (fp32) (+)= acc;
 // MODE 3: as 0 without bias, and the half-split rotary embedding (head_dim 128) applied to the
 //         columns below rope_cols: a wavefront's 128 columns are one head, so the pair
@@ -366,8 +370,8 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
                   hi[e] = from_f<T>(acc[i][j + 2][4 * q + e]);
                 }
               }
-              *(V4*)(srow + (((j * 4 + q) ^ sw) * 16) + hf * 8) = lo;
-              *(V4*)(srow + (((j * 4 + q + 8) ^ sw) * 16) + hf * 8) = hi;
+              *(u32x2_a*)(srow + (((j * 4 + q) ^ sw) * 16) + hf * 8) = __builtin_bit_cast(u32x2_t, lo);
+              *(u32x2_a*)(srow + (((j * 4 + q + 8) ^ sw) * 16) + hf * 8) = __builtin_bit_cast(u32x2_t, hi);
             }
         }
       } else {
@@ -388,9 +392,9 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
               V4 o;
 #pragma unroll
               for (int e = 0; e < 4; ++e) o[e] = from_f<T>(v[e]);
-              *(V4*)(srow + (((j * 4 + q) ^ sw) * 16) + hf * 8) = o;
+              *(u32x2_a*)(srow + (((j * 4 + q) ^ sw) * 16) + hf * 8) = __builtin_bit_cast(u32x2_t, o);
             } else {
-              *(f32x4*)(srow + (((j * 8 + 2 * q + hf) ^ sw) * 16)) = v;
+              *(f32x4_a*)(srow + (((j * 8 + 2 * q + hf) ^ sw) * 16)) = v;
             }
           }
       }
@@ -403,9 +407,9 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
       const int m = m0 + wm + pass * ROWS_P + r;
       const int n = n0 + wn + c * (16 / ESZ);
       if (m >= g.M || n >= g.N) continue;
-      const f32x4 v = *(const f32x4*)(stg + r * ROWB + ((c ^ (r & (CPR - 1))) * 16));
+      const f32x4 v = *(const f32x4_a*)(stg + r * ROWB + ((c ^ (r & (CPR - 1))) * 16));
       if constexpr (ESZ == 2) {
-        *(f32x4*)((T*)g.C + (long)m * g.ldc + n) = v;
+        *(f32x4_a*)((T*)g.C + (long)m * g.ldc + n) = v;
       } else if constexpr (MODE == 1) {
         *(f32x4*)((float*)g.C + (long)m * g.ldc + n) = v + *(const f32x4*)(g.resid + (long)m * g.ldr + n);
       } else {
