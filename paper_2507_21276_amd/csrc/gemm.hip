@@ -292,6 +292,8 @@ ls_status gemm_dma_try(int, int, int, int, const void*, long, int, const void*, 
 
 ls_status gemm_dma_splitk_try(int, int, int, int, const void*, long, const void*, long, void*, long, int, const void*,
                               int, const float*, long, float*, size_t, hipStream_t);
+ls_status gemm_dma_skinny_try(int, int, int, int, const void*, long, const void*, long, void*, long, int, const void*,
+                              int, const float*, long, float*, size_t, hipStream_t);
 
 // LS_GEMM_IMPL=staged forces the register-staged kernel (for A/B comparisons)
 static bool use_dma_kernel() {
@@ -356,6 +358,16 @@ extern "C" ls_status lsk_gemm_ws(int op_dtype, int M, int N, int K, const void* 
                                  void* stream) {
   LS_REQUIRE(M > 0 && N > 0 && K > 0, "gemm_ws: non-positive size M=%d N=%d K=%d", M, N, K);
   LS_REQUIRE(X && W && C, "gemm_ws: null operand");
+  // decode batches (M <= 64): weights stream through LDS in 64 x 128 tiles; LS_SKINNY_IMPL=mfma keeps the
+  // register-streaming kernel (lsk_gemm_skinny) for A/B comparisons
+  static const bool skinny_dma = [] { const char* e = getenv("LS_SKINNY_IMPL"); return !(e && strcmp(e, "mfma") == 0); }();
+  if (skinny_dma && use_dma_kernel() && scratch && (op_dtype == LS_BF16 || op_dtype == LS_F16) && M <= 64 && K % 8 == 0 &&
+      ldx % 8 == 0 && ldw % 8 == 0 && (uintptr_t)X % 16 == 0 && (uintptr_t)W % 16 == 0 &&
+      (c_dtype == LS_F32 || c_dtype == op_dtype)) {
+    const ls_status r = gemm_dma_skinny_try(op_dtype, M, N, K, X, ldx, W, ldw, C, ldc, c_dtype, bias, bias_dtype, resid,
+                                            ldr, scratch, scratch_floats, (hipStream_t)stream);
+    if (r != LS_ESTATE) return r;
+  }
   if (use_dma_kernel() && scratch && (op_dtype == LS_BF16 || op_dtype == LS_F16) && M >= 256 && K % 8 == 0 &&
       ldx % 8 == 0 && ldw % 8 == 0 && (uintptr_t)X % 16 == 0 && (uintptr_t)W % 16 == 0 &&
       (c_dtype == LS_F32 || c_dtype == op_dtype)) {

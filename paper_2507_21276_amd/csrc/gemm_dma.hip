@@ -155,7 +155,7 @@ __device__ __forceinline__ void read_frag(Frag<T, KMAJOR>& f, const char* lds_ti
 
 template <class T, bool KMAJOR, int N>
 __device__ __forceinline__ void wait_frags(Frag<T, KMAJOR> (&f)[N]) {
-  static_assert(N == 2 || N == 4, "fragment count");
+  static_assert(KMAJOR || N == 2 || N == 4, "fragment count");
   if constexpr (!KMAJOR) {
     if constexpr (N == 4)
       asm volatile("s_waitcnt lgkmcnt(0)"
@@ -496,13 +496,13 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* partial
   }
 }
 
-template <class T>
+template <class T, int BM = 128>
 ls_status run_splitk(DmaArgs g, int splits, float* scratch, void* C, long ldc, int c_dtype, const void* bias,
                      int bias_dtype, const float* resid, long ldr, hipStream_t st) {
   const long MN = (long)g.M * g.N;
   g.C = scratch; g.ldc = g.N; g.c_dtype = LS_F32; g.bias = nullptr; g.resid = nullptr; g.accumulate = 0;
   g.split_stride = MN;
-  LS_TRY((launch<T, 128, 128, true, true, 2>(g, st, splits)));
+  LS_TRY((launch<T, BM, 128, true, true, 2>(g, st, splits)));
   splitk_reduce_kernel<T><<<(unsigned)((MN / 4 + 255) / 256), 256, 0, st>>>(scratch, splits, MN, g.N, C, ldc, c_dtype,
                                                                           bias, bias_dtype, resid, ldr);
   LS_CHECK_LAUNCH();
@@ -537,6 +537,34 @@ ls_status gemm_dma_splitk_try(int op_dtype, int M, int N, int K, const void* A, 
     return run_splitk<bf16_t>(g, splits, scratch, C, ldc, c_dtype, bias, bias_dtype, resid, ldr, st);
   if (op_dtype == LS_F16)
     return run_splitk<f16_t>(g, splits, scratch, C, ldc, c_dtype, bias, bias_dtype, resid, ldr, st);
+  return LS_ESTATE;
+}
+
+// Weight-streaming product for a few rows (decode batches, M <= 64): tiles of 64 x 128 so that
+// three workgroups share a compute unit, the weights stream through LDS as whole cache lines,
+// and the contraction is split until the chip has about three workgroups per compute unit.
+ls_status gemm_dma_skinny_try(int op_dtype, int M, int N, int K, const void* A, long lda, const void* B, long ldb,
+                              void* C, long ldc, int c_dtype, const void* bias, int bias_dtype,
+                              const float* resid, long ldr, float* scratch, size_t scratch_floats,
+                              hipStream_t st) {
+  if (!scratch || K % TK != 0 || M < 1 || M > 64 || N < 64 || N % 4 != 0) return LS_ESTATE;
+  const int per16 = c_dtype == LS_F32 ? 4 : 8;
+  if (ldc % per16 != 0 || (uintptr_t)C % 16 != 0 || (uintptr_t)scratch % 16 != 0) return LS_ESTATE;
+  if (resid && (ldr % 4 != 0 || (uintptr_t)resid % 16 != 0)) return LS_ESTATE;
+  const long tiles = (N + 127) / 128;
+  const int nk = K / TK;
+  int splits = (int)(768 / tiles);   // one round of workgroups: three 48 KB tiles fit a compute unit
+  if (splits < 1) splits = 1;
+  if (splits > 16) splits = 16;
+  while (splits > 1 && nk / splits < 6) --splits;
+  while (splits > 1 && (size_t)splits * M * N > scratch_floats) --splits;
+  if ((size_t)splits * M * N > scratch_floats) return LS_ESTATE;
+  DmaArgs g{M, N, K, A, lda, 1, B, ldb, 1, nullptr, 0, LS_F32, nullptr, 0, nullptr, 0, 0, nullptr, 0, 0, 0, nullptr,
+            nullptr, 0};
+  if (op_dtype == LS_BF16)
+    return run_splitk<bf16_t, 64>(g, splits, scratch, C, ldc, c_dtype, bias, bias_dtype, resid, ldr, st);
+  if (op_dtype == LS_F16)
+    return run_splitk<f16_t, 64>(g, splits, scratch, C, ldc, c_dtype, bias, bias_dtype, resid, ldr, st);
   return LS_ESTATE;
 }
 

@@ -228,7 +228,8 @@ struct FwdBufs {
 ls_status linear(const ls_stage* s, int T, int N, int K, const void* X, const void* W, void* C, int c_dtype,
                  const void* bias, const float* resid, float* scratch, hipStream_t st) {
   const int mt = s->cfg.mma_dtype;
-  if (mt != LS_F32 && T <= 128 && scratch)
+  static const bool skinny_dma = [] { const char* e = getenv("LS_SKINNY_IMPL"); return !(e && strcmp(e, "mfma") == 0); }();
+  if (mt != LS_F32 && T <= 128 && scratch && !(skinny_dma && T <= 64))
     return lsk_gemm_skinny(mt, T, N, K, X, K, W, K, C, N, c_dtype, bias, s->cfg.dtype, resid, N, scratch, st);
   return lsk_gemm_ws(mt, T, N, K, X, K, W, K, C, N, c_dtype, bias, s->cfg.dtype, resid, N, scratch,
                      scratch ? serve_scratch_floats(s) : 0, st);

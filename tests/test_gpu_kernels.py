@@ -90,7 +90,11 @@ def test_gemm_skinny_weight_streaming(name, M, N, K, split):
 
 @pytest.mark.parametrize("name", ["f16", "bf16"])
 @pytest.mark.parametrize("M,N,K,out,res", [(512, 4096, 4096, "f32", True), (512, 4096, 11008, "f32", True),
-                                            (300, 520, 2048, "op", False), (256, 264, 4096, "op", False)])
+                                            (300, 520, 2048, "op", False), (256, 264, 4096, "op", False),
+                                            # decode batches: 64 x 128 weight-streaming tiles
+                                            (64, 4096, 4096, "f32", True), (64, 12288, 4096, "op", False),
+                                            (33, 264, 1024, "op", False), (1, 128, 512, "f32", True),
+                                            (7, 1048, 11008, "op", False)])
 def test_gemm_split_k_through_a_workspace(name, M, N, K, out, res):
     """Few output tiles: the contraction is split over workgroups and summed in a fixed order."""
     dt = DT[name]
