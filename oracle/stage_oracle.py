@@ -453,3 +453,51 @@ def stage_train_bwd(cfg, flat_params, saved, dY):
                 dlayers[l][name] += val
         dX[b] = dx
     return dX, dflat
+
+
+# ---------------------------------------------------------------------------------------
+# Model update after a training task (Model Update Synchronization: every co-located
+# instance applies its own local updates, so that later inference tasks on the same stage
+# are served from the updated weights).  The paper names no optimizer; the two textbook
+# rules are written out as plain definitions.
+#
+#   SGD with momentum and L2 decay:   g' = g + wd w ;  b <- mu b + g' ;  w <- w - lr b
+#   AdamW (decoupled weight decay):   m <- b1 m + (1 - b1) g ;  v <- b2 v + (1 - b2) g^2
+#                                     w <- w - lr ( m / (1 - b1^t) / (sqrt(v / (1 - b2^t)) + eps) + wd w )
+#
+# `decay` is a 0/1 array: decay applies to the linear maps' weight matrices only (not to
+# normalisation gains or biases).  `g` is first multiplied by grad_scale (e.g. one over the
+# number of accumulated micro-batches).  `t` counts steps from 1.
+def optimizer_step(kind, w, g, m, v, t, lr, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.0,
+                   momentum=0.0, grad_scale=1.0, decay=None):
+    """Returns (w, m, v) after one update; inputs are not modified.  For SGD `m` is the
+    momentum buffer and `v` passes through unchanged."""
+    w = np.array(w, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64) * grad_scale
+    m = np.array(m, dtype=np.float64)
+    v = np.array(v, dtype=np.float64)
+    wd = weight_decay * (np.ones_like(w) if decay is None else np.asarray(decay, dtype=np.float64))
+    if kind == "sgd":
+        g = g + wd * w
+        m = momentum * m + g
+        return w - lr * m, m, v
+    if kind == "adamw":
+        m = beta1 * m + (1.0 - beta1) * g
+        v = beta2 * v + (1.0 - beta2) * g * g
+        m_hat = m / (1.0 - beta1 ** t)
+        v_hat = v / (1.0 - beta2 ** t)
+        return w - lr * (m_hat / (np.sqrt(v_hat) + eps) + wd * w), m, v
+    raise ValueError(kind)
+
+
+def decay_mask(cfg):
+    """1 for elements of weight matrices (2-D fields), 0 for gains and biases, in boundary order."""
+    out = np.zeros(n_params(cfg))
+    off = 0
+    for _ in range(cfg["n_layers"]):
+        for _name, shape in _layer_fields(cfg):
+            n = int(np.prod(shape))
+            if len(shape) == 2:
+                out[off:off + n] = 1.0
+            off += n
+    return out

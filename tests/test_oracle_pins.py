@@ -432,3 +432,80 @@ def test_sampled_rows_equal_the_full_block(block, act):
     full, _, _, _ = O.block_forward(cfg, p, x, np.arange(11))
     rows = [0, 3, 10]
     np.testing.assert_allclose(O.block_forward_rows(cfg, p, x, rows), full[rows], rtol=0, atol=1e-12)
+
+
+# ---- model update rules (textbook SGD with momentum, AdamW) ---------------------------------
+
+def test_adamw_first_step_is_lr_times_the_sign_like_ratio():
+    rng = np.random.default_rng(3)
+    w, g = rng.normal(size=50), rng.normal(size=50)
+    w1, m1, v1 = O.optimizer_step("adamw", w, g, np.zeros(50), np.zeros(50), 1, lr=1e-2, eps=1e-8, weight_decay=0.1)
+    # t = 1 with zero state: m_hat = g, v_hat = g^2
+    assert np.allclose(w1, w - 1e-2 * (g / (np.abs(g) + 1e-8) + 0.1 * w), rtol=0, atol=1e-15)
+    assert np.allclose(m1, 0.1 * g) and np.allclose(v1, 0.001 * g * g)
+
+
+def test_adamw_constant_gradient_keeps_bias_corrected_moments_exact():
+    # with a constant gradient the bias-corrected moments are g and g^2 at every step, so every
+    # step moves by lr g / (|g| + eps) (no decay): n steps give a closed form
+    g = np.array([0.3, -2.0, 1e-3])
+    w, m, v = np.array([1.0, 2.0, 3.0]), np.zeros(3), np.zeros(3)
+    for t in range(1, 8):
+        w, m, v = O.optimizer_step("adamw", w, g, m, v, t, lr=0.05, eps=1e-6)
+    assert np.allclose(w, np.array([1.0, 2.0, 3.0]) - 7 * 0.05 * g / (np.abs(g) + 1e-6), atol=1e-12)
+
+
+def test_adamw_decay_alone_is_a_geometric_shrink_and_respects_the_mask():
+    w0 = np.array([2.0, -4.0, 8.0])
+    w, m, v = w0.copy(), np.zeros(3), np.zeros(3)
+    for t in range(1, 6):
+        w, m, v = O.optimizer_step("adamw", w, np.zeros(3), m, v, t, lr=0.1, weight_decay=0.5, decay=[1, 1, 0])
+    assert np.allclose(w[:2], w0[:2] * (1 - 0.1 * 0.5) ** 5) and w[2] == 8.0
+
+
+def test_adamw_update_is_invariant_to_gradient_scale_without_eps():
+    rng = np.random.default_rng(4)
+    w, g = rng.normal(size=20), rng.normal(size=20)
+    m, v = np.abs(rng.normal(size=20)) * 0.0, np.zeros(20)
+    a = O.optimizer_step("adamw", w, g, m, v, 1, lr=1e-3, eps=0.0)[0]
+    b = O.optimizer_step("adamw", w, g, m, v, 1, lr=1e-3, eps=0.0, grad_scale=37.0)[0]
+    assert np.allclose(a, b, atol=1e-15)
+
+
+def test_sgd_momentum_closed_form_for_a_constant_gradient():
+    g, mu, lr = np.array([0.5, -1.0]), 0.9, 0.1
+    w, m = np.array([1.0, 1.0]), np.zeros(2)
+    for t in range(1, 11):
+        w, m, _ = O.optimizer_step("sgd", w, g, m, np.zeros(2), t, lr=lr, momentum=mu)
+    # b_n = g (1 - mu^n) / (1 - mu);  sum_{n<=N} b_n = g (N - mu (1 - mu^N) / (1 - mu)) / (1 - mu)
+    N = 10
+    total = g * (N - mu * (1 - mu ** N) / (1 - mu)) / (1 - mu)
+    assert np.allclose(w, 1.0 - lr * total, atol=1e-12)
+    assert np.allclose(m, g * (1 - mu ** N) / (1 - mu))
+
+
+def test_sgd_l2_decay_enters_through_the_gradient():
+    w1, _, _ = O.optimizer_step("sgd", np.array([2.0]), np.array([0.5]), np.zeros(1), np.zeros(1), 1, lr=0.1, weight_decay=0.25)
+    assert np.allclose(w1, 2.0 - 0.1 * (0.5 + 0.25 * 2.0))
+
+
+def test_optimizer_matches_a_scalar_loop():
+    rng = np.random.default_rng(5)
+    n = 17
+    w, g, m, v = rng.normal(size=n), rng.normal(size=n), rng.normal(size=n) * 0.1, np.abs(rng.normal(size=n)) * 0.01
+    dec = (rng.random(n) > 0.5).astype(float)
+    got = O.optimizer_step("adamw", w, g, m, v, 5, lr=3e-3, beta1=0.8, beta2=0.95, eps=1e-7, weight_decay=0.02,
+                           grad_scale=0.25, decay=dec)
+    for i in range(n):
+        gi = g[i] * 0.25
+        mi = 0.8 * m[i] + 0.2 * gi
+        vi = 0.95 * v[i] + 0.05 * gi * gi
+        wi = w[i] - 3e-3 * ((mi / (1 - 0.8 ** 5)) / (math.sqrt(vi / (1 - 0.95 ** 5)) + 1e-7) + 0.02 * dec[i] * w[i])
+        assert abs(got[0][i] - wi) < 1e-14 and abs(got[1][i] - mi) < 1e-15 and abs(got[2][i] - vi) < 1e-15
+
+
+def test_decay_mask_marks_weight_matrices_only():
+    cfg = S.CONFIGS["tiny_gpt_f32"]
+    mask = O.decay_mask(cfg)
+    n_w = sum(int(np.prod(sh)) for _, _, sh, init in S.param_layout(cfg) if init == "normal")
+    assert mask.sum() == n_w and set(np.unique(mask)) == {0.0, 1.0}
