@@ -81,6 +81,7 @@ def main():
     ap.add_argument("--mma", default="f16", choices=["f16", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
+    ap.add_argument("--no-update", action="store_true", help="skip the model-update measurement (3 fp32 vectors of the stage's size)")
     ap.add_argument("--legs", default="train,decode,prefill",
                     help="comma list of the legs that make up a step (profiling aid; the default is the full "
                          "step; 'gemms' = the 12 GEMM launches of one block on their own; 'calib' = a 256 MiB copy kernel "
@@ -256,6 +257,31 @@ def main():
                  "decode_tok_s_alone": Bq / ms[0] * 1e3, "decode_tok_s_together": Bq / ms[2] * 1e3,
                  "train_tok_s_alone": Bt * Lt / ms[1] * 1e3, "train_tok_s_together": Bt * Lt / ms[3] * 1e3}
 
+    # ---- model update (a row beyond the step: AdamW over the stage's parameters, last because it
+    #      rewrites the weights) -------------------------------------------------------------------
+    roofline_update = None
+    if not args.no_update:
+        n_par = st.ls_param_count()
+        master = params.to(torch.float32)
+        m_buf = torch.zeros(n_par, dtype=torch.float32, device=dev)
+        v_buf = torch.zeros(n_par, dtype=torch.float32, device=dev)
+        step_no = [0]
+
+        def update():
+            step_no[0] += 1
+            st.stage_optimizer_step(params, master, m_buf, v_buf, dP, kind=Bd.LS_OPT_ADAMW, lr=1e-5,
+                                    step=step_no[0], weight_decay=0.01)
+
+        ms_upd = time_events(torch, update, 3)
+        upd_bytes = 32.0 * n_par    # g, m, v, w read; m, v, w written; bf16 parameter and fp16 operand copy written
+        roofline_update = {"bound": "hbm", "kernel": "optimizer_kernel (AdamW, fused refresh of the bf16 parameters "
+                           "and the fp16 operand copy)", "achieved": upd_bytes / (ms_upd * 1e-3) / 1e9,
+                           "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                           "frac": upd_bytes / (ms_upd * 1e-3) / 1e9 / PEAK_HBM_GBS, "ms": ms_upd,
+                           "bytes_per_step": upd_bytes, "traffic": None}
+        log(f"model update: {ms_upd:.2f} ms -> {roofline_update['achieved']:.0f} GB/s")
+        del master, m_buf, v_buf
+
     out = {
         "metric": "stage tok/s (train fwd+bwd + ragged decode + prefill chunks), LLaMA-7B-shaped 8-block stage, 1 MI355X",
         "value": tokens_per_step / (ms_per_step * 1e-3), "unit": "tok/s", "n_gpus": 1,
@@ -271,7 +297,8 @@ def main():
                       "prefill_tok_s": sum(chunks) / ms_pre * 1e3, "prefill_ms": ms_pre,
                       "train_frac_of_mfma_peak": (3.0 * T * nL * (8.0 * d * d + 6.0 * d * F)
                                                   + 3.0 * 2.0 * L * L * d * B * nL) / (ms_train * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS},
-        "roofline": roofline, "roofline_decode": roofline_decode, "probe": probe,
+        "roofline": roofline, "roofline_decode": roofline_decode, "roofline_update": roofline_update,
+        "probe": probe,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, S)

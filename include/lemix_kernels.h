@@ -130,6 +130,21 @@ ls_status lsk_attn_bwd_rope(int impl, const void* qkv, const void* o, const void
                             const float* table, void* stream);
 
 /*
+ * The update of one parameter tensor of n elements (see stage_optimizer_step
+ * for the rules): kind 0 = SGD with momentum, 1 = AdamW; step >= 1.  grad, m,
+ * v (AdamW only), master are fp32 device vectors; params is the tensor in its
+ * storage type param_dtype (LS_F32, in which case it may be `master` itself,
+ * or LS_BF16), rewritten as round(master); params_op (nullable) is the
+ * matrix-core operand copy in op_dtype (LS_F16 / LS_BF16), rewritten as the
+ * conversion of the stored parameter.  Algorithmic bytes per element: 16 read,
+ * 12 written, plus 2 per 16-bit copy.
+ */
+ls_status lsk_optimizer(int kind, float lr, float beta1, float beta2, float eps, float weight_decay,
+                        float momentum, float grad_scale, int step, size_t n, const float* grad,
+                        float* m, float* v, float* master, void* params, int param_dtype,
+                        void* params_op, int op_dtype, void* stream);
+
+/*
  * The forward-layout product of a decoder block's linear maps (Model
  * Architecture): C[M, N] = X[M, K] W[N, K]^T + bias + resid, as lsk_gemm with
  * both operands k-major, plus a caller workspace `scratch` (device, fp32,

@@ -181,6 +181,43 @@ ls_status stage_train_bwd(ls_stage* s, const void* dY, int B, int L, const void*
                           void* stream);
 
 /*
+ * Model update after training tasks (Model Update Synchronization: every
+ * co-located instance applies its own local updates, and the inference tasks
+ * that follow on the same stage are served from the updated weights).  The
+ * paper names no optimizer; the two textbook rules are offered:
+ *   LS_OPT_SGD    g' = g + wd w;  b <- momentum b + g';  w <- w - lr b
+ *   LS_OPT_ADAMW  m <- beta1 m + (1 - beta1) g;  v <- beta2 v + (1 - beta2) g^2;
+ *                 w <- w - lr (m / (1 - beta1^step) / (sqrt(v / (1 - beta2^step)) + eps) + wd w)
+ * where g = grad_scale * dParams (e.g. one over the number of accumulated
+ * micro-batches) and the decay wd applies to the weight matrices only, not to
+ * normalisation gains or biases.  step counts updates from 1.
+ */
+typedef enum { LS_OPT_SGD = 0, LS_OPT_ADAMW = 1 } ls_opt_kind;
+typedef struct {
+  int32_t kind;
+  float lr, beta1, beta2, eps, weight_decay, momentum, grad_scale;
+  int32_t step;
+} ls_optim;
+
+/*
+ * One fused bandwidth-bound pass over the stage's parameters, enqueued on
+ * `stream`.  All vectors are device memory of ls_param_count(s) elements in
+ * boundary order, caller-owned:
+ *   params   the vector bound with ls_bind_params (cfg.dtype), rewritten as
+ *            the rounded master weights; the library's operand-format copy is
+ *            rewritten in the same pass, so stage_* calls enqueued afterwards
+ *            on the same stream compute with the new weights;
+ *   master   fp32 weights (may be `params` itself for an fp32 stage), updated;
+ *   m, v     fp32 optimizer state (m = momentum buffer for SGD, v unused and
+ *            may be null), updated;
+ *   dParams  fp32 gradients from stage_train_bwd, read only.
+ * fp32 vectors must be 16-byte aligned.  LS_EINVAL on null arguments, an
+ * unknown kind, step < 1 or a `params` that is not the bound vector.
+ */
+ls_status stage_optimizer_step(ls_stage* s, const ls_optim* opt, void* params, float* master,
+                               float* m, float* v, const float* dParams, void* stream);
+
+/*
  * Interference probe (the co-location effect the paper measures: training
  * and inference contending for one GPU).  Runs `iters` repetitions of
  *   A: one stage_decode(dec_X, dec_B, kv, dec_Y, ws_a) on stream_a,

@@ -42,6 +42,15 @@ class ls_config(C.Structure):
                 ("page_size", C.c_int32), ("max_pos", C.c_int32)]
 
 
+class ls_optim(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("lr", C.c_float), ("beta1", C.c_float), ("beta2", C.c_float),
+                ("eps", C.c_float), ("weight_decay", C.c_float), ("momentum", C.c_float),
+                ("grad_scale", C.c_float), ("step", C.c_int32)]
+
+
+LS_OPT_SGD, LS_OPT_ADAMW = 0, 1
+
+
 class ls_kv(C.Structure):
     _fields_ = [("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("block_table", C.c_void_p),
                 ("ctx_len", C.c_void_p), ("ctx_len_host", C.c_void_p),
@@ -65,9 +74,11 @@ SIGNATURES = {
     "stage_train_bwd": (_I, [_VP, _VP, _I, _I, _VP, _VP, _VP, _I, _VP, _VP]),
     "stage_probe_interference": (_I, [_VP, _VP, _I, C.POINTER(ls_kv), _VP, _VP, _VP, _I, _I, _VP, _VP,
                                       _VP, _VP, _VP, _VP, _VP, _VP, _I, C.POINTER(C.c_float)]),
+    "stage_optimizer_step": (_I, [_VP, C.POINTER(ls_optim), _VP, _VP, _VP, _VP, _VP, _VP]),
     "ls_last_error": (C.c_char_p, []),
     "lsk_gemm": (_I, [_I, _I, _I, _I, _VP, _L, _I, _VP, _L, _I, _VP, _L, _I, _VP, _I, _VP, _L, _I, _VP]),
     "lsk_gemm_ws": (_I, [_I, _I, _I, _I, _VP, _L, _VP, _L, _VP, _L, _I, _VP, _I, _VP, _L, _VP, _SZ, _VP]),
+    "lsk_optimizer": (_I, [_I, _F, _F, _F, _F, _F, _F, _F, _I, _SZ, _VP, _VP, _VP, _VP, _VP, _I, _VP, _I, _VP]),
     "lsk_convert": (_I, [_VP, _I, _VP, _I, _SZ, _VP]),
     "lsk_grad_scale": (_I, [_VP, _I, _SZ, _VP, _VP]),
     "lsk_gemm_scaled": (_I, [_I, _I, _I, _I, _VP, _L, _I, _VP, _L, _I, _VP, _L, _I, _VP, _I, _VP, _L, _I, _VP, _VP]),
@@ -228,6 +239,12 @@ class Stage:
         _check(lib().stage_train_bwd(self.h, _p(dY), B, L, _p(saved), _p(dX), _p(dParams),
                                      int(accumulate), _p(workspace), _stream(stream)))
 
+    def stage_optimizer_step(self, params, master, m, v, dParams, *, kind, lr, step, beta1=0.9, beta2=0.999,
+                             eps=1e-8, weight_decay=0.0, momentum=0.0, grad_scale=1.0, stream=None):
+        o = ls_optim(kind, lr, beta1, beta2, eps, weight_decay, momentum, grad_scale, step)
+        _check(lib().stage_optimizer_step(self.h, C.byref(o), _p(params), _p(master), _p(m),
+                                          _p(v) if v is not None else None, _p(dParams), _stream(stream)))
+
     def stage_probe_interference(self, dec_X, dec_B, kv: KV, dec_Y, ws_a, trn_X, trn_B, trn_L, trn_Y,
                                  trn_saved, trn_dY, trn_dX, trn_dParams, ws_b, stream_a, stream_b,
                                  iters):
@@ -328,6 +345,16 @@ def lsk_attn_bwd(impl, qkv, o, dO, lse, B, L, n_heads, head_dim, dqkv, stream=No
     dvec = torch.empty(lib().lsk_attn_bwd_scratch_floats(B, L, n_heads), dtype=torch.float32, device=qkv.device)
     _check(lib().lsk_attn_bwd(impl, _p(qkv), _p(o), _p(dO), _p(lse), CODE_OF_TORCH[qkv.dtype], B, L,
                               n_heads, head_dim, _p(dqkv), _p(dvec), _stream(stream)))
+
+
+def lsk_optimizer(kind, grad, m, v, master, params, params_op, *, lr, step, beta1=0.9, beta2=0.999, eps=1e-8,
+                  weight_decay=0.0, momentum=0.0, grad_scale=1.0, stream=None):
+    _check(lib().lsk_optimizer(kind, lr, beta1, beta2, eps, weight_decay, momentum, grad_scale, step,
+                               grad.numel(), _p(grad), _p(m), _p(v) if v is not None else None, _p(master),
+                               _p(params), CODE_OF_TORCH[params.dtype],
+                               _p(params_op) if params_op is not None else None,
+                               CODE_OF_TORCH[params_op.dtype] if params_op is not None else 0,
+                               _stream(stream)))
 
 
 def lsk_gemm_ws(x, w, c, scratch, bias=None, resid=None, stream=None):

@@ -41,6 +41,8 @@ ls_status lsk_gemm_qkv_rope(int, int, int, const void*, const void*, void*, int,
                             void*);
 ls_status lsk_gemm_ws(int, int, int, int, const void*, long, const void*, long, void*, long, int, const void*, int,
                       const float*, long, float*, size_t, void*);
+ls_status lsk_optimizer(int, float, float, float, float, float, float, float, int, size_t, const float*, float*, float*,
+                        float*, void*, int, void*, int, void*);
 ls_status lsk_attn_bwd_rope(int, const void*, const void*, const void*, const float*, int, int, int, int, int,
                             void*, float*, const int32_t*, const float*, void*);
 ls_status lsk_rope_kv_write(void*, int, int, int, int, const int32_t*, const int32_t*, const float*, void*, void*,
@@ -554,6 +556,43 @@ ls_status stage_train_bwd(ls_stage* s, const void* dY, int B, int L, const void*
                         dParams + o.n1_g, gpt ? dParams + o.n1_b : nullptr, acc, w.partial, inv, st));
   }
   return lsk_convert_scaled(w.g, LS_F32, dX, c.io_dtype, (size_t)T * d, inv, st);
+}
+
+// Model update: one fused pass per parameter tensor (decay on the weight matrices only)
+ls_status stage_optimizer_step(ls_stage* s, const ls_optim* opt, void* params, float* master, float* m, float* v,
+                               const float* dParams, void* stream) {
+  LS_TRY(check_stage(s, true));
+  LS_REQUIRE(opt && params && master && m && dParams, "stage_optimizer_step: null argument");
+  LS_REQUIRE(params == s->params, "stage_optimizer_step: params must be the vector bound with ls_bind_params");
+  LS_REQUIRE(opt->kind == LS_OPT_SGD || opt->kind == LS_OPT_ADAMW, "stage_optimizer_step: unknown optimizer %d", opt->kind);
+  LS_REQUIRE(opt->kind == LS_OPT_SGD || v, "stage_optimizer_step: AdamW needs the second-moment vector");
+  LS_REQUIRE(opt->step >= 1, "stage_optimizer_step: steps count from 1 (got %d)", opt->step);
+  const ls_config& c = s->cfg;
+  const size_t d = c.d_model, F = c.d_ff, U = s->up_cols;
+  const bool gpt = c.block == LS_BLOCK_GPT_PRELN;
+  const size_t psz = dtype_size(c.dtype), osz_ = dtype_size(c.mma_dtype);
+  auto one = [&](size_t off, size_t n, bool decay) -> ls_status {
+    void* pop = s->owns_op ? (char*)s->params_op + off * osz_ : nullptr;
+    return lsk_optimizer(opt->kind, opt->lr, opt->beta1, opt->beta2, opt->eps, decay ? opt->weight_decay : 0.f,
+                         opt->momentum, opt->grad_scale, opt->step, n, dParams + off, m + off, v ? v + off : nullptr,
+                         master + off, (char*)params + off * psz, c.dtype, pop, c.mma_dtype, stream);
+  };
+  for (int l = 0; l < c.n_layers; ++l) {
+    const LayerOff& o = s->off[l];
+    LS_TRY(one(o.n1_g, d, false));
+    if (gpt) LS_TRY(one(o.n1_b, d, false));
+    LS_TRY(one(o.w_qkv, 3 * d * d, true));
+    if (gpt) LS_TRY(one(o.b_qkv, 3 * d, false));
+    LS_TRY(one(o.w_o, d * d, true));
+    if (gpt) LS_TRY(one(o.b_o, d, false));
+    LS_TRY(one(o.n2_g, d, false));
+    if (gpt) LS_TRY(one(o.n2_b, d, false));
+    LS_TRY(one(o.w_up, U * d, true));
+    if (gpt) LS_TRY(one(o.b_up, U, false));
+    LS_TRY(one(o.w_dn, d * F, true));
+    if (gpt) LS_TRY(one(o.b_dn, d, false));
+  }
+  return LS_OK;
 }
 
 ls_status stage_probe_interference(ls_stage* s, const void* dec_X, int dec_B, const ls_kv* kv, void* dec_Y,
