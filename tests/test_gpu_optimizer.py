@@ -107,3 +107,18 @@ def test_stage_update_then_serving_uses_the_new_weights(which, kind):
     ys_old = O.stage_prefill(cfg, flat.astype(np.float64), [Xs.astype(np.float64)], O.new_cache(cfg, 1))
     assert np.abs(ys_old[0] - ys[0]).max() > 4 * TOL["bf16"] * np.sqrt((ys[0] ** 2).mean())
     st.close()
+
+
+def test_offline_profiler_sweep_runs_the_stage_and_reduces_its_timings():
+    """Small stage, tiny sweep: every timing is positive, backward costs more than forward, the
+    memory demand grows with C * l, and the summary carries the paper's coefficients."""
+    from paper_2507_21276_amd import profiler as PR
+    rows = PR.sweep(SMALL_LLAMA, [1, 2], [64, 128], reps=2)
+    assert len(rows) == 4
+    for r in rows:
+        assert r["train_fwd_s"] > 0 and r["train_bwd_s"] > r["train_fwd_s"] * 0.8 and r["prefill_s"] > 0
+    assert rows[-1]["saved_bytes"] > rows[0]["saved_bytes"]
+    s = PR.summarise(rows, kappa=0.9)
+    for k in ("eta_F_train", "eta_F_prefill", "eta_B"):
+        assert s[k]["eta_s_per_token_sq"] > 0
+    assert s["M_threshold_bytes"] == pytest.approx(0.9 * s["M_peak_bytes"])
