@@ -140,6 +140,20 @@ def main():
     Xp = S.normal_torch(0, "Xprefill", (sum(chunks), d), 1.0, dev, io)
     Yp = torch.empty_like(Xp)
 
+    # hybrid iteration-level mini-batch: the same 64 decode rows plus one 512-token prompt chunk in one call
+    ctx_h = np.concatenate([ctx, np.zeros(1, ctx.dtype)])
+    new_h = np.concatenate([np.ones_like(ctx), np.array([chunks[0]], ctx.dtype)])
+    htab, hn = S.page_tables(ctx_h, new_h, P, seed=2)
+    kvh = Bd.KV(st, hn, htab, ctx_h)
+    kvh.k_pool.copy_(S.normal_torch(0, "Khyb", kvh.k_pool.shape, 1.0, dev, kvh.k_pool.dtype))
+    kvh.v_pool.copy_(S.normal_torch(0, "Vhyb", kvh.v_pool.shape, 1.0, dev, kvh.v_pool.dtype))
+    Xh = S.normal_torch(0, "Xhyb", (Bq + chunks[0], d), 1.0, dev, io)
+    Yh = torch.empty_like(Xh)
+    ws_h = st.new_workspace(Bq + chunks[0])
+
+    def hybrid():
+        st.stage_step(Xh, Bq, [chunks[0]], kvh, Yh, ws_h)
+
     def decode():
         st.stage_decode(Xd, Bq, kv, Yd, ws_a)
 
@@ -215,7 +229,9 @@ def main():
         print(json.dumps({"legs": legs, "ms_per_step": ms_per_step, "train_ms": ms_train, "decode_ms": ms_dec,
                           "prefill_ms": ms_pre}), flush=True)
         return
-    log(f"train {ms_train:.2f} ms, decode {ms_dec:.3f} ms, prefill {ms_pre:.2f} ms")
+    ms_hyb = time_events(torch, hybrid, it)
+    log(f"train {ms_train:.2f} ms, decode {ms_dec:.3f} ms, prefill {ms_pre:.2f} ms; hybrid 64 decode rows + one "
+        f"512-token chunk in one call {ms_hyb:.2f} ms")
 
     # ---- GEMM roofline ---------------------------------------------------------------------
     traffic = {}
@@ -295,6 +311,8 @@ def main():
         "breakdown": {"train_fwd_bwd_tok_s": T / ms_train * 1e3, "train_ms": ms_train,
                       "decode_tok_s": Bq / ms_dec * 1e3, "decode_ms": ms_dec,
                       "prefill_tok_s": sum(chunks) / ms_pre * 1e3, "prefill_ms": ms_pre,
+                      "hybrid_decode64_chunk512_ms": ms_hyb,
+                      "hybrid_separate_calls_ms": ms_dec + ms_pre / len(chunks),
                       "train_frac_of_mfma_peak": (3.0 * T * nL * (8.0 * d * d + 6.0 * d * F)
                                                   + 3.0 * 2.0 * L * L * d * B * nL) / (ms_train * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS},
         "roofline": roofline, "roofline_decode": roofline_decode, "roofline_update": roofline_update,

@@ -181,6 +181,25 @@ ls_status stage_train_bwd(ls_stage* s, const void* dY, int B, int L, const void*
                           void* stream);
 
 /*
+ * One forward over a hybrid iteration-level mini-batch (Continuous Batching:
+ * a mini-batch holds the ongoing decodes together with newly admitted prompt
+ * chunks; Algorithm 3 forms it, this call executes it on the stage).  Requests
+ * 0 .. n_decode-1 contribute one row each (a decode step at position
+ * ctx_len[b]); requests n_decode .. n_decode+n_prefill-1 contribute
+ * chunk_len[b - n_decode] rows each (positions ctx_len[b] ..), in that order:
+ *   X, Y [dev] [n_decode + sum(chunk_len), d] io_dtype;  chunk_len [host];
+ *   kv describes all n_decode + n_prefill requests (block_table rows and
+ *   ctx_len in the same order).
+ * The projections and FFN run once over all rows, so the decode rows share
+ * the weight traffic of the prompt chunks; attention runs the decode kernel
+ * on the first n_decode rows and the prompt-chunk kernel on the rest.  Row
+ * results equal those of separate stage_decode / stage_prefill calls up to
+ * rounding order.  n_prefill <= 32; errors as stage_prefill.
+ */
+ls_status stage_step(ls_stage* s, const void* X, int n_decode, const int32_t* chunk_len,
+                     int n_prefill, const ls_kv* kv, void* Y, void* workspace, void* stream);
+
+/*
  * Model update after training tasks (Model Update Synchronization: every
  * co-located instance applies its own local updates, and the inference tasks
  * that follow on the same stage are served from the updated weights).  The

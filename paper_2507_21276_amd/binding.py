@@ -70,6 +70,7 @@ SIGNATURES = {
     "ls_saved_bytes": (_SZ, [_VP, _I, _I]),
     "stage_prefill": (_I, [_VP, _VP, C.POINTER(C.c_int32), _I, C.POINTER(ls_kv), _VP, _VP, _VP]),
     "stage_decode": (_I, [_VP, _VP, _I, C.POINTER(ls_kv), _VP, _VP, _VP]),
+    "stage_step": (_I, [_VP, _VP, _I, C.POINTER(C.c_int32), _I, C.POINTER(ls_kv), _VP, _VP, _VP]),
     "stage_train_fwd": (_I, [_VP, _VP, _I, _I, _VP, _VP, _VP, _VP]),
     "stage_train_bwd": (_I, [_VP, _VP, _I, _I, _VP, _VP, _VP, _I, _VP, _VP]),
     "stage_probe_interference": (_I, [_VP, _VP, _I, C.POINTER(ls_kv), _VP, _VP, _VP, _I, _I, _VP, _VP,
@@ -226,6 +227,12 @@ class Stage:
         d = kv.desc(with_host)
         _check(lib().stage_prefill(self.h, _p(X), cl, len(chunk_len), C.byref(d), _p(Y), _p(workspace),
                                    _stream(stream)))
+
+    def stage_step(self, X, n_decode, chunk_len, kv: KV, Y, workspace, stream=None, with_host=True):
+        cl = (C.c_int32 * max(1, len(chunk_len)))(*[int(v) for v in chunk_len])
+        d = kv.desc(with_host)
+        _check(lib().stage_step(self.h, _p(X), n_decode, cl, len(chunk_len), C.byref(d), _p(Y), _p(workspace),
+                                _stream(stream)))
 
     def stage_decode(self, X, B, kv: KV, Y, workspace, stream=None, with_host=True):
         d = kv.desc(with_host)

@@ -95,6 +95,21 @@ __global__ void token_index_kernel(Chunks ch, const int32_t* ctx_len, int32_t* p
   pos[t] = ctx_len[b] + (t - ch.start[b]);
   req[t] = b;
 }
+// hybrid batch: n_dec single-token rows (request t), then the chunk rows of requests n_dec + b
+__global__ void hybrid_index_kernel(int n_dec, Chunks ch, const int32_t* ctx_len, int32_t* pos, int32_t* req) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < n_dec) {
+    pos[t] = ctx_len[t];
+    req[t] = t;
+    return;
+  }
+  const int u = t - n_dec;
+  if (u >= ch.start[ch.n]) return;
+  int b = 0;
+  while (u >= ch.start[b + 1]) ++b;
+  pos[t] = ctx_len[n_dec + b] + (u - ch.start[b]);
+  req[t] = n_dec + b;
+}
 __global__ void decode_index_kernel(int B, const int32_t* ctx_len, int32_t* pos, int32_t* req) {
   const int t = blockIdx.x * blockDim.x + threadIdx.x;
   if (t >= B) return;
@@ -237,9 +252,11 @@ ls_status linear(const ls_stage* s, int T, int N, int K, const void* X, const vo
                      scratch ? serve_scratch_floats(s) : 0, st);
 }
 
+// n_decode (serving with chunk_start only): the first n_decode rows are single-token decode rows of
+// requests 0 .. n_decode - 1; chunk_start then describes requests n_decode .. B - 1 (rows after them)
 ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const int32_t* pos,
                         const int32_t* req, int B, int L, const ls_kv* kv, int max_ctx,
-                        const int32_t* chunk_start, hipStream_t st) {
+                        const int32_t* chunk_start, int n_decode, hipStream_t st) {
   const ls_config& c = s->cfg;
   const LayerOff& o = s->off[l];
   const int d = c.d_model, F = c.d_ff, mt = c.mma_dtype, pt = c.dtype;
@@ -264,9 +281,19 @@ ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const
     LS_TRY(lsk_rope_kv_write(f.qkv, mt, T, c.n_heads, c.head_dim, pos, req, gpt || roped ? nullptr : s->rope_table, kp, vp,
                              kv->block_table, kv->max_pages_per_req, c.page_size, st));
     if (chunk_start && mt != LS_F32 && c.head_dim >= 64) {
+      // decode rows of a hybrid batch: the bandwidth-bound kernel, one row per request
+      if (n_decode > 0)
+        LS_TRY(lsk_attn_paged(1, f.qkv, mt, n_decode, c.n_heads, c.head_dim, pos, req, kp, vp, kv->block_table,
+                              kv->max_pages_per_req, c.page_size, max_ctx, f.o,
+                              (long)n_decode * c.n_heads < 2048 ? f.scratch : nullptr, st));
       // prompt chunks: matrix-core attention over the pages (queries of a chunk share the K/V tiles)
-      LS_TRY(lsk_attn_prefill_mfma(f.qkv, mt, B, chunk_start, c.n_heads, c.head_dim, kp, vp, kv->block_table,
-                                   kv->ctx_len, kv->max_pages_per_req, c.page_size, f.o, st));
+      const size_t e = osz(s);
+      if (B > n_decode)
+        LS_TRY(lsk_attn_prefill_mfma((const char*)f.qkv + (size_t)n_decode * 3 * d * e, mt, B - n_decode, chunk_start,
+                                     c.n_heads, c.head_dim, kp, vp,
+                                     kv->block_table + (size_t)n_decode * kv->max_pages_per_req,
+                                     kv->ctx_len + n_decode, kv->max_pages_per_req, c.page_size,
+                                     (char*)f.o + (size_t)n_decode * d * e, st));
     } else {
       LS_TRY(lsk_attn_paged(mt == LS_F32 ? 0 : 1, f.qkv, mt, T, c.n_heads, c.head_dim, pos, req, kp, vp,
                             kv->block_table, kv->max_pages_per_req, c.page_size, max_ctx, f.o,
@@ -311,13 +338,13 @@ ls_status check_kv(const ls_stage* s, const ls_kv* kv, int B, const int32_t* new
 }
 
 ls_status serve_forward(ls_stage* s, const void* X, int T, int B, const ls_kv* kv, int max_ctx, void* Y,
-                        const FwdWs& w, const int32_t* chunk_start, hipStream_t st) {
+                        const FwdWs& w, const int32_t* chunk_start, int n_decode, hipStream_t st) {
   const ls_config& c = s->cfg;
   LS_TRY(lsk_convert(X, c.io_dtype, w.xa, LS_F32, (size_t)T * c.d_model, st));
   for (int l = 0; l < c.n_layers; ++l) {
     FwdBufs f{w.xa, w.xb, w.xa, nullptr, nullptr, nullptr, nullptr, nullptr,
               w.h, w.qkv, w.o, w.h, w.up, w.act, w.scratch};
-    LS_TRY(block_forward(s, l, T, f, w.pos, w.req, B, 0, kv, max_ctx, chunk_start, st));
+    LS_TRY(block_forward(s, l, T, f, w.pos, w.req, B, 0, kv, max_ctx, chunk_start, n_decode, st));
   }
   return lsk_convert(w.xa, LS_F32, Y, c.io_dtype, (size_t)T * c.d_model, st);
 }
@@ -454,7 +481,7 @@ ls_status stage_prefill(ls_stage* s, const void* X, const int32_t* chunk_len, in
   carve_fwd(s, workspace, T, &w);
   token_index_kernel<<<(T + 255) / 256, 256, 0, st>>>(ch, kv->ctx_len, w.pos, w.req);
   LS_CHECK_LAUNCH();
-  return serve_forward(s, X, T, B, kv, max_ctx, Y, w, ch.start, st);
+  return serve_forward(s, X, T, B, kv, max_ctx, Y, w, ch.start, 0, st);
 }
 
 ls_status stage_decode(ls_stage* s, const void* X, int B, const ls_kv* kv, void* Y, void* workspace,
@@ -469,7 +496,37 @@ ls_status stage_decode(ls_stage* s, const void* X, int B, const ls_kv* kv, void*
   carve_fwd(s, workspace, B, &w);
   decode_index_kernel<<<(B + 255) / 256, 256, 0, st>>>(B, kv->ctx_len, w.pos, w.req);
   LS_CHECK_LAUNCH();
-  return serve_forward(s, X, B, B, kv, max_ctx, Y, w, nullptr, st);
+  return serve_forward(s, X, B, B, kv, max_ctx, Y, w, nullptr, 0, st);
+}
+
+ls_status stage_step(ls_stage* s, const void* X, int n_decode, const int32_t* chunk_len, int n_prefill,
+                     const ls_kv* kv, void* Y, void* workspace, void* stream) {
+  LS_TRY(check_stage(s, true));
+  LS_REQUIRE(X && Y && workspace, "stage_step: null argument");
+  LS_REQUIRE(n_decode >= 0 && n_prefill >= 0 && n_decode + n_prefill > 0, "stage_step: empty batch (%d decode, %d prefill)",
+             n_decode, n_prefill);
+  LS_REQUIRE(n_prefill <= 32, "stage_step: at most 32 prompt chunks per call, got %d", n_prefill);
+  LS_REQUIRE(n_prefill == 0 || chunk_len, "stage_step: null chunk_len");
+  const int B = n_decode + n_prefill;
+  std::vector<int32_t> new_tokens((size_t)B, 1);
+  Chunks ch;
+  ch.n = n_prefill;
+  ch.start[0] = 0;
+  for (int b = 0; b < n_prefill; ++b) {
+    new_tokens[(size_t)n_decode + b] = chunk_len[b];
+    LS_REQUIRE(chunk_len[b] > 0, "stage_step: chunk %d has %d tokens", b, chunk_len[b]);
+    ch.start[b + 1] = ch.start[b] + chunk_len[b];
+  }
+  int max_ctx = 0;
+  LS_TRY(check_kv(s, kv, B, new_tokens.data(), &max_ctx));
+  const int T = n_decode + ch.start[n_prefill];
+  hipStream_t st = (hipStream_t)stream;
+  FwdWs w;
+  carve_fwd(s, workspace, T, &w);
+  hybrid_index_kernel<<<(T + 255) / 256, 256, 0, st>>>(n_decode, ch, kv->ctx_len, w.pos, w.req);
+  LS_CHECK_LAUNCH();
+  // without prompt chunks this is a decode step (no chunk table: every row goes to the decode kernel)
+  return serve_forward(s, X, T, B, kv, max_ctx, Y, w, n_prefill > 0 ? ch.start : nullptr, n_decode, st);
 }
 
 ls_status stage_train_fwd(ls_stage* s, const void* X, int B, int L, void* Y, void* saved, void* workspace,
@@ -492,7 +549,7 @@ ls_status stage_train_fwd(ls_stage* s, const void* X, int B, int L, void* Y, voi
     float* y = l + 1 < c.n_layers ? sv[l + 1].x_in : w.xa;
     FwdBufs f{sv[l].x_in, sv[l].x1, y, sv[l].mean1, sv[l].rstd1, sv[l].mean2, sv[l].rstd2, sv[l].lse,
               sv[l].h1, sv[l].qkv, sv[l].o, sv[l].h2, sv[l].up, sv[l].act, w.scratch};
-    LS_TRY(block_forward(s, l, T, f, w.pos, nullptr, B, L, nullptr, 0, nullptr, st));
+    LS_TRY(block_forward(s, l, T, f, w.pos, nullptr, B, L, nullptr, 0, nullptr, 0, st));
   }
   return lsk_convert(w.xa, LS_F32, Y, c.io_dtype, (size_t)T * c.d_model, st);
 }
