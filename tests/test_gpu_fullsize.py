@@ -244,3 +244,66 @@ def test_cfg5_llama13b_block_forward_1x4096_sampled_rows():
 
 def test_cfg5_lognormal_decode_128_requests_full_width():
     check_decode_against_oracle(S.scaled(LLAMA13B, n_layers=1), S.WORKLOADS["cfg5"]["serve"], "cfg5 (1 block)")
+
+
+# ------------------------------------------------------------- rows beyond the step (full sizes)
+def test_cfg4_hybrid_batch_64_decode_rows_plus_a_512_token_chunk_full_width():
+    """The launch configuration bench.py times for the hybrid mini-batch (two blocks keep the float64
+    oracle to seconds).  Rows of different requests never mix, so the oracle's batched decode step
+    gives the decode rows and its prefill of the one chunk request gives sampled chunk rows."""
+    cfg = S.scaled(LLAMA7B, n_layers=2)
+    st, pd = stage_with_device_params(cfg)
+    d = cfg["d_model"]
+    serve = S.WORKLOADS["cfg4"]["serve"]
+    ctx = S.context_lengths(serve)
+    Bq, C = len(ctx), serve["prefill_chunks"][0]
+    ctx_h = np.concatenate([ctx, np.zeros(1, ctx.dtype)])
+    new_h = np.concatenate([np.ones_like(ctx), np.array([C], ctx.dtype)])
+    kv, table, cache = filled_kv(st, cfg, ctx_h, new_h, seed=5)
+    Xd = S.normal_torch(0, "Xhyb", (Bq + C, d), 1.0, "cuda", torch.bfloat16).float()
+    Y = torch.empty_like(Xd)
+    st.stage_step(Xd, Bq, [C], kv, Y, st.new_workspace(Bq + C))
+    torch.cuda.synchronize()
+    say("cfg4 hybrid: GPU done, running the oracle")
+    flat = host(pd)
+    dec_cache = [layer[:Bq] for layer in cache]
+    Yr_dec = O.stage_decode(cfg, flat, host(Xd[:Bq]), dec_cache)
+    assert_close(host(Y[:Bq]), Yr_dec, TOL["bf16"], "hybrid decode rows")
+    chunk_cache = [[layer[Bq]] for layer in cache]
+    Yr_chunk = O.stage_prefill(cfg, flat, [host(Xd[Bq:])], chunk_cache)[0]
+    e = assert_close(host(Y[Bq:]), Yr_chunk, TOL["bf16"], "hybrid chunk rows")
+    say(f"cfg4 hybrid: chunk error {e:.2e}")
+    st.close()
+
+
+def test_cfg3_model_update_of_the_full_stage_on_sampled_elements():
+    """AdamW over the 1.6 G parameters of the bench stage; 40 k sampled elements (plus the first and
+    last element of every tensor) against the oracle, decay on weight matrices only."""
+    cfg = LLAMA7B
+    st, pd = stage_with_device_params(cfg)
+    n = st.ls_param_count()
+    flat0 = pd.clone()
+    g = S.normal_torch(9, "grad", (n,), 1e-3, "cuda", torch.float32)
+    master = pd.float()
+    m = S.normal_torch(9, "m", (n,), 1e-3, "cuda", torch.float32)
+    v = S.normal_torch(9, "v", (n,), 1e-3, "cuda", torch.float32).abs_()
+    layout = S.param_layout(cfg)
+    idx = [S.uniform_ints(9, "idx", 40000, 0, n - 1)]
+    for _, off, shape, _ in layout:
+        idx.append(np.array([off, off + int(np.prod(shape)) - 1]))
+    idx = np.unique(np.concatenate(idx))
+    ti = torch.as_tensor(idx, device="cuda")
+    w0, g0, m0, v0 = (host(t[ti]) for t in (master, g, m, v))
+    hyper = dict(lr=1e-3, beta1=0.9, beta2=0.98, eps=1e-7, weight_decay=0.05, grad_scale=0.25)
+    st.stage_optimizer_step(pd, master, m, v, g, kind=Bd.LS_OPT_ADAMW, step=3, **hyper)
+    torch.cuda.synchronize()
+    starts = np.array([off for _, off, _, _ in layout])
+    is_w = np.array([init == "normal" for _, _, _, init in layout])
+    decay = is_w[np.searchsorted(starts, idx, side="right") - 1].astype(np.float64)
+    wr, mr, vr = O.optimizer_step("adamw", w0, g0, m0, v0, 3, decay=decay, **hyper)
+    assert_close(host(master[ti]), wr, 1e-5, "master weights (sampled)")
+    assert_close(host(m[ti]), mr, 1e-5, "first moment (sampled)")
+    assert_close(host(v[ti]), vr, 1e-5, "second moment (sampled)")
+    assert torch.equal(pd, master.to(torch.bfloat16))
+    assert not torch.equal(pd, flat0)
+    st.close()
