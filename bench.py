@@ -273,6 +273,20 @@ def main():
                  "decode_tok_s_alone": Bq / ms[0] * 1e3, "decode_tok_s_together": Bq / ms[2] * 1e3,
                  "train_tok_s_alone": Bt * Lt / ms[1] * 1e3, "train_tok_s_together": Bt * Lt / ms[3] * 1e3}
 
+    # ---- KV offload / reload of the longest request (PCIe-bound; reported, not part of the step) ------
+    b_long = int(np.argmax(ctx))
+    n_long = int(ctx[b_long])
+    off_bytes = Bd.lsk_kv_packed_bytes(st, n_long)
+    staging = torch.empty(off_bytes, dtype=torch.uint8, device=dev)
+    hbuf = torch.empty(off_bytes, dtype=torch.uint8, pin_memory=True)
+    ms_off = time_events(torch, lambda: Bd.lsk_kv_offload(st, kv, b_long, n_long, staging, hbuf), 3)
+    ms_rel = time_events(torch, lambda: Bd.lsk_kv_reload(st, kv, b_long, n_long, hbuf, staging), 3)
+    kv_move = {"request_tokens": n_long, "bytes": off_bytes, "offload_ms": ms_off, "reload_ms": ms_rel,
+               "offload_gbs": off_bytes / (ms_off * 1e-3) / 1e9, "reload_gbs": off_bytes / (ms_rel * 1e-3) / 1e9,
+               "note": "gather / scatter kernel plus one PCIe copy to / from pinned host memory"}
+    log(f"KV offload of a {n_long}-token request ({off_bytes / 1e6:.0f} MB): {ms_off:.2f} ms out, {ms_rel:.2f} ms back")
+    del staging, hbuf
+
     # ---- model update (a row beyond the step: AdamW over the stage's parameters, last because it
     #      rewrites the weights) -------------------------------------------------------------------
     roofline_update = None
@@ -316,7 +330,7 @@ def main():
                       "train_frac_of_mfma_peak": (3.0 * T * nL * (8.0 * d * d + 6.0 * d * F)
                                                   + 3.0 * 2.0 * L * L * d * B * nL) / (ms_train * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS},
         "roofline": roofline, "roofline_decode": roofline_decode, "roofline_update": roofline_update,
-        "probe": probe,
+        "probe": probe, "kv_offload": kv_move,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, S)

@@ -130,6 +130,34 @@ ls_status lsk_attn_bwd_rope(int impl, const void* qkv, const void* o, const void
                             const float* table, void* stream);
 
 /*
+ * Offload and reload of one request's paged K/V (Algorithm 2, memory-aware
+ * execution: after waiting T_max a task's KV cache is moved to host memory and
+ * the task resumes from that copy).  The packed form holds whole pages,
+ * ceil(n_tokens / page_size) of them, for all layers:
+ *   packed[layer][0 = K, 1 = V][j][head][slot][head_dim]
+ *       = pool[layer][block_table[request][j]][head][slot][:]
+ * lsk_kv_packed_bytes gives its size.  lsk_kv_offload enqueues a gather into
+ * `staging` (device, that many bytes) and one copy to `host`; lsk_kv_reload
+ * enqueues the copy back and a scatter into the pages that kv->block_table
+ * assigns to the request at that time (they may differ from the pages it was
+ * offloaded from).  `host` should be pinned memory for the copy to be
+ * asynchronous; both buffers are the caller's and must stay untouched until
+ * the stream has passed the call.  Bit-exact.  cfg is the stage's
+ * configuration (layout of the pool).  LS_EINVAL when the request needs more
+ * pages than a block-table row holds.
+ * lsk_memory_available: used + need_bytes <= threshold_bytes, with used =
+ * total - free device memory as the driver reports it (Algorithm 2's
+ * MemoryAvailable test against M_threshold); *used_bytes (nullable) gets used.
+ */
+size_t lsk_kv_packed_bytes(const ls_config* cfg, int n_tokens);
+ls_status lsk_kv_offload(const ls_config* cfg, const ls_kv* kv, int request, int n_tokens,
+                         void* staging, void* host, void* stream);
+ls_status lsk_kv_reload(const ls_config* cfg, const ls_kv* kv, int request, int n_tokens,
+                        const void* host, void* staging, void* stream);
+ls_status lsk_memory_available(size_t need_bytes, size_t threshold_bytes, int* available,
+                               size_t* used_bytes);
+
+/*
  * The update of one parameter tensor of n elements (see stage_optimizer_step
  * for the rules): kind 0 = SGD with momentum, 1 = AdamW; step >= 1.  grad, m,
  * v (AdamW only), master are fp32 device vectors; params is the tensor in its

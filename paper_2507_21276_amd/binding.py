@@ -79,6 +79,10 @@ SIGNATURES = {
     "ls_last_error": (C.c_char_p, []),
     "lsk_gemm": (_I, [_I, _I, _I, _I, _VP, _L, _I, _VP, _L, _I, _VP, _L, _I, _VP, _I, _VP, _L, _I, _VP]),
     "lsk_gemm_ws": (_I, [_I, _I, _I, _I, _VP, _L, _VP, _L, _VP, _L, _I, _VP, _I, _VP, _L, _VP, _SZ, _VP]),
+    "lsk_kv_packed_bytes": (_SZ, [C.POINTER(ls_config), _I]),
+    "lsk_kv_offload": (_I, [C.POINTER(ls_config), C.POINTER(ls_kv), _I, _I, _VP, _VP, _VP]),
+    "lsk_kv_reload": (_I, [C.POINTER(ls_config), C.POINTER(ls_kv), _I, _I, _VP, _VP, _VP]),
+    "lsk_memory_available": (_I, [_SZ, _SZ, C.POINTER(C.c_int), C.POINTER(_SZ)]),
     "lsk_optimizer": (_I, [_I, _F, _F, _F, _F, _F, _F, _F, _I, _SZ, _VP, _VP, _VP, _VP, _VP, _I, _VP, _I, _VP]),
     "lsk_convert": (_I, [_VP, _I, _VP, _I, _SZ, _VP]),
     "lsk_grad_scale": (_I, [_VP, _I, _SZ, _VP, _VP]),
@@ -352,6 +356,28 @@ def lsk_attn_bwd(impl, qkv, o, dO, lse, B, L, n_heads, head_dim, dqkv, stream=No
     dvec = torch.empty(lib().lsk_attn_bwd_scratch_floats(B, L, n_heads), dtype=torch.float32, device=qkv.device)
     _check(lib().lsk_attn_bwd(impl, _p(qkv), _p(o), _p(dO), _p(lse), CODE_OF_TORCH[qkv.dtype], B, L,
                               n_heads, head_dim, _p(dqkv), _p(dvec), _stream(stream)))
+
+
+def lsk_kv_packed_bytes(stage, n_tokens):
+    return lib().lsk_kv_packed_bytes(C.byref(stage.c), n_tokens)
+
+
+def lsk_kv_offload(stage, kv, request, n_tokens, staging, host_buf, stream=None):
+    d = kv.desc(True)
+    _check(lib().lsk_kv_offload(C.byref(stage.c), C.byref(d), request, n_tokens, _p(staging), host_buf.data_ptr(),
+                                _stream(stream)))
+
+
+def lsk_kv_reload(stage, kv, request, n_tokens, host_buf, staging, stream=None):
+    d = kv.desc(True)
+    _check(lib().lsk_kv_reload(C.byref(stage.c), C.byref(d), request, n_tokens, host_buf.data_ptr(), _p(staging),
+                               _stream(stream)))
+
+
+def lsk_memory_available(need_bytes, threshold_bytes):
+    ok, used = C.c_int(0), C.c_size_t(0)
+    _check(lib().lsk_memory_available(need_bytes, threshold_bytes, C.byref(ok), C.byref(used)))
+    return bool(ok.value), used.value
 
 
 def lsk_optimizer(kind, grad, m, v, master, params, params_op, *, lr, step, beta1=0.9, beta2=0.999, eps=1e-8,
