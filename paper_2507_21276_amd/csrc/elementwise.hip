@@ -118,6 +118,168 @@ template <> struct Ld8<float> {
   }
 };
 
+// eight consecutive values of a parameter vector whose type is known only at run time
+__device__ __forceinline__ void load8_param(const void* p, int c, int dt, float (&v)[8]) {
+  if (dt == LS_F32) Ld8<float>::load((const float*)p + c, v);
+  else if (dt == LS_BF16) Ld8<bf16_t>::load((const bf16_t*)p + c, v);
+  else Ld8<f16_t>::load((const f16_t*)p + c, v);
+}
+
+// eight values kept in the form they were loaded in (four registers for a 16-bit type)
+template <class TD> struct Raw8 {
+  typename vec8<TD>::type t;
+  __device__ __forceinline__ void load(const TD* p) { t = *(const typename vec8<TD>::type*)p; }
+  __device__ __forceinline__ float get(int i) const { return to_f(t[i]); }
+};
+template <> struct Raw8<float> {
+  f32x4 a, b;
+  __device__ __forceinline__ void load(const float* p) { a = *(const f32x4*)p; b = *(const f32x4*)(p + 4); }
+  __device__ __forceinline__ float get(int i) const { return i < 4 ? a[i] : b[i - 4]; }
+};
+
+// Forward, one wavefront per row (four rows per workgroup): a lane owns eight
+// consecutive columns out of every 512, the row stays in registers between the
+// statistics and the output, and no LDS or barrier is involved.  Needs
+// d % 8 == 0, d <= 512 * NIT and 16-byte aligned rows and parameters.
+template <class TH, int NIT>
+__global__ __launch_bounds__(256) void norm_fwd_rows_kernel(int kind, const float* x, int T, int d,
+                                                            const void* gamma, const void* beta, int pdt,
+                                                            float eps, TH* h, float* mean, float* rstd) {
+  const int row = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (row >= T) return;
+  const size_t off = (size_t)row * d;
+  float v[NIT][8];
+  float s = 0.f;
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int c = lane * 8 + it * 512;
+    if (c < d) Ld8<float>::load(x + off + c, v[it]);
+    else
+#pragma unroll
+      for (int i = 0; i < 8; ++i) v[it][i] = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) s += v[it][i];
+  }
+  const float mu = kind == 0 ? wave_sum(s) / d : 0.f;
+  float q = 0.f;
+#pragma unroll
+  for (int it = 0; it < NIT; ++it)
+    if (lane * 8 + it * 512 < d)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        const float t = v[it][i] - mu;
+        q += t * t;
+      }
+  const float r = 1.0f / sqrtf(wave_sum(q) / d + eps);
+#pragma unroll
+  for (int it = 0; it < NIT; ++it) {
+    const int c = lane * 8 + it * 512;
+    if (c < d) {
+      float gam[8], o[8];
+      load8_param(gamma, c, pdt, gam);
+#pragma unroll
+      for (int i = 0; i < 8; ++i) o[i] = (v[it][i] - mu) * r * gam[i];
+      if (kind == 0 && beta) {
+        load8_param(beta, c, pdt, gam);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) o[i] += gam[i];
+      }
+      Ld8<TH>::store(h + off + c, o);
+    }
+  }
+  if (lane == 0) {
+    if (mean && kind == 0) mean[row] = mu;
+    if (rstd) rstd[row] = r;
+  }
+}
+
+// Backward in one pass over the data, one wavefront per row and NB_ROWS rows per
+// 512-thread workgroup: the row's dh and xhat stay in registers between the two
+// row means and dx, each wave keeps its dgamma / dbeta column sums in registers
+// and the eight waves' sums are combined in a fixed order through LDS into
+// partial[workgroup][2][d] (RMSNorm leaves the dbeta half unwritten).  Needs d % 8 == 0, d <= 512 * NIT, 16-byte alignment.
+template <class TD, int KIND, int NIT>
+__global__ __launch_bounds__(512) void norm_bwd_rows_kernel(const TD* dh, const float* x, const float* mean,
+                                                            const float* rstd, const void* gamma, int pdt,
+                                                            int T, int d, const float* dres, float* dx,
+                                                            TD* dx16, float* partial) {
+  extern __shared__ float sred[];  // [8][d]
+  const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int r0 = blockIdx.x * NB_ROWS, r1 = min(T, r0 + NB_ROWS);
+  constexpr int NB = KIND == 0 ? NIT : 1;
+  float dg[NIT][8], db[NB][8];
+#pragma unroll
+  for (int it = 0; it < NIT; ++it)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) dg[it][i] = 0.f;
+#pragma unroll
+  for (int it = 0; it < NB; ++it)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) db[it][i] = 0.f;
+  for (int row = r0 + w; row < r1; row += 8) {
+    const size_t off = (size_t)row * d;
+    const float mu = KIND == 0 ? mean[row] : 0.f, r = rstd[row];
+    Raw8<TD> g[NIT];
+    float xh[NIT][8];
+    float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int c = lane * 8 + it * 512;
+      if (c < d) {
+        float gam[8];
+        g[it].load(dh + off + c);
+        Ld8<float>::load(x + off + c, xh[it]);
+        load8_param(gamma, c, pdt, gam);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float dxh = g[it].get(i) * gam[i];
+          xh[it][i] = (xh[it][i] - mu) * r;
+          s1 += dxh;
+          s2 += dxh * xh[it][i];
+        }
+      }
+    }
+    const float m1 = KIND == 0 ? wave_sum(s1) / d : 0.f;
+    const float m2 = wave_sum(s2) / d;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int c = lane * 8 + it * 512;
+      if (c < d) {
+        float gam[8], o[8];
+        load8_param(gamma, c, pdt, gam);
+        if (dres) Ld8<float>::load(dres + off + c, o);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float gi = g[it].get(i);
+          const float val = r * (gi * gam[i] - m1 - xh[it][i] * m2);
+          o[i] = dres ? o[i] + val : val;
+          dg[it][i] += gi * xh[it][i];
+          if (KIND == 0) db[it][i] += gi;
+        }
+        Ld8<float>::store(dx + off + c, o);
+        if (dx16) Ld8<TD>::store(dx16 + off + c, o);
+      }
+    }
+  }
+  float* p = partial + (size_t)blockIdx.x * 2 * d;
+#pragma unroll
+  for (int pass = 0; pass < (KIND == 0 ? 2 : 1); ++pass) {
+    if (pass) __syncthreads();
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int c = lane * 8 + it * 512;
+      if (c < d) Ld8<float>::store(sred + (size_t)w * d + c, pass == 0 ? dg[it] : db[KIND == 0 ? it : 0]);
+    }
+    __syncthreads();
+    for (int c = threadIdx.x * 4; c < d; c += 2048) {
+      f32x4 a = *(const f32x4*)(sred + c);
+#pragma unroll
+      for (int k = 1; k < 8; ++k) a += *(const f32x4*)(sred + (size_t)k * d + c);
+      *(f32x4*)(p + pass * d + c) = a;
+    }
+  }
+}
+
 template <class TD>
 __global__ __launch_bounds__(256) void norm_bwd_stats_kernel(int kind, const TD* dh, const float* x,
                                                              const float* mean, const float* rstd,
@@ -186,39 +348,87 @@ __global__ __launch_bounds__(256) void norm_bwd_apply_kernel(int kind, const TD*
   Ld8<float>::store(p + d, db);
 }
 
-// 64 columns x 4 row groups per workgroup; the four partial sums of a column are combined in
-// a fixed order through LDS
+// 32 columns (eight float4 lanes) x 32 row groups per workgroup; the 32 partial sums of a
+// column are combined in a fixed order through LDS.  d % 4 == 0.
 __global__ __launch_bounds__(256) void norm_bwd_finish_kernel(const float* partial, int nwg, int d, float* dgamma,
                                                               float* dbeta, int accumulate, const float* alpha) {
-  __shared__ float sg[4][64], sb[4][64];
-  const int cl = threadIdx.x & 63, rg = threadIdx.x >> 6;
-  const int i = blockIdx.x * 64 + cl;
-  float g = 0.f, b = 0.f;
+  __shared__ float sg[32][32], sb[32][32];
+  const int cg = threadIdx.x & 7, rg = threadIdx.x >> 3;
+  const int i = blockIdx.x * 32 + cg * 4;
+  f32x4 g = {0.f, 0.f, 0.f, 0.f}, b = {0.f, 0.f, 0.f, 0.f};
   if (i < d)
-    for (int w = rg; w < nwg; w += 4) {
-      g += partial[(size_t)w * 2 * d + i];
-      b += partial[(size_t)w * 2 * d + d + i];
+    for (int w = rg; w < nwg; w += 32) {
+      g += *(const f32x4*)(partial + (size_t)w * 2 * d + i);
+      if (dbeta) b += *(const f32x4*)(partial + (size_t)w * 2 * d + d + i);
     }
-  sg[rg][cl] = g;
-  sb[rg][cl] = b;
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    sg[rg][cg * 4 + k] = g[k];
+    sb[rg][cg * 4 + k] = b[k];
+  }
   __syncthreads();
-  if (rg != 0 || i >= d) return;
-  g = (sg[0][cl] + sg[1][cl]) + (sg[2][cl] + sg[3][cl]);
-  b = (sb[0][cl] + sb[1][cl]) + (sb[2][cl] + sb[3][cl]);
-  if (alpha) { g *= *alpha; b *= *alpha; }
-  if (dgamma) dgamma[i] = accumulate ? dgamma[i] + g : g;
-  if (dbeta) dbeta[i] = accumulate ? dbeta[i] + b : b;
+  const int col = blockIdx.x * 32 + threadIdx.x;
+  if (threadIdx.x >= 32 || col >= d) return;
+  float tg = 0.f, tb = 0.f;
+#pragma unroll
+  for (int k = 0; k < 32; ++k) {
+    tg += sg[k][threadIdx.x];
+    tb += sb[k][threadIdx.x];
+  }
+  if (alpha) { tg *= *alpha; tb *= *alpha; }
+  if (dgamma) dgamma[col] = accumulate ? dgamma[col] + tg : tg;
+  if (dbeta) dbeta[col] = accumulate ? dbeta[col] + tb : tb;
+}
+
+inline bool aligned16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+template <class TD, int KIND, int NIT>
+ls_status launch_norm_bwd_rows(const void* dh, const float* x, const float* mean, const float* rstd,
+                               const void* gamma, int pdt, int T, int d, const float* dres, float* dx,
+                               void* dx16, float* partial, hipStream_t st) {
+  static bool attr_set = false;
+  const size_t lds = (size_t)8 * d * sizeof(float);
+  auto* kern = norm_bwd_rows_kernel<TD, KIND, NIT>;
+  if (!attr_set) {
+    LS_CHECK_HIP(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, 8 * 512 * NIT * 4));
+    attr_set = true;
+  }
+  kern<<<(T + NB_ROWS - 1) / NB_ROWS, 512, lds, st>>>((const TD*)dh, x, mean, rstd, gamma, pdt, T, d, dres, dx,
+                                                      (TD*)dx16, partial);
+  return LS_OK;
 }
 
 template <class TD>
-void launch_norm_bwd(int kind, const void* dh, const float* x, const float* mean, const float* rstd,
-                     const void* gamma, int pdt, int T, int d, const float* dres, float* dx, void* dx16,
-                     float* partial, hipStream_t st) {
+ls_status launch_norm_bwd(int kind, const void* dh, const float* x, const float* mean, const float* rstd,
+                          const void* gamma, int pdt, int T, int d, const float* dres, float* dx, void* dx16,
+                          float* partial, hipStream_t st) {
+  // LayerNorm's second set of column sums does not fit the register file beyond 2048 columns
+  const bool rows_ok = d <= (kind == 0 ? 2048 : 4096) && aligned16(dh) && aligned16(x) && aligned16(gamma) && aligned16(dx) &&
+                       aligned16(partial) && (!dres || aligned16(dres)) && (!dx16 || aligned16(dx16));
+  if (rows_ok) {
+#define LS_NB(K, N) launch_norm_bwd_rows<TD, K, N>(dh, x, mean, rstd, gamma, pdt, T, d, dres, dx, dx16, partial, st)
+    if (kind == 0) return LS_NB(0, 4);
+    return d <= 2048 ? LS_NB(1, 4) : LS_NB(1, 8);
+#undef LS_NB
+  }
   const int nchunk = (T + NB_ROWS - 1) / NB_ROWS;
   float* stats = partial + (size_t)nchunk * 2 * d;
   norm_bwd_stats_kernel<TD><<<(T + 3) / 4, 256, 0, st>>>(kind, (const TD*)dh, x, mean, rstd, gamma, pdt, T, d, stats);
   norm_bwd_apply_kernel<TD><<<dim3((d + 2047) / 2048, nchunk), 256, 0, st>>>(
       kind, (const TD*)dh, x, mean, rstd, gamma, pdt, T, d, stats, dres, dx, (TD*)dx16, partial);
+  return LS_OK;
+}
+
+template <class TH>
+void launch_norm_fwd_rows(int kind, const float* x, int T, int d, const void* gamma, const void* beta, int pdt,
+                          float eps, void* h, float* mean, float* rstd, hipStream_t st) {
+  const int grid = (T + 3) / 4;
+  if (d <= 2048)
+    norm_fwd_rows_kernel<TH, 4><<<grid, 256, 0, st>>>(kind, x, T, d, gamma, beta, pdt, eps, (TH*)h, mean, rstd);
+  else if (d <= 4096)
+    norm_fwd_rows_kernel<TH, 8><<<grid, 256, 0, st>>>(kind, x, T, d, gamma, beta, pdt, eps, (TH*)h, mean, rstd);
+  else
+    norm_fwd_rows_kernel<TH, 16><<<grid, 256, 0, st>>>(kind, x, T, d, gamma, beta, pdt, eps, (TH*)h, mean, rstd);
 }
 
 // -------------------------------------------------------------------- rope
@@ -362,7 +572,14 @@ ls_status lsk_norm_fwd(int kind, const float* x, int T, int d, const void* gamma
   LS_REQUIRE(x && gamma && h && T > 0 && d > 0, "norm_fwd: bad argument");
   LS_REQUIRE(kind == 0 || kind == 1, "norm_fwd: kind must be 0 (LayerNorm) or 1 (RMSNorm)");
   LS_REQUIRE(d <= 256 * NF_MAXCOL, "norm_fwd: d_model %d exceeds %d", d, 256 * NF_MAXCOL);
-  norm_fwd_kernel<<<T, 256, 0, (hipStream_t)stream>>>(kind, x, d, gamma, beta, pdt, eps, h, hdt, mean, rstd);
+  hipStream_t st = (hipStream_t)stream;
+  if (d % 8 == 0 && aligned16(x) && aligned16(h) && aligned16(gamma) && (!beta || aligned16(beta))) {
+    if (hdt == LS_F32) launch_norm_fwd_rows<float>(kind, x, T, d, gamma, beta, pdt, eps, h, mean, rstd, st);
+    else if (hdt == LS_BF16) launch_norm_fwd_rows<bf16_t>(kind, x, T, d, gamma, beta, pdt, eps, h, mean, rstd, st);
+    else launch_norm_fwd_rows<f16_t>(kind, x, T, d, gamma, beta, pdt, eps, h, mean, rstd, st);
+  } else {
+    norm_fwd_kernel<<<T, 256, 0, st>>>(kind, x, d, gamma, beta, pdt, eps, h, hdt, mean, rstd);
+  }
   LS_CHECK_LAUNCH();
   return LS_OK;
 }
@@ -381,13 +598,13 @@ ls_status lsk_norm_bwd_scaled(int kind, const void* dh, int dhdt, const float* x
   LS_REQUIRE(d % 8 == 0, "norm_bwd: d_model must be a multiple of 8");
   LS_REQUIRE(!dx16 || dx16dt == dhdt, "norm_bwd: the 16-bit copy of dx must have the type of dh");
   hipStream_t st = (hipStream_t)stream;
-  if (dhdt == LS_F32) launch_norm_bwd<float>(kind, dh, x, mean, rstd, gamma, pdt, T, d, dres, dx, dx16, partial, st);
-  else if (dhdt == LS_BF16) launch_norm_bwd<bf16_t>(kind, dh, x, mean, rstd, gamma, pdt, T, d, dres, dx, dx16, partial, st);
-  else launch_norm_bwd<f16_t>(kind, dh, x, mean, rstd, gamma, pdt, T, d, dres, dx, dx16, partial, st);
+  if (dhdt == LS_F32) LS_TRY(launch_norm_bwd<float>(kind, dh, x, mean, rstd, gamma, pdt, T, d, dres, dx, dx16, partial, st));
+  else if (dhdt == LS_BF16) LS_TRY(launch_norm_bwd<bf16_t>(kind, dh, x, mean, rstd, gamma, pdt, T, d, dres, dx, dx16, partial, st));
+  else LS_TRY(launch_norm_bwd<f16_t>(kind, dh, x, mean, rstd, gamma, pdt, T, d, dres, dx, dx16, partial, st));
   LS_CHECK_LAUNCH();
   if (dgamma || dbeta) {
     const int nchunk = (T + NB_ROWS - 1) / NB_ROWS;
-    norm_bwd_finish_kernel<<<(d + 63) / 64, 256, 0, st>>>(partial, nchunk, d, dgamma,
+    norm_bwd_finish_kernel<<<(d + 31) / 32, 256, 0, st>>>(partial, nchunk, d, dgamma,
                                                             kind == 0 ? dbeta : nullptr, accumulate, alpha_dev);
     LS_CHECK_LAUNCH();
   }

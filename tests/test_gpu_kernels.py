@@ -165,7 +165,7 @@ def test_gemm_rejects_unaligned_operands():
 
 @pytest.mark.parametrize("kind", [0, 1])
 @pytest.mark.parametrize("hname", ["f32", "f16", "bf16"])
-@pytest.mark.parametrize("T,d", [(37, 128), (70, 768), (33, 4096)])
+@pytest.mark.parametrize("T,d", [(37, 128), (70, 768), (33, 4096), (70, 1600), (19, 2560), (9, 8192), (600, 1024)])
 def test_norm_forward_and_backward(kind, hname, T, d):
     x = S.normal(3, "x", (T, d)) * 1.7 + 0.3
     pn = "f32" if hname == "f32" else "bf16"
