@@ -61,6 +61,7 @@ _lib: Optional[C.CDLL] = None
 
 # name -> (restype, argtypes); every symbol the two headers declare
 _VP, _I, _L, _SZ, _F = C.c_void_p, C.c_int, C.c_long, C.c_size_t, C.c_float
+_D, _DP = C.c_double, C.POINTER(C.c_double)
 SIGNATURES = {
     "ls_create": (_I, [C.POINTER(ls_config), C.POINTER(_VP)]),
     "ls_destroy": (None, [_VP]),
@@ -112,6 +113,26 @@ SIGNATURES = {
     "lsk_attn_paged_scratch_floats": (_SZ, [_I, _I, _I, _I, _I]),
     "lsk_gemm_skinny_scratch_floats": (_SZ, [_I, _I, _I]),
     "lsk_gemm_skinny": (_I, [_I, _I, _I, _I, _VP, _L, _VP, _L, _VP, _L, _I, _VP, _I, _VP, _L, _VP, _VP]),
+    # lemix_sched.h (host bookkeeping; wrappers in sched.py)
+    "ls_node_create": (_I, [_I, _D, _D, C.POINTER(_VP)]),
+    "ls_node_destroy": (None, [_VP]),
+    "ls_node_plan": (_I, [_VP, _VP, _I, _DP, _DP, _DP, C.POINTER(C.c_int64)]),
+    "ls_node_queue_len": (_I, [_VP, _I]),
+    "ls_node_prune": (_I, [_VP]),
+    "ls_node_task_path": (_I, [_VP, C.c_int64, _DP]),
+    "ls_node_calibrate": (_I, [_VP, C.c_int64, _I, _I, _D, _D]),
+    "ls_node_score": (_I, [_VP, _VP, _D, _VP, _DP, _DP, _DP, _DP, _DP]),
+    "ls_select_node": (_I, [C.POINTER(_VP), _I, _VP, _D, _VP, C.POINTER(_I), _DP]),
+    "ls_deprioritize": (_I, [C.POINTER(_VP), _I, _VP, _D, C.POINTER(_I), _DP]),
+    "ls_node_execute": (_I, [_VP, _D, _D, _VP, _VP]),
+    "ls_batcher_create": (_I, [_I, _D, C.POINTER(_VP)]),
+    "ls_batcher_destroy": (None, [_VP]),
+    "ls_batcher_push": (_I, [_VP, C.c_int64, _I]),
+    "ls_batcher_form": (_I, [_VP, _D, C.POINTER(C.c_int64), C.POINTER(_I), C.POINTER(_I), C.POINTER(_I)]),
+    "ls_batcher_take_training": (_I, [_VP, C.POINTER(C.c_int64)]),
+    "ls_batcher_finish": (_I, [_VP, C.POINTER(C.c_int64), _I]),
+    "ls_batcher_queued": (_I, [_VP]),
+    "ls_batcher_batch_size": (_I, [_VP]),
 }
 
 
