@@ -104,6 +104,9 @@ typedef struct {
 ls_status ls_create(const ls_config* cfg, ls_stage** out);
 void ls_destroy(ls_stage* s);
 
+/* Copies the configuration the stage was created with. */
+ls_status ls_get_config(const ls_stage* s, ls_config* out);
+
 /* Number of parameter elements of the whole stage. */
 size_t ls_param_count(const ls_stage* s);
 

@@ -66,6 +66,7 @@ SIGNATURES = {
     "ls_create": (_I, [C.POINTER(ls_config), C.POINTER(_VP)]),
     "ls_destroy": (None, [_VP]),
     "ls_param_count": (_SZ, [_VP]),
+    "ls_get_config": (_I, [_VP, C.POINTER(ls_config)]),
     "ls_bind_params": (_I, [_VP, _VP, _VP]),
     "ls_workspace_bytes": (_SZ, [_VP, _I]),
     "ls_saved_bytes": (_SZ, [_VP, _I, _I]),
@@ -133,6 +134,12 @@ SIGNATURES = {
     "ls_batcher_finish": (_I, [_VP, C.POINTER(C.c_int64), _I]),
     "ls_batcher_queued": (_I, [_VP]),
     "ls_batcher_batch_size": (_I, [_VP]),
+    # lemix_serve.h (wrappers in sched.py)
+    "ls_server_create": (_I, [_VP, _VP, _VP, _VP, C.POINTER(_VP)]),
+    "ls_server_destroy": (None, [_VP]),
+    "ls_server_submit": (_I, [_VP, C.c_int64, _VP, _VP, _I, _I]),
+    "ls_server_pass": (_I, [_VP, _D, _VP, _VP, _VP, C.POINTER(C.c_int64), C.POINTER(C.c_int64)]),
+    "ls_server_in_flight": (_I, [_VP]),
 }
 
 

@@ -442,6 +442,12 @@ void ls_destroy(ls_stage* s) {
 
 size_t ls_param_count(const ls_stage* s) { return s ? s->n_params : 0; }
 
+ls_status ls_get_config(const ls_stage* s, ls_config* out) {
+  LS_REQUIRE(s && out, "ls_get_config: null argument");
+  *out = s->cfg;
+  return LS_OK;
+}
+
 ls_status ls_bind_params(ls_stage* s, const void* params, void* stream) {
   LS_TRY(check_stage(s, false));
   LS_REQUIRE(params != nullptr, "ls_bind_params: null parameter vector");

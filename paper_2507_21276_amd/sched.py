@@ -164,3 +164,53 @@ class Batcher:
 
     def batch_size(self):
         return Bd.lib().ls_batcher_batch_size(self.h)
+
+
+class ls_server_config(C.Structure):
+    _fields_ = [("max_batch", C.c_int32), ("max_wait", C.c_double), ("n_pages", C.c_int32),
+                ("max_pages_per_req", C.c_int32), ("max_chunk", C.c_int32), ("max_tokens", C.c_int32)]
+
+
+class ls_pass_report(C.Structure):
+    _fields_ = [(k, C.c_int32) for k in ("n_batch", "n_new", "n_decode", "n_prefill", "n_rows", "n_stalled",
+                                         "n_finished", "free_pages")]
+
+
+class Server:
+    """Continuous-batching loop of one stage (include/lemix_serve.h).  k_pool, v_pool, and every
+    request's X and Y are torch tensors the caller keeps alive."""
+
+    def __init__(self, stage, k_pool, v_pool, *, max_batch, max_wait, max_pages_per_req, max_chunk, max_tokens):
+        self.stage, self.k_pool, self.v_pool = stage, k_pool, v_pool
+        self.cfg = ls_server_config(max_batch, max_wait, k_pool.shape[1], max_pages_per_req, max_chunk,
+                                    max_tokens)
+        self.h = C.c_void_p()
+        Bd._check(Bd.lib().ls_server_create(stage.h, C.byref(self.cfg), k_pool.data_ptr(), v_pool.data_ptr(),
+                                            C.byref(self.h)))
+        self.workspace = stage.new_workspace(max_tokens)
+        self._keep = {}
+
+    def close(self):
+        if getattr(self, "h", None):
+            Bd.lib().ls_server_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+    def submit(self, rid, X, Y, prompt_len, n_decode):
+        Bd._check(Bd.lib().ls_server_submit(self.h, rid, X.data_ptr(), Y.data_ptr(), prompt_len, n_decode))
+        self._keep[rid] = (X, Y)
+
+    def run_pass(self, now, stream=None):
+        rep = ls_pass_report()
+        ran = (C.c_int64 * self.cfg.max_batch)()
+        fin = (C.c_int64 * self.cfg.max_batch)()
+        Bd._check(Bd.lib().ls_server_pass(self.h, now, Bd._p(self.workspace), Bd._stream(stream), C.byref(rep),
+                                          ran, fin))
+        out = {k: getattr(rep, k) for k, _ in ls_pass_report._fields_}
+        out["ran"] = list(ran[:rep.n_decode + rep.n_prefill])
+        out["finished"] = list(fin[:rep.n_finished])
+        return out
+
+    def in_flight(self):
+        return Bd.lib().ls_server_in_flight(self.h)
