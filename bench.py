@@ -81,6 +81,7 @@ def main():
     ap.add_argument("--mma", default="f16", choices=["f16", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
+    ap.add_argument("--no-serve-loop", action="store_true", help="skip the continuous-batching loop measurement")
     ap.add_argument("--no-update", action="store_true", help="skip the model-update measurement (3 fp32 vectors of the stage's size)")
     ap.add_argument("--legs", default="train,decode,prefill",
                     help="comma list of the legs that make up a step (profiling aid; the default is the full "
@@ -287,6 +288,43 @@ def main():
     log(f"KV offload of a {n_long}-token request ({off_bytes / 1e6:.0f} MB): {ms_off:.2f} ms out, {ms_rel:.2f} ms back")
     del staging, hbuf
 
+    # ---- continuous-batching loop (Algorithm 3) over the same stage: 96 queued requests of 512 prompt
+    #      tokens and 64 decode steps, C = 64, one hybrid mini-batch of at most 576 rows per pass ---------
+    serve_loop = None
+    if not args.no_serve_loop:
+        from paper_2507_21276_amd import sched as Sc
+        n_req, p_len, n_dec = 96, 512, 64
+        pages_per_req = -(-(p_len + n_dec) // P)
+        pool_shape = (nL, Bq * pages_per_req + 32, h, P, dh)
+        kpl = torch.zeros(pool_shape, dtype=kv.k_pool.dtype, device=dev)
+        vpl = torch.zeros_like(kpl)
+        srv = Sc.Server(st, kpl, vpl, max_batch=Bq, max_wait=1e9, max_pages_per_req=pages_per_req,
+                        max_chunk=p_len, max_tokens=Bq + p_len)
+        Xr = S.normal_torch(0, "Xserve", (p_len + n_dec, d), 1.0, dev, io)
+        Yr = [torch.empty_like(Xr) for _ in range(n_req)]
+        for r in range(n_req):
+            srv.submit(r, Xr, Yr[r], p_len, n_dec)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        passes = rows = 0
+        host_s = 0.0
+        while srv.in_flight():
+            h0 = time.perf_counter()
+            rep = srv.run_pass(time.perf_counter() - t0)
+            host_s += time.perf_counter() - h0
+            passes += 1
+            rows += rep["n_rows"]
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+        serve_loop = {"requests": n_req, "prompt_tokens": p_len, "decode_steps": n_dec, "max_batch": Bq,
+                      "passes": passes, "rows": rows, "wall_ms": wall * 1e3, "rows_per_s": rows / wall,
+                      "requests_per_s": n_req / wall, "ms_per_pass": wall * 1e3 / passes,
+                      "host_us_per_pass": host_s * 1e6 / passes}
+        log(f"serve loop: {n_req} requests ({p_len} + {n_dec} rows) in {passes} passes, {wall * 1e3:.0f} ms "
+            f"-> {rows / wall:.0f} rows/s, host {host_s * 1e6 / passes:.0f} us per pass")
+        srv.close()
+        del kpl, vpl, Yr
+
     # ---- model update (a row beyond the step: AdamW over the stage's parameters, last because it
     #      rewrites the weights) -------------------------------------------------------------------
     roofline_update = None
@@ -330,7 +368,7 @@ def main():
                       "train_frac_of_mfma_peak": (3.0 * T * nL * (8.0 * d * d + 6.0 * d * F)
                                                   + 3.0 * 2.0 * L * L * d * B * nL) / (ms_train * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS},
         "roofline": roofline, "roofline_decode": roofline_decode, "roofline_update": roofline_update,
-        "probe": probe, "kv_offload": kv_move,
+        "probe": probe, "kv_offload": kv_move, "serve_loop": serve_loop,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, S)
