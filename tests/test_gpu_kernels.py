@@ -91,10 +91,13 @@ def test_gemm_skinny_weight_streaming(name, M, N, K, split):
 @pytest.mark.parametrize("name", ["f16", "bf16"])
 @pytest.mark.parametrize("M,N,K,out,res", [(512, 4096, 4096, "f32", True), (512, 4096, 11008, "f32", True),
                                             (300, 520, 2048, "op", False), (256, 264, 4096, "op", False),
-                                            # decode batches: 64 x 128 weight-streaming tiles
+                                            # decode batches: weight-streaming kernel, 32 weight rows per workgroup
                                             (64, 4096, 4096, "f32", True), (64, 12288, 4096, "op", False),
                                             (33, 264, 1024, "op", False), (1, 128, 512, "f32", True),
-                                            (7, 1048, 11008, "op", False)])
+                                            (7, 1048, 11008, "op", False), (64, 22016, 4096, "op", False),
+                                            (64, 4096, 11008, "f32", True), (32, 72, 64, "op", False),
+                                            (17, 40, 320, "f32", False), (64, 8, 192, "op", True),
+                                            (48, 2000, 1600, "f32", True)])
 def test_gemm_split_k_through_a_workspace(name, M, N, K, out, res):
     """Few output tiles: the contraction is split over workgroups and summed in a fixed order."""
     dt = DT[name]
