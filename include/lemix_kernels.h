@@ -248,6 +248,52 @@ ls_status lsk_norm_bwd_scaled(int kind, const void* dh, int dh_dtype, const floa
 ls_status lsk_colsum_scaled(const void* x, int dtype, int T, int N, long ld, float* out,
                             int accumulate, float* partial, const float* alpha_dev, void* stream);
 
+/*
+ * Decode batches (Autoregressive Generation: decoding requests extend their
+ * prefilled context one token per iteration; at most 64 rows per call).  The
+ * projections of such a batch stream the weights once and split the
+ * contraction over workgroups; lsk_gemm_partials leaves the split results
+ *   partial[s][M][N] (device, fp32), s < *splits (host, written on return),
+ *   sum over s = X[M, K] W[N, K]^T,
+ * and each lsk_finish_* call sums them in the order s = 0, 1, .. and applies,
+ * in the same pass, the step that follows that projection in the block
+ * (Model Architecture: attention and feed-forward sub-layers with residual
+ * connections and normalisation).  16-bit operands; M <= 64, N >= 64 and a
+ * multiple of 4, K a multiple of 64, partial_floats >= M * N (more allows more
+ * splits, at most 16).  LS_EINVAL outside these limits.
+ */
+ls_status lsk_gemm_partials(int op_dtype, int M, int N, int K, const void* X, long ldx, const void* W,
+                            long ldw, float* partial, size_t partial_floats, int* splits, void* stream);
+
+/*
+ * x_out[T, d] (fp32) = sum of partials + bias + resid, then, unless kind < 0,
+ * h[T, d] (hdt) = LayerNorm (kind 0) or RMSNorm (kind 1) of x_out with gamma,
+ * beta (pdt; beta may be null), eps inside the square root.  bias (pdt) and
+ * resid (fp32) may be null; x_out may be resid.  d a multiple of 4, <= 8192.
+ */
+ls_status lsk_finish_resid_norm(const float* partial, int splits, int T, int d, const void* bias,
+                                const float* resid, float* x_out, int kind, const void* gamma,
+                                const void* beta, int pdt, float eps, void* h, int hdt, void* stream);
+
+/*
+ * FFN-up: out[T, F] (odt) = GELU(sum of partials[T, F] + bias) for act
+ * LS_ACT_GELU_*, or SiLU(gate) * up with [gate | up] = sum of partials[T, 2F]
+ * + bias for LS_ACT_SWIGLU.  bias (pdt) may be null.  F a multiple of 4.
+ */
+ls_status lsk_finish_act(const float* partial, int splits, int T, int F, int act, const void* bias, int pdt,
+                         void* out, int odt, void* stream);
+
+/*
+ * QKV: [q | k | v][T, 3 h dh] = sum of partials + bias (pdt, may be null); when
+ * table is non-null q and k are rotated by pos[t] (half-split pairs, table as
+ * in lsk_rope); q, k, v are written to qkv (dt, 16-bit) and the k and v rows
+ * into the page slot of request req[t], position pos[t], as lsk_kv_write does.
+ */
+ls_status lsk_finish_qkv(const float* partial, int splits, int T, int h, int dh, const void* bias, int pdt,
+                         const int32_t* pos, const int32_t* req, const float* table, void* qkv, int dt,
+                         void* k_pool, void* v_pool, const int32_t* block_table, int max_pages, int page,
+                         void* stream);
+
 #ifdef __cplusplus
 }
 #endif

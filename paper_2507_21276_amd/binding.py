@@ -114,6 +114,10 @@ SIGNATURES = {
     "lsk_attn_paged_scratch_floats": (_SZ, [_I, _I, _I, _I, _I]),
     "lsk_gemm_skinny_scratch_floats": (_SZ, [_I, _I, _I]),
     "lsk_gemm_skinny": (_I, [_I, _I, _I, _I, _VP, _L, _VP, _L, _VP, _L, _I, _VP, _I, _VP, _L, _VP, _VP]),
+    "lsk_gemm_partials": (_I, [_I, _I, _I, _I, _VP, _L, _VP, _L, _VP, _SZ, C.POINTER(_I), _VP]),
+    "lsk_finish_resid_norm": (_I, [_VP, _I, _I, _I, _VP, _VP, _VP, _I, _VP, _VP, _I, _F, _VP, _I, _VP]),
+    "lsk_finish_act": (_I, [_VP, _I, _I, _I, _I, _VP, _I, _VP, _I, _VP]),
+    "lsk_finish_qkv": (_I, [_VP, _I, _I, _I, _I, _VP, _I, _VP, _VP, _VP, _VP, _I, _VP, _VP, _VP, _I, _I, _VP]),
     # lemix_sched.h (host bookkeeping; wrappers in sched.py)
     "ls_node_create": (_I, [_I, _D, _D, C.POINTER(_VP)]),
     "ls_node_destroy": (None, [_VP]),
@@ -455,3 +459,39 @@ def lsk_attn_paged(impl, qkv, n_heads, head_dim, pos, req, k_pool, v_pool, block
     _check(lib().lsk_attn_paged(impl, _p(qkv), CODE_OF_TORCH[qkv.dtype], T, n_heads, head_dim, _p(pos),
                                 _p(req), _p(k_pool), _p(v_pool), _p(block_table), block_table.shape[1],
                                 page_size, max_ctx, _p(o), _p(scratch), _stream(stream)))
+
+
+def _opt(t):
+    return _p(t) if t is not None else None
+
+
+def lsk_gemm_partials(x, w, partial, stream=None):
+    """Split-K partial products of a decode batch: returns the number of splits written to partial[s][M][N]."""
+    M, K = x.shape
+    N = w.shape[0]
+    splits = C.c_int(0)
+    _check(lib().lsk_gemm_partials(CODE_OF_TORCH[x.dtype], M, N, K, _p(x), x.stride(0), _p(w), w.stride(0),
+                                   _p(partial), partial.numel(), C.byref(splits), _stream(stream)))
+    return splits.value
+
+
+def lsk_finish_resid_norm(partial, splits, T, d, x_out, *, bias=None, resid=None, kind=-1, gamma=None, beta=None,
+                          eps=1e-5, h=None, stream=None):
+    pdt = CODE_OF_TORCH[(gamma if gamma is not None else bias).dtype] if (gamma is not None or bias is not None) else 0
+    _check(lib().lsk_finish_resid_norm(_p(partial), splits, T, d, _opt(bias), _opt(resid), _p(x_out), kind,
+                                       _opt(gamma), _opt(beta), pdt, eps, _opt(h),
+                                       CODE_OF_TORCH[h.dtype] if h is not None else 0, _stream(stream)))
+
+
+def lsk_finish_act(partial, splits, T, F, act, out, bias=None, stream=None):
+    _check(lib().lsk_finish_act(_p(partial), splits, T, F, act, _opt(bias),
+                                CODE_OF_TORCH[bias.dtype] if bias is not None else 0, _p(out),
+                                CODE_OF_TORCH[out.dtype], _stream(stream)))
+
+
+def lsk_finish_qkv(partial, splits, n_heads, head_dim, pos, req, table, qkv, k_pool, v_pool, block_table, page_size,
+                   bias=None, stream=None):
+    _check(lib().lsk_finish_qkv(_p(partial), splits, qkv.shape[0], n_heads, head_dim, _opt(bias),
+                                CODE_OF_TORCH[bias.dtype] if bias is not None else 0, _p(pos), _p(req), _opt(table),
+                                _p(qkv), CODE_OF_TORCH[qkv.dtype], _p(k_pool), _p(v_pool), _p(block_table),
+                                block_table.shape[1], page_size, _stream(stream)))

@@ -62,6 +62,12 @@ __device__ __forceinline__ float block_sum(float v, float* red) {
   return t;
 }
 
+constexpr float kGeluC = 0.7978845608028654f;  // sqrt(2/pi)
+__device__ __forceinline__ float gelu_f(float u, int kind) {
+  if (kind == LS_ACT_GELU_TANH) return 0.5f * u * (1.f + tanhf(kGeluC * (u + 0.044715f * u * u * u)));
+  return 0.5f * u * (1.f + erff(u * 0.70710678118654752f));
+}
+
 static inline size_t dtype_size(int dt) { return dt == LS_F32 ? 4 : 2; }
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 

@@ -6,8 +6,6 @@
 
 namespace {
 
-constexpr float kGeluC = 0.7978845608028654f;  // sqrt(2/pi)
-
 // ------------------------------------------------------------------ convert
 __global__ void convert_kernel(const void* src, int sdt, void* dst, int ddt, size_t n, const float* scale) {
   const float sc = scale ? *scale : 1.f;
@@ -453,10 +451,6 @@ __global__ void rope_kernel(void* qkv, int dt, int T, int h, int dh, const int32
 }
 
 // ------------------------------------------------------------- activations
-__device__ __forceinline__ float gelu_f(float u, int kind) {
-  if (kind == LS_ACT_GELU_TANH) return 0.5f * u * (1.f + tanhf(kGeluC * (u + 0.044715f * u * u * u)));
-  return 0.5f * u * (1.f + erff(u * 0.70710678118654752f));
-}
 __device__ __forceinline__ float gelu_grad_f(float u, int kind) {
   if (kind == LS_ACT_GELU_TANH) {
     const float t = tanhf(kGeluC * (u + 0.044715f * u * u * u));

@@ -543,14 +543,10 @@ ls_status gemm_dma_splitk_try(int op_dtype, int M, int N, int K, const void* A, 
 // Weight-streaming product for a few rows (decode batches, M <= 64): tiles of 64 x 128 so that
 // three workgroups share a compute unit, the weights stream through LDS as whole cache lines,
 // and the contraction is split until the chip has about three workgroups per compute unit.
-ls_status gemm_dma_skinny_try(int op_dtype, int M, int N, int K, const void* A, long lda, const void* B, long ldb,
-                              void* C, long ldc, int c_dtype, const void* bias, int bias_dtype,
-                              const float* resid, long ldr, float* scratch, size_t scratch_floats,
-                              hipStream_t st) {
+ls_status gemm_dma_skinny_partials(int op_dtype, int M, int N, int K, const void* A, long lda, const void* B,
+                                   long ldb, float* scratch, size_t scratch_floats, int* splits_out, hipStream_t st) {
   if (!scratch || K % TK != 0 || M < 1 || M > 64 || N < 64 || N % 4 != 0) return LS_ESTATE;
-  const int per16 = c_dtype == LS_F32 ? 4 : 8;
-  if (ldc % per16 != 0 || (uintptr_t)C % 16 != 0 || (uintptr_t)scratch % 16 != 0) return LS_ESTATE;
-  if (resid && (ldr % 4 != 0 || (uintptr_t)resid % 16 != 0)) return LS_ESTATE;
+  if ((uintptr_t)scratch % 16 != 0) return LS_ESTATE;
   const long tiles = (N + 127) / 128;
   const int nk = K / TK;
   int splits = (int)(768 / tiles);   // one round of workgroups: three 48 KB tiles fit a compute unit
@@ -559,13 +555,34 @@ ls_status gemm_dma_skinny_try(int op_dtype, int M, int N, int K, const void* A, 
   while (splits > 1 && nk / splits < 6) --splits;
   while (splits > 1 && (size_t)splits * M * N > scratch_floats) --splits;
   if ((size_t)splits * M * N > scratch_floats) return LS_ESTATE;
-  DmaArgs g{M, N, K, A, lda, 1, B, ldb, 1, nullptr, 0, LS_F32, nullptr, 0, nullptr, 0, 0, nullptr, 0, 0, 0, nullptr,
+  DmaArgs g{M, N, K, A, lda, 1, B, ldb, 1, scratch, N, LS_F32, nullptr, 0, nullptr, 0, 0, nullptr, 0, 0, 0, nullptr,
             nullptr, 0};
+  g.split_stride = (long)M * N;
+  if (op_dtype == LS_BF16) LS_TRY((launch<bf16_t, 64, 128, true, true, 2>(g, st, splits)));
+  else if (op_dtype == LS_F16) LS_TRY((launch<f16_t, 64, 128, true, true, 2>(g, st, splits)));
+  else return LS_ESTATE;
+  *splits_out = splits;
+  return LS_OK;
+}
+
+ls_status gemm_dma_skinny_try(int op_dtype, int M, int N, int K, const void* A, long lda, const void* B, long ldb,
+                              void* C, long ldc, int c_dtype, const void* bias, int bias_dtype,
+                              const float* resid, long ldr, float* scratch, size_t scratch_floats,
+                              hipStream_t st) {
+  const int per16 = c_dtype == LS_F32 ? 4 : 8;
+  if (ldc % per16 != 0 || (uintptr_t)C % 16 != 0) return LS_ESTATE;
+  if (resid && (ldr % 4 != 0 || (uintptr_t)resid % 16 != 0)) return LS_ESTATE;
+  int splits = 0;
+  const ls_status r = gemm_dma_skinny_partials(op_dtype, M, N, K, A, lda, B, ldb, scratch, scratch_floats, &splits, st);
+  if (r != LS_OK) return r;
+  const long MN = (long)M * N;
+  const unsigned grid = (unsigned)((MN / 4 + 255) / 256);
   if (op_dtype == LS_BF16)
-    return run_splitk<bf16_t, 64>(g, splits, scratch, C, ldc, c_dtype, bias, bias_dtype, resid, ldr, st);
-  if (op_dtype == LS_F16)
-    return run_splitk<f16_t, 64>(g, splits, scratch, C, ldc, c_dtype, bias, bias_dtype, resid, ldr, st);
-  return LS_ESTATE;
+    splitk_reduce_kernel<bf16_t><<<grid, 256, 0, st>>>(scratch, splits, MN, N, C, ldc, c_dtype, bias, bias_dtype, resid, ldr);
+  else
+    splitk_reduce_kernel<f16_t><<<grid, 256, 0, st>>>(scratch, splits, MN, N, C, ldc, c_dtype, bias, bias_dtype, resid, ldr);
+  LS_CHECK_LAUNCH();
+  return LS_OK;
 }
 
 // Returns LS_OK after launching, or LS_ESTATE (without touching the error text)

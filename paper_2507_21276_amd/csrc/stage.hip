@@ -41,6 +41,12 @@ ls_status lsk_gemm_qkv_rope(int, int, int, const void*, const void*, void*, int,
                             void*);
 ls_status lsk_gemm_ws(int, int, int, int, const void*, long, const void*, long, void*, long, int, const void*, int,
                       const float*, long, float*, size_t, void*);
+ls_status lsk_gemm_partials(int, int, int, int, const void*, long, const void*, long, float*, size_t, int*, void*);
+ls_status lsk_finish_resid_norm(const float*, int, int, int, const void*, const float*, float*, int, const void*,
+                                const void*, int, float, void*, int, void*);
+ls_status lsk_finish_act(const float*, int, int, int, int, const void*, int, void*, int, void*);
+ls_status lsk_finish_qkv(const float*, int, int, int, int, const void*, int, const int32_t*, const int32_t*,
+                         const float*, void*, int, void*, void*, const int32_t*, int, int, void*);
 ls_status lsk_optimizer(int, float, float, float, float, float, float, float, int, size_t, const float*, float*, float*,
                         float*, void*, int, void*, int, void*);
 ls_status lsk_attn_bwd_rope(int, const void*, const void*, const void*, const float*, int, int, int, int, int,
@@ -252,6 +258,33 @@ ls_status linear(const ls_stage* s, int T, int N, int K, const void* X, const vo
                      scratch ? serve_scratch_floats(s) : 0, st);
 }
 
+// attention of a serving call over the pages of layer-local pools kp / vp (the new rows are already in them)
+ls_status serve_attention(const ls_stage* s, int T, const FwdBufs& f, const int32_t* pos, const int32_t* req, int B,
+                          const ls_kv* kv, void* kp, void* vp, int max_ctx, const int32_t* chunk_start, int n_decode,
+                          hipStream_t st) {
+  const ls_config& c = s->cfg;
+  const int d = c.d_model, mt = c.mma_dtype;
+  if (chunk_start && mt != LS_F32 && c.head_dim >= 64) {
+    // decode rows of a hybrid batch: the bandwidth-bound kernel, one row per request
+    if (n_decode > 0)
+      LS_TRY(lsk_attn_paged(1, f.qkv, mt, n_decode, c.n_heads, c.head_dim, pos, req, kp, vp, kv->block_table,
+                            kv->max_pages_per_req, c.page_size, max_ctx, f.o,
+                            (long)n_decode * c.n_heads < 2048 ? f.scratch : nullptr, st));
+    // prompt chunks: matrix-core attention over the pages (queries of a chunk share the K/V tiles)
+    const size_t e = osz(s);
+    if (B > n_decode)
+      LS_TRY(lsk_attn_prefill_mfma((const char*)f.qkv + (size_t)n_decode * 3 * d * e, mt, B - n_decode, chunk_start,
+                                   c.n_heads, c.head_dim, kp, vp,
+                                   kv->block_table + (size_t)n_decode * kv->max_pages_per_req,
+                                   kv->ctx_len + n_decode, kv->max_pages_per_req, c.page_size,
+                                   (char*)f.o + (size_t)n_decode * d * e, st));
+    return LS_OK;
+  }
+  return lsk_attn_paged(mt == LS_F32 ? 0 : 1, f.qkv, mt, T, c.n_heads, c.head_dim, pos, req, kp, vp,
+                        kv->block_table, kv->max_pages_per_req, c.page_size, max_ctx, f.o,
+                        (long)T * c.n_heads < 2048 ? f.scratch : nullptr, st);
+}
+
 // n_decode (serving with chunk_start only): the first n_decode rows are single-token decode rows of
 // requests 0 .. n_decode - 1; chunk_start then describes requests n_decode .. B - 1 (rows after them)
 ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const int32_t* pos,
@@ -280,25 +313,7 @@ ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const
     void* vp = (char*)kv->v_pool + (size_t)l * slab;
     LS_TRY(lsk_rope_kv_write(f.qkv, mt, T, c.n_heads, c.head_dim, pos, req, gpt || roped ? nullptr : s->rope_table, kp, vp,
                              kv->block_table, kv->max_pages_per_req, c.page_size, st));
-    if (chunk_start && mt != LS_F32 && c.head_dim >= 64) {
-      // decode rows of a hybrid batch: the bandwidth-bound kernel, one row per request
-      if (n_decode > 0)
-        LS_TRY(lsk_attn_paged(1, f.qkv, mt, n_decode, c.n_heads, c.head_dim, pos, req, kp, vp, kv->block_table,
-                              kv->max_pages_per_req, c.page_size, max_ctx, f.o,
-                              (long)n_decode * c.n_heads < 2048 ? f.scratch : nullptr, st));
-      // prompt chunks: matrix-core attention over the pages (queries of a chunk share the K/V tiles)
-      const size_t e = osz(s);
-      if (B > n_decode)
-        LS_TRY(lsk_attn_prefill_mfma((const char*)f.qkv + (size_t)n_decode * 3 * d * e, mt, B - n_decode, chunk_start,
-                                     c.n_heads, c.head_dim, kp, vp,
-                                     kv->block_table + (size_t)n_decode * kv->max_pages_per_req,
-                                     kv->ctx_len + n_decode, kv->max_pages_per_req, c.page_size,
-                                     (char*)f.o + (size_t)n_decode * d * e, st));
-    } else {
-      LS_TRY(lsk_attn_paged(mt == LS_F32 ? 0 : 1, f.qkv, mt, T, c.n_heads, c.head_dim, pos, req, kp, vp,
-                            kv->block_table, kv->max_pages_per_req, c.page_size, max_ctx, f.o,
-                            (long)T * c.n_heads < 2048 ? f.scratch : nullptr, st));
-    }
+    LS_TRY(serve_attention(s, T, f, pos, req, B, kv, kp, vp, max_ctx, chunk_start, n_decode, st));
   } else {
     LS_TRY(lsk_attn_fwd(mt == LS_F32 ? 0 : 1, f.qkv, mt, B, L, c.n_heads, c.head_dim, f.o, f.lse, st));
   }
@@ -311,6 +326,51 @@ ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const
   else LS_TRY(lsk_swiglu_fwd(f.up, f.act, mt, T, F, st));
   LS_TRY(linear(s, T, d, F, f.act, wptr(s, o.w_dn), f.y, LS_F32, gpt ? pptr(s, o.b_dn) : nullptr, f.x1, f.scratch, st));
   return LS_OK;
+}
+
+// Serving calls of at most 64 rows with 16-bit operands: every projection leaves split-K partial
+// products and one small kernel per projection sums them and applies what follows it in the block
+// (rotary embedding + K/V page write, residual + next normalisation, activation).  h1 of block l + 1
+// is produced by block l's last kernel; block 0 normalises its input itself.
+bool fused_decode_ok(const ls_stage* s, int T) {
+  const ls_config& c = s->cfg;
+  static const bool on = [] { const char* e = getenv("LS_DECODE_FUSED"); return !(e && strcmp(e, "0") == 0); }();
+  static const bool skinny_dma = [] { const char* e = getenv("LS_SKINNY_IMPL"); return !(e && strcmp(e, "mfma") == 0); }();
+  static const bool gemm_dma = [] { const char* e = getenv("LS_GEMM_IMPL"); return !(e && strcmp(e, "staged") == 0); }();
+  return on && skinny_dma && gemm_dma && T <= 64 && c.mma_dtype != LS_F32 && c.d_model % 64 == 0 && c.d_ff % 64 == 0 &&
+         c.d_model <= 8192;
+}
+
+ls_status block_forward_fused(const ls_stage* s, int l, int T, const FwdBufs& f, const int32_t* pos, const int32_t* req,
+                              int B, const ls_kv* kv, int max_ctx, const int32_t* chunk_start, int n_decode,
+                              hipStream_t st) {
+  const ls_config& c = s->cfg;
+  const LayerOff& o = s->off[l];
+  const int d = c.d_model, F = c.d_ff, mt = c.mma_dtype, pt = c.dtype;
+  const bool gpt = c.block == LS_BLOCK_GPT_PRELN, last = l + 1 == c.n_layers;
+  const int nk = gpt ? 0 : 1;
+  const size_t sf = serve_scratch_floats(s);
+  int splits = 0;
+  if (l == 0)
+    LS_TRY(lsk_norm_fwd(nk, f.x, T, d, pptr(s, o.n1_g), gpt ? pptr(s, o.n1_b) : nullptr, pt, c.norm_eps, f.h1, mt,
+                        nullptr, nullptr, st));
+  const size_t slab = (size_t)kv->n_pages * c.n_heads * c.page_size * c.head_dim * osz(s);
+  void* kp = (char*)kv->k_pool + (size_t)l * slab;
+  void* vp = (char*)kv->v_pool + (size_t)l * slab;
+  LS_TRY(lsk_gemm_partials(mt, T, 3 * d, d, f.h1, d, wptr(s, o.w_qkv), d, f.scratch, sf, &splits, st));
+  LS_TRY(lsk_finish_qkv(f.scratch, splits, T, c.n_heads, c.head_dim, gpt ? pptr(s, o.b_qkv) : nullptr, pt, pos, req,
+                        gpt ? nullptr : s->rope_table, f.qkv, mt, kp, vp, kv->block_table, kv->max_pages_per_req,
+                        c.page_size, st));
+  LS_TRY(serve_attention(s, T, f, pos, req, B, kv, kp, vp, max_ctx, chunk_start, n_decode, st));
+  LS_TRY(lsk_gemm_partials(mt, T, d, d, f.o, d, wptr(s, o.w_o), d, f.scratch, sf, &splits, st));
+  LS_TRY(lsk_finish_resid_norm(f.scratch, splits, T, d, gpt ? pptr(s, o.b_o) : nullptr, f.x, f.x1, nk, pptr(s, o.n2_g),
+                               gpt ? pptr(s, o.n2_b) : nullptr, pt, c.norm_eps, f.h2, mt, st));
+  LS_TRY(lsk_gemm_partials(mt, T, s->up_cols, d, f.h2, d, wptr(s, o.w_up), d, f.scratch, sf, &splits, st));
+  LS_TRY(lsk_finish_act(f.scratch, splits, T, F, c.act, gpt ? pptr(s, o.b_up) : nullptr, pt, f.act, mt, st));
+  LS_TRY(lsk_gemm_partials(mt, T, d, F, f.act, F, wptr(s, o.w_dn), F, f.scratch, sf, &splits, st));
+  const LayerOff& nx = s->off[last ? l : l + 1];
+  return lsk_finish_resid_norm(f.scratch, splits, T, d, gpt ? pptr(s, o.b_dn) : nullptr, f.x1, f.y, last ? -1 : nk,
+                               pptr(s, nx.n1_g), gpt ? pptr(s, nx.n1_b) : nullptr, pt, c.norm_eps, f.h1, mt, st);
 }
 
 ls_status check_kv(const ls_stage* s, const ls_kv* kv, int B, const int32_t* new_tokens, int* max_ctx) {
@@ -341,10 +401,12 @@ ls_status serve_forward(ls_stage* s, const void* X, int T, int B, const ls_kv* k
                         const FwdWs& w, const int32_t* chunk_start, int n_decode, hipStream_t st) {
   const ls_config& c = s->cfg;
   LS_TRY(lsk_convert(X, c.io_dtype, w.xa, LS_F32, (size_t)T * c.d_model, st));
+  const bool fused = fused_decode_ok(s, T);
   for (int l = 0; l < c.n_layers; ++l) {
     FwdBufs f{w.xa, w.xb, w.xa, nullptr, nullptr, nullptr, nullptr, nullptr,
               w.h, w.qkv, w.o, w.h, w.up, w.act, w.scratch};
-    LS_TRY(block_forward(s, l, T, f, w.pos, w.req, B, 0, kv, max_ctx, chunk_start, n_decode, st));
+    if (fused) LS_TRY(block_forward_fused(s, l, T, f, w.pos, w.req, B, kv, max_ctx, chunk_start, n_decode, st));
+    else LS_TRY(block_forward(s, l, T, f, w.pos, w.req, B, 0, kv, max_ctx, chunk_start, n_decode, st));
   }
   return lsk_convert(w.xa, LS_F32, Y, c.io_dtype, (size_t)T * c.d_model, st);
 }
