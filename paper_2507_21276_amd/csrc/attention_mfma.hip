@@ -15,6 +15,10 @@
 // holds per 16-key step consecutive keys, i.e. exactly the B-operand layout.
 //
 // Backward (dQ, dK, dV) follows the same scheme; see flash_bwd_kernel.
+#include <cstdlib>
+#include <cstring>
+#include <type_traits>
+
 #include "common.h"
 
 namespace {
@@ -300,33 +304,6 @@ __global__ __launch_bounds__(256) void flash_fwd_kernel(const T* __restrict__ qk
   }
 }
 
-template <class T, int DH>
-ls_status launch_fwd(const void* qkv, int B, int L, int h, void* o, float* lse, hipStream_t st) {
-  const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
-  PagedGeom pg{};
-  if (L > 512) {
-    constexpr int QT = 2;
-    dim3 grid(B * h, (L + 4 * QT * 32 - 1) / (4 * QT * 32));
-    flash_fwd_kernel<T, DH, QT, false><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, lse, L, h, scale_log2, pg);
-  } else {
-    constexpr int QT = 1;
-    dim3 grid(B * h, (L + 4 * QT * 32 - 1) / (4 * QT * 32));
-    flash_fwd_kernel<T, DH, QT, false><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, lse, L, h, scale_log2, pg);
-  }
-  LS_CHECK_LAUNCH();
-  return LS_OK;
-}
-
-template <class T, int DH>
-ls_status launch_prefill(const void* qkv, int h, void* o, const PagedGeom& pg, int max_chunk, hipStream_t st) {
-  const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
-  constexpr int QT = 1;
-  dim3 grid(pg.n_req * h, (max_chunk + 4 * QT * 32 - 1) / (4 * QT * 32));
-  flash_fwd_kernel<T, DH, QT, true><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, nullptr, 0, h, scale_log2, pg);
-  LS_CHECK_LAUNCH();
-  return LS_OK;
-}
-
 // ---------------------------------------------------------------------------------
 // Backward.  Two kernels, no atomics (deterministic):
 //   flash_bwd_dq_kernel : a workgroup owns 128 query rows, walks key tiles j <= i
@@ -538,6 +515,301 @@ template <class T>
 __device__ __forceinline__ typename Mma<T>::V8 tr_value(const TrFrag& f) {
   const s16x8_t w = __builtin_shufflevector(f.lo, f.hi, 0, 1, 2, 3, 4, 5, 6, 7);
   return __builtin_bit_cast(typename Mma<T>::V8, w);
+}
+
+// Forward through the tile ring.  A workgroup owns 4 * QT * 32 queries (QT tiles of 32 per
+// wavefront, Q fragments in registers) and walks the 64-key tiles below its diagonal; K and V
+// tiles arrive by direct-to-LDS loads through a ring of NS stages (three tiles in flight), so no
+// wavefront waits on a global load inside the loop.  S^T = K Q^T puts the softmax state of a
+// query in one lane; V^T for O^T += V^T P^T is read from the V tile with the transposing LDS
+// load, and P goes from the first product's accumulators straight into the second product's
+// B operand.  PAGED: the tiles are gathered from the request's pages (block-table row copied
+// to LDS once), queries sit at positions past .. past + Lq - 1.
+template <class T, int DH>
+__device__ __forceinline__ void dma_rows_paged(const T* kpool, const T* vpool, const int* page_of, int shift, int h,
+                                               int head, int key0, int nkeys, char* k_tile, char* v_tile, int l,
+                                               int lane) {
+  constexpr int CPR = DH / 8, RPL = 64 / CPR;
+  const int row = l * RPL + lane / CPR;
+  const int gch = (lane % CPR) ^ tile_swz<DH>(row);
+  const int key = min(key0 + row, nkeys - 1);
+  const long off = ((((long)page_of[key >> shift] * h + head) << shift) + (key & ((1 << shift) - 1))) * DH + gch * 8;
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kpool + off),
+                                   (__attribute__((address_space(3))) void*)(k_tile + l * 1024), 16, 0, 0);
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vpool + off),
+                                   (__attribute__((address_space(3))) void*)(v_tile + l * 1024), 16, 0, 0);
+}
+
+template <class T, int DH, int QT, bool PAGED, int NS, int OCC>
+__global__ __launch_bounds__(256, OCC) void flash_fwd_ring_kernel(const T* __restrict__ qkv, T* __restrict__ o,
+                                                             float* __restrict__ lse, int L, int h,
+                                                             float scale_log2, PagedGeom pg) {
+  typedef typename Mma<T>::V8 V8;
+  typedef typename Mma<T>::V4 V4;
+  constexpr int BQ = 4 * QT * 32, KS = DH / 16, DT = DH / 32;
+  constexpr int TILE_B = KT * DH * 2;            // bytes of a K or V tile
+  constexpr int STAGE_B = 2 * TILE_B;
+  constexpr int NLT = TILE_B / 1024 / 4;         // wave loads per wavefront and tile
+  constexpr int NLD = 2 * NLT;                   // loads per wavefront and stage
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  int* page_of = (int*)(smem + NS * STAGE_B);
+
+  const int b = blockIdx.x / h, head = blockIdx.x % h;
+  const int d = h * DH;
+  const long ld = 3L * d;
+  const long row0 = PAGED ? pg.start[b] : (long)b * L;
+  const int Lq = PAGED ? pg.start[b + 1] - pg.start[b] : L;
+  const int past = PAGED ? pg.ctx_len[b] : 0;
+  const int n_qt = (Lq + BQ - 1) / BQ;
+  if ((int)blockIdx.y >= n_qt) return;
+  const int qtile = n_qt - 1 - blockIdx.y;   // heaviest tiles of all heads first
+  const T* qb = qkv + row0 * ld + (long)head * DH;
+  const T* kb = qb + d;
+  const T* vb = qb + 2 * d;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int col = lane & 31, hf = lane >> 5;
+  const int wq0 = qtile * BQ + wave * QT * 32;
+  const int nkeys = past + Lq;
+  const int shift = PAGED ? 31 - __builtin_clz(pg.page) : 0;
+  if (PAGED) {
+    const int np = (nkeys + pg.page - 1) >> shift;
+    for (int i = threadIdx.x; i < np; i += 256) page_of[i] = pg.block_table[(long)b * pg.max_pages + i];
+  }
+
+  V8 qf[QT][KS];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    const int q = wq0 + t * 32 + col;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      u32x4 z = {0u, 0u, 0u, 0u};
+      if (q < Lq) z = *(const u32x4*)(qb + (long)q * ld + s * 16 + hf * 8);
+      qf[t][s] = __builtin_bit_cast(V8, z);
+    }
+  }
+  f32x16 oacc[QT][DT];
+  float m_run[QT], l_run[QT];
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    m_run[t] = -INFINITY;
+    l_run[t] = 0.f;
+#pragma unroll
+    for (int j = 0; j < DT; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[t][j][e] = 0.f;
+  }
+  // the wait counts below assume that only direct-to-LDS loads are in flight
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+  if (PAGED) __syncthreads();
+
+  const int q_hi = min(Lq, qtile * BQ + BQ) - 1;
+  const int nt = (past + q_hi) / KT + 1;
+  // tile t -> stage t % NS; tiles past the end re-fetch the last one (never used), so that
+  // every wavefront always has the same number of loads in flight
+  auto issue = [&](int t) {
+    const int key0 = min(t, nt - 1) * KT;
+    char* st = smem + (t % NS) * STAGE_B;
+#pragma unroll
+    for (int j = 0; j < NLT; ++j) {
+      if (PAGED) {
+        dma_rows_paged<T, DH>((const T*)pg.k_pool, (const T*)pg.v_pool, page_of, shift, h, head, key0, nkeys, st,
+                              st + TILE_B, wave * NLT + j, lane);
+      } else {
+        dma_rows<T, DH>(kb, ld, key0, nkeys, st, wave * NLT + j, lane);
+        dma_rows<T, DH>(vb, ld, key0, nkeys, st + TILE_B, wave * NLT + j, lane);
+      }
+    }
+  };
+#pragma unroll
+  for (int t = 0; t < NS; ++t) issue(t);
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 1) * NLD) : "memory");
+  __syncthreads();
+
+  for (int t = 0; t < nt; ++t) {
+    const int key0 = t * KT;
+    const char* ks = smem + (t % NS) * STAGE_B;
+    const char* vs = ks + TILE_B;
+    // One tile for this wavefront.  MASKED: the tile reaches the diagonal of some query of the wavefront.
+    auto tile_body = [&](auto masked_tag) {
+      constexpr bool MASKED = decltype(masked_tag)::value;
+      f32x16 sacc[QT][2];
+#pragma unroll
+      for (int tq = 0; tq < QT; ++tq)
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) sacc[tq][c][e] = 0.f;
+      // S^T = K Q^T; MFMA row r is key pi(r): a lane's 8 values per 16-key step are consecutive keys
+#pragma unroll
+      for (int s = 0; s < KS; ++s)
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+          const V8 kf = frag_rows<T, DH>(ks, c * 32 + pi_row(col), 2 * s + hf);
+#pragma unroll
+          for (int tq = 0; tq < QT; ++tq) sacc[tq][c] = Mma<T>::run(kf, qf[tq][s], sacc[tq][c]);
+        }
+      TrFrag fr[2][DT];
+#pragma unroll
+      for (int j = 0; j < DT; ++j) tr_read<DH>(fr[0][j], vs, j * 32, 0, lane);
+      // online softmax per query (lane); element e of block c <-> key key0 + 32 c + 16 (e / 8) + 8 hf + e % 8.
+      // m_run is the reference the exponentials are taken against.  It follows the running maximum
+      // lazily: only when some query of the wavefront exceeds it by more than 2^8 are the sums and
+      // the accumulators rescaled (exact either way; until then p <= 256, far inside every format
+      // involved), which removes the rescaling from all but the first tiles of a row.
+      V8 pf[QT][4];
+#pragma unroll
+      for (int tq = 0; tq < QT; ++tq) {
+        const int q = past + wq0 + tq * 32 + col;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) {
+            if (MASKED) {
+              const int key = key0 + c * 32 + 16 * (e >> 3) + 8 * hf + (e & 7);
+              if (key > q) sacc[tq][c][e] = -INFINITY;
+            }
+            mx = fmaxf(mx, sacc[tq][c][e]);
+          }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
+        if (__builtin_amdgcn_ballot_w64(mx > m_run[tq] + 8.f) != 0) {
+          const float m_new = fmaxf(m_run[tq], mx);
+          const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run[tq] - m_new);
+          l_run[tq] *= alpha;
+          m_run[tq] = m_new;
+#pragma unroll
+          for (int j = 0; j < DT; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[tq][j][e] *= alpha;
+        }
+        const float m_ref = m_run[tq] == -INFINITY ? 0.f : m_run[tq];   // a row with no visible key yet
+        float rs = 0.f;
+#pragma unroll
+        for (int c = 0; c < 2; ++c)
+#pragma unroll
+          for (int g = 0; g < 2; ++g) {
+            V8 pv;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+              const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[tq][c][g * 8 + i], scale_log2, -m_ref));
+              rs += pr;
+              pv[i] = from_f<T>(pr);
+            }
+            pf[tq][c * 2 + g] = pv;
+          }
+        l_run[tq] += rs;
+      }
+      // O^T += V^T P^T in four steps of 16 keys
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        tr_wait(fr[kk & 1]);
+        if (kk < 3) {
+#pragma unroll
+          for (int j = 0; j < DT; ++j) tr_read<DH>(fr[(kk + 1) & 1][j], vs, j * 32, (kk + 1) * 16, lane);
+        }
+#pragma unroll
+        for (int j = 0; j < DT; ++j) {
+          const V8 vf = tr_value<T>(fr[kk & 1][j]);
+#pragma unroll
+          for (int tq = 0; tq < QT; ++tq) oacc[tq][j] = Mma<T>::run(vf, pf[tq][kk], oacc[tq][j]);
+        }
+      }
+    };
+    // this wavefront's rows are past + wq0 .. + QT * 32 - 1: tiles entirely above its diagonal add
+    // nothing, tiles entirely below the first row's diagonal need no mask
+    if (key0 + KT - 1 <= past + wq0) tile_body(std::false_type{});
+    else if (key0 <= past + wq0 + QT * 32 - 1) tile_body(std::true_type{});
+    // tile t + 1 has landed when only the loads of tiles t + 2 .. t + NS - 1 are outstanding;
+    // after the barrier nobody reads tile t any more and its stage is refilled
+    asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((NS - 2) * NLD) : "memory");
+    __syncthreads();
+    issue(t + NS);
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no direct-to-LDS write may outlive the workgroup
+
+  // normalise and write O[q][dh]; a lane holds dh rows j * 32 + 8 (e / 4) + 4 hf + e % 4 of its query
+#pragma unroll
+  for (int t = 0; t < QT; ++t) {
+    const int q = wq0 + t * 32 + col;
+    const float l = l_run[t] + __shfl_xor(l_run[t], 32, 64);
+    if (q >= Lq) continue;
+    const float inv = 1.0f / l;
+    T* orow = o + (row0 + q) * d + (long)head * DH;
+#pragma unroll
+    for (int j = 0; j < DT; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        V4 v;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = from_f<T>(oacc[t][j][g * 4 + i] * inv);
+        *(V4*)(orow + j * 32 + 8 * g + 4 * hf) = v;
+      }
+    if (lse && hf == 0)
+      lse[(row0 + q) * h + head] = (m_run[t] + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+  }
+}
+
+// Four stages.  With head_dim 64 (64 KB of ring, under 256 registers) two workgroups share a compute
+// unit and cover each other's waits; with head_dim 128 one does (two stages and two workgroups were
+// measured slower: 227 against 164 us at 2 x 2048 x 32 heads, the registers no longer fit).
+template <int DH> struct RingCfg { static constexpr int NS = 4, OCC = DH == 128 ? 1 : 2; };
+
+template <class T, int DH, int QT, bool PAGED>
+ls_status launch_ring(const void* qkv, void* o, float* lse, int L, int h, float scale_log2, const PagedGeom& pg,
+                      dim3 grid, int extra_lds, hipStream_t st) {
+  constexpr int NS = RingCfg<DH>::NS;
+  const int lds = NS * 2 * KT * DH * 2 + extra_lds;
+  static bool attr_set = false;
+  if (!attr_set) {
+    LS_CHECK_HIP(hipFuncSetAttribute((const void*)flash_fwd_ring_kernel<T, DH, QT, PAGED, NS, RingCfg<DH>::OCC>,
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024));
+    attr_set = true;
+  }
+  flash_fwd_ring_kernel<T, DH, QT, PAGED, NS, RingCfg<DH>::OCC><<<grid, 256, lds, st>>>((const T*)qkv, (T*)o, lse, L, h, scale_log2, pg);
+  LS_CHECK_LAUNCH();
+  return LS_OK;
+}
+
+// LS_ATTN_FWD=staged keeps the register-staged forward kernel (for A/B comparisons)
+inline bool fwd_ring_enabled() {
+  static const bool on = [] { const char* e = getenv("LS_ATTN_FWD"); return !(e && strcmp(e, "staged") == 0); }();
+  return on;
+}
+
+template <class T, int DH>
+ls_status launch_fwd(const void* qkv, int B, int L, int h, void* o, float* lse, hipStream_t st) {
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
+  PagedGeom pg{};
+  if constexpr (DH >= 64) {
+    if (fwd_ring_enabled()) {
+      // 128 queries per workgroup: with 256 the two code paths of a tile (masked / unmasked, rescaling
+      // or not) no longer fit the register file for head_dim 128
+      return launch_ring<T, DH, 1, false>(qkv, o, lse, L, h, scale_log2, pg, dim3(B * h, (L + 127) / 128), 0, st);
+    }
+  }
+  if (L > 512) {
+    constexpr int QT = 2;
+    dim3 grid(B * h, (L + 4 * QT * 32 - 1) / (4 * QT * 32));
+    flash_fwd_kernel<T, DH, QT, false><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, lse, L, h, scale_log2, pg);
+  } else {
+    constexpr int QT = 1;
+    dim3 grid(B * h, (L + 4 * QT * 32 - 1) / (4 * QT * 32));
+    flash_fwd_kernel<T, DH, QT, false><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, lse, L, h, scale_log2, pg);
+  }
+  LS_CHECK_LAUNCH();
+  return LS_OK;
+}
+
+template <class T, int DH>
+ls_status launch_prefill(const void* qkv, int h, void* o, const PagedGeom& pg, int max_chunk, hipStream_t st) {
+  const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
+  constexpr int QT = 1;
+  dim3 grid(pg.n_req * h, (max_chunk + 4 * QT * 32 - 1) / (4 * QT * 32));
+  if (fwd_ring_enabled() && pg.max_pages <= 4096 && pg.page >= 8 && (pg.page & (pg.page - 1)) == 0)
+    return launch_ring<T, DH, 1, true>(qkv, o, nullptr, 0, h, scale_log2, pg, grid, pg.max_pages * 4, st);
+  flash_fwd_kernel<T, DH, QT, true><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, nullptr, 0, h, scale_log2, pg);
+  LS_CHECK_LAUNCH();
+  return LS_OK;
 }
 
 // dQ.  A workgroup owns 128 queries (32 per wavefront, Q and dO fragments in registers) and

@@ -299,7 +299,9 @@ def attn_ref(qkv, B, L, h, dh):
 
 @pytest.mark.parametrize("impl", [0, 1])
 @pytest.mark.parametrize("name,B,L,h,dh", [("f32", 2, 64, 4, 32), ("f16", 2, 200, 3, 64), ("bf16", 1, 300, 2, 128),
-                                             ("f16", 3, 129, 2, 128), ("f16", 1, 1, 2, 64)])
+                                             ("f16", 3, 129, 2, 128), ("f16", 1, 1, 2, 64),
+                                             # longer than 512: 256 queries per workgroup, several key tiles in the ring
+                                             ("f16", 1, 700, 2, 128), ("bf16", 2, 600, 1, 64), ("f16", 1, 1025, 1, 128)])
 def test_attention_forward_and_backward(impl, name, B, L, h, dh):
     if impl == 1 and name == "f32":
         pytest.skip("matrix-core attention is 16-bit only")
