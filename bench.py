@@ -81,6 +81,7 @@ def main():
     ap.add_argument("--mma", default="f16", choices=["f16", "bf16"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-probe", action="store_true")
+    ap.add_argument("--no-cfg5", action="store_true", help="skip the config-5 decode measurement")
     ap.add_argument("--no-serve-loop", action="store_true", help="skip the continuous-batching loop measurement")
     ap.add_argument("--no-update", action="store_true", help="skip the model-update measurement (3 fp32 vectors of the stage's size)")
     ap.add_argument("--legs", default="train,decode,prefill",
@@ -325,6 +326,33 @@ def main():
         srv.close()
         del kpl, vpl, Yr
 
+    # ---- BASELINE config 5 decode (LLaMA-13B-shaped blocks, 128 requests, lognormal contexts), four of
+    #      its ten blocks: bytes and time both scale with the block count ------------------------------
+    decode_cfg5 = None
+    if not args.no_cfg5:
+        cfg5 = S.scaled(S.CONFIGS["llama13b_bf16"], n_layers=4)
+        st5 = Bd.Stage(cfg5, io_dtype="bf16", mma_dtype=args.mma)
+        p5 = S.make_params_torch(cfg5, seed=0, device=dev)
+        st5.ls_bind_params(p5)
+        sv5 = S.WORKLOADS["cfg5"]["serve"]
+        ctx5 = S.context_lengths(sv5, seed=0)
+        B5, d5, F5, nL5 = sv5["B"], cfg5["d_model"], cfg5["d_ff"], cfg5["n_layers"]
+        tab5, np5 = S.page_tables(ctx5, np.ones_like(ctx5), cfg5["page_size"], seed=0)
+        kv5 = Bd.KV(st5, np5, tab5, ctx5)
+        kv5.k_pool.copy_(S.normal_torch(0, "Kpool5", kv5.k_pool.shape, 1.0, dev, kv5.k_pool.dtype))
+        kv5.v_pool.copy_(S.normal_torch(0, "Vpool5", kv5.v_pool.shape, 1.0, dev, kv5.v_pool.dtype))
+        X5 = S.normal_torch(0, "Xdec5", (B5, d5), 1.0, dev, io)
+        Y5 = torch.empty_like(X5)
+        ws5 = st5.new_workspace(B5)
+        ms5 = time_events(torch, lambda: st5.stage_decode(X5, B5, kv5, Y5, ws5), 10, warm=2)
+        by5 = 2.0 * nL5 * (4.0 * d5 * d5 + 3.0 * d5 * F5) + float((ctx5 + 1).sum()) * nL5 * 2 * d5 * 2
+        decode_cfg5 = {"workload": "cfg5 decode B=128 ctx~lognormal(median 1024) clipped [64, 4096], 4 of 10 blocks",
+                       "ms": ms5, "tok_s_4_blocks": B5 / ms5 * 1e3, "bytes": by5, "achieved_gbs": by5 / (ms5 * 1e-3) / 1e9,
+                       "frac_of_hbm_peak": by5 / (ms5 * 1e-3) / 1e9 / PEAK_HBM_GBS}
+        log(f"cfg5-shaped decode (4 blocks): {ms5:.2f} ms -> {decode_cfg5['achieved_gbs']:.0f} GB/s")
+        st5.close()
+        del kv5, p5, X5, Y5, ws5
+
     # ---- model update (a row beyond the step: AdamW over the stage's parameters, last because it
     #      rewrites the weights) -------------------------------------------------------------------
     roofline_update = None
@@ -368,7 +396,7 @@ def main():
                       "train_frac_of_mfma_peak": (3.0 * T * nL * (8.0 * d * d + 6.0 * d * F)
                                                   + 3.0 * 2.0 * L * L * d * B * nL) / (ms_train * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS},
         "roofline": roofline, "roofline_decode": roofline_decode, "roofline_update": roofline_update,
-        "probe": probe, "kv_offload": kv_move, "serve_loop": serve_loop,
+        "probe": probe, "kv_offload": kv_move, "serve_loop": serve_loop, "decode_cfg5": decode_cfg5,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, S)

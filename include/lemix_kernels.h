@@ -250,7 +250,7 @@ ls_status lsk_colsum_scaled(const void* x, int dtype, int T, int N, long ld, flo
 
 /*
  * Decode batches (Autoregressive Generation: decoding requests extend their
- * prefilled context one token per iteration; at most 64 rows per call).  The
+ * prefilled context one token per iteration; at most 128 rows per call).  The
  * projections of such a batch stream the weights once and split the
  * contraction over workgroups; lsk_gemm_partials leaves the split results
  *   partial[s][M][N] (device, fp32), s < *splits (host, written on return),
@@ -258,7 +258,7 @@ ls_status lsk_colsum_scaled(const void* x, int dtype, int T, int N, long ld, flo
  * and each lsk_finish_* call sums them in the order s = 0, 1, .. and applies,
  * in the same pass, the step that follows that projection in the block
  * (Model Architecture: attention and feed-forward sub-layers with residual
- * connections and normalisation).  16-bit operands; M <= 64, N >= 64 and a
+ * connections and normalisation).  16-bit operands; M <= 128, N >= 64 and a
  * multiple of 4, K a multiple of 64, partial_floats >= M * N (more allows more
  * splits, at most 16).  LS_EINVAL outside these limits.
  */

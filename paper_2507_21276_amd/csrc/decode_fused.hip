@@ -1,4 +1,4 @@
-// Decode batches (at most 64 rows): the split-K projections leave fp32 partial
+// Decode batches (at most 128 rows): the split-K projections leave fp32 partial
 // products; the kernels here sum them in a fixed order and apply, in the same
 // pass, the step that follows the projection in the block:
 //   QKV projection   -> bias, rotary embedding of q and k, K/V page write
@@ -170,8 +170,8 @@ ls_status lsk_gemm_partials(int op_dtype, int M, int N, int K, const void* X, lo
                             float* partial, size_t partial_floats, int* splits, void* stream) {
   LS_REQUIRE(X && W && partial && splits, "gemm_partials: null argument");
   LS_REQUIRE(half_type(op_dtype), "gemm_partials: 16-bit operands only");
-  LS_REQUIRE(M >= 1 && M <= 64 && N >= 64 && N % 4 == 0 && K >= 64 && K % 64 == 0,
-             "gemm_partials: need 1 <= M <= 64, N >= 64 and a multiple of 4, K a multiple of 64 (M=%d N=%d K=%d)", M, N, K);
+  LS_REQUIRE(M >= 1 && M <= 128 && N >= 64 && N % 4 == 0 && K >= 64 && K % 64 == 0,
+             "gemm_partials: need 1 <= M <= 128, N >= 64 and a multiple of 4, K a multiple of 64 (M=%d N=%d K=%d)", M, N, K);
   LS_REQUIRE(ldx % 8 == 0 && ldw % 8 == 0 && (uintptr_t)X % 16 == 0 && (uintptr_t)W % 16 == 0 &&
                  (uintptr_t)partial % 16 == 0,
              "gemm_partials: operands must be 16-byte aligned with leading dimensions that are multiples of 8");

@@ -358,10 +358,10 @@ extern "C" ls_status lsk_gemm_ws(int op_dtype, int M, int N, int K, const void* 
                                  void* stream) {
   LS_REQUIRE(M > 0 && N > 0 && K > 0, "gemm_ws: non-positive size M=%d N=%d K=%d", M, N, K);
   LS_REQUIRE(X && W && C, "gemm_ws: null operand");
-  // decode batches (M <= 64): weights stream through LDS in 64 x 128 tiles; LS_SKINNY_IMPL=mfma keeps the
+  // decode batches (M <= 128): weights stream through LDS in 64 x 128 or 128 x 128 tiles; LS_SKINNY_IMPL=mfma keeps the
   // register-streaming kernel (lsk_gemm_skinny) for A/B comparisons
   static const bool skinny_dma = [] { const char* e = getenv("LS_SKINNY_IMPL"); return !(e && strcmp(e, "mfma") == 0); }();
-  if (skinny_dma && use_dma_kernel() && scratch && (op_dtype == LS_BF16 || op_dtype == LS_F16) && M <= 64 && K % 8 == 0 &&
+  if (skinny_dma && use_dma_kernel() && scratch && (op_dtype == LS_BF16 || op_dtype == LS_F16) && M <= 128 && K % 8 == 0 &&
       ldx % 8 == 0 && ldw % 8 == 0 && (uintptr_t)X % 16 == 0 && (uintptr_t)W % 16 == 0 &&
       (c_dtype == LS_F32 || c_dtype == op_dtype)) {
     const ls_status r = gemm_dma_skinny_try(op_dtype, M, N, K, X, ldx, W, ldw, C, ldc, c_dtype, bias, bias_dtype, resid,

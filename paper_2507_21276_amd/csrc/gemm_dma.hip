@@ -540,16 +540,19 @@ ls_status gemm_dma_splitk_try(int op_dtype, int M, int N, int K, const void* A, 
   return LS_ESTATE;
 }
 
-// Weight-streaming product for a few rows (decode batches, M <= 64): tiles of 64 x 128 so that
-// three workgroups share a compute unit, the weights stream through LDS as whole cache lines,
+// Weight-streaming product for a few rows (decode batches, M <= 128): tiles of 64 x 128 so that
+// three workgroups share a compute unit (128 x 128 and two workgroups above 64 rows), the weights stream through LDS as whole cache lines,
 // and the contraction is split until the chip has about three workgroups per compute unit.
 ls_status gemm_dma_skinny_partials(int op_dtype, int M, int N, int K, const void* A, long lda, const void* B,
                                    long ldb, float* scratch, size_t scratch_floats, int* splits_out, hipStream_t st) {
-  if (!scratch || K % TK != 0 || M < 1 || M > 64 || N < 64 || N % 4 != 0) return LS_ESTATE;
+  if (!scratch || K % TK != 0 || M < 1 || M > 128 || N < 64 || N % 4 != 0) return LS_ESTATE;
   if ((uintptr_t)scratch % 16 != 0) return LS_ESTATE;
+  // up to 64 rows: 64 x 128 tiles, three 48 KB workgroups per compute unit; up to 128 rows: 128 x 128
+  // tiles, two 64 KB workgroups
+  const bool tall = M > 64;
   const long tiles = (N + 127) / 128;
   const int nk = K / TK;
-  int splits = (int)(768 / tiles);   // one round of workgroups: three 48 KB tiles fit a compute unit
+  int splits = (int)((tall ? 512 : 768) / tiles);   // one round of workgroups
   if (splits < 1) splits = 1;
   if (splits > 16) splits = 16;
   while (splits > 1 && nk / splits < 6) --splits;
@@ -558,9 +561,15 @@ ls_status gemm_dma_skinny_partials(int op_dtype, int M, int N, int K, const void
   DmaArgs g{M, N, K, A, lda, 1, B, ldb, 1, scratch, N, LS_F32, nullptr, 0, nullptr, 0, 0, nullptr, 0, 0, 0, nullptr,
             nullptr, 0};
   g.split_stride = (long)M * N;
-  if (op_dtype == LS_BF16) LS_TRY((launch<bf16_t, 64, 128, true, true, 2>(g, st, splits)));
-  else if (op_dtype == LS_F16) LS_TRY((launch<f16_t, 64, 128, true, true, 2>(g, st, splits)));
-  else return LS_ESTATE;
+  if (op_dtype == LS_BF16) {
+    if (tall) LS_TRY((launch<bf16_t, 128, 128, true, true, 2>(g, st, splits)));
+    else LS_TRY((launch<bf16_t, 64, 128, true, true, 2>(g, st, splits)));
+  } else if (op_dtype == LS_F16) {
+    if (tall) LS_TRY((launch<f16_t, 128, 128, true, true, 2>(g, st, splits)));
+    else LS_TRY((launch<f16_t, 64, 128, true, true, 2>(g, st, splits)));
+  } else {
+    return LS_ESTATE;
+  }
   *splits_out = splits;
   return LS_OK;
 }

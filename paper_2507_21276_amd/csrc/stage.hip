@@ -252,7 +252,7 @@ ls_status linear(const ls_stage* s, int T, int N, int K, const void* X, const vo
                  const void* bias, const float* resid, float* scratch, hipStream_t st) {
   const int mt = s->cfg.mma_dtype;
   static const bool skinny_dma = [] { const char* e = getenv("LS_SKINNY_IMPL"); return !(e && strcmp(e, "mfma") == 0); }();
-  if (mt != LS_F32 && T <= 128 && scratch && !(skinny_dma && T <= 64))
+  if (mt != LS_F32 && T <= 128 && scratch && !skinny_dma)
     return lsk_gemm_skinny(mt, T, N, K, X, K, W, K, C, N, c_dtype, bias, s->cfg.dtype, resid, N, scratch, st);
   return lsk_gemm_ws(mt, T, N, K, X, K, W, K, C, N, c_dtype, bias, s->cfg.dtype, resid, N, scratch,
                      scratch ? serve_scratch_floats(s) : 0, st);
@@ -328,7 +328,7 @@ ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const
   return LS_OK;
 }
 
-// Serving calls of at most 64 rows with 16-bit operands: every projection leaves split-K partial
+// Serving calls of at most 128 rows with 16-bit operands: every projection leaves split-K partial
 // products and one small kernel per projection sums them and applies what follows it in the block
 // (rotary embedding + K/V page write, residual + next normalisation, activation).  h1 of block l + 1
 // is produced by block l's last kernel; block 0 normalises its input itself.
@@ -337,7 +337,7 @@ bool fused_decode_ok(const ls_stage* s, int T) {
   static const bool on = [] { const char* e = getenv("LS_DECODE_FUSED"); return !(e && strcmp(e, "0") == 0); }();
   static const bool skinny_dma = [] { const char* e = getenv("LS_SKINNY_IMPL"); return !(e && strcmp(e, "mfma") == 0); }();
   static const bool gemm_dma = [] { const char* e = getenv("LS_GEMM_IMPL"); return !(e && strcmp(e, "staged") == 0); }();
-  return on && skinny_dma && gemm_dma && T <= 64 && c.mma_dtype != LS_F32 && c.d_model % 64 == 0 && c.d_ff % 64 == 0 &&
+  return on && skinny_dma && gemm_dma && T <= 128 && c.mma_dtype != LS_F32 && c.d_model % 64 == 0 && c.d_ff % 64 == 0 &&
          c.d_model <= 8192;
 }
 

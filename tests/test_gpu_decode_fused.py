@@ -37,7 +37,8 @@ def partials_of(name, M, N, K, seed, floats=None):
 
 @pytest.mark.parametrize("name", ["f16", "bf16"])
 @pytest.mark.parametrize("M,N,K", [(64, 4096, 4096), (64, 12288, 4096), (33, 264, 1024), (1, 128, 512),
-                                   (64, 4096, 11008), (7, 1048, 704)])
+                                   (64, 4096, 11008), (7, 1048, 704), (128, 5120, 5120), (100, 27648, 5120),
+                                   (65, 264, 1024)])
 def test_partials_sum_to_the_product(name, M, N, K):
     x, w, part, splits = partials_of(name, M, N, K, 41)
     assert 1 <= splits <= 16
@@ -49,7 +50,7 @@ def test_partials_sum_to_the_product(name, M, N, K):
     assert s1 == 1
     assert_close(host(part1.view(M, N)), ref, 1e-5, "single split")
     with pytest.raises(Bd.LsError):
-        partials_of(name, 65, N, K, 41)
+        partials_of(name, 129, N, K, 41)
     with pytest.raises(Bd.LsError):
         partials_of(name, M, N, K, 41, floats=M * N - 4)
 

@@ -97,7 +97,8 @@ def test_gemm_skinny_weight_streaming(name, M, N, K, split):
                                             (7, 1048, 11008, "op", False), (64, 22016, 4096, "op", False),
                                             (64, 4096, 11008, "f32", True), (32, 72, 64, "op", False),
                                             (17, 40, 320, "f32", False), (64, 8, 192, "op", True),
-                                            (48, 2000, 1600, "f32", True)])
+                                            (48, 2000, 1600, "f32", True), (128, 5120, 13824, "f32", True),
+                                            (100, 15360, 5120, "op", False)])
 def test_gemm_split_k_through_a_workspace(name, M, N, K, out, res):
     """Few output tiles: the contraction is split over workgroups and summed in a fixed order."""
     dt = DT[name]
