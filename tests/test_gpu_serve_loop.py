@@ -81,6 +81,15 @@ def test_serve_loop_small_llama_f16():
     print(f"serve loop, small llama f16: worst relative error {worst:.2e}")
 
 
+def test_serve_loop_widths_that_take_the_fused_decode_path():
+    # d_ff a multiple of 64 and at most 128 rows per pass: every pass (decode rows, prompt chunks, or both)
+    # runs the partial-product projections and the fused finish kernels
+    cfg = S.scaled(S.CONFIGS["llama7b_bf16"], n_layers=3, d_model=256, n_heads=2, d_ff=704)
+    worst = run_trace(cfg, "f16", C=8, T_w=0.05, n_pages=40, max_chunk=64, max_tokens=128, n_req=20,
+                      seed=7, max_prompt=200, max_decode=10)
+    print(f"serve loop, fused decode path: worst relative error {worst:.2e}")
+
+
 def test_serve_loop_tiny_gpt_f32():
     worst = run_trace(TINY, None, C=4, T_w=0.03, n_pages=24, max_chunk=16, max_tokens=40, n_req=16, seed=6,
                       max_prompt=40, max_decode=8)
