@@ -1108,29 +1108,33 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const T* __restrict_
 
 // also records max|dO| per workgroup in dvec[n_items + blockIdx.x]; amax_finish_kernel
 // folds those into dvec[n_items + gridDim.x] (no atomics: deterministic and contention-free)
-template <class T>
-__global__ __launch_bounds__(256) void dvec_kernel(const T* o, const T* dO, long n_items, int dh, float* dvec) {
+template <class T, int DH>
+__global__ __launch_bounds__(256) void dvec_kernel(const T* o, const T* dO, long n_items, float* dvec) {
+  typedef typename Mma<T>::V8 V8;
+  constexpr int LPI = DH / 8, IPW = 64 / LPI;   // lanes per (row, head) item (16 bytes each), items per wavefront
   __shared__ float wmax[4];
-  const long item = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
-  const int lane = threadIdx.x & 63;
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const long item = ((long)blockIdx.x * 4 + wave) * IPW + lane / LPI;
   float s = 0.f, m = 0.f;
   if (item < n_items) {
-    for (int c = lane; c < dh; c += 64) {
-      const float g = to_f(dO[item * dh + c]);
-      s += to_f(o[item * dh + c]) * g;
-      m = fmaxf(m, fabsf(g));
+    const V8 a = *(const V8*)(o + item * DH + (lane % LPI) * 8), g = *(const V8*)(dO + item * DH + (lane % LPI) * 8);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float gi = to_f(g[i]);
+      s += to_f(a[i]) * gi;
+      m = fmaxf(m, fabsf(gi));
     }
   }
-  s = wave_sum(s);
+#pragma unroll
+  for (int off = 1; off < LPI; off <<= 1) s += __shfl_xor(s, off, 64);
   m = wave_max(m);
-  if (lane == 0) {
-    if (item < n_items) dvec[item] = s;
-    wmax[threadIdx.x >> 6] = m;
-  }
+  if (item < n_items && lane % LPI == 0) dvec[item] = s;
+  if (lane == 0) wmax[wave] = m;
   __syncthreads();
   if (threadIdx.x == 0) dvec[n_items + blockIdx.x] = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
 }
-__global__ __launch_bounds__(1024) void amax_finish_kernel(float* blockmax, long nb) {
+// maximum of blockmax[0 .. nb - 1] -> blockmax[out]
+__global__ __launch_bounds__(1024) void amax_finish_kernel(float* blockmax, long nb, long out) {
   __shared__ float red[16];
   // independent partial maxima per thread: the loads of one thread do not wait for each other
   float m0 = 0.f, m1 = 0.f, m2 = 0.f, m3 = 0.f;
@@ -1147,7 +1151,7 @@ __global__ __launch_bounds__(1024) void amax_finish_kernel(float* blockmax, long
   __syncthreads();
   if (threadIdx.x < 64) {
     m = wave_max(threadIdx.x < 16 ? red[threadIdx.x] : 0.f);
-    if (threadIdx.x == 0) blockmax[nb] = m;
+    if (threadIdx.x == 0) blockmax[out] = m;
   }
 }
 
@@ -1157,8 +1161,10 @@ ls_status launch_bwd(const void* qkv, const void* o, const void* dO, const float
   const float scale = 1.0f / sqrtf((float)DH);
   const long items = (long)B * L * h;
   const long nb = (items + 3) / 4;
-  dvec_kernel<T><<<(unsigned)nb, 256, 0, st>>>((const T*)o, (const T*)dO, items, DH, dvec);
-  amax_finish_kernel<<<1, 1024, 0, st>>>(dvec + items, nb);
+  // the scratch keeps room for one maximum per four items; the kernel fills one per 4 * (512 / head_dim)
+  const long nwg = (items + 4 * (512 / DH) - 1) / (4 * (512 / DH));
+  dvec_kernel<T, DH><<<(unsigned)nwg, 256, 0, st>>>((const T*)o, (const T*)dO, items, dvec);
+  amax_finish_kernel<<<1, 1024, 0, st>>>(dvec + items, nwg, nb);
   LS_CHECK_LAUNCH();
   dim3 gq(B * h, (L + 127) / 128), gk(B * h, (L + 127) / 128);
   constexpr int dq_lds = 4 * (2 * KT * DH * 2);
