@@ -116,6 +116,19 @@ template <> struct Ld8<float> {
   }
 };
 
+// conversion of eight consecutive elements per thread (16-byte accesses on the 16-bit side)
+template <class TS, class TD>
+__global__ void convert8_kernel(const TS* src, TD* dst, size_t n8, const float* scale) {
+  const float sc = scale ? *scale : 1.f;
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n8; i += (size_t)gridDim.x * blockDim.x) {
+    float v[8];
+    Ld8<TS>::load(src + i * 8, v);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] *= sc;
+    Ld8<TD>::store(dst + i * 8, v);
+  }
+}
+
 // eight consecutive values of a parameter vector whose type is known only at run time
 __device__ __forceinline__ void load8_param(const void* p, int c, int dt, float (&v)[8]) {
   if (dt == LS_F32) Ld8<float>::load((const float*)p + c, v);
@@ -543,7 +556,18 @@ ls_status lsk_convert_scaled(const void* src, int sdt, void* dst, int ddt, size_
                              void* stream) {
   LS_REQUIRE(src && dst && ok_dtype(sdt) && ok_dtype(ddt), "convert: bad argument");
   if (n == 0) return LS_OK;
-  convert_kernel<<<grid_for(n), 256, 0, (hipStream_t)stream>>>(src, sdt, dst, ddt, n, scale_dev);
+  hipStream_t st = (hipStream_t)stream;
+  if (n % 8 == 0 && ((uintptr_t)src & 15) == 0 && ((uintptr_t)dst & 15) == 0) {
+    const size_t n8 = n / 8;
+    const int g = grid_for(n8);
+#define LS_CV(TS, TD) convert8_kernel<TS, TD><<<g, 256, 0, st>>>((const TS*)src, (TD*)dst, n8, scale_dev)
+    if (sdt == LS_F32) { if (ddt == LS_F32) LS_CV(float, float); else if (ddt == LS_BF16) LS_CV(float, bf16_t); else LS_CV(float, f16_t); }
+    else if (sdt == LS_BF16) { if (ddt == LS_F32) LS_CV(bf16_t, float); else if (ddt == LS_BF16) LS_CV(bf16_t, bf16_t); else LS_CV(bf16_t, f16_t); }
+    else { if (ddt == LS_F32) LS_CV(f16_t, float); else if (ddt == LS_BF16) LS_CV(f16_t, bf16_t); else LS_CV(f16_t, f16_t); }
+#undef LS_CV
+  } else {
+    convert_kernel<<<grid_for(n), 256, 0, st>>>(src, sdt, dst, ddt, n, scale_dev);
+  }
   LS_CHECK_LAUNCH();
   return LS_OK;
 }

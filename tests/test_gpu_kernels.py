@@ -433,3 +433,15 @@ def test_paged_attention_ragged(impl, name, h, dh, P):
             assert np.array_equal(kh[table[b, j // P], :, j % P], kn[i])
         t0 += new[b]
     assert_close(host(o), ref, otol(name, ref, 1e-4), "paged attention")
+
+
+@pytest.mark.parametrize("src,dst", [("f32", "bf16"), ("f32", "f16"), ("bf16", "f32"), ("f16", "f32"), ("bf16", "f16"),
+                                     ("f16", "bf16"), ("f32", "f32")])
+@pytest.mark.parametrize("n,offset", [(8 * 1000, 0), (8 * 1000 + 3, 0), (4096, 1), (5, 0)])
+def test_convert_is_the_rounding_of_each_element(src, dst, n, offset):
+    """Bit-exact against the host conversion (round to nearest even), on the 8-wide path (length a multiple of
+    8, 16-byte aligned) and on the element-wise path (ragged length, misaligned views)."""
+    x = S.normal_torch(51, "cv", (n + offset,), 3.0, dtype=DT[src])[offset:]
+    y = torch.full((n + offset,), 7.0, dtype=DT[dst], device="cuda")[offset:]
+    Bd.lsk_convert(x, y)
+    assert torch.equal(y, x.to(DT[dst]))
