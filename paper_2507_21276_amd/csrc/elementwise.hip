@@ -129,6 +129,21 @@ __global__ void convert8_kernel(const TS* src, TD* dst, size_t n8, const float* 
   }
 }
 
+// maximum of |x| over eight consecutive elements per thread
+template <class TS>
+__global__ void amax8_kernel(const TS* x, size_t n8, unsigned* amax_bits) {
+  float m = 0.f;
+  for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n8; i += (size_t)gridDim.x * blockDim.x) {
+    float v[8];
+    Ld8<TS>::load(x + i * 8, v);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) m = fmaxf(m, fabsf(v[k]));
+  }
+  m = wave_max(m);
+  if ((threadIdx.x & 63) == 0 && m <= 3.0e38f && __float_as_uint(m) > __hip_atomic_load(amax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))
+    atomicMax(amax_bits, __float_as_uint(m));
+}
+
 // eight consecutive values of a parameter vector whose type is known only at run time
 __device__ __forceinline__ void load8_param(const void* p, int c, int dt, float (&v)[8]) {
   if (dt == LS_F32) Ld8<float>::load((const float*)p + c, v);
@@ -579,7 +594,14 @@ ls_status lsk_grad_scale(const void* x, int dt, size_t n, float* out3, void* str
   LS_REQUIRE(x && out3 && ok_dtype(dt) && n > 0, "grad_scale: bad argument");
   hipStream_t st = (hipStream_t)stream;
   scale_reset_kernel<<<1, 1, 0, st>>>(out3);
-  amax_kernel<<<grid_for(n, 256, 2048), 256, 0, st>>>(x, dt, n, (unsigned*)(out3 + 2));
+  if (n % 8 == 0 && ((uintptr_t)x & 15) == 0) {
+    const int g = grid_for(n / 8, 256, 2048);
+    if (dt == LS_F32) amax8_kernel<float><<<g, 256, 0, st>>>((const float*)x, n / 8, (unsigned*)(out3 + 2));
+    else if (dt == LS_BF16) amax8_kernel<bf16_t><<<g, 256, 0, st>>>((const bf16_t*)x, n / 8, (unsigned*)(out3 + 2));
+    else amax8_kernel<f16_t><<<g, 256, 0, st>>>((const f16_t*)x, n / 8, (unsigned*)(out3 + 2));
+  } else {
+    amax_kernel<<<grid_for(n, 256, 2048), 256, 0, st>>>(x, dt, n, (unsigned*)(out3 + 2));
+  }
   scale_finish_kernel<<<1, 1, 0, st>>>(out3);
   LS_CHECK_LAUNCH();
   return LS_OK;

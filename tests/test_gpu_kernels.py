@@ -268,6 +268,12 @@ def test_grad_scale_is_a_power_of_two_that_brings_the_maximum_to_8_16():
     out = torch.zeros(3, dtype=torch.float32, device="cuda")
     Bd.lsk_grad_scale(x, out)
     assert out.cpu().tolist()[:2] == [1.0, 1.0]          # all-zero gradient: no scaling
+    # 16-bit input on the eight-wide path, and a ragged length on the element-wise one
+    for dt, n in ((torch.bfloat16, 4096), (torch.float16, 8 * 333), (torch.float32, 1001)):
+        x = (S.normal_torch(52, "gs", (n,), 1.0, dtype=torch.float32) * 0.01).to(dt)
+        out = torch.zeros(3, dtype=torch.float32, device="cuda")
+        Bd.lsk_grad_scale(x, out)
+        assert out[2].item() == x.float().abs().max().item()
 
 
 @pytest.mark.parametrize("name", ["f32", "f16"])
