@@ -81,6 +81,26 @@ def test_null_arguments_are_errors_not_crashes():
                         0, None) == Bd.LS_EINVAL
     assert b"non-positive" in lib.ls_last_error()
     lib.ls_destroy(None)
+    # the decode-batch entry points and the serving loop validate on the host too
+    splits = C.c_int(0)
+    assert lib.lsk_gemm_partials(Bd.LS_F16, 64, 128, 64, None, 64, None, 64, None, 0, C.byref(splits), None) == Bd.LS_EINVAL
+    assert lib.lsk_finish_resid_norm(None, 1, 4, 64, None, None, None, 1, None, None, 0, 1e-5, None, 0, None) == Bd.LS_EINVAL
+    assert lib.lsk_finish_act(None, 1, 4, 64, Bd.LS_ACT_SWIGLU, None, 0, None, 0, None) == Bd.LS_EINVAL
+    assert lib.lsk_finish_qkv(None, 1, 4, 2, 64, None, 0, None, None, None, None, Bd.LS_F16, None, None, None, 4, 16,
+                              None) == Bd.LS_EINVAL
+    srv = C.c_void_p()
+    assert lib.ls_server_create(None, None, None, None, C.byref(srv)) == Bd.LS_EINVAL
+    assert lib.ls_server_submit(None, 0, None, None, 1, 1) == Bd.LS_EINVAL
+    assert lib.ls_server_pass(None, 0.0, None, None, None, None, None) == Bd.LS_EINVAL
+    assert lib.ls_server_in_flight(None) == 0
+    lib.ls_server_destroy(None)
+    assert lib.ls_get_config(None, None) == Bd.LS_EINVAL
+    assert lib.ls_node_plan(None, None, 0, None, None, None, None) == Bd.LS_EINVAL
+    assert lib.ls_node_queue_len(None, 0) == 0 and lib.ls_node_prune(None) == 0
+    assert lib.ls_batcher_form(None, 0.0, None, None, None, None) == Bd.LS_EINVAL
+    assert lib.ls_batcher_queued(None) == 0 and lib.ls_batcher_batch_size(None) == 0
+    lib.ls_node_destroy(None)
+    lib.ls_batcher_destroy(None)
 
 
 def test_no_instruction_touches_a_register_with_an_assembly_issued_lds_read_in_flight(tmp_path):
