@@ -42,11 +42,12 @@ class Node:
     def __init__(self, S, eta_f, eta_b):
         self.S = S
         self.h = C.c_void_p()
+        self._destroy = Bd.lib().ls_node_destroy      # kept on the object: module globals may be gone at exit
         Bd._check(Bd.lib().ls_node_create(S, eta_f, eta_b, C.byref(self.h)))
 
     def __del__(self):
         if getattr(self, "h", None):
-            Bd.lib().ls_node_destroy(self.h)
+            self._destroy(self.h)
             self.h = None
 
     def plan(self, a, l, Cb, require_backward=False, commit=False):
@@ -133,11 +134,12 @@ class Batcher:
     def __init__(self, Cmax, T_w):
         self.C = Cmax
         self.h = C.c_void_p()
+        self._destroy = Bd.lib().ls_batcher_destroy
         Bd._check(Bd.lib().ls_batcher_create(Cmax, T_w, C.byref(self.h)))
 
     def __del__(self):
         if getattr(self, "h", None):
-            Bd.lib().ls_batcher_destroy(self.h)
+            self._destroy(self.h)
             self.h = None
 
     def push(self, rid, require_backward=False):
@@ -185,6 +187,7 @@ class Server:
         self.cfg = ls_server_config(max_batch, max_wait, k_pool.shape[1], max_pages_per_req, max_chunk,
                                     max_tokens)
         self.h = C.c_void_p()
+        self._destroy = Bd.lib().ls_server_destroy
         Bd._check(Bd.lib().ls_server_create(stage.h, C.byref(self.cfg), k_pool.data_ptr(), v_pool.data_ptr(),
                                             C.byref(self.h)))
         self.workspace = stage.new_workspace(max_tokens)
@@ -192,7 +195,7 @@ class Server:
 
     def close(self):
         if getattr(self, "h", None):
-            Bd.lib().ls_server_destroy(self.h)
+            self._destroy(self.h)
             self.h = None
 
     __del__ = close
