@@ -625,105 +625,114 @@ __global__ __launch_bounds__(256, OCC) void flash_fwd_ring_kernel(const T* __res
   asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 1) * NLD) : "memory");
   __syncthreads();
 
-  for (int t = 0; t < nt; ++t) {
+  // One tile for this wavefront.  MASKED: the tile reaches the diagonal of some query of the wavefront.
+  auto tile_body = [&](auto masked_tag, int t) {
+    constexpr bool MASKED = decltype(masked_tag)::value;
     const int key0 = t * KT;
     const char* ks = smem + (t % NS) * STAGE_B;
     const char* vs = ks + TILE_B;
-    // One tile for this wavefront.  MASKED: the tile reaches the diagonal of some query of the wavefront.
-    auto tile_body = [&](auto masked_tag) {
-      constexpr bool MASKED = decltype(masked_tag)::value;
-      f32x16 sacc[QT][2];
+    f32x16 sacc[QT][2];
 #pragma unroll
-      for (int tq = 0; tq < QT; ++tq)
+    for (int tq = 0; tq < QT; ++tq)
 #pragma unroll
-        for (int c = 0; c < 2; ++c)
+      for (int c = 0; c < 2; ++c)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) sacc[tq][c][e] = 0.f;
-      // S^T = K Q^T; MFMA row r is key pi(r): a lane's 8 values per 16-key step are consecutive keys
+        for (int e = 0; e < 16; ++e) sacc[tq][c][e] = 0.f;
+    // S^T = K Q^T; MFMA row r is key pi(r): a lane's 8 values per 16-key step are consecutive keys
 #pragma unroll
-      for (int s = 0; s < KS; ++s)
+    for (int s = 0; s < KS; ++s)
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
-          const V8 kf = frag_rows<T, DH>(ks, c * 32 + pi_row(col), 2 * s + hf);
+      for (int c = 0; c < 2; ++c) {
+        const V8 kf = frag_rows<T, DH>(ks, c * 32 + pi_row(col), 2 * s + hf);
 #pragma unroll
-          for (int tq = 0; tq < QT; ++tq) sacc[tq][c] = Mma<T>::run(kf, qf[tq][s], sacc[tq][c]);
-        }
-      TrFrag fr[2][DT];
-#pragma unroll
-      for (int j = 0; j < DT; ++j) tr_read<DH>(fr[0][j], vs, j * 32, 0, lane);
-      // online softmax per query (lane); element e of block c <-> key key0 + 32 c + 16 (e / 8) + 8 hf + e % 8.
-      // m_run is the reference the exponentials are taken against.  It follows the running maximum
-      // lazily: only when some query of the wavefront exceeds it by more than 2^8 are the sums and
-      // the accumulators rescaled (exact either way; until then p <= 256, far inside every format
-      // involved), which removes the rescaling from all but the first tiles of a row.
-      V8 pf[QT][4];
-#pragma unroll
-      for (int tq = 0; tq < QT; ++tq) {
-        const int q = past + wq0 + tq * 32 + col;
-        float mx = -INFINITY;
-#pragma unroll
-        for (int c = 0; c < 2; ++c)
-#pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            if (MASKED) {
-              const int key = key0 + c * 32 + 16 * (e >> 3) + 8 * hf + (e & 7);
-              if (key > q) sacc[tq][c][e] = -INFINITY;
-            }
-            mx = fmaxf(mx, sacc[tq][c][e]);
-          }
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
-        if (__builtin_amdgcn_ballot_w64(mx > m_run[tq] + 8.f) != 0) {
-          const float m_new = fmaxf(m_run[tq], mx);
-          const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run[tq] - m_new);
-          l_run[tq] *= alpha;
-          m_run[tq] = m_new;
-#pragma unroll
-          for (int j = 0; j < DT; ++j)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) oacc[tq][j][e] *= alpha;
-        }
-        const float m_ref = m_run[tq] == -INFINITY ? 0.f : m_run[tq];   // a row with no visible key yet
-        float rs = 0.f;
-#pragma unroll
-        for (int c = 0; c < 2; ++c)
-#pragma unroll
-          for (int g = 0; g < 2; ++g) {
-            V8 pv;
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-              const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[tq][c][g * 8 + i], scale_log2, -m_ref));
-              rs += pr;
-              pv[i] = from_f<T>(pr);
-            }
-            pf[tq][c * 2 + g] = pv;
-          }
-        l_run[tq] += rs;
+        for (int tq = 0; tq < QT; ++tq) sacc[tq][c] = Mma<T>::run(kf, qf[tq][s], sacc[tq][c]);
       }
-      // O^T += V^T P^T in four steps of 16 keys
+    TrFrag fr[2][DT];
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        tr_wait(fr[kk & 1]);
-        if (kk < 3) {
+    for (int j = 0; j < DT; ++j) tr_read<DH>(fr[0][j], vs, j * 32, 0, lane);
+    // online softmax per query (lane); element e of block c <-> key key0 + 32 c + 16 (e / 8) + 8 hf + e % 8.
+    // m_run is the reference the exponentials are taken against.  It follows the running maximum
+    // lazily: only when some query of the wavefront exceeds it by more than 2^8 are the sums and
+    // the accumulators rescaled (exact either way; until then p <= 256, far inside every format
+    // involved), which removes the rescaling from all but the first tiles of a row.
+    V8 pf[QT][4];
 #pragma unroll
-          for (int j = 0; j < DT; ++j) tr_read<DH>(fr[(kk + 1) & 1][j], vs, j * 32, (kk + 1) * 16, lane);
+    for (int tq = 0; tq < QT; ++tq) {
+      const int q = past + wq0 + tq * 32 + col;
+      float mx = -INFINITY;
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          if (MASKED) {
+            const int key = key0 + c * 32 + 16 * (e >> 3) + 8 * hf + (e & 7);
+            if (key > q) sacc[tq][c][e] = -INFINITY;
+          }
+          mx = fmaxf(mx, sacc[tq][c][e]);
         }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
+      if (__builtin_amdgcn_ballot_w64(mx > m_run[tq] + 8.f) != 0) {
+        const float m_new = fmaxf(m_run[tq], mx);
+        const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run[tq] - m_new);
+        l_run[tq] *= alpha;
+        m_run[tq] = m_new;
 #pragma unroll
-        for (int j = 0; j < DT; ++j) {
-          const V8 vf = tr_value<T>(fr[kk & 1][j]);
+        for (int j = 0; j < DT; ++j)
 #pragma unroll
-          for (int tq = 0; tq < QT; ++tq) oacc[tq][j] = Mma<T>::run(vf, pf[tq][kk], oacc[tq][j]);
-        }
+          for (int e = 0; e < 16; ++e) oacc[tq][j][e] *= alpha;
       }
-    };
-    // this wavefront's rows are past + wq0 .. + QT * 32 - 1: tiles entirely above its diagonal add
-    // nothing, tiles entirely below the first row's diagonal need no mask
-    if (key0 + KT - 1 <= past + wq0) tile_body(std::false_type{});
-    else if (key0 <= past + wq0 + QT * 32 - 1) tile_body(std::true_type{});
-    // tile t + 1 has landed when only the loads of tiles t + 2 .. t + NS - 1 are outstanding;
-    // after the barrier nobody reads tile t any more and its stage is refilled
+      const float m_ref = m_run[tq] == -INFINITY ? 0.f : m_run[tq];   // a row with no visible key yet
+      float rs = 0.f;
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int g = 0; g < 2; ++g) {
+          V8 pv;
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const float pr = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[tq][c][g * 8 + i], scale_log2, -m_ref));
+            rs += pr;
+            pv[i] = from_f<T>(pr);
+          }
+          pf[tq][c * 2 + g] = pv;
+        }
+      l_run[tq] += rs;
+    }
+    // O^T += V^T P^T in four steps of 16 keys
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      tr_wait(fr[kk & 1]);
+      if (kk < 3) {
+#pragma unroll
+        for (int j = 0; j < DT; ++j) tr_read<DH>(fr[(kk + 1) & 1][j], vs, j * 32, (kk + 1) * 16, lane);
+      }
+#pragma unroll
+      for (int j = 0; j < DT; ++j) {
+        const V8 vf = tr_value<T>(fr[kk & 1][j]);
+#pragma unroll
+        for (int tq = 0; tq < QT; ++tq) oacc[tq][j] = Mma<T>::run(vf, pf[tq][kk], oacc[tq][j]);
+      }
+    }
+  };
+  // tile t + 1 has landed when only the loads of tiles t + 2 .. t + NS - 1 are outstanding; after the
+  // barrier nobody reads tile t any more and its stage is refilled
+  auto ring_step = [&](int t) {
     asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"((NS - 2) * NLD) : "memory");
     __syncthreads();
     issue(t + NS);
+  };
+  // This wavefront's rows are past + wq0 .. + QT * 32 - 1.  Tiles entirely below the first row's diagonal
+  // need no mask (first loop), the rest are masked, and tiles entirely above the last row's diagonal add
+  // nothing.  The two loops together make nt trips in every wavefront, so the barriers match.
+  const int t_plain = min(nt, max(0, (past + wq0 + 1) / KT));
+  int t = 0;
+  for (; t < t_plain; ++t) {
+    tile_body(std::false_type{}, t);
+    ring_step(t);
+  }
+  for (; t < nt; ++t) {
+    if (t * KT <= past + wq0 + QT * 32 - 1) tile_body(std::true_type{}, t);
+    ring_step(t);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // no direct-to-LDS write may outlive the workgroup
 
