@@ -235,8 +235,6 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
   b_base += kt0 * b_step;
   issue_tile<BM>(a_base, a_off, smem, wave);
   issue_tile<BN>(b_base, b_off, smem + A_BYTES, wave);
-  __builtin_amdgcn_s_waitcnt(0);
-  __syncthreads();
 
   // Software pipeline of one k tile (4 sub-steps of 16 k): while the MFMAs of a sub-step run, the
   // fragments of the next one are read from LDS, and during the first LDKS sub-steps the next
@@ -251,6 +249,17 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
   constexpr int RCH = GRP > 2 ? GRP * 3 / 4 : 1;  // chunks that carry fragment reads (the rest cover their latency)
   constexpr int NLD = (BM + BN) / 32;    // direct-to-LDS loads per tile and wavefront
   constexpr int LDKS = 2;                // k sub-steps over which they are issued
+  constexpr int LD_FIRST = 3;            // the first of them: sub-step 3 is the first after the barrier that frees a buffer
+  if (LD_FIRST > 0) {
+    // what sub-steps LD_FIRST .. 3 of the tile before the first would have issued
+    const int t1 = nk > 1 ? 1 : 0;
+#pragma unroll
+    for (int l = 0; l < (4 - LD_FIRST) * NLD / LDKS; ++l)
+      issue_one<BM, BN>(l, a_base + t1 * a_step, a_off, b_base + t1 * b_step, b_off, smem + BUF_BYTES,
+                        smem + BUF_BYTES + A_BYTES, wave);
+  }
+  __builtin_amdgcn_s_waitcnt(0);
+  __syncthreads();
   Frag<T, AK> fa[2][TI];
   Frag<T, BK> fb[2][TJ];
 #pragma unroll
@@ -264,10 +273,12 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
     const char* lb = la + A_BYTES;
     char* na = smem + (cur ^ 1) * BUF_BYTES;
     char* nb = na + A_BYTES;
-    // the tile after the last is the last again: fetched, never multiplied
-    const int tn = kt + 1 < nk ? kt + 1 : kt;
-    const char* ga = a_base + tn * a_step;
-    const char* gb = b_base + tn * b_step;
+    // tiles after the last are the last again: fetched, never multiplied
+    const int t1 = min(kt + 1, nk - 1), t2 = min(kt + 2, nk - 1);
+    const char* ga1 = a_base + t1 * a_step;
+    const char* gb1 = b_base + t1 * b_step;
+    const char* ga2 = a_base + t2 * a_step;
+    const char* gb2 = b_base + t2 * b_step;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const int c = ks & 1;
@@ -297,11 +308,16 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
           if (r < TI) read_frag<T, AK, BM>(fa[c ^ 1][r], ra, wm + r * 32, kn, lane);
           else read_frag<T, BK, BN>(fb[c ^ 1][r - TI], rb, wn + (r - TI) * 32, kn, lane);
         }
-        if (ks < LDKS) {
-          const int sl = ks * GRP + u;
+        // sub-steps LD_FIRST .. 3 come after this tile's barrier: the buffer being vacated takes the tile
+        // after the next; sub-steps before LD_FIRST complete the next tile in the other buffer
+        const int ph = (ks - LD_FIRST) & 3;
+        if (ph < LDKS) {
+          const bool ahead = LD_FIRST > 0 && ks >= LD_FIRST;
+          const int sl = ph * GRP + u;
 #pragma unroll
           for (int l = sl * NLD / (LDKS * GRP); l < (sl + 1) * NLD / (LDKS * GRP); ++l)
-            issue_one<BM, BN>(l, ga, a_off, gb, b_off, na, nb, wave);
+            issue_one<BM, BN>(l, ahead ? ga2 : ga1, a_off, ahead ? gb2 : gb1, b_off, ahead ? (char*)la : na,
+                              ahead ? (char*)lb : nb, wave);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
