@@ -73,6 +73,56 @@ def cpu_baseline(cfg, S):
                       f"({dt:.1f} s), time scaled x{scale:g} to the full stage"}
 
 
+def gemm_study():
+    """C[4096, 4096] = A B^T in fp16 for K = 1024 .. 8192: microseconds per launch for `lsk_gemm` and for
+    torch.matmul (the vendor library), first with all-zero operands (no data toggling, the clock stays up),
+    then with N(0,1) operands.  The slope over K is the cost of a 64-wide k tile, the intercept the fixed
+    cost of a launch (first loads, ramp, epilogue)."""
+    import torch
+    from paper_2507_21276_amd import binding as Bd
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    Bd.lib()
+
+    def timed(fn, iters=100, warm=10):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(iters):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / iters * 1e3
+
+    M = N = 4096
+    out = {}
+    for kind in ("zeros", "normal"):
+        rows = []
+        for K in (1024, 2048, 4096, 8192):
+            if kind == "zeros":
+                A = torch.zeros(M, K, device="cuda", dtype=torch.float16)
+                B = torch.zeros(N, K, device="cuda", dtype=torch.float16)
+            else:
+                g = torch.Generator(device="cuda").manual_seed(K)
+                A = torch.randn(M, K, device="cuda", generator=g).to(torch.float16)
+                B = torch.randn(N, K, device="cuda", generator=g).to(torch.float16)
+            C = torch.empty(M, N, device="cuda", dtype=torch.float16)
+            ours = timed(lambda: Bd.lsk_gemm(A, B, C, M=M, N=N, K=K))
+            lib = timed(lambda: torch.matmul(A, B.T, out=C))
+            rows.append((K, ours, lib))
+            print(f"{kind:6s} K={K:5d}: lsk_gemm {ours:7.1f} us ({2 * M * N * K / ours / 1e6:5.0f} TFLOP/s)   "
+                  f"torch.matmul {lib:7.1f} us ({2 * M * N * K / lib / 1e6:5.0f} TFLOP/s)", flush=True)
+        (k0, a0, b0), (k1, a1, b1) = rows[2], rows[3]
+        sa, sb = (a1 - a0) / (k1 - k0) * 64, (b1 - b0) / (k1 - k0) * 64
+        print(f"{kind:6s} per 64-wide k tile (K 4096 -> 8192): lsk_gemm {sa:.3f} us, torch.matmul {sb:.3f} us; "
+              f"fixed per launch: lsk_gemm {a0 - sa * k0 / 64:.1f} us, torch.matmul {b0 - sb * k0 / 64:.1f} us", flush=True)
+        out[kind] = {"k_tile_us": [sa, sb], "fixed_us": [a0 - sa * k0 / 64, b0 - sb * k0 / 64]}
+    print(json.dumps({"gemm_study": out}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -88,7 +138,12 @@ def main():
                     help="comma list of the legs that make up a step (profiling aid; the default is the full "
                          "step; 'gemms' = the 12 GEMM launches of one block on their own; 'calib' = a 256 MiB copy kernel "
                          "used to scale the HBM byte counters)")
+    ap.add_argument("--gemm-study", action="store_true",
+                    help="instead of the step: time the GEMM kernel over contraction lengths with all-zero and with "
+                         "N(0,1) operands (the chip clocks down on real data) beside torch.matmul, print a table and exit")
     args = ap.parse_args()
+    if args.gemm_study:
+        return gemm_study()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (one pipeline stage on one MI355X); "
                  "run with --gpus 1")
