@@ -350,6 +350,33 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
   const float alpha = g.alpha ? *g.alpha : 1.f;
   __syncthreads();   // every wavefront is done with the operand tiles
   char* stg = smem + wave * REGION;
+  // A lane's columns are the same for all of its rows: its bias values are fetched once, outside the
+  // staging loops (a fetch with a type switch inside them, once per element, made the epilogue some
+  // thousands of instructions long and cost 3 - 6 us per launch even without a bias).
+  float bv[TJ][4][4];
+#pragma unroll
+  for (int j = 0; j < TJ; ++j)
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) bv[j][q][e] = 0.f;
+  if ((MODE == 0 || MODE == 1) && g.bias) {
+    const int nb = n0 + wn + 4 * hf;
+    auto fetch = [&](auto* b) {
+#pragma unroll
+      for (int j = 0; j < TJ; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const int n = nb + j * 32 + 8 * q + e;
+            bv[j][q][e] = (float)b[n < g.N ? n : g.N - 1];
+          }
+    };
+    if (g.bias_dtype == LS_F32) fetch((const float*)g.bias);
+    else if (g.bias_dtype == LS_BF16) fetch((const bf16_t*)g.bias);
+    else fetch((const f16_t*)g.bias);
+  }
 #pragma unroll
   for (int pass = 0; pass < NPASS; ++pass) {
 #pragma unroll
@@ -398,11 +425,9 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
             f32x4 v;
 #pragma unroll
             for (int e = 0; e < 4; ++e) v[e] = acc[i][j][4 * q + e] * alpha;
-            if (MODE != 2 && g.bias) {
-              const int n = n0 + wn + j * 32 + 8 * q + 4 * hf;
+            if constexpr (MODE == 0 || MODE == 1) {
 #pragma unroll
-              for (int e = 0; e < 4; ++e)
-                if (n + e < g.N) v[e] += load_as_f(g.bias, n + e, g.bias_dtype);
+              for (int e = 0; e < 4; ++e) v[e] += bv[j][q][e];
             }
             if constexpr (ESZ == 2) {
               V4 o;
