@@ -114,6 +114,14 @@ def test_no_instruction_touches_a_register_with_an_assembly_issued_lds_read_in_f
     # a planted hazard is found (the checker itself works)
     planted = "_Zk:\n\tds_read_b64_tr_b16 v[4:5], v9\n\tv_mov_b32_e32 v4, 0\n\ts_waitcnt lgkmcnt(0)\n\ts_endpgm\n"
     assert isa_lint.scan(planted) == {"_Zk": [(2, "v_mov_b32_e32 v4, 0")]}
+    # a counted wait retires the older read only
+    counted = ("_Zk:\n\tds_read_b128 v[4:7], v9\n\tds_read_b128 v[10:13], v9\n\ts_waitcnt lgkmcnt(1)\n"
+               "\tv_mov_b32_e32 v0, v4\n\tv_mov_b32_e32 v1, v10\n\ts_waitcnt lgkmcnt(0)\n\ts_endpgm\n")
+    assert isa_lint.scan(counted) == {"_Zk": [(5, "v_mov_b32_e32 v1, v10")]}
+    # a read issued late in a loop body and used at the top of the next iteration before any wait
+    looped = ("_Zk:\n.LBB0_1:\n\tv_mov_b32_e32 v0, v4\n\ts_waitcnt lgkmcnt(0)\n\tds_read_b128 v[4:7], v9\n"
+              "\ts_cbranch_scc0 .LBB0_1\n\ts_waitcnt lgkmcnt(0)\n\ts_endpgm\n")
+    assert isa_lint.scan(looped) == {"_Zk": [(2, "v_mov_b32_e32 v0, v4")]}
     for src in ("gemm_dma.hip", "attention_mfma.hip"):
         out = tmp_path / (src + ".s")
         subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
