@@ -305,7 +305,7 @@ def main():
                 "frac": gemm_tflops / PEAK_MFMA_TFLOPS, "avg_launch_ms": ms_gemms / 12,
                 "flop_per_launch": flop_block / 12,
                 "traffic": traffic.get("gemm_dma_kernel_bytes_per_launch"),
-                "peak_measured_gaussian_operands": 1625.0}
+                "peak_measured_gaussian_operands": 1650.0}
     log(f"GEMMs of one block: {ms_gemms:.2f} ms -> {gemm_tflops:.0f} TFLOP/s")
 
     # ---- decode roofline: weights once + the KV of every cached token ---------------------------
