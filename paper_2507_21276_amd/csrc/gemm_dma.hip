@@ -94,15 +94,24 @@ __device__ __forceinline__ void tile_offsets(uint32_t (&off)[ROWS / 32], long ld
   }
 }
 
+// One direct-to-LDS wave load in the scalar-base form: address = uniform 64-bit base + per-lane 32-bit
+// offset, LDS destination in M0.  Issued from assembly: the builtin takes a flat pointer, which the
+// compiler forms with a 64-bit vector add per load (1 % of the GEMM leg).  The compiler therefore does not
+// count these loads: every wait for them in this file is explicit (s_waitcnt with vmcnt(0)).
+__device__ __forceinline__ void dma_load(const char* base, uint32_t off, const char* lds_dst) {
+  const uint32_t l = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)lds_dst;
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               :
+               : "s"(l), "v"(off), "s"(base)
+               : "memory", "m0");
+}
+
 template <int ROWS>
 __device__ __forceinline__ void issue_tile(const char* tile_base, const uint32_t (&off)[ROWS / 32], char* lds_tile,
                                            int wave) {
   constexpr int NL = ROWS / 32;
 #pragma unroll
-  for (int j = 0; j < NL; ++j)
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(tile_base + off[j]),
-                                     (__attribute__((address_space(3))) void*)(lds_tile + (wave * NL + j) * 1024),
-                                     16, 0, 0);
+  for (int j = 0; j < NL; ++j) dma_load(tile_base, off[j], lds_tile + (wave * NL + j) * 1024);
 }
 
 // load `l` (0 .. (BM + BN) / 32 - 1) of a wavefront's share of the A and B tiles
@@ -111,14 +120,8 @@ __device__ __forceinline__ void issue_one(int l, const char* a_tile, const uint3
                                           const char* b_tile, const uint32_t (&b_off)[BN / 32], char* lds_a,
                                           char* lds_b, int wave) {
   constexpr int NA = BM / 32, NB = BN / 32;
-  if (l < NA)
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(a_tile + a_off[l]),
-                                     (__attribute__((address_space(3))) void*)(lds_a + (wave * NA + l) * 1024),
-                                     16, 0, 0);
-  else
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(b_tile + b_off[l - NA]),
-                                     (__attribute__((address_space(3))) void*)(lds_b + (wave * NB + l - NA) * 1024),
-                                     16, 0, 0);
+  if (l < NA) dma_load(a_tile, a_off[l], lds_a + (wave * NA + l) * 1024);
+  else dma_load(b_tile, b_off[l - NA], lds_b + (wave * NB + l - NA) * 1024);
 }
 
 // One operand fragment: 8 k for 32 rows of an operand tile.
