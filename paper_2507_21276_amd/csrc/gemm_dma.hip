@@ -179,6 +179,28 @@ __device__ __forceinline__ typename Mf<T>::V8 frag_value(const Frag<T, KMAJOR>& 
   }
 }
 
+// Where in a k sub-step of NM MFMAs the other instructions go: one LDS fragment read or one
+// direct-to-LDS load in the gap after an MFMA, instead of a chunk's reads and load together after
+// every second MFMA (1.1 % on the GEMM leg).  Reads take the gaps 0, 1, 3, 4, 6, 7, ... of the first
+// three quarters of the sub-step (the last quarter covers their latency), loads take the gaps in
+// between and the last quarter; with more loads than free gaps they share gaps from the first on.
+template <int NM, int NF, int LPK>
+struct GapPlan {
+  int read_gap[NF];
+  int load_gap[LPK > 0 ? LPK : 1];
+  constexpr GapPlan() : read_gap{}, load_gap{} {
+    const int span = NM * 3 / 4 > 0 ? NM * 3 / 4 : 1;
+    for (int r = 0; r < NF; ++r) read_gap[r] = r * span / NF;
+    int cnt = 0;
+    for (int g = 0; g < NM && cnt < LPK; ++g) {
+      bool taken = false;
+      for (int r = 0; r < NF; ++r) taken = taken || read_gap[r] == g;
+      if (!taken) load_gap[cnt++] = g;
+    }
+    for (int l = cnt; l < LPK; ++l) load_gap[l] = (l - cnt) % NM;
+  }
+};
+
 typedef f32x4 __attribute__((may_alias)) f32x4_a;
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 typedef u32x2_t __attribute__((may_alias)) u32x2_a;
@@ -240,19 +262,20 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
   issue_tile<BN>(b_base, b_off, smem + A_BYTES, wave);
 
   // Software pipeline of one k tile (4 sub-steps of 16 k): while the MFMAs of a sub-step run, the
-  // fragments of the next one are read from LDS, and during the first LDKS sub-steps the next
-  // tile's direct-to-LDS loads are issued, a few per chunk of two MFMAs (a burst would stall the
-  // wavefront, and with it the matrix pipe, on the address path).  The workgroup barrier sits
+  // fragments of the next one are read from LDS, and during LDKS sub-steps direct-to-LDS loads are
+  // issued, at most one memory instruction between two MFMAs (a burst would stall the wavefront,
+  // and with it the matrix pipe, on the address path).  The workgroup barrier sits
   // before the last sub-step: by then every wavefront holds its last fragments of the current
   // tile in registers, so the fragments read during the last sub-step come from the next tile.
-  // Chunks are fenced with scheduling barriers: the source order below is the issue order.
+  // Every MFMA and what follows it are fenced with scheduling barriers: the source order below is the issue order.
   constexpr int NM = TI * TJ;            // MFMAs per k sub-step
-  constexpr int GRP = NM / 2;            // chunks of two MFMAs
   constexpr int NF = TI + TJ;            // fragments per k sub-step
-  constexpr int RCH = GRP > 2 ? GRP * 3 / 4 : 1;  // chunks that carry fragment reads (the rest cover their latency)
   constexpr int NLD = (BM + BN) / 32;    // direct-to-LDS loads per tile and wavefront
   constexpr int LDKS = 2;                // k sub-steps over which they are issued
   constexpr int LD_FIRST = 3;            // the first of them: sub-step 3 is the first after the barrier that frees a buffer
+  constexpr int LPK = NLD / LDKS;        // loads per sub-step
+  static_assert(NLD % LDKS == 0, "loads per sub-step");
+  constexpr GapPlan<NM, NF, LPK> plan{};
   if (LD_FIRST > 0) {
     // what sub-steps LD_FIRST .. 3 of the tile before the first would have issued
     const int t1 = nk > 1 ? 1 : 0;
@@ -300,27 +323,27 @@ __global__ __launch_bounds__(256) void gemm_dma_kernel(DmaArgs g) {
       const char* rb = ks < 3 ? lb : nb;
       const int kn = (ks + 1) & 3;
       __builtin_amdgcn_sched_barrier(0);
+      // sub-steps LD_FIRST .. 3 come after this tile's barrier: the buffer being vacated takes the tile
+      // after the next; sub-steps before LD_FIRST complete the next tile in the other buffer
+      const int ph = (ks - LD_FIRST) & 3;
+      const bool ahead = LD_FIRST > 0 && ks >= LD_FIRST;
 #pragma unroll
-      for (int u = 0; u < GRP; ++u) {
-#pragma unroll
-        for (int m = 2 * u; m < 2 * u + 2; ++m) acc[m / TJ][m % TJ] = Mf<T>::run(vb[m % TJ], va[m / TJ], acc[m / TJ][m % TJ]);
-        __builtin_amdgcn_sched_barrier(0);   // MFMAs first: the memory operations issue in their shadow
+      for (int m = 0; m < NM; ++m) {
+        acc[m / TJ][m % TJ] = Mf<T>::run(vb[m % TJ], va[m / TJ], acc[m / TJ][m % TJ]);
+        __builtin_amdgcn_sched_barrier(0);   // the MFMA first: what follows issues in its shadow
 #pragma unroll
         for (int r = 0; r < NF; ++r) {
-          if (r * RCH / NF != u) continue;
+          if (plan.read_gap[r] != m) continue;
           if (r < TI) read_frag<T, AK, BM>(fa[c ^ 1][r], ra, wm + r * 32, kn, lane);
           else read_frag<T, BK, BN>(fb[c ^ 1][r - TI], rb, wn + (r - TI) * 32, kn, lane);
         }
-        // sub-steps LD_FIRST .. 3 come after this tile's barrier: the buffer being vacated takes the tile
-        // after the next; sub-steps before LD_FIRST complete the next tile in the other buffer
-        const int ph = (ks - LD_FIRST) & 3;
         if (ph < LDKS) {
-          const bool ahead = LD_FIRST > 0 && ks >= LD_FIRST;
-          const int sl = ph * GRP + u;
 #pragma unroll
-          for (int l = sl * NLD / (LDKS * GRP); l < (sl + 1) * NLD / (LDKS * GRP); ++l)
-            issue_one<BM, BN>(l, ahead ? ga2 : ga1, a_off, ahead ? gb2 : gb1, b_off, ahead ? (char*)la : na,
+          for (int l = 0; l < LPK; ++l) {
+            if (plan.load_gap[l] != m) continue;
+            issue_one<BM, BN>(ph * LPK + l, ahead ? ga2 : ga1, a_off, ahead ? gb2 : gb1, b_off, ahead ? (char*)la : na,
                               ahead ? (char*)lb : nb, wave);
+          }
         }
         __builtin_amdgcn_sched_barrier(0);
       }
