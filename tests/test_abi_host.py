@@ -122,7 +122,7 @@ def test_no_instruction_touches_a_register_with_an_assembly_issued_lds_read_in_f
     looped = ("_Zk:\n.LBB0_1:\n\tv_mov_b32_e32 v0, v4\n\ts_waitcnt lgkmcnt(0)\n\tds_read_b128 v[4:7], v9\n"
               "\ts_cbranch_scc0 .LBB0_1\n\ts_waitcnt lgkmcnt(0)\n\ts_endpgm\n")
     assert isa_lint.scan(looped) == {"_Zk": [(2, "v_mov_b32_e32 v0, v4")]}
-    for src in ("gemm_dma.hip", "attention_mfma.hip"):
+    for src in ("gemm_dma.hip", "gemm_dma16.hip", "attention_mfma.hip"):
         out = tmp_path / (src + ".s")
         subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
                         "-packed-fp32-ops", "-S", "--cuda-device-only", os.path.join(csrc, src), "-o", str(out)],
