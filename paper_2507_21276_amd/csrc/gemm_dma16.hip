@@ -284,6 +284,20 @@ __global__ __launch_bounds__(256) void gemm_dma16_kernel(DmaArgs g) {
     else if (g.bias_dtype == LS_BF16) fetch((const bf16_t*)g.bias);
     else fetch((const f16_t*)g.bias);
   }
+  // MODE 3: q or k section (uniform over the wavefront), and the table rows of this lane's row blocks
+  const bool rot = MODE == 3 && n0 + wn < g.rope_cols;
+  f32x4 cs_cur[TJ / 2][2], cs_nxt[TJ / 2][2];
+#pragma unroll
+  for (int j = 0; j < TJ / 2; ++j) cs_cur[j][0] = cs_cur[j][1] = cs_nxt[j][0] = cs_nxt[j][1] = f32x4{1.f, 0.f, 1.f, 0.f};
+  auto rope_fetch = [&](int i, f32x4 (&cs)[TJ / 2][2]) {
+    const int m = min(m0 + wm + i * 16 + row_in, g.M - 1);   // rows past the edge are staged, never stored
+    const float* tab = g.rope_table + (long)g.rope_pos[m] * 128 + 8 * cg;   // 64 (cos, sin) pairs per position
+#pragma unroll
+    for (int j = 0; j < TJ / 2; ++j) {
+      cs[j][0] = *(const f32x4*)(tab + j * 32);       // pairs 16 j + 4 cg + 0, 1
+      cs[j][1] = *(const f32x4*)(tab + j * 32 + 4);   // pairs 16 j + 4 cg + 2, 3
+    }
+  };
 #pragma unroll
   for (int pass = 0; pass < NPASS; ++pass) {
 #pragma unroll
@@ -293,33 +307,32 @@ __global__ __launch_bounds__(256) void gemm_dma16_kernel(DmaArgs g) {
       char* srow = stg + r * ROWB;
       const int sw = r & (CPR - 1);
       if constexpr (MODE == 3) {
-        const int m = min(m0 + wm + i * 16 + row_in, g.M - 1);   // rows past the edge are staged, never stored
-        const bool rot = n0 + wn < g.rope_cols;   // q or k section: uniform over the wavefront
-        const float* tab = g.rope_table + (long)g.rope_pos[m] * 128 + 8 * cg;   // 64 (cos, sin) pairs
+        // (cos, sin) of this lane's four column pairs in each of the TJ / 2 block pairs; the values for the
+        // next row block are fetched while this one is rotated (a fetch per block pair, each behind its own
+        // branch and wait, cost 50 us per tile)
+        if (rot) {
+          if (ii == 0) rope_fetch(i, cs_cur);
+          if (ii + 1 < TIP) rope_fetch(i + 1, cs_nxt);
+        }
 #pragma unroll
         for (int j = 0; j < TJ / 2; ++j) {
           V4 lo, hi;
-          if (rot) {
-            const f32x4 cs0 = *(const f32x4*)(tab + j * 32);       // pairs 16 j + 4 cg + 0, 1
-            const f32x4 cs1 = *(const f32x4*)(tab + j * 32 + 4);   // pairs 16 j + 4 cg + 2, 3
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              const float c = e < 2 ? cs0[2 * e] : cs1[2 * (e - 2)];
-              const float sn = e < 2 ? cs0[2 * e + 1] : cs1[2 * (e - 2) + 1];
-              const float a = acc[i][j][e], bb = acc[i][j + TJ / 2][e];
-              lo[e] = from_f<T>(a * c - bb * sn);
-              hi[e] = from_f<T>(bb * c + a * sn);
-            }
-          } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-              lo[e] = from_f<T>(acc[i][j][e]);
-              hi[e] = from_f<T>(acc[i][j + TJ / 2][e]);
-            }
+          for (int e = 0; e < 4; ++e) {
+            const float c = e < 2 ? cs_cur[j][0][2 * e] : cs_cur[j][1][2 * (e - 2)];
+            const float sn = e < 2 ? cs_cur[j][0][2 * e + 1] : cs_cur[j][1][2 * (e - 2) + 1];
+            const float a = acc[i][j][e], bb = acc[i][j + TJ / 2][e];
+            lo[e] = from_f<T>(rot ? a * c - bb * sn : a);
+            hi[e] = from_f<T>(rot ? bb * c + a * sn : bb);
           }
           // columns 16 j + 4 cg .. + 3: chunk 2 j + (cg >> 1), half cg & 1
           *(u32x2_a*)(srow + (((2 * j + (cg >> 1)) ^ sw) * 16) + (cg & 1) * 8) = __builtin_bit_cast(u32x2_t, lo);
           *(u32x2_a*)(srow + (((2 * (j + TJ / 2) + (cg >> 1)) ^ sw) * 16) + (cg & 1) * 8) = __builtin_bit_cast(u32x2_t, hi);
+        }
+#pragma unroll
+        for (int j = 0; j < TJ / 2; ++j) {
+          cs_cur[j][0] = cs_nxt[j][0];
+          cs_cur[j][1] = cs_nxt[j][1];
         }
       } else {
 #pragma unroll
@@ -379,21 +392,10 @@ ls_status launch16(DmaArgs g, hipStream_t st) {
   return LS_OK;
 }
 
-// the rotary epilogue of this kernel measured 37 % slower than the 32x32x16 kernel's (cause not found yet):
-// off unless LS_GEMM16_ROPE=1
-bool gemm16_rope_enabled() {
-  static const bool on = [] {
-    const char* e = std::getenv("LS_GEMM16_ROPE");
-    return e && std::strcmp(e, "1") == 0;
-  }();
-  return on;
-}
-
 template <class T>
 ls_status dispatch16(const DmaArgs& g, hipStream_t st) {
   if (g.rope_table) {
-    if (g.a_kmajor && g.b_kmajor && g.c_dtype != LS_F32 && !g.bias && gemm16_rope_enabled())
-      return launch16<T, true, true, 3>(g, st);
+    if (g.a_kmajor && g.b_kmajor && g.c_dtype != LS_F32 && !g.bias) return launch16<T, true, true, 3>(g, st);
     return LS_ESTATE;
   }
   const int mode = g.c_dtype != LS_F32 ? 0 : (g.resid ? 1 : 2);
