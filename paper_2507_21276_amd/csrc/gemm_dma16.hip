@@ -55,7 +55,9 @@ __device__ __forceinline__ void read_frag16(Frag16<T, KMAJOR>& f, const char* ld
     const int i16 = lane & 15, a = i16 >> 2, j4 = i16 & 3;
     const int nb = r0 + 4 * j4;     // first of the 4 rows this lane addresses
     const int kb = kh * 32 + 8 * kg;
-    const int phys = (nb >> 3) ^ (4 * a);
+    // chunk permutation of the tile: 4 (k & 3) as in the 32x32x16 kernel, and 2 ((k >> 3) & 1) = 2 (kg & 1),
+    // which keeps the two 16-lane groups of a 32-lane access (k and k + 8) on different banks
+    const int phys = (nb >> 3) ^ (4 * a) ^ (2 * (kg & 1));
     const char* p0 = lds_tile + (kb + a) * KROW + phys * 16 + ((nb >> 2) & 1) * 8;
     const uint32_t addr = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)p0;
     asm volatile("ds_read_b64_tr_b16 %0, %1" : "=v"(f.lo) : "v"(addr) : "memory");
@@ -143,8 +145,8 @@ __global__ __launch_bounds__(256) void gemm_dma16_kernel(DmaArgs g) {
   const long a_step = (AK ? (long)TK : (long)TK * g.lda) * 2;
   const long b_step = (BK ? (long)TK : (long)TK * g.ldb) * 2;
   uint32_t a_off[BM / 32], b_off[BN / 32];
-  tile_offsets<AK, BM>(a_off, g.lda, m0, g.M, wave, lane);
-  tile_offsets<BK, BN>(b_off, g.ldb, n0, g.N, wave, lane);
+  tile_offsets<AK, BM, true>(a_off, g.lda, m0, g.M, wave, lane);
+  tile_offsets<BK, BN, true>(b_off, g.ldb, n0, g.N, wave, lane);
 
   f32x4 acc[TI][TJ];
 #pragma unroll
@@ -408,7 +410,7 @@ ls_status dispatch16(const DmaArgs& g, hipStream_t st) {
   if (g.a_kmajor && !g.b_kmajor && mode == 2) return launch16<T, true, false, 2>(g, st);
   // Both operands k-strided (weight gradients): left to the 32x32x16 kernel.  Every fragment is two
   // transposing reads there, 24 in a quarter of 32 short MFMAs, and this kernel measured 8 - 10 % slower on
-  // those shapes (faster by 5 - 12 % on the other two layouts).
+  // those shapes (faster by 5 - 12 % on the other two layouts), also with the LDS reads free of bank conflicts.
   return LS_ESTATE;
 }
 

@@ -28,7 +28,9 @@ constexpr int TK = 64;  // k extent of a tile; a tile of ROWS rows is ROWS * 128
 // Direct-to-LDS loads of one operand tile of ROWS rows (256 or 128): ROWS / 32
 // wave loads per wavefront.  The per-lane byte offsets inside the tile are fixed
 // for the whole k loop (`off`, computed once); only the uniform tile base moves.
-template <bool KMAJOR, int ROWS>
+// K8: the chunk index of a k-strided tile is also XOR-permuted with 2 * ((k >> 3) & 1) (the 16x16x32 kernel,
+// whose transposing reads put k and k + 8 into the same 32 lanes)
+template <bool KMAJOR, int ROWS, bool K8 = false>
 __device__ __forceinline__ void tile_offsets(uint32_t (&off)[ROWS / 32], long ld, int row0, int nrows, int wave,
                                              int lane) {
   constexpr int NL = ROWS / 32;         // wave loads per wavefront
@@ -44,7 +46,7 @@ __device__ __forceinline__ void tile_offsets(uint32_t (&off)[ROWS / 32], long ld
       off[j] = (uint32_t)(((long)(gr - row0) * ld + kc * 8) * 2);
     } else {
       const int krow = q * (64 / LPR) + lane / LPR;
-      const int cl = (lane % LPR) ^ (4 * (krow & 3));
+      const int cl = (lane % LPR) ^ (4 * (krow & 3)) ^ (K8 ? 2 * ((krow >> 3) & 1) : 0);
       int gr = row0 + cl * 8;
       gr = gr + 8 <= nrows ? gr : nrows - 8;
       off[j] = (uint32_t)(((long)krow * ld + (gr - row0)) * 2);
