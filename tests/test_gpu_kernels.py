@@ -129,7 +129,8 @@ def test_gemm_full_size_launch_configuration_on_sampled_outputs(name):
     256 x 256 tile kernel with direct-to-LDS loads and all three operand
     layouts): sampled rows of each result against float64 dot products."""
     T, d, F = 4096, 4096, 11008
-    rows = [0, 1, 255, 256, 2047, 3000, 4095]
+    # one row of every 16-row block of a 256-row tile (the blocks of the 16x16x32 kernel), and the edges
+    rows = sorted(set(list(range(3, 256, 16)) + [0, 1, 255, 256, 2047, 3000, 4095]))
     dt = DT[name]
     X = S.normal_torch(11, "X", (T, d), 1.0, "cuda", dt)
     dY = S.normal_torch(11, "dY", (T, 2 * F), 1.0, "cuda", dt)
