@@ -93,23 +93,24 @@ __device__ __forceinline__ typename Mf16<T>::V8 frag_value16(const Frag16<T, KMA
 
 // Gaps (after MFMA m of a quarter of NM) for the NF fragment reads and the LPK loads of a quarter.  A
 // 16x16x32 MFMA is half as long as a 32x32x16 one, and the compute unit's load path takes a wave load
-// per 16 cycles: the loads are spread evenly over the quarter (one per NM / LPK MFMAs), stepping aside
-// where a read sits; the reads are spread over the first seven eighths.
+// per 16 cycles: the loads are spread evenly over the quarter (one per NM / LPK MFMAs, from the first gap
+// on), stepping aside where a read sits; the reads are spread over the first three quarters (this
+// placement measured 0.3 - 0.5 % better than reads over seven eighths and loads from the third gap on).
 template <int NM, int NF, int LPK>
 struct SpreadPlan {
   int read_at[NM];   // fragment read in the gap after MFMA m, or -1
   int load_at[NM];   // load issued in that gap, or -1
   constexpr SpreadPlan() : read_at{}, load_at{} {
     for (int m = 0; m < NM; ++m) read_at[m] = load_at[m] = -1;
-    for (int r = 0; r < NF; ++r) read_at[r * (NM * 7 / 8) / NF] = r;
+    for (int r = 0; r < NF; ++r) read_at[r * (NM * 3 / 4) / NF] = r;
     for (int l = 0; l < LPK; ++l) {
-      int g = l * NM / LPK + NM / LPK / 2;
+      int g = l * NM / LPK;
       while (read_at[g] >= 0 || load_at[g] >= 0) g = (g + 1) % NM;
       load_at[g] = l;
     }
   }
 };
-static_assert(32 * 7 / 8 >= 12, "one read per gap");
+static_assert(32 * 3 / 4 >= 12, "one read per gap");
 
 // MODE 0: C (16-bit) = acc + bias;  1: C (fp32) = resid + acc + bias;  2: C (fp32) (+)= acc;
 // MODE 3: as 0 without bias, and the half-split rotary embedding (head_dim 128) applied to the
