@@ -71,6 +71,37 @@ def test_gemm_input_and_weight_gradient_layouts(name, T, N, K):
 
 
 @pytest.mark.parametrize("name", ["bf16", "f16"])
+@pytest.mark.parametrize("K", [64, 192])
+def test_gemm_large_tile_kernels_with_ragged_edges(name, K):
+    """More than 160 tiles of 256 x 256 with partial tiles on both edges and one or three k tiles: the
+    16x16x32 kernel (forward and input-gradient layouts) and the 32x32x16 kernel (weight gradient),
+    every element against float64."""
+    M, N = 4104, 2568   # 17 x 11 = 187 tiles, 8 rows and 8 columns in the last ones
+    A = q(S.normal(5, "A", (M, K)), name)
+    W = q(S.normal(5, "W", (N, K), 0.05), name)
+    bias = q(S.normal(5, "b", (N,)), "bf16")
+    R = S.normal(5, "R", (M, N))
+    Ad, Wd = dev(A, DT[name]), dev(W, DT[name])
+    ref = A.astype(np.float64) @ W.astype(np.float64).T
+    out = torch.empty(M, N, dtype=torch.float32, device="cuda")
+    Bd.lsk_gemm(Ad, Wd, out, M=M, N=N, K=K, bias=dev(bias, torch.bfloat16), resid=dev(R, torch.float32))
+    assert_close(host(out), ref + bias + R, 1e-5, "forward, bias and residual")
+    out16 = torch.empty(M, N, dtype=DT[name], device="cuda")
+    Bd.lsk_gemm(Ad, Wd, out16, M=M, N=N, K=K, bias=dev(bias, torch.bfloat16))
+    assert_close(host(out16), ref + bias, otol(name, ref + bias), "forward, 16-bit result")
+    # input-gradient layout: C[M, N] = A[M, K] B[K, N], B k-strided
+    Bk = q(S.normal(5, "Bk", (K, N), 0.05), name)
+    out16.zero_()
+    Bd.lsk_gemm(Ad, dev(Bk, DT[name]), out16, M=M, N=N, K=K, a_kmajor=True, b_kmajor=False, lda=K, ldb=N)
+    r2 = A.astype(np.float64) @ Bk.astype(np.float64)
+    assert_close(host(out16), r2, otol(name, r2), "input-gradient layout")
+    # weight-gradient layout: C[M, N] = At[K, M]^T Bk[K, N], both k-strided, fp32 result
+    At = q(S.normal(5, "At", (K, M)), name)
+    Bd.lsk_gemm(dev(At, DT[name]), dev(Bk, DT[name]), out, M=M, N=N, K=K, a_kmajor=False, b_kmajor=False, lda=M, ldb=N)
+    assert_close(host(out), At.astype(np.float64).T @ Bk.astype(np.float64), 1e-5, "weight-gradient layout")
+
+
+@pytest.mark.parametrize("name", ["bf16", "f16"])
 @pytest.mark.parametrize("M,N,K", [(64, 1048, 4096), (4, 72, 136), (33, 264, 11008), (128, 520, 768), (1, 64, 32)])
 @pytest.mark.parametrize("split", [True, False])
 def test_gemm_skinny_weight_streaming(name, M, N, K, split):
