@@ -300,7 +300,7 @@ def main():
     ms_gemms = time_events(torch, gemms, 5)
     flop_block = 3.0 * T * (8.0 * d * d + 6.0 * d * F)       # fwd + dX + dW of one block
     gemm_tflops = flop_block / (ms_gemms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "gemm_dma_kernel (12 launches per block: 4 fwd, 4 dX, 4 dW)",
+    roofline = {"bound": "mfma", "kernel": "gemm_dma16_kernel (4 fwd, 4 dX) + gemm_dma_kernel<256,256> (4 dW): 12 launches per block",
                 "achieved": gemm_tflops, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
                 "frac": gemm_tflops / PEAK_MFMA_TFLOPS, "avg_launch_ms": ms_gemms / 12,
                 "flop_per_launch": flop_block / 12,
