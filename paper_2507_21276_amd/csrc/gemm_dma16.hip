@@ -112,7 +112,7 @@ struct SpreadPlan {
 };
 static_assert(32 * 3 / 4 >= 12, "one read per gap");
 
-// MODE 0: C (16-bit) = acc + bias;  1: C (fp32) = resid + acc + bias;  2: C (fp32) (+)= acc;
+// MODE 0: C (16-bit) = acc + bias;  1: C (fp32) = resid + acc + bias;  2: C (fp32) = acc;  4: C (fp32) += acc;
 // MODE 3: as 0 without bias, and the half-split rotary embedding (head_dim 128) applied to the
 //         columns below rope_cols: a wavefront's 128 columns are one head, so the pair
 //         (c, c + 64) sits in accumulator blocks j and j + 4 of the same lane
@@ -303,6 +303,21 @@ __global__ __launch_bounds__(256) void gemm_dma16_kernel(DmaArgs g) {
   };
 #pragma unroll
   for (int pass = 0; pass < NPASS; ++pass) {
+    // accumulating output: what the pass adds to is fetched first, all of it at once, and arrives while the
+    // accumulators are staged (a load per store, each behind its own branch and wait, made the launch a third longer)
+    constexpr int NOUT = ROWS_P * CPR / 64;
+    f32x4 c_old[MODE == 4 ? NOUT : 1];
+    if constexpr (MODE == 4) {
+      {
+#pragma unroll
+        for (int it = 0; it < NOUT; ++it) {
+          const int idx = it * 64 + lane;
+          const int m = m0 + wm + pass * ROWS_P + idx / CPR;
+          const int n = n0 + wn + (idx % CPR) * (16 / ESZ);
+          c_old[it] = m < g.M && n < g.N ? *(const f32x4*)((const float*)g.C + (long)m * g.ldc + n) : f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+      }
+    }
 #pragma unroll
     for (int ii = 0; ii < TIP; ++ii) {
       const int i = pass * TIP + ii;
@@ -372,8 +387,7 @@ __global__ __launch_bounds__(256) void gemm_dma16_kernel(DmaArgs g) {
       } else if constexpr (MODE == 1) {
         *(f32x4*)((float*)g.C + (long)m * g.ldc + n) = v + *(const f32x4*)(g.resid + (long)m * g.ldr + n);
       } else {
-        f32x4* cp = (f32x4*)((float*)g.C + (long)m * g.ldc + n);
-        *cp = g.accumulate ? *cp + v : v;
+        *(f32x4*)((float*)g.C + (long)m * g.ldc + n) = MODE == 4 ? c_old[it] + v : v;
       }
     }
   }
@@ -401,14 +415,16 @@ ls_status dispatch16(const DmaArgs& g, hipStream_t st) {
     if (g.a_kmajor && g.b_kmajor && g.c_dtype != LS_F32 && !g.bias) return launch16<T, true, true, 3>(g, st);
     return LS_ESTATE;
   }
-  const int mode = g.c_dtype != LS_F32 ? 0 : (g.resid ? 1 : 2);
-  if (mode == 2 && g.bias) return LS_ESTATE;
+  const int mode = g.c_dtype != LS_F32 ? 0 : (g.resid ? 1 : (g.accumulate ? 4 : 2));
+  if (mode >= 2 && g.bias) return LS_ESTATE;
   if (mode == 1 && g.accumulate) return LS_ESTATE;
   if (g.a_kmajor && g.b_kmajor && mode == 0) return launch16<T, true, true, 0>(g, st);
   if (g.a_kmajor && g.b_kmajor && mode == 1) return launch16<T, true, true, 1>(g, st);
   if (g.a_kmajor && g.b_kmajor && mode == 2) return launch16<T, true, true, 2>(g, st);
+  if (g.a_kmajor && g.b_kmajor && mode == 4) return launch16<T, true, true, 4>(g, st);
   if (g.a_kmajor && !g.b_kmajor && mode == 0) return launch16<T, true, false, 0>(g, st);
   if (g.a_kmajor && !g.b_kmajor && mode == 2) return launch16<T, true, false, 2>(g, st);
+  if (g.a_kmajor && !g.b_kmajor && mode == 4) return launch16<T, true, false, 4>(g, st);
   // Both operands k-strided (weight gradients): left to the 32x32x16 kernel.  Every fragment is two
   // transposing reads there, 24 in a quarter of 32 short MFMAs, and this kernel measured 8 - 10 % slower on
   // those shapes (faster by 5 - 12 % on the other two layouts), also with the LDS reads free of bank conflicts.

@@ -98,7 +98,19 @@ def test_gemm_large_tile_kernels_with_ragged_edges(name, K):
     # weight-gradient layout: C[M, N] = At[K, M]^T Bk[K, N], both k-strided, fp32 result
     At = q(S.normal(5, "At", (K, M)), name)
     Bd.lsk_gemm(dev(At, DT[name]), dev(Bk, DT[name]), out, M=M, N=N, K=K, a_kmajor=False, b_kmajor=False, lda=M, ldb=N)
-    assert_close(host(out), At.astype(np.float64).T @ Bk.astype(np.float64), 1e-5, "weight-gradient layout")
+    r3 = At.astype(np.float64).T @ Bk.astype(np.float64)
+    assert_close(host(out), r3, 1e-5, "weight-gradient layout")
+    # accumulating fp32 results: a second launch adds to what the first one wrote (both kernels fetch the old
+    # values of an epilogue pass before they stage the accumulators)
+    Bd.lsk_gemm(dev(At, DT[name]), dev(Bk, DT[name]), out, M=M, N=N, K=K, a_kmajor=False, b_kmajor=False, lda=M, ldb=N,
+                accumulate=True)
+    assert_close(host(out), 2.0 * r3, 1e-5, "weight-gradient layout, accumulated")
+    out.copy_(dev(R, torch.float32))
+    Bd.lsk_gemm(Ad, Wd, out, M=M, N=N, K=K, accumulate=True)
+    assert_close(host(out), ref + R, 1e-5, "forward layout, fp32 result added to the buffer")
+    out.copy_(dev(R, torch.float32))
+    Bd.lsk_gemm(Ad, dev(Bk, DT[name]), out, M=M, N=N, K=K, a_kmajor=True, b_kmajor=False, lda=K, ldb=N, accumulate=True)
+    assert_close(host(out), r2 + R, 1e-5, "input-gradient layout, fp32 result added to the buffer")
 
 
 @pytest.mark.parametrize("name", ["bf16", "f16"])
