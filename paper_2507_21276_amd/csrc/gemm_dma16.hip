@@ -303,19 +303,21 @@ __global__ __launch_bounds__(256) void gemm_dma16_kernel(DmaArgs g) {
   };
 #pragma unroll
   for (int pass = 0; pass < NPASS; ++pass) {
-    // accumulating output: what the pass adds to is fetched first, all of it at once, and arrives while the
-    // accumulators are staged (a load per store, each behind its own branch and wait, made the launch a third longer)
+    // results added to a buffer (the residual stream, or the output itself): what the pass adds to is fetched
+    // first, all of it at once, and arrives while the accumulators are staged (a load per store, each behind its
+    // own branch and wait, made an accumulating launch a sixth longer)
     constexpr int NOUT = ROWS_P * CPR / 64;
-    f32x4 c_old[MODE == 4 ? NOUT : 1];
-    if constexpr (MODE == 4) {
-      {
+    constexpr bool ADDS = MODE == 1 || MODE == 4;
+    f32x4 c_old[ADDS ? NOUT : 1];
+    if constexpr (ADDS) {
+      const float* src = MODE == 1 ? g.resid : (const float*)g.C;
+      const long ld_src = MODE == 1 ? g.ldr : g.ldc;
 #pragma unroll
-        for (int it = 0; it < NOUT; ++it) {
-          const int idx = it * 64 + lane;
-          const int m = m0 + wm + pass * ROWS_P + idx / CPR;
-          const int n = n0 + wn + (idx % CPR) * (16 / ESZ);
-          c_old[it] = m < g.M && n < g.N ? *(const f32x4*)((const float*)g.C + (long)m * g.ldc + n) : f32x4{0.f, 0.f, 0.f, 0.f};
-        }
+      for (int it = 0; it < NOUT; ++it) {
+        const int idx = it * 64 + lane;
+        const int m = m0 + wm + pass * ROWS_P + idx / CPR;
+        const int n = n0 + wn + (idx % CPR) * (16 / ESZ);
+        c_old[it] = m < g.M && n < g.N ? *(const f32x4*)(src + (long)m * ld_src + n) : f32x4{0.f, 0.f, 0.f, 0.f};
       }
     }
 #pragma unroll
@@ -385,7 +387,7 @@ __global__ __launch_bounds__(256) void gemm_dma16_kernel(DmaArgs g) {
       if constexpr (ESZ == 2) {
         *(f32x4_a*)((T*)g.C + (long)m * g.ldc + n) = v;
       } else if constexpr (MODE == 1) {
-        *(f32x4*)((float*)g.C + (long)m * g.ldc + n) = v + *(const f32x4*)(g.resid + (long)m * g.ldr + n);
+        *(f32x4*)((float*)g.C + (long)m * g.ldc + n) = v + c_old[it];
       } else {
         *(f32x4*)((float*)g.C + (long)m * g.ldc + n) = MODE == 4 ? c_old[it] + v : v;
       }
