@@ -120,7 +120,35 @@ def gemm_study():
         print(f"{kind:6s} per 64-wide k tile (K 4096 -> 8192): lsk_gemm {sa:.3f} us, torch.matmul {sb:.3f} us; "
               f"fixed per launch: lsk_gemm {a0 - sa * k0 / 64:.1f} us, torch.matmul {b0 - sb * k0 / 64:.1f} us", flush=True)
         out[kind] = {"k_tile_us": [sa, sb], "fixed_us": [a0 - sa * k0 / 64, b0 - sb * k0 / 64]}
-    print(json.dumps({"gemm_study": out}))
+    # the gradient layouts at the four projection shapes of a LLaMA-7B block (T = 4096 tokens, N(0, 0.05) / N(0, 1)
+    # operands): weight gradient dW[M, N] = dY[T, M]^T X[T, N] (both operands k-strided; fp32 result from
+    # lsk_gemm, fp16 from torch.matmul) and input gradient dX[T, N] = dY[T, M] W[M, N] (W k-strided)
+    T = 4096
+    layouts = []
+    for (Mo, No) in ((4096, 11008), (4096, 4096), (22016, 4096), (12288, 4096)):
+        g = torch.Generator(device="cuda").manual_seed(1)
+        dY = (torch.randn(T, Mo, device="cuda", generator=g) * 0.05).to(torch.float16)
+        X = torch.randn(T, No, device="cuda", generator=g).to(torch.float16)
+        W = (torch.randn(Mo, No, device="cuda", generator=g) * 0.05).to(torch.float16)
+        C32 = torch.zeros(Mo, No, device="cuda", dtype=torch.float32)
+        C16 = torch.zeros(Mo, No, device="cuda", dtype=torch.float16)
+        dX = torch.zeros(T, No, device="cuda", dtype=torch.float16)
+        fl = 2.0 * Mo * No * T
+        row = {"shape": [Mo, No]}
+        for name, ours, lib in (
+                ("dW", lambda: Bd.lsk_gemm(dY, X, C32, M=Mo, N=No, K=T, a_kmajor=False, b_kmajor=False),
+                 lambda: torch.matmul(dY.T, X, out=C16)),
+                ("dW+=", lambda: Bd.lsk_gemm(dY, X, C32, M=Mo, N=No, K=T, a_kmajor=False, b_kmajor=False, accumulate=True),
+                 None),
+                ("dX", lambda: Bd.lsk_gemm(dY, W, dX, M=T, N=No, K=Mo, a_kmajor=True, b_kmajor=False),
+                 lambda: torch.matmul(dY, W, out=dX))):
+            a = timed(ours, iters=50, warm=5)
+            b = timed(lib, iters=50, warm=5) if lib else None
+            row[name] = [a, b]
+            print(f"{name:4s} {Mo:5d} x {No:5d}: lsk_gemm {a:7.1f} us ({fl / a / 1e6:5.0f} TFLOP/s)"
+                  + (f"   torch.matmul {b:7.1f} us ({fl / b / 1e6:5.0f} TFLOP/s)" if b else ""), flush=True)
+        layouts.append(row)
+    print(json.dumps({"gemm_study": out, "gradient_layouts": layouts}))
 
 
 def main():
