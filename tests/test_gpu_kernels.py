@@ -114,6 +114,36 @@ def test_gemm_large_tile_kernels_with_ragged_edges(name, K):
 
 
 @pytest.mark.parametrize("name", ["bf16", "f16"])
+def test_gemm_accumulates_into_fp32_buffers_with_128_tiles(name):
+    """Few tiles (the 128 x 128 kernel), partial tiles on both edges: a launch with accumulate adds to the
+    buffer in the forward, input-gradient and weight-gradient layouts, and the residual mode adds the residual."""
+    M, N, K = 520, 392, 256
+    A = q(S.normal(6, "A", (M, K)), name)
+    W = q(S.normal(6, "W", (N, K), 0.05), name)
+    Bk = q(S.normal(6, "Bk", (K, N), 0.05), name)
+    At = q(S.normal(6, "At", (K, M)), name)
+    R = S.normal(6, "R", (M, N))
+    Rd = dev(R, torch.float32)
+    out = torch.empty(M, N, dtype=torch.float32, device="cuda")
+    f64 = lambda x: x.astype(np.float64)
+    out.copy_(Rd)
+    Bd.lsk_gemm(dev(A, DT[name]), dev(W, DT[name]), out, M=M, N=N, K=K, accumulate=True)
+    assert_close(host(out), f64(A) @ f64(W).T + R, 1e-5, "forward layout")
+    Bd.lsk_gemm(dev(A, DT[name]), dev(W, DT[name]), out, M=M, N=N, K=K, resid=Rd)
+    assert_close(host(out), f64(A) @ f64(W).T + R, 1e-5, "forward layout, residual")
+    out.copy_(Rd)
+    Bd.lsk_gemm(dev(A, DT[name]), dev(Bk, DT[name]), out, M=M, N=N, K=K, a_kmajor=True, b_kmajor=False, lda=K, ldb=N,
+                accumulate=True)
+    assert_close(host(out), f64(A) @ f64(Bk) + R, 1e-5, "input-gradient layout")
+    out.copy_(Rd)
+    Bd.lsk_gemm(dev(At, DT[name]), dev(Bk, DT[name]), out, M=M, N=N, K=K, a_kmajor=False, b_kmajor=False, lda=M, ldb=N,
+                accumulate=True)
+    assert_close(host(out), f64(At).T @ f64(Bk) + R, 1e-5, "weight-gradient layout")
+    Bd.lsk_gemm(dev(At, DT[name]), dev(Bk, DT[name]), out, M=M, N=N, K=K, a_kmajor=False, b_kmajor=False, lda=M, ldb=N)
+    assert_close(host(out), f64(At).T @ f64(Bk), 1e-5, "weight-gradient layout, overwriting")
+
+
+@pytest.mark.parametrize("name", ["bf16", "f16"])
 @pytest.mark.parametrize("M,N,K", [(64, 1048, 4096), (4, 72, 136), (33, 264, 11008), (128, 520, 768), (1, 64, 32)])
 @pytest.mark.parametrize("split", [True, False])
 def test_gemm_skinny_weight_streaming(name, M, N, K, split):
