@@ -383,13 +383,20 @@ extern "C" ls_status lsk_gemm_ws(int op_dtype, int M, int N, int K, const void* 
 // every q and k head of row t rotated by pos[t] * theta^(-2i/128).  Falls back to
 // the plain GEMM followed by the in-place rotary kernel for shapes the fused
 // epilogue does not cover.
+// whether lsk_gemm_qkv_rope applies the rotary embedding in the projection's epilogue at this shape (the
+// 256 x 256 tile kernel, which needs enough tiles to fill the chip); otherwise it runs the projection and
+// the rotary kernel one after the other
+bool gemm_qkv_rope_fuses(int op_dtype, int T, int d, int head_dim) {
+  return use_dma_kernel() && head_dim == 128 && T >= 256 && (long)((T + 255) / 256) * ((3 * d + 255) / 256) >= 160 &&
+         (op_dtype == LS_BF16 || op_dtype == LS_F16);
+}
+
 extern "C" ls_status lsk_gemm_qkv_rope(int op_dtype, int T, int d, const void* H, const void* Wqkv, void* qkv,
                                        int n_heads, int head_dim, const int32_t* pos, const float* table,
                                        void* stream) {
   LS_REQUIRE(H && Wqkv && qkv && pos && table && T > 0 && d == n_heads * head_dim, "gemm_qkv_rope: bad argument");
   hipStream_t st = (hipStream_t)stream;
-  if (use_dma_kernel() && head_dim == 128 && T >= 256 && (long)((T + 255) / 256) * ((3 * d + 255) / 256) >= 160 &&
-      (op_dtype == LS_BF16 || op_dtype == LS_F16)) {
+  if (gemm_qkv_rope_fuses(op_dtype, T, d, head_dim)) {
     const ls_status r = gemm_dma_try(op_dtype, T, 3 * d, d, H, d, 1, Wqkv, d, 1, qkv, 3 * d, op_dtype, nullptr, 0,
                                      nullptr, 0, 0, nullptr, pos, table, 2 * d, st);
     if (r != LS_ESTATE) return r;

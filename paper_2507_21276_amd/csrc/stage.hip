@@ -42,6 +42,9 @@ ls_status lsk_gemm_qkv_rope(int, int, int, const void*, const void*, void*, int,
 ls_status lsk_gemm_ws(int, int, int, int, const void*, long, const void*, long, void*, long, int, const void*, int,
                       const float*, long, float*, size_t, void*);
 ls_status lsk_gemm_partials(int, int, int, int, const void*, long, const void*, long, float*, size_t, int*, void*);
+}
+bool gemm_qkv_rope_fuses(int op_dtype, int T, int d, int head_dim);
+extern "C" {
 ls_status lsk_finish_resid_norm(const float*, int, int, int, const void*, const float*, float*, int, const void*,
                                 const void*, int, float, void*, int, void*);
 ls_status lsk_finish_act(const float*, int, int, int, int, const void*, int, void*, int, void*);
@@ -297,10 +300,12 @@ ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const
   const int nk = gpt ? 0 : 1;
   LS_TRY(lsk_norm_fwd(nk, f.x, T, d, pptr(s, o.n1_g), gpt ? pptr(s, o.n1_b) : nullptr, pt, c.norm_eps,
                       f.h1, mt, f.mean1, f.rstd1, st));
-  const bool roped = !gpt && mt != LS_F32 && (!kv || T >= 256);
+  // training: rotary embedding in the projection's epilogue where the tile shape allows, else by the rotary
+  // kernel.  Serving: in the epilogue only where it is fused there; otherwise the kernel that writes K and V
+  // to the pages rotates q and k in the same pass (a prompt chunk of 512 rows has too few tiles for the fused
+  // epilogue, and a rotary kernel of its own before the page write cost 13 us per block).
+  const bool roped = !gpt && mt != LS_F32 && (!kv || gemm_qkv_rope_fuses(mt, T, d, c.head_dim));
   if (roped) {
-    // training and prompt chunks: rotary embedding fused into the projection's epilogue where the
-    // tile shape allows
     LS_TRY(lsk_gemm_qkv_rope(mt, T, d, f.h1, wptr(s, o.w_qkv), f.qkv, c.n_heads, c.head_dim, pos, s->rope_table, st));
   } else {
     LS_TRY(linear(s, T, 3 * d, d, f.h1, wptr(s, o.w_qkv), f.qkv, mt, gpt ? pptr(s, o.b_qkv) : nullptr, nullptr,
