@@ -238,6 +238,46 @@ __global__ void rope_kv_kernel(void* qkv, int dt, int T, int h, int dh, const in
   }
 }
 
+// The same for 16-bit data, head_dim % 8 == 0: one thread per (row, q / k / v, head, four pairs
+// i .. i + 3 < dh / 2), 8-byte accesses.  v and (without a table) q are not rewritten in place.
+template <class TH>
+__global__ void rope_kv_vec_kernel(TH* qkv, int T, int h, int dh, const int32_t* pos, const int32_t* req,
+                                   const float* table, TH* k_pool, TH* v_pool, const int32_t* block_table,
+                                   int max_pages, int page) {
+  typedef TH V4 __attribute__((ext_vector_type(4)));
+  const int half = dh / 2, d = h * dh, q4 = half / 4;
+  const size_t n = (size_t)T * 3 * h * q4;
+  for (size_t idx = blockIdx.x * (size_t)blockDim.x + threadIdx.x; idx < n; idx += (size_t)gridDim.x * blockDim.x) {
+    const int i = (int)(idx % q4) * 4, hp = (int)((idx / q4) % (3 * h));   // hp = part * h + head
+    const int part = hp / h, head = hp % h;
+    const size_t t = idx / ((size_t)q4 * 3 * h);
+    if (part == 0 && !table) continue;
+    const size_t qi = t * 3 * d + (size_t)hp * dh + i;
+    V4 a = *(const V4*)(qkv + qi), b = *(const V4*)(qkv + qi + half);
+    const int p = pos[t];
+    if (table && part < 2) {
+      const float* tb = table + ((size_t)p * half + i) * 2;   // (cos, sin) pairs
+      const f32x4 cs0 = *(const f32x4*)tb, cs1 = *(const f32x4*)(tb + 4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float c = e < 2 ? cs0[2 * e] : cs1[2 * (e - 2)], sn = e < 2 ? cs0[2 * e + 1] : cs1[2 * (e - 2) + 1];
+        const float xa = to_f(a[e]), xb = to_f(b[e]);
+        a[e] = from_f<TH>(xa * c - xb * sn);
+        b[e] = from_f<TH>(xb * c + xa * sn);
+      }
+      *(V4*)(qkv + qi) = a;
+      *(V4*)(qkv + qi + half) = b;
+    }
+    if (part > 0) {
+      TH* pool = part == 1 ? k_pool : v_pool;
+      const int pg = block_table[(size_t)req[t] * max_pages + p / page];
+      const size_t dst = (((size_t)pg * h + head) * page + p % page) * dh + i;
+      *(V4*)(pool + dst) = a;
+      *(V4*)(pool + dst + half) = b;
+    }
+  }
+}
+
 ls_status set_lds(const void* fn, size_t bytes) {
   LS_REQUIRE(bytes <= 160 * 1024, "attention: context too long for the plain kernel (%zu bytes of LDS)", bytes);
   if (bytes > 48 * 1024)
@@ -303,6 +343,20 @@ ls_status lsk_rope_kv_write(void* qkv, int dt, int T, int h, int dh, const int32
                             int max_pages, int page, void* stream) {
   LS_REQUIRE(qkv && pos && req && k_pool && v_pool && block_table && T > 0 && dh % 2 == 0,
              "rope_kv_write: bad argument");
+  if (dt != LS_F32 && dh % 8 == 0 && ((uintptr_t)qkv | (uintptr_t)k_pool | (uintptr_t)v_pool) % 8 == 0 &&
+      (!table || (uintptr_t)table % 16 == 0)) {
+    const size_t nv = (size_t)T * 3 * h * (dh / 8);
+    size_t gv = (nv + 255) / 256;
+    if (gv > 8192) gv = 8192;
+    if (dt == LS_BF16)
+      rope_kv_vec_kernel<bf16_t><<<(unsigned)gv, 256, 0, (hipStream_t)stream>>>(
+          (bf16_t*)qkv, T, h, dh, pos, req, table, (bf16_t*)k_pool, (bf16_t*)v_pool, block_table, max_pages, page);
+    else
+      rope_kv_vec_kernel<f16_t><<<(unsigned)gv, 256, 0, (hipStream_t)stream>>>(
+          (f16_t*)qkv, T, h, dh, pos, req, table, (f16_t*)k_pool, (f16_t*)v_pool, block_table, max_pages, page);
+    LS_CHECK_LAUNCH();
+    return LS_OK;
+  }
   const size_t n = (size_t)T * h * (dh / 2);
   size_t g = (n + 255) / 256;
   if (g > 8192) g = 8192;
