@@ -214,6 +214,16 @@ ls_status lsk_kv_write(const void* qkv, int dtype, int T, int n_heads, int head_
                        const int32_t* pos, const int32_t* req, void* k_pool, void* v_pool,
                        const int32_t* block_table, int max_pages_per_req, int page_size,
                        void* stream);
+/*
+ * lsk_kv_write with the rotary embedding in the same pass (serving path of the blocks of Table 2's
+ * LLaMA family): when table is non-null, q and k of qkv (device, [T, 3d], modified in place) are rotated
+ * by pos[t] exactly as lsk_rope does with sign +1, and the rotated k rows and the v rows go to the page
+ * slots; with a null table only the page write happens.  head_dim even.  16-bit data with head_dim a
+ * multiple of 8 and 8-byte-aligned buffers take a vectorised kernel.  LS_EINVAL on null arguments.
+ */
+ls_status lsk_rope_kv_write(void* qkv, int dtype, int T, int n_heads, int head_dim, const int32_t* pos,
+                            const int32_t* req, const float* table, void* k_pool, void* v_pool,
+                            const int32_t* block_table, int max_pages_per_req, int page_size, void* stream);
 ls_status lsk_attn_paged(int impl, const void* qkv, int dtype, int T, int n_heads, int head_dim,
                          const int32_t* pos, const int32_t* req, const void* k_pool,
                          const void* v_pool, const int32_t* block_table, int max_pages_per_req,

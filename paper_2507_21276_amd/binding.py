@@ -110,6 +110,7 @@ SIGNATURES = {
     "lsk_attn_bwd_rope": (_I, [_I, _VP, _VP, _VP, _VP, _I, _I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP]),
     "lsk_gemm_qkv_rope": (_I, [_I, _I, _I, _VP, _VP, _VP, _I, _I, _VP, _VP, _VP]),
     "lsk_kv_write": (_I, [_VP, _I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP, _I, _I, _VP]),
+    "lsk_rope_kv_write": (_I, [_VP, _I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP, _VP, _I, _I, _VP]),
     "lsk_attn_paged": (_I, [_I, _VP, _I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP, _I, _I, _I, _VP, _VP, _VP]),
     "lsk_attn_paged_scratch_floats": (_SZ, [_I, _I, _I, _I, _I]),
     "lsk_gemm_skinny_scratch_floats": (_SZ, [_I, _I, _I]),
@@ -443,6 +444,12 @@ def lsk_attn_bwd_rope(impl, qkv, o, dO, lse, B, L, n_heads, head_dim, dqkv, pos,
 def lsk_gemm_qkv_rope(h, w, qkv, n_heads, head_dim, pos, table, stream=None):
     _check(lib().lsk_gemm_qkv_rope(CODE_OF_TORCH[h.dtype], h.shape[0], h.shape[1], _p(h), _p(w), _p(qkv),
                                    n_heads, head_dim, _p(pos), _p(table), _stream(stream)))
+
+
+def lsk_rope_kv_write(qkv, n_heads, head_dim, pos, req, table, k_pool, v_pool, block_table, page_size, stream=None):
+    _check(lib().lsk_rope_kv_write(_p(qkv), CODE_OF_TORCH[qkv.dtype], qkv.shape[0], n_heads, head_dim, _p(pos),
+                                   _p(req), _p(table), _p(k_pool), _p(v_pool), _p(block_table),
+                                   block_table.shape[1], page_size, _stream(stream)))
 
 
 def lsk_kv_write(qkv, n_heads, head_dim, pos, req, k_pool, v_pool, block_table, page_size, stream=None):

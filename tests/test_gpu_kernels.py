@@ -515,6 +515,48 @@ def test_paged_attention_ragged(impl, name, h, dh, P):
     assert_close(host(o), ref, otol(name, ref, 1e-4), "paged attention")
 
 
+@pytest.mark.parametrize("name,h,dh,P", [("f32", 2, 32, 16), ("f16", 3, 128, 16), ("bf16", 2, 64, 8), ("f16", 2, 36, 4)])
+@pytest.mark.parametrize("rotate", [True, False])
+def test_rope_and_page_write_in_one_pass(name, h, dh, P, rotate):
+    """q and k rotated in place as the oracle's rope does, the (rotated) k rows and the v rows bit-exactly in
+    their page slots, every other slot untouched; 16-bit data with head_dim % 8 == 0 takes the vectorised
+    kernel, head_dim 36 and fp32 the scalar one."""
+    d = h * dh
+    ctx = np.array([0, 7, 16, 250])
+    new = np.array([1, 3, 33, 70])
+    table, n_pages = S.page_tables(ctx, new, P, seed=5)
+    T = int(new.sum())
+    qkv = q(S.normal(11, "qkv", (T, 3 * d)), name)
+    rng = np.random.default_rng(1)
+    kp = q(rng.normal(0, 1, (n_pages, h, P, dh)), name)
+    vp = q(rng.normal(0, 1, (n_pages, h, P, dh)), name)
+    pos = np.concatenate([ctx[b] + np.arange(new[b]) for b in range(len(ctx))]).astype(np.int32)
+    req = np.concatenate([np.full(new[b], b) for b in range(len(ctx))]).astype(np.int32)
+    qd, kd, vd = dev(qkv, DT[name]), dev(kp, DT[name]), dev(vp, DT[name])
+    bt = torch.as_tensor(table, dtype=torch.int32, device="cuda")
+    Bd.lsk_rope_kv_write(qd, h, dh, torch.as_tensor(pos, device="cuda"), torch.as_tensor(req, device="cuda"),
+                         dev(rope_table(512, dh), torch.float32) if rotate else None, kd, vd, bt, P)
+    out, kh, vh = host(qd), host(kd), host(vd)
+    ref = qkv.astype(np.float64).copy()
+    if rotate:
+        for part in (0, 1):
+            blk = ref[:, part * d:(part + 1) * d].reshape(T, h, dh)
+            ref[:, part * d:(part + 1) * d] = O.rope(blk, pos, 1e4, 1.0).reshape(T, d)
+        assert_close(out, ref, otol(name, ref), "q and k rotated in place")
+    else:
+        assert np.array_equal(out, ref)
+    assert np.array_equal(out[:, 2 * d:], qkv[:, 2 * d:].astype(np.float64))   # v untouched
+    written = np.zeros((n_pages, P), dtype=bool)
+    for t in range(T):
+        pg, slot = table[req[t], pos[t] // P], pos[t] % P
+        written[pg, slot] = True
+        assert np.array_equal(kh[pg, :, slot], out[t, d:2 * d].reshape(h, dh)), t
+        assert np.array_equal(vh[pg, :, slot], out[t, 2 * d:].reshape(h, dh)), t
+    keep = ~written
+    assert np.array_equal(kh.transpose(0, 2, 1, 3)[keep], kp.astype(np.float64).transpose(0, 2, 1, 3)[keep])
+    assert np.array_equal(vh.transpose(0, 2, 1, 3)[keep], vp.astype(np.float64).transpose(0, 2, 1, 3)[keep])
+
+
 @pytest.mark.parametrize("src,dst", [("f32", "bf16"), ("f32", "f16"), ("bf16", "f32"), ("f16", "f32"), ("bf16", "f16"),
                                      ("f16", "bf16"), ("f32", "f32")])
 @pytest.mark.parametrize("n,offset", [(8 * 1000, 0), (8 * 1000 + 3, 0), (4096, 1), (5, 0)])
