@@ -526,6 +526,30 @@ ls_status gemm_dma_splitk_try(int op_dtype, int M, int N, int K, const void* A, 
   return LS_ESTATE;
 }
 
+// The first half of gemm_dma_splitk_try: the partial products stay in `scratch` as [splits][M][N] for a
+// caller that sums them together with its next step.  LS_ESTATE when the shape does not call for a split.
+ls_status gemm_dma_splitk_partials(int op_dtype, int M, int N, int K, const void* A, long lda, const void* B, long ldb,
+                                   float* scratch, size_t scratch_floats, int* splits_out, hipStream_t st) {
+  if (!scratch || K % TK != 0 || M < 256 || N < 64 || N % 4 != 0 || (uintptr_t)scratch % 16 != 0) return LS_ESTATE;
+  if (lda % 8 != 0 || ldb % 8 != 0 || (uintptr_t)A % 16 != 0 || (uintptr_t)B % 16 != 0) return LS_ESTATE;
+  const long tiles = (long)((M + 127) / 128) * ((N + 127) / 128);
+  const int nk = K / TK;
+  if (tiles >= 200 || nk < 32) return LS_ESTATE;
+  int splits = (int)(512 / tiles);
+  if (splits > 8) splits = 8;
+  while (splits > 1 && nk / splits < 8) --splits;
+  while (splits > 1 && (size_t)splits * M * N > scratch_floats) --splits;
+  if (splits < 2) return LS_ESTATE;
+  DmaArgs g{M, N, K, A, lda, 1, B, ldb, 1, scratch, N, LS_F32, nullptr, 0, nullptr, 0, 0, nullptr, 0, 0, 0, nullptr,
+            nullptr, 0};
+  g.split_stride = (long)M * N;
+  if (op_dtype == LS_BF16) LS_TRY((launch<bf16_t, 128, 128, true, true, 2>(g, st, splits)));
+  else if (op_dtype == LS_F16) LS_TRY((launch<f16_t, 128, 128, true, true, 2>(g, st, splits)));
+  else return LS_ESTATE;
+  *splits_out = splits;
+  return LS_OK;
+}
+
 // Weight-streaming product for a few rows (decode batches, M <= 128): tiles of 64 x 128 so that
 // three workgroups share a compute unit (128 x 128 and two workgroups above 64 rows), the weights stream through LDS as whole cache lines,
 // and the contraction is split until the chip has about three workgroups per compute unit.

@@ -44,6 +44,8 @@ ls_status lsk_gemm_ws(int, int, int, int, const void*, long, const void*, long, 
 ls_status lsk_gemm_partials(int, int, int, int, const void*, long, const void*, long, float*, size_t, int*, void*);
 }
 bool gemm_qkv_rope_fuses(int op_dtype, int T, int d, int head_dim);
+ls_status gemm_dma_splitk_partials(int, int, int, int, const void*, long, const void*, long, float*, size_t, int*,
+                                   hipStream_t);
 extern "C" {
 ls_status lsk_finish_resid_norm(const float*, int, int, int, const void*, const float*, float*, int, const void*,
                                 const void*, int, float, void*, int, void*);
@@ -322,9 +324,24 @@ ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const
   } else {
     LS_TRY(lsk_attn_fwd(mt == LS_F32 ? 0 : 1, f.qkv, mt, B, L, c.n_heads, c.head_dim, f.o, f.lse, st));
   }
-  LS_TRY(linear(s, T, d, d, f.o, wptr(s, o.w_o), f.x1, LS_F32, gpt ? pptr(s, o.b_o) : nullptr, f.x, f.scratch, st));
-  LS_TRY(lsk_norm_fwd(nk, f.x1, T, d, pptr(s, o.n2_g), gpt ? pptr(s, o.n2_b) : nullptr, pt, c.norm_eps,
-                      f.h2, mt, f.mean2, f.rstd2, st));
+  // serving calls whose output projection is split over k (prompt chunks): the kernel that sums the partial
+  // products also adds the residual and normalises for the FFN, in place of a reduce kernel and a norm kernel
+  int splits = 0;
+  static const bool fuse_on = [] {
+    const char* e = getenv("LS_DECODE_FUSED");
+    const char* gi = getenv("LS_GEMM_IMPL");
+    return !(e && strcmp(e, "0") == 0) && !(gi && strcmp(gi, "staged") == 0);
+  }();
+  if (kv && fuse_on && mt != LS_F32 && d <= 8192 && d % 4 == 0 && f.scratch &&
+      gemm_dma_splitk_partials(mt, T, d, d, f.o, d, wptr(s, o.w_o), d, f.scratch, serve_scratch_floats(s), &splits,
+                               st) == LS_OK) {
+    LS_TRY(lsk_finish_resid_norm(f.scratch, splits, T, d, gpt ? pptr(s, o.b_o) : nullptr, f.x, f.x1, nk, pptr(s, o.n2_g),
+                                 gpt ? pptr(s, o.n2_b) : nullptr, pt, c.norm_eps, f.h2, mt, st));
+  } else {
+    LS_TRY(linear(s, T, d, d, f.o, wptr(s, o.w_o), f.x1, LS_F32, gpt ? pptr(s, o.b_o) : nullptr, f.x, f.scratch, st));
+    LS_TRY(lsk_norm_fwd(nk, f.x1, T, d, pptr(s, o.n2_g), gpt ? pptr(s, o.n2_b) : nullptr, pt, c.norm_eps,
+                        f.h2, mt, f.mean2, f.rstd2, st));
+  }
   LS_TRY(linear(s, T, s->up_cols, d, f.h2, wptr(s, o.w_up), f.up, mt, gpt ? pptr(s, o.b_up) : nullptr, nullptr,
                 f.scratch, st));
   if (gpt) LS_TRY(lsk_gelu_fwd(f.up, f.act, mt, (size_t)T * F, c.act, st));
