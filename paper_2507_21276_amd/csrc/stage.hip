@@ -292,16 +292,20 @@ ls_status serve_attention(const ls_stage* s, int T, const FwdBufs& f, const int3
 
 // n_decode (serving with chunk_start only): the first n_decode rows are single-token decode rows of
 // requests 0 .. n_decode - 1; chunk_start then describes requests n_decode .. B - 1 (rows after them)
+// h1_ready (serving calls only, else null): on entry, whether the previous block's last kernel has already
+// written this block's normalised input to f.h1; on return, whether this block has done so for the next one.
 ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const int32_t* pos,
                         const int32_t* req, int B, int L, const ls_kv* kv, int max_ctx,
-                        const int32_t* chunk_start, int n_decode, hipStream_t st) {
+                        const int32_t* chunk_start, int n_decode, hipStream_t st, bool* h1_ready = nullptr) {
   const ls_config& c = s->cfg;
   const LayerOff& o = s->off[l];
   const int d = c.d_model, F = c.d_ff, mt = c.mma_dtype, pt = c.dtype;
   const bool gpt = c.block == LS_BLOCK_GPT_PRELN;
   const int nk = gpt ? 0 : 1;
-  LS_TRY(lsk_norm_fwd(nk, f.x, T, d, pptr(s, o.n1_g), gpt ? pptr(s, o.n1_b) : nullptr, pt, c.norm_eps,
-                      f.h1, mt, f.mean1, f.rstd1, st));
+  if (!(h1_ready && *h1_ready))
+    LS_TRY(lsk_norm_fwd(nk, f.x, T, d, pptr(s, o.n1_g), gpt ? pptr(s, o.n1_b) : nullptr, pt, c.norm_eps,
+                        f.h1, mt, f.mean1, f.rstd1, st));
+  if (h1_ready) *h1_ready = false;
   // training: rotary embedding in the projection's epilogue where the tile shape allows, else by the rotary
   // kernel.  Serving: in the epilogue only where it is fused there; otherwise the kernel that writes K and V
   // to the pages rotates q and k in the same pass (a prompt chunk of 512 rows has too few tiles for the fused
@@ -346,6 +350,17 @@ ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const
                 f.scratch, st));
   if (gpt) LS_TRY(lsk_gelu_fwd(f.up, f.act, mt, (size_t)T * F, c.act, st));
   else LS_TRY(lsk_swiglu_fwd(f.up, f.act, mt, T, F, st));
+  // the same for the down projection, whose sum kernel normalises for the next block
+  if (h1_ready && kv && fuse_on && mt != LS_F32 && d <= 8192 && d % 4 == 0 && f.scratch &&
+      gemm_dma_splitk_partials(mt, T, d, F, f.act, F, wptr(s, o.w_dn), F, f.scratch, serve_scratch_floats(s), &splits,
+                               st) == LS_OK) {
+    const bool last = l + 1 == c.n_layers;
+    const LayerOff& nx = s->off[last ? l : l + 1];
+    LS_TRY(lsk_finish_resid_norm(f.scratch, splits, T, d, gpt ? pptr(s, o.b_dn) : nullptr, f.x1, f.y, last ? -1 : nk,
+                                 pptr(s, nx.n1_g), gpt ? pptr(s, nx.n1_b) : nullptr, pt, c.norm_eps, f.h1, mt, st));
+    *h1_ready = !last;
+    return LS_OK;
+  }
   LS_TRY(linear(s, T, d, F, f.act, wptr(s, o.w_dn), f.y, LS_F32, gpt ? pptr(s, o.b_dn) : nullptr, f.x1, f.scratch, st));
   return LS_OK;
 }
@@ -424,11 +439,12 @@ ls_status serve_forward(ls_stage* s, const void* X, int T, int B, const ls_kv* k
   const ls_config& c = s->cfg;
   LS_TRY(lsk_convert(X, c.io_dtype, w.xa, LS_F32, (size_t)T * c.d_model, st));
   const bool fused = fused_decode_ok(s, T);
+  bool h1_ready = false;
   for (int l = 0; l < c.n_layers; ++l) {
     FwdBufs f{w.xa, w.xb, w.xa, nullptr, nullptr, nullptr, nullptr, nullptr,
               w.h, w.qkv, w.o, w.h, w.up, w.act, w.scratch};
     if (fused) LS_TRY(block_forward_fused(s, l, T, f, w.pos, w.req, B, kv, max_ctx, chunk_start, n_decode, st));
-    else LS_TRY(block_forward(s, l, T, f, w.pos, w.req, B, 0, kv, max_ctx, chunk_start, n_decode, st));
+    else LS_TRY(block_forward(s, l, T, f, w.pos, w.req, B, 0, kv, max_ctx, chunk_start, n_decode, st, &h1_ready));
   }
   return lsk_convert(w.xa, LS_F32, Y, c.io_dtype, (size_t)T * c.d_model, st);
 }
