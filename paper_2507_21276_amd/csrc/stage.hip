@@ -765,13 +765,22 @@ ls_status stage_probe_interference(ls_stage* s, const void* dec_X, int dec_B, co
   LS_TRY(check_stage(s, true));
   LS_REQUIRE(out_ms && iters > 0, "probe: bad iters or null out_ms");
   LS_REQUIRE(stream_a != stream_b, "probe: the two streams must differ");
-  LS_REQUIRE(ws_a != ws_b, "probe: the two calls need separate workspaces");
+  LS_REQUIRE(ws_a && ws_b && ws_a != ws_b, "probe: the two calls need separate, non-null workspaces");
+  LS_REQUIRE(dec_X && dec_Y && kv, "probe: null decode argument");
+  LS_REQUIRE(trn_X && trn_Y && trn_saved && trn_dY && trn_dX && trn_dParams, "probe: null training argument");
+  LS_REQUIRE(dec_B > 0 && trn_B > 0 && trn_L > 0, "probe: non-positive batch (decode %d, train %d x %d)", dec_B, trn_B,
+             trn_L);
   hipStream_t sa = (hipStream_t)stream_a, sb = (hipStream_t)stream_b;
-  hipEvent_t ea0, ea1, eb0, eb1;
-  LS_CHECK_HIP(hipEventCreate(&ea0));
-  LS_CHECK_HIP(hipEventCreate(&ea1));
-  LS_CHECK_HIP(hipEventCreate(&eb0));
-  LS_CHECK_HIP(hipEventCreate(&eb1));
+  // the four events are destroyed on every way out of the call
+  struct Events {
+    hipEvent_t e[4] = {nullptr, nullptr, nullptr, nullptr};
+    ~Events() {
+      for (hipEvent_t v : e)
+        if (v) (void)hipEventDestroy(v);
+    }
+  } ev;
+  for (hipEvent_t& v : ev.e) LS_CHECK_HIP(hipEventCreate(&v));
+  hipEvent_t ea0 = ev.e[0], ea1 = ev.e[1], eb0 = ev.e[2], eb1 = ev.e[3];
   ls_status rc = LS_OK;
   auto run_a = [&]() { return stage_decode(s, dec_X, dec_B, kv, dec_Y, ws_a, sa); };
   auto run_b = [&]() {
@@ -825,8 +834,6 @@ ls_status stage_probe_interference(ls_stage* s, const void* dec_X, int dec_B, co
   if (rc == LS_EHIP) ls_set_error("probe: a HIP synchronisation failed");
   (void)hipStreamSynchronize(sa);
   (void)hipStreamSynchronize(sb);
-  (void)hipEventDestroy(ea0); (void)hipEventDestroy(ea1);
-  (void)hipEventDestroy(eb0); (void)hipEventDestroy(eb1);
   return rc;
 }
 

@@ -103,6 +103,32 @@ def test_null_arguments_are_errors_not_crashes():
     lib.ls_batcher_destroy(None)
 
 
+def test_probe_validates_its_arguments_before_any_launch():
+    """The interference probe's own checks (two different streams, two different workspaces, a positive
+    repetition count, somewhere to write the times) need no GPU: an fp32 stage allocates nothing."""
+    st, h = _create()
+    assert st == Bd.LS_OK
+    lib = Bd.lib()
+    out = (C.c_float * 6)()
+    kv = Bd.ls_kv(0x1000, 0x1000, 0x1000, 0x1000, None, 4, 2)
+    P = 0x1000            # never dereferenced: every case below fails validation on the host
+
+    def call(ws_a=P, ws_b=2 * P, sa=P, sb=2 * P, iters=1, out_ms=out, dec_B=1, trn_B=1, dec_X=P):
+        return lib.stage_probe_interference(h, dec_X, dec_B, C.byref(kv), P, ws_a, P, trn_B, 8, P, P, P, P, P, ws_b,
+                                            sa, sb, iters, out_ms)
+
+    assert call() == Bd.LS_ESTATE                      # no parameters bound yet
+    assert lib.ls_bind_params(h, P, None) == Bd.LS_OK
+    assert call(sb=P) == Bd.LS_EINVAL and b"streams" in lib.ls_last_error()
+    assert call(ws_b=P) == Bd.LS_EINVAL and b"workspaces" in lib.ls_last_error()
+    assert call(ws_a=None) == Bd.LS_EINVAL
+    assert call(iters=0) == Bd.LS_EINVAL and call(iters=-3) == Bd.LS_EINVAL
+    assert call(out_ms=None) == Bd.LS_EINVAL
+    assert call(dec_B=0) == Bd.LS_EINVAL and call(trn_B=0) == Bd.LS_EINVAL
+    assert call(dec_X=None) == Bd.LS_EINVAL and b"decode" in lib.ls_last_error()
+    lib.ls_destroy(h)
+
+
 def test_no_instruction_touches_a_register_with_an_assembly_issued_lds_read_in_flight(tmp_path):
     """Compiles the two sources that use transposing LDS reads to ISA and lints them."""
     import shutil
