@@ -33,18 +33,6 @@ ls_status lsk_gemm(int op_dtype, int M, int N, int K, const void* A, long lda, i
                    const void* bias, int bias_dtype, const float* resid, long ldr,
                    int accumulate, void* stream);
 
-/*
- * The same forward map for decode batches (M <= 128 rows, both operands
- * k-major, 16-bit): weights are streamed once from HBM, the contraction is
- * split over ksplit slabs of K whose fp32 partial results live in `scratch`
- * (lsk_gemm_skinny_scratch_floats(M, N, K) floats; null = no split).
- */
-size_t lsk_gemm_skinny_scratch_floats(int M, int N, int K);
-ls_status lsk_gemm_skinny(int op_dtype, int M, int N, int K, const void* X, long ldx,
-                          const void* W, long ldw, void* C, long ldc, int c_dtype,
-                          const void* bias, int bias_dtype, const float* resid, long ldr,
-                          float* scratch, void* stream);
-
 /* dst[i] = (dst_dtype) src[i], i < n. */
 ls_status lsk_convert(const void* src, int src_dtype, void* dst, int dst_dtype, size_t n,
                       void* stream);

@@ -132,7 +132,10 @@ size_t ls_saved_bytes(const ls_stage* s, int B, int L);
  *   ctx_len_host   [host] the same values; used for argument validation and
  *                         launch sizing only.
  * A call appends the K/V rows of its new tokens at positions ctx_len[b].. and
- * does not change ctx_len: the caller advances it afterwards.
+ * does not change ctx_len: the caller advances it afterwards.  The pools need
+ * no initialisation: slots beyond a request's context (the tail of its last
+ * page, spare pages) may hold any bit pattern, NaN and infinity included, and
+ * never reach a result.
  */
 typedef struct {
   void* k_pool;

@@ -113,8 +113,6 @@ SIGNATURES = {
     "lsk_rope_kv_write": (_I, [_VP, _I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP, _VP, _I, _I, _VP]),
     "lsk_attn_paged": (_I, [_I, _VP, _I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP, _I, _I, _I, _VP, _VP, _VP]),
     "lsk_attn_paged_scratch_floats": (_SZ, [_I, _I, _I, _I, _I]),
-    "lsk_gemm_skinny_scratch_floats": (_SZ, [_I, _I, _I]),
-    "lsk_gemm_skinny": (_I, [_I, _I, _I, _I, _VP, _L, _VP, _L, _VP, _L, _I, _VP, _I, _VP, _L, _VP, _VP]),
     "lsk_gemm_partials": (_I, [_I, _I, _I, _I, _VP, _L, _VP, _L, _VP, _SZ, C.POINTER(_I), _VP]),
     "lsk_finish_resid_norm": (_I, [_VP, _I, _I, _I, _VP, _VP, _VP, _I, _VP, _VP, _I, _F, _VP, _I, _VP]),
     "lsk_finish_act": (_I, [_VP, _I, _I, _I, _I, _VP, _I, _VP, _I, _VP]),
@@ -312,17 +310,6 @@ def lsk_gemm(A, B, C_out, *, M, N, K, a_kmajor=True, b_kmajor=True, lda=None, ld
                           CODE_OF_TORCH[C_out.dtype], _p(bias),
                           CODE_OF_TORCH[bias.dtype] if bias is not None else 0, _p(resid),
                           ldr if ldr is not None else N, int(accumulate), _stream(stream)))
-
-
-def lsk_gemm_skinny(X, W, C_out, *, bias=None, resid=None, split=True, stream=None):
-    M, K = X.shape
-    N = W.shape[0]
-    n = lib().lsk_gemm_skinny_scratch_floats(M, N, K) if split else 0
-    scratch = torch.empty(max(n, 1), dtype=torch.float32, device=X.device) if split else None
-    _check(lib().lsk_gemm_skinny(CODE_OF_TORCH[X.dtype], M, N, K, _p(X), K, _p(W), K, _p(C_out), N,
-                                 CODE_OF_TORCH[C_out.dtype], _p(bias),
-                                 CODE_OF_TORCH[bias.dtype] if bias is not None else 0, _p(resid), N,
-                                 _p(scratch), _stream(stream)))
 
 
 def lsk_grad_scale(x, out3, stream=None):

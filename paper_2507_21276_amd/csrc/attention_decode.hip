@@ -89,6 +89,9 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
         if (i0 + i < loads_per_page) {
           const float pr = __builtin_amdgcn_exp2f(s[i] - m_new);
           l += pr;
+          // slots of the last page beyond the context were never written: whatever bit patterns they hold
+          // (NaN, infinity) must not reach the sum through 0 * x
+          if (s[i] == -INFINITY) vv[i] = V8{};
 #pragma unroll
           for (int c = 0; c < 8; ++c) acc[c] = fmaf(pr, to_f(vv[i][c]), acc[c]);
         }

@@ -779,34 +779,28 @@ ls_status launch_ring(const void* qkv, void* o, float* lse, int L, int h, float 
   return LS_OK;
 }
 
-// LS_ATTN_FWD=staged keeps the register-staged forward kernel (for A/B comparisons)
-inline bool fwd_ring_enabled() {
-  static const bool on = [] { const char* e = getenv("LS_ATTN_FWD"); return !(e && strcmp(e, "staged") == 0); }();
-  return on;
-}
-
 template <class T, int DH>
 ls_status launch_fwd(const void* qkv, int B, int L, int h, void* o, float* lse, hipStream_t st) {
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
   PagedGeom pg{};
   if constexpr (DH >= 64) {
-    if (fwd_ring_enabled()) {
-      // 128 queries per workgroup: with 256 the two code paths of a tile (masked / unmasked, rescaling
-      // or not) no longer fit the register file for head_dim 128
-      return launch_ring<T, DH, 1, false>(qkv, o, lse, L, h, scale_log2, pg, dim3(B * h, (L + 127) / 128), 0, st);
-    }
-  }
-  if (L > 512) {
-    constexpr int QT = 2;
-    dim3 grid(B * h, (L + 4 * QT * 32 - 1) / (4 * QT * 32));
-    flash_fwd_kernel<T, DH, QT, false><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, lse, L, h, scale_log2, pg);
+    // the tile-ring kernel.  128 queries per workgroup: with 256 the two code paths of a tile (masked /
+    // unmasked, rescaling or not) no longer fit the register file for head_dim 128
+    return launch_ring<T, DH, 1, false>(qkv, o, lse, L, h, scale_log2, pg, dim3(B * h, (L + 127) / 128), 0, st);
   } else {
-    constexpr int QT = 1;
-    dim3 grid(B * h, (L + 4 * QT * 32 - 1) / (4 * QT * 32));
-    flash_fwd_kernel<T, DH, QT, false><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, lse, L, h, scale_log2, pg);
+    // head_dim 32: the register-staged kernel
+    if (L > 512) {
+      constexpr int QT = 2;
+      dim3 grid(B * h, (L + 4 * QT * 32 - 1) / (4 * QT * 32));
+      flash_fwd_kernel<T, DH, QT, false><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, lse, L, h, scale_log2, pg);
+    } else {
+      constexpr int QT = 1;
+      dim3 grid(B * h, (L + 4 * QT * 32 - 1) / (4 * QT * 32));
+      flash_fwd_kernel<T, DH, QT, false><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, lse, L, h, scale_log2, pg);
+    }
+    LS_CHECK_LAUNCH();
+    return LS_OK;
   }
-  LS_CHECK_LAUNCH();
-  return LS_OK;
 }
 
 template <class T, int DH>
@@ -814,7 +808,7 @@ ls_status launch_prefill(const void* qkv, int h, void* o, const PagedGeom& pg, i
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
   constexpr int QT = 1;
   dim3 grid(pg.n_req * h, (max_chunk + 4 * QT * 32 - 1) / (4 * QT * 32));
-  if (fwd_ring_enabled() && pg.max_pages <= 4096 && pg.page >= 8 && (pg.page & (pg.page - 1)) == 0)
+  if (pg.max_pages <= 4096 && pg.page >= 8 && (pg.page & (pg.page - 1)) == 0)
     return launch_ring<T, DH, 1, true>(qkv, o, nullptr, 0, h, scale_log2, pg, grid, pg.max_pages * 4, st);
   flash_fwd_kernel<T, DH, QT, true><<<grid, 256, 0, st>>>((const T*)qkv, (T*)o, nullptr, 0, h, scale_log2, pg);
   LS_CHECK_LAUNCH();

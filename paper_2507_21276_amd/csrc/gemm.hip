@@ -295,16 +295,6 @@ ls_status gemm_dma_splitk_try(int, int, int, int, const void*, long, const void*
 ls_status gemm_dma_skinny_try(int, int, int, int, const void*, long, const void*, long, void*, long, int, const void*,
                               int, const float*, long, float*, size_t, hipStream_t);
 
-// LS_GEMM_IMPL=staged forces the register-staged kernel (for A/B comparisons)
-static bool use_dma_kernel() {
-  static int v = -1;
-  if (v < 0) {
-    const char* e = getenv("LS_GEMM_IMPL");
-    v = (e && strcmp(e, "staged") == 0) ? 0 : 1;
-  }
-  return v == 1;
-}
-
 extern "C" ls_status lsk_gemm_scaled(int op_dtype, int M, int N, int K, const void* A, long lda,
                                      int a_kmajor, const void* B, long ldb, int b_kmajor, void* C,
                                      long ldc, int c_dtype, const void* bias, int bias_dtype,
@@ -330,7 +320,7 @@ extern "C" ls_status lsk_gemm_scaled(int op_dtype, int M, int N, int K, const vo
   LS_REQUIRE(a_kmajor ? (K % 8 == 0) : (M % 8 == 0), "gemm: A contiguous extent must be a multiple of 8");
   LS_REQUIRE(b_kmajor ? (K % 8 == 0) : (N % 8 == 0), "gemm: B contiguous extent must be a multiple of 8");
   LS_REQUIRE(c_dtype == LS_F32 || c_dtype == op_dtype, "gemm: output type must be fp32 or the operand type");
-  if (use_dma_kernel() && M >= 256) {
+  if (M >= 256) {
     const ls_status r = gemm_dma_try(op_dtype, M, N, K, A, lda, a_kmajor, B, ldb, b_kmajor, C, ldc, c_dtype, bias,
                                      bias_dtype, resid, ldr, accumulate, alpha_dev, nullptr, nullptr, 0, st);
     if (r != LS_ESTATE) return r;
@@ -358,17 +348,15 @@ extern "C" ls_status lsk_gemm_ws(int op_dtype, int M, int N, int K, const void* 
                                  void* stream) {
   LS_REQUIRE(M > 0 && N > 0 && K > 0, "gemm_ws: non-positive size M=%d N=%d K=%d", M, N, K);
   LS_REQUIRE(X && W && C, "gemm_ws: null operand");
-  // decode batches (M <= 128): weights stream through LDS in 64 x 128 or 128 x 128 tiles; LS_SKINNY_IMPL=mfma keeps the
-  // register-streaming kernel (lsk_gemm_skinny) for A/B comparisons
-  static const bool skinny_dma = [] { const char* e = getenv("LS_SKINNY_IMPL"); return !(e && strcmp(e, "mfma") == 0); }();
-  if (skinny_dma && use_dma_kernel() && scratch && (op_dtype == LS_BF16 || op_dtype == LS_F16) && M <= 128 && K % 8 == 0 &&
+  // decode batches (M <= 128): weights stream through LDS in 64 x 128 or 128 x 128 tiles
+  if (scratch && (op_dtype == LS_BF16 || op_dtype == LS_F16) && M <= 128 && K % 8 == 0 &&
       ldx % 8 == 0 && ldw % 8 == 0 && (uintptr_t)X % 16 == 0 && (uintptr_t)W % 16 == 0 &&
       (c_dtype == LS_F32 || c_dtype == op_dtype)) {
     const ls_status r = gemm_dma_skinny_try(op_dtype, M, N, K, X, ldx, W, ldw, C, ldc, c_dtype, bias, bias_dtype, resid,
                                             ldr, scratch, scratch_floats, (hipStream_t)stream);
     if (r != LS_ESTATE) return r;
   }
-  if (use_dma_kernel() && scratch && (op_dtype == LS_BF16 || op_dtype == LS_F16) && M >= 256 && K % 8 == 0 &&
+  if (scratch && (op_dtype == LS_BF16 || op_dtype == LS_F16) && M >= 256 && K % 8 == 0 &&
       ldx % 8 == 0 && ldw % 8 == 0 && (uintptr_t)X % 16 == 0 && (uintptr_t)W % 16 == 0 &&
       (c_dtype == LS_F32 || c_dtype == op_dtype)) {
     const ls_status r = gemm_dma_splitk_try(op_dtype, M, N, K, X, ldx, W, ldw, C, ldc, c_dtype, bias, bias_dtype, resid,
@@ -387,7 +375,7 @@ extern "C" ls_status lsk_gemm_ws(int op_dtype, int M, int N, int K, const void* 
 // 256 x 256 tile kernel, which needs enough tiles to fill the chip); otherwise it runs the projection and
 // the rotary kernel one after the other
 bool gemm_qkv_rope_fuses(int op_dtype, int T, int d, int head_dim) {
-  return use_dma_kernel() && head_dim == 128 && T >= 256 && (long)((T + 255) / 256) * ((3 * d + 255) / 256) >= 160 &&
+  return head_dim == 128 && T >= 256 && (long)((T + 255) / 256) * ((3 * d + 255) / 256) >= 160 &&
          (op_dtype == LS_BF16 || op_dtype == LS_F16);
 }
 

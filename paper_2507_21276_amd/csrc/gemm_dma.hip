@@ -604,7 +604,6 @@ ls_status gemm_dma_skinny_try(int op_dtype, int M, int N, int K, const void* A, 
   return LS_OK;
 }
 
-bool gemm_dma16_enabled();
 ls_status gemm_dma16_try(int, int, int, int, const void*, long, int, const void*, long, int, void*, long, int,
                          const void*, int, const float*, long, int, const float*, const int32_t*, const float*, int,
                          hipStream_t);
@@ -621,12 +620,10 @@ ls_status gemm_dma_try(int op_dtype, int M, int N, int K, const void* A, long ld
   const int per16 = c_dtype == LS_F32 ? 4 : 8;
   if (N % per16 != 0 || ldc % per16 != 0 || (uintptr_t)C % 16 != 0) return LS_ESTATE;
   if (resid && (ldr % 4 != 0 || (uintptr_t)resid % 16 != 0)) return LS_ESTATE;
-  if (gemm_dma16_enabled()) {
-    // problems with enough 256 x 256 tiles run the 16x16x32 kernel
-    const ls_status r16 = gemm_dma16_try(op_dtype, M, N, K, A, lda, a_kmajor, B, ldb, b_kmajor, C, ldc, c_dtype, bias,
-                                         bias_dtype, resid, ldr, accumulate, alpha, rope_pos, rope_table, rope_cols, st);
-    if (r16 != LS_ESTATE) return r16;
-  }
+  // problems with enough 256 x 256 tiles run the 16x16x32 kernel
+  const ls_status r16 = gemm_dma16_try(op_dtype, M, N, K, A, lda, a_kmajor, B, ldb, b_kmajor, C, ldc, c_dtype, bias,
+                                       bias_dtype, resid, ldr, accumulate, alpha, rope_pos, rope_table, rope_cols, st);
+  if (r16 != LS_ESTATE) return r16;
   DmaArgs g{M, N, K, A, lda, a_kmajor, B, ldb, b_kmajor, C, ldc, c_dtype, bias, bias_dtype, resid, ldr,
             accumulate, alpha, 0, 0, 0, rope_pos, rope_table, rope_cols};
   if (op_dtype == LS_BF16) return dispatch<bf16_t>(g, st);

@@ -435,15 +435,6 @@ ls_status dispatch16(const DmaArgs& g, hipStream_t st) {
 
 }  // namespace
 
-// LS_GEMM_MFMA=32 keeps every GEMM on the 32x32x16 kernel
-bool gemm_dma16_enabled() {
-  static const bool on = [] {
-    const char* e = std::getenv("LS_GEMM_MFMA");
-    return !(e && std::strcmp(e, "32") == 0);
-  }();
-  return on;
-}
-
 // The large-tile GEMM for problems with enough 256 x 256 tiles; LS_ESTATE (error text untouched) when the
 // shape or the combination of layouts is outside what this kernel covers.  Arguments as gemm_dma_try, whose
 // checks of alignment and sizes have run before this is called.

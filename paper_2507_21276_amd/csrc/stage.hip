@@ -252,13 +252,11 @@ struct FwdBufs {
   float* scratch;
 };
 
-// forward linear map: weight-streaming kernel for decode-sized batches, tiled MFMA kernel otherwise
+// forward linear map (the launcher picks weight-streaming tiles for decode-sized batches, split-K for prompt
+// chunks, the large-tile kernels otherwise)
 ls_status linear(const ls_stage* s, int T, int N, int K, const void* X, const void* W, void* C, int c_dtype,
                  const void* bias, const float* resid, float* scratch, hipStream_t st) {
   const int mt = s->cfg.mma_dtype;
-  static const bool skinny_dma = [] { const char* e = getenv("LS_SKINNY_IMPL"); return !(e && strcmp(e, "mfma") == 0); }();
-  if (mt != LS_F32 && T <= 128 && scratch && !skinny_dma)
-    return lsk_gemm_skinny(mt, T, N, K, X, K, W, K, C, N, c_dtype, bias, s->cfg.dtype, resid, N, scratch, st);
   return lsk_gemm_ws(mt, T, N, K, X, K, W, K, C, N, c_dtype, bias, s->cfg.dtype, resid, N, scratch,
                      scratch ? serve_scratch_floats(s) : 0, st);
 }
@@ -331,14 +329,16 @@ ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const
   // serving calls whose output projection is split over k (prompt chunks): the kernel that sums the partial
   // products also adds the residual and normalises for the FFN, in place of a reduce kernel and a norm kernel
   int splits = 0;
-  static const bool fuse_on = [] {
-    const char* e = getenv("LS_DECODE_FUSED");
-    const char* gi = getenv("LS_GEMM_IMPL");
-    return !(e && strcmp(e, "0") == 0) && !(gi && strcmp(gi, "staged") == 0);
-  }();
-  if (kv && fuse_on && mt != LS_F32 && d <= 8192 && d % 4 == 0 && f.scratch &&
-      gemm_dma_splitk_partials(mt, T, d, d, f.o, d, wptr(s, o.w_o), d, f.scratch, serve_scratch_floats(s), &splits,
-                               st) == LS_OK) {
+  // LS_ESTATE from the split-K launcher means "this shape is not split": the plain path runs instead.
+  // Any other status is a failure of the launch itself and ends the call.
+  bool split_o = false;
+  if (kv && mt != LS_F32 && d <= 8192 && d % 4 == 0 && f.scratch) {
+    const ls_status r = gemm_dma_splitk_partials(mt, T, d, d, f.o, d, wptr(s, o.w_o), d, f.scratch,
+                                                 serve_scratch_floats(s), &splits, st);
+    if (r != LS_OK && r != LS_ESTATE) return r;
+    split_o = r == LS_OK;
+  }
+  if (split_o) {
     LS_TRY(lsk_finish_resid_norm(f.scratch, splits, T, d, gpt ? pptr(s, o.b_o) : nullptr, f.x, f.x1, nk, pptr(s, o.n2_g),
                                  gpt ? pptr(s, o.n2_b) : nullptr, pt, c.norm_eps, f.h2, mt, st));
   } else {
@@ -351,9 +351,14 @@ ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const
   if (gpt) LS_TRY(lsk_gelu_fwd(f.up, f.act, mt, (size_t)T * F, c.act, st));
   else LS_TRY(lsk_swiglu_fwd(f.up, f.act, mt, T, F, st));
   // the same for the down projection, whose sum kernel normalises for the next block
-  if (h1_ready && kv && fuse_on && mt != LS_F32 && d <= 8192 && d % 4 == 0 && f.scratch &&
-      gemm_dma_splitk_partials(mt, T, d, F, f.act, F, wptr(s, o.w_dn), F, f.scratch, serve_scratch_floats(s), &splits,
-                               st) == LS_OK) {
+  bool split_dn = false;
+  if (h1_ready && kv && mt != LS_F32 && d <= 8192 && d % 4 == 0 && f.scratch) {
+    const ls_status r = gemm_dma_splitk_partials(mt, T, d, F, f.act, F, wptr(s, o.w_dn), F, f.scratch,
+                                                 serve_scratch_floats(s), &splits, st);
+    if (r != LS_OK && r != LS_ESTATE) return r;
+    split_dn = r == LS_OK;
+  }
+  if (split_dn) {
     const bool last = l + 1 == c.n_layers;
     const LayerOff& nx = s->off[last ? l : l + 1];
     LS_TRY(lsk_finish_resid_norm(f.scratch, splits, T, d, gpt ? pptr(s, o.b_dn) : nullptr, f.x1, f.y, last ? -1 : nk,
@@ -371,10 +376,7 @@ ls_status block_forward(const ls_stage* s, int l, int T, const FwdBufs& f, const
 // is produced by block l's last kernel; block 0 normalises its input itself.
 bool fused_decode_ok(const ls_stage* s, int T) {
   const ls_config& c = s->cfg;
-  static const bool on = [] { const char* e = getenv("LS_DECODE_FUSED"); return !(e && strcmp(e, "0") == 0); }();
-  static const bool skinny_dma = [] { const char* e = getenv("LS_SKINNY_IMPL"); return !(e && strcmp(e, "mfma") == 0); }();
-  static const bool gemm_dma = [] { const char* e = getenv("LS_GEMM_IMPL"); return !(e && strcmp(e, "staged") == 0); }();
-  return on && skinny_dma && gemm_dma && T <= 128 && c.mma_dtype != LS_F32 && c.d_model % 64 == 0 && c.d_ff % 64 == 0 &&
+  return T <= 128 && c.mma_dtype != LS_F32 && c.d_model % 64 == 0 && c.d_ff % 64 == 0 &&
          c.d_model <= 8192;
 }
 

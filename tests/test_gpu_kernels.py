@@ -143,24 +143,6 @@ def test_gemm_accumulates_into_fp32_buffers_with_128_tiles(name):
     assert_close(host(out), f64(At).T @ f64(Bk), 1e-5, "weight-gradient layout, overwriting")
 
 
-@pytest.mark.parametrize("name", ["bf16", "f16"])
-@pytest.mark.parametrize("M,N,K", [(64, 1048, 4096), (4, 72, 136), (33, 264, 11008), (128, 520, 768), (1, 64, 32)])
-@pytest.mark.parametrize("split", [True, False])
-def test_gemm_skinny_weight_streaming(name, M, N, K, split):
-    X = q(S.normal(9, "X", (M, K)), name)
-    W = q(S.normal(9, "W", (N, K), 0.05), name)
-    bias = q(S.normal(9, "b", (N,)), "bf16")
-    R = S.normal(9, "R", (M, N))
-    ref = X.astype(np.float64) @ W.astype(np.float64).T
-    out = torch.empty(M, N, dtype=torch.float32, device="cuda")
-    Bd.lsk_gemm_skinny(dev(X, DT[name]), dev(W, DT[name]), out, bias=dev(bias, torch.bfloat16),
-                       resid=dev(R, torch.float32), split=split)
-    assert_close(host(out), ref + bias + R, 1e-5, "skinny gemm fp32 out")
-    out16 = torch.empty(M, N, dtype=DT[name], device="cuda")
-    Bd.lsk_gemm_skinny(dev(X, DT[name]), dev(W, DT[name]), out16, split=split)
-    assert_close(host(out16), ref, otol(name, ref), "skinny gemm 16-bit out")
-
-
 @pytest.mark.parametrize("name", ["f16", "bf16"])
 @pytest.mark.parametrize("M,N,K,out,res", [(512, 4096, 4096, "f32", True), (512, 4096, 11008, "f32", True),
                                             (300, 520, 2048, "op", False), (256, 264, 4096, "op", False),
@@ -441,6 +423,54 @@ def test_attention_backward_with_rotary_backward(impl, name, B, L, h, dh):
         assert_close(got[:, i * d:(i + 1) * d], r_, otol(name, r_, 1e-4), nm + " (rotary backward)")
 
 
+@pytest.mark.parametrize("name,B,L,h,heads", [
+    ("f16", 2, 2048, 32, [(0, 0), (0, 17), (1, 31)]),      # the training micro-batch of the LLaMA-7B-shaped stage
+    ("bf16", 1, 2048, 32, [(0, 5)]),                       # config 4's training stream, bf16 operands
+    ("f16", 1, 4096, 40, [(0, 0), (0, 39)]),               # LLaMA-13B-shaped stage, one sequence of 4096
+    ("f16", 1, 4096, 2, [(0, 0), (0, 1)]),                 # few heads: every (sequence, head) pair checked
+])
+def test_attention_at_the_benchmarked_sizes_on_sampled_heads(name, B, L, h, heads):
+    """The launches bench.py times (head_dim 128, all heads, L = 2048 and 4096: 16 and 32 query tiles
+    per head, dispatched heaviest first over every head), forward and both backward kernels, with and
+    without the fused rotary backward.  The float64 definition is formed for the sampled (sequence,
+    head) pairs only: heads do not interact, and one head's 4096 x 4096 probability matrix is 134 MB."""
+    dh = 128
+    d = h * dh
+    dt = DT[name]
+    qd = S.normal_torch(23, "qkv", (B * L, 3 * d), 1.0, "cuda", dt)
+    dOd = S.normal_torch(23, "dO", (B * L, d), 1.0, "cuda", dt)
+    o = torch.empty(B * L, d, dtype=dt, device="cuda")
+    lse = torch.empty(B * L, h, dtype=torch.float32, device="cuda")
+    Bd.lsk_attn_fwd(1, qd, B, L, h, dh, o, lse)
+    dqkv = torch.empty(B * L, 3 * d, dtype=dt, device="cuda")
+    Bd.lsk_attn_bwd(1, qd, o, dOd, lse, B, L, h, dh, dqkv)
+    dqkv_r = torch.empty_like(dqkv)
+    pos = torch.arange(L, dtype=torch.int32, device="cuda").repeat(B)
+    Bd.lsk_attn_bwd_rope(1, qd, o, dOd, lse, B, L, h, dh, dqkv_r, pos, dev(rope_table(L, dh), torch.float32))
+    torch.cuda.synchronize()
+    assert torch.isfinite(o.float()).all() and torch.isfinite(dqkv.float()).all()
+    for b, j in heads:
+        rows = slice(b * L, (b + 1) * L)
+        col = lambda part: slice(part * d + j * dh, part * d + (j + 1) * dh)
+        qq, kk, vv = (host(qd[rows, col(i)]).reshape(L, 1, dh) for i in range(3))
+        do = host(dOd[rows, col(0)]).reshape(L, 1, dh)
+        o_ref, P = O.attention(qq, kk, vv, 0)
+        what = f"{name} L={L} sequence {b} head {j}: "
+        assert_close(host(o[rows, col(0)]), o_ref.reshape(L, dh), otol(name, o_ref, 1e-4), what + "o")
+        sc = (qq[:, 0] @ kk[:, 0].T) / math.sqrt(dh)
+        sc = np.where(np.tril(np.ones((L, L), bool)), sc, -np.inf)
+        m = sc.max(1)
+        lse_ref = m + np.log(np.exp(sc - m[:, None]).sum(1))
+        assert np.abs(host(lse[rows, j]) - lse_ref).max() < 2e-2
+        dq, dk, dv = O.attention_bwd(do, qq, kk, vv, P)
+        for i, (nm, r_) in enumerate((("dq", dq), ("dk", dk), ("dv", dv))):
+            r_ = r_.reshape(L, dh)
+            assert_close(host(dqkv[rows, col(i)]), r_, otol(name, r_, 1e-4), what + nm)
+            if i < 2:
+                r_ = O.rope(r_.reshape(L, 1, dh), np.arange(L), 1e4, -1.0).reshape(L, dh)
+            assert_close(host(dqkv_r[rows, col(i)]), r_, otol(name, r_, 1e-4), what + nm + " (rotary backward)")
+
+
 @pytest.mark.parametrize("name", ["f16", "bf16"])
 @pytest.mark.parametrize("T,h,dh", [(70, 2, 64), (300, 3, 128), (4096, 32, 128), (2304, 16, 128)])
 def test_qkv_projection_with_fused_rotary_embedding(name, T, h, dh):
@@ -469,9 +499,13 @@ def test_qkv_projection_with_fused_rotary_embedding(name, T, h, dh):
         assert_close(got[:, sl], ref[:, sl], tol, "qkv+rope " + nm)
 
 
+@pytest.mark.parametrize("fill", ["gauss", "nan", "inf"])
 @pytest.mark.parametrize("impl", [0, 1])
 @pytest.mark.parametrize("name,h,dh,P", [("f32", 4, 32, 16), ("f16", 2, 128, 16), ("bf16", 3, 64, 8)])
-def test_paged_attention_ragged(impl, name, h, dh, P):
+def test_paged_attention_ragged(impl, name, h, dh, P, fill):
+    """`fill`: what the slots that no request has written hold - the tail of every last page and the spare
+    pages.  A pool straight from the allocator may hold any bit pattern there, NaN and infinity included,
+    and none of it may reach a result."""
     if impl == 1 and name == "f32":
         pytest.skip("optimised paged attention is 16-bit only")
     d = h * dh
@@ -483,6 +517,11 @@ def test_paged_attention_ragged(impl, name, h, dh, P):
     qkv = q(S.normal(8, "qkv", (T, 3 * d)), name)
     kp = q(rng.normal(0, 1, (n_pages, h, P, dh)), name)   # garbage everywhere, real rows overwritten below
     vp = q(rng.normal(0, 1, (n_pages, h, P, dh)), name)
+    if fill == "nan":
+        kp[:], vp[:] = np.nan, np.nan
+    elif fill == "inf":
+        kp[:] = np.where(rng.random(kp.shape) < 0.5, np.inf, -np.inf)
+        vp[:] = np.where(rng.random(vp.shape) < 0.5, np.inf, -np.inf)
     Kc = [q(S.normal(8, f"K{b}", (int(c), h, dh)), name) for b, c in enumerate(ctx)]
     Vc = [q(S.normal(8, f"V{b}", (int(c), h, dh)), name) for b, c in enumerate(ctx)]
     for b in range(len(ctx)):

@@ -165,7 +165,7 @@ def test_accumulate_adds_microbatch_gradients():
     st.close()
 
 
-def serve_case(cfg, mma, ctx, new, seed=0):
+def serve_case(cfg, mma, ctx, new, seed=0, junk_kind="gauss"):
     """Direct-filled cache (seeded N(0,1) K/V per layer), then one call with
     `new[b]` new tokens per request; returns (gpu Y, oracle Y, errors on new KV rows)."""
     st, flat, _ = make_stage(cfg, mma=mma, io="f32" if cfg["dtype"] == "bf16" else None)
@@ -184,6 +184,10 @@ def serve_case(cfg, mma, ctx, new, seed=0):
     kp, vp = pool_from_oracle_cache(cache, table, n_pages, cfg)
     # unused slots hold garbage that must not leak into any result
     junk = np.random.default_rng(1).normal(0, 50, kp.shape).astype(np.float32)
+    if junk_kind == "nan":
+        junk[:] = np.nan
+    elif junk_kind == "inf":
+        junk[:] = np.where(junk > 0, np.inf, -np.inf)
     used = np.zeros(kp.shape[:2] + (1, P, 1), bool)
     for b in range(Bq):
         for j in range(int(ctx[b])):
@@ -221,6 +225,21 @@ def test_ragged_decode_over_shuffled_pages(which, mma):
     ctx = np.array([0, 1, 15, 16, 17, 100, 333, 257, 64, 31])
     Y, Yr, kv_err = serve_case(cfg, mma, ctx, np.ones_like(ctx))
     assert_close(Y, Yr, TOL["bf16"], "decode Y")
+    assert kv_err <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("junk", ["nan", "inf"])
+def test_unwritten_page_slots_may_hold_nan_or_infinity(junk):
+    """A caller may hand over pools straight from the allocator: the slots of a last page beyond the context,
+    and the spare pages, hold NaN or infinities here.  Decode steps and prompt chunks give the oracle's result."""
+    ctx = np.array([0, 1, 15, 16, 17, 100, 333, 257, 64, 31])
+    Y, Yr, kv_err = serve_case(SMALL_LLAMA, "f16", ctx, np.ones_like(ctx), junk_kind=junk)
+    assert np.isfinite(Y).all()
+    assert_close(Y, Yr, TOL["bf16"], "decode Y")
+    assert kv_err <= TOL["bf16"]
+    Y, Yr, kv_err = serve_case(SMALL_LLAMA, "f16", np.array([0, 128, 37, 5]), np.array([96, 64, 1, 130]), junk_kind=junk)
+    assert np.isfinite(Y).all()
+    assert_close(Y, Yr, TOL["bf16"], "prefill Y")
     assert kv_err <= TOL["bf16"]
 
 
