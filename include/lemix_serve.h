@@ -7,7 +7,9 @@
  *
  * The server owns what the loop needs beyond the stage: the batcher, the page
  * allocator over the caller's KV pool (a free list; a request holds
- * ceil(tokens / page_size) pages and returns them when it finishes), the
+ * ceil(tokens / page_size) pages and returns them when it finishes; it starts
+ * only once the pages of its whole sequence can be set aside, so every started
+ * request runs to its end and the loop always drains), the
  * per-request progress, and small device buffers allocated in
  * ls_server_create (the batch's X and Y rows, block table, context lengths,
  * row pointers) and freed in ls_server_destroy.
@@ -55,9 +57,12 @@ typedef struct {
   int32_t n_decode;         /* decode rows executed */
   int32_t n_prefill;        /* prompt chunks executed */
   int32_t n_rows;           /* rows executed = n_decode + sum of chunk lengths; 0: nothing launched */
-  int32_t n_stalled;        /* batch members left out of this pass (no free page, chunk or row budget) */
+  int32_t n_stalled;        /* batch members left out of this pass (pages of the whole sequence cannot be
+                               set aside yet, or the pass has no chunk or row left) */
   int32_t n_finished;       /* requests that completed with this pass */
-  int32_t free_pages;       /* after the pass */
+  int32_t free_pages;       /* pages in no request's hands, after the pass */
+  int32_t unreserved_pages; /* pages that no started request has set aside, after the pass: a waiting
+                               request starts when its ceil((prompt_len + n_decode) / page_size) fit here */
 } ls_pass_report;
 
 /* k_pool, v_pool [dev]: as in ls_kv, with cfg->n_pages pages.  LS_EINVAL for

@@ -12,7 +12,11 @@ file models which rows run in which pass:
     and max_tokens rows per pass; members that get no row wait for the next pass;
   - KV pages: a request holds ceil(cached tokens / page_size) pages, taken from a free list
     (page 0 first; returned pages are reused last-in first-out) just before the rows that need
-    them run, all or nothing; a member that cannot get its pages waits.
+    them run.  A request gets its first rows only when the pages of its whole sequence,
+    ceil((prompt_len + n_decode) / page_size), can be set aside out of the pages that no started
+    request has set aside; until then it waits in the batch.  Started requests therefore always
+    find their pages and finish, which returns their pages: the loop cannot stall with the pool
+    full of partly served requests.
 A request of prompt_len prompt rows and n_decode decode steps is finished after
 prompt_len + n_decode rows.
 """
@@ -23,17 +27,23 @@ class ServeModel:
     def __init__(self, C, T_w, n_pages, page_size, max_chunk, max_tokens):
         self.b = Batcher(C, T_w)
         self.free = list(range(n_pages - 1, -1, -1))
+        self.unreserved = n_pages
         self.P, self.max_chunk, self.max_tokens = page_size, max_chunk, max_tokens
         self.req = {}
 
     def submit(self, rid, prompt_len, n_decode):
         self.b.push(rid, False)
-        self.req[rid] = dict(prompt=prompt_len, total=prompt_len + n_decode, done=0, pages=[])
+        self.req[rid] = dict(prompt=prompt_len, total=prompt_len + n_decode, done=0, pages=[], reserved=0)
 
     def _take(self, r, rows):
+        if not r["reserved"]:
+            whole = -(-r["total"] // self.P)
+            if whole > self.unreserved:
+                return False
+            r["reserved"] = whole
+            self.unreserved -= whole
         need = -(-(r["done"] + rows) // self.P) - len(r["pages"])
-        if need > len(self.free):
-            return False
+        assert need <= len(self.free)
         for _ in range(need):
             r["pages"].append(self.free.pop())
         return True
@@ -66,6 +76,8 @@ class ServeModel:
             if r["done"] >= r["total"]:
                 finished.append(rid)
         for rid in finished:
-            self.free.extend(self.req.pop(rid)["pages"])
+            r = self.req.pop(rid)
+            self.free.extend(r["pages"])
+            self.unreserved += r["reserved"]
         self.b.finish(finished)
         return members, finished, pages, len(batch), len(new)

@@ -25,6 +25,7 @@ struct Request {
   const char* X;
   char* Y;
   int prompt_len, total, done;
+  int reserved = 0;   // pages set aside for the whole sequence once the request has started (0: not started)
   std::vector<int32_t> pages;
 };
 
@@ -40,6 +41,7 @@ struct ls_server {
   ls_batcher* batcher = nullptr;
   std::unordered_map<int64_t, Request> req;
   std::vector<int32_t> free_pages;
+  int unreserved = 0;   // pages of the pool that no started request has set aside
   int row_bytes;
   // per pass: [block table B x maxp][ctx_len B] int32, then [x ptr rows][y ptr rows] u64
   size_t stage_bytes, ptr_off;
@@ -86,6 +88,7 @@ ls_status ls_server_create(ls_stage* s, const ls_server_config* cfg, void* k_poo
   sv->row_bytes = sv->c.d_model * (int)dtype_size(sv->c.io_dtype);
   sv->free_pages.resize(cfg->n_pages);
   for (int i = 0; i < cfg->n_pages; ++i) sv->free_pages[i] = cfg->n_pages - 1 - i;  // page 0 is handed out first
+  sv->unreserved = cfg->n_pages;
   sv->ptr_off = align_up(((size_t)cfg->max_batch * cfg->max_pages_per_req + cfg->max_batch) * sizeof(int32_t), 16);
   sv->stage_bytes = sv->ptr_off + 2 * (size_t)cfg->max_tokens * sizeof(uint64_t);
   bool ok = true;
@@ -140,15 +143,24 @@ ls_status ls_server_pass(ls_server* sv, double now, void* workspace, void* strea
   std::vector<int64_t> batch(sv->cfg.max_batch);
   int n_batch = 0, n_new = 0, blocked = 0;
   LS_TRY(ls_batcher_form(sv->batcher, now, batch.data(), &n_batch, &n_new, &blocked));
-  ls_pass_report rep = {n_batch, n_new, 0, 0, 0, 0, 0, 0};
+  ls_pass_report rep = {n_batch, n_new, 0, 0, 0, 0, 0, 0, 0};
 
   // the pass's members: decode rows first, then prompt chunks, each in batch order
   struct Member { int64_t id; int rows; };
   std::vector<Member> dec, pre;
   int rows_left = sv->cfg.max_tokens;
+  // A request starts only when the pages of its whole sequence can be set aside: members that have started
+  // then always find the pages their next rows need, so every one of them finishes and the pool cannot fill
+  // up with partly served requests that all wait for each other.  (One request alone always fits: submit
+  // checks it.)  The pages themselves are still taken from the free list just before the rows that need them.
   auto take_pages = [&](Request& r, int rows) {
+    if (r.reserved == 0) {
+      const int whole = (r.total + P - 1) / P;
+      if (whole > sv->unreserved) return false;
+      r.reserved = whole;
+      sv->unreserved -= whole;
+    }
     const int need = (r.done + rows + P - 1) / P - (int)r.pages.size();
-    if (need > (int)sv->free_pages.size()) return false;
     for (int i = 0; i < need; ++i) { r.pages.push_back(sv->free_pages.back()); sv->free_pages.pop_back(); }
     return true;
   };
@@ -223,6 +235,7 @@ ls_status ls_server_pass(ls_server* sv, double now, void* workspace, void* strea
     for (size_t i = 0; i < fin.size(); ++i) {
       Request& r = sv->req.at(fin[i]);
       for (int32_t pg : r.pages) sv->free_pages.push_back(pg);
+      sv->unreserved += r.reserved;
       sv->req.erase(fin[i]);
       if (finished_ids) finished_ids[i] = fin[i];
     }
@@ -230,6 +243,7 @@ ls_status ls_server_pass(ls_server* sv, double now, void* workspace, void* strea
     rep.n_finished = (int)fin.size();
   }
   rep.free_pages = (int)sv->free_pages.size();
+  rep.unreserved_pages = sv->unreserved;
   if (report) *report = rep;
   return LS_OK;
 }

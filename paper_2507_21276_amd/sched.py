@@ -175,7 +175,7 @@ class ls_server_config(C.Structure):
 
 class ls_pass_report(C.Structure):
     _fields_ = [(k, C.c_int32) for k in ("n_batch", "n_new", "n_decode", "n_prefill", "n_rows", "n_stalled",
-                                         "n_finished", "free_pages")]
+                                         "n_finished", "free_pages", "unreserved_pages")]
 
 
 class Server:

@@ -12,6 +12,7 @@ import torch
 from oracle import stage_oracle as O
 from paper_2507_21276_amd import binding as Bd
 from paper_2507_21276_amd import synth_inputs as S
+import storage_rounding_model as M
 from parity_util import (TOL, assert_close, dev, gather_rows_from_pool, host, param_slices,
                          pool_from_oracle_cache, rel_err)
 
@@ -46,17 +47,25 @@ def run_train(st, cfg, X, dY, B, L, accumulate_twice=False):
 
 
 def check_train(cfg, B, L, mma, dy_std=1.0, io=None, tol=None, perturb=0.1):
+    """tol: one bar for every tensor, or "storage model": per tensor, the larger of the 2e-2 bar and twice what
+    bf16 storage alone costs that tensor (tests/storage_rounding_model.py)."""
     st, flat, _ = make_stage(cfg, mma=mma, io=io, perturb=perturb)
-    tol = tol or TOL[cfg["dtype"]]
     d = cfg["d_model"]
     X = S.make_activations(cfg, "X", (B, L, d))
     dY = S.make_activations(cfg, "dY", (B, L, d), std=dy_std)
-    Yr, saved = O.stage_train_fwd(cfg, flat.astype(np.float64), X.astype(np.float64))
-    dXr, dPr = O.stage_train_bwd(cfg, flat.astype(np.float64), saved, dY.astype(np.float64))
+    f64 = flat.astype(np.float64)
+    Yr, saved = O.stage_train_fwd(cfg, f64, X.astype(np.float64))
+    dXr, dPr = O.stage_train_bwd(cfg, f64, saved, dY.astype(np.float64))
+    if tol == "storage model":
+        model = M.errors(cfg, (Yr, dXr, dPr), M.train(cfg, f64, X.astype(np.float64), dY.astype(np.float64),
+                                                      set(M.NAMES), M.round_bf16))
+        bar = lambda name: max(TOL["bf16"], 2.0 * model[name])
+    else:
+        bar = lambda name: tol or TOL[cfg["dtype"]]
     Y, dX, dP = run_train(st, cfg, X, dY, B, L)
-    errs = {"Y": assert_close(Y, Yr, tol, "Y"), "dX": assert_close(dX, dXr, tol, "dX")}
+    errs = {"Y": assert_close(Y, Yr, bar("Y"), "Y"), "dX": assert_close(dX, dXr, bar("dX"), "dX")}
     for name, off, n in param_slices(cfg):
-        errs[name] = assert_close(dP[off:off + n], dPr[off:off + n], tol, "grad " + name)
+        errs[name] = assert_close(dP[off:off + n], dPr[off:off + n], bar(name), "grad " + name)
     st.close()
     return errs
 
@@ -118,12 +127,14 @@ SMALL_LLAMA = S.scaled(S.CONFIGS["llama7b_bf16"], n_layers=2, d_model=256, n_hea
 def test_small_bf16_stage_train(which, mma):
     cfg = SMALL_GPT if which == "gpt" else SMALL_LLAMA
     B, L = (2, 160) if which == "gpt" else (2, 200)   # several tiles and a ragged tail
-    # fp16 operands meet the 2e-2 bar.  bf16 operands cannot: every stored
-    # activation carries a 2^-9 relative rounding and the weight gradients sum
-    # thousands of such products, so that mode is held to a looser 1e-1 and is
-    # offered for range, not accuracy.
+    # fp16 operands meet the 2e-2 bar.  With bf16 operands every activation and gradient the stage stores carries
+    # a 2^-9 relative rounding, and that storage alone - exact arithmetic otherwise - puts 4-7e-2 into the weight
+    # gradients (tests/test_storage_rounding_model.py derives it on the CPU): the bar for that mode is, per
+    # tensor, the larger of 2e-2 and twice the storage model's figure.  Y and dX meet 2e-2 in both modes.
     errs = check_train(cfg, B, L, mma, dy_std=1.0 if which == "gpt" else 1e-2, io="f32",
-                       tol=TOL["bf16"] if mma == "f16" else 1e-1)
+                       tol=TOL["bf16"] if mma == "f16" else "storage model")
+    if mma == "bf16":
+        assert errs["Y"] <= TOL["bf16"] and errs["dX"] <= TOL["bf16"]
     print(which, mma, "worst", max(errs.items(), key=lambda kv: kv[1]))
 
 
@@ -355,10 +366,9 @@ def test_hybrid_batch_of_decode_rows_and_prompt_chunks(which, mma):
     new = np.array([1, 1, 1, 1, 1, 1, 70, 300, 33])
     Y, Yr, kv_err = hybrid_case(cfg, mma, ctx, new, n_decode=6)
     tol = TOL["bf16"] if mma else TOL["f32"]
-    if mma == "bf16":
-        tol = 1e-1   # bf16 operands: outside the 2e-2 bar by design, held to 1e-1 (see the stage tests)
     assert_close(Y, Yr, tol, "hybrid Y")
-    assert kv_err <= tol
+    # K / V rows stored in bf16 carry half an ulp of their largest element (about 4 RMS): 2^-9 * 4 on top of the bar
+    assert kv_err <= tol + (2.0 ** -7 if mma == "bf16" else 0.0)
     # degenerate mixes: decode rows only, prompt chunks only
     Y, Yr, _ = hybrid_case(cfg, mma, ctx[:6], new[:6], n_decode=6)
     assert_close(Y, Yr, tol, "hybrid, decode rows only")

@@ -46,3 +46,24 @@ def test_row_budget_and_page_shortage_make_members_wait():
     m.submit(1, 2, 0)
     assert m.run_pass(0.0)[0] == [(0, 0, 2)]
     assert m.run_pass(0.1)[0] == [(1, 0, 2)]
+
+
+def test_a_pool_that_cannot_hold_two_whole_requests_serves_them_one_after_the_other():
+    """Two requests of three pages each over a pool of three pages.  Handing out pages chunk by chunk would give
+    each of them one page in the first pass and leave both waiting for ever; with the pages of the whole
+    sequence set aside at the start, request 1 waits until request 0 has finished, and the loop drains."""
+    m = ServeModel(2, 1.0, 3, 4, 4, 8)
+    m.submit(0, 8, 4)
+    m.submit(1, 8, 4)
+    assert m.run_pass(0.0)[0] == [(0, 0, 4)] and m.unreserved == 0
+    assert m.run_pass(0.1)[0] == [(0, 4, 4)]
+    for k in range(4):
+        mem, fin, pages, nb, _ = m.run_pass(0.2 + 0.1 * k)
+        assert mem == [(0, 8 + k, 1)] and nb == 2 and fin == ([0] if k == 3 else [])
+    assert m.unreserved == 3 and sorted(m.free) == [0, 1, 2]
+    assert m.run_pass(0.7)[0] == [(1, 0, 4)]
+    n = 1
+    while m.req:
+        assert m.run_pass(0.7 + 0.1 * n)[0]     # every pass makes progress
+        n += 1
+    assert n == 6 and m.unreserved == 3
