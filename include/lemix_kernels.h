@@ -223,6 +223,22 @@ ls_status lsk_attn_paged(int impl, const void* qkv, int dtype, int T, int n_head
 size_t lsk_attn_paged_scratch_floats(int T, int n_heads, int head_dim, int max_ctx, int page_size);
 
 /*
+ * lsk_attn_paged (impl 1: 16-bit pools, head_dim 64 or 128, page_size * head_dim a multiple of 512) for callers
+ * that cannot allocate device memory: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid it.  Same arguments without `scratch`, same kernels, same result bit for bit; the per-split partial
+ * results go to a static array inside the library (2.03 MiB per GPU, held until the process ends) and the call
+ * allocates nothing, on the device or through any library.  LS_EINVAL when the launch would need more than the
+ * array holds (it cannot for the head sizes above: a launch splits only below 2048 (row, head) pairs), or on the
+ * argument errors of lsk_attn_paged.  Every call on one GPU shares that GPU's array: calls that overlap in time
+ * on the same GPU (two streams, two threads) race on it and must be serialised by the caller.  Nothing in the
+ * array needs clearing between calls: every launch writes each partial it later reads.
+ */
+ls_status lsk_attn_paged_noalloc(const void* qkv, int dtype, int T, int n_heads, int head_dim,
+                                 const int32_t* pos, const int32_t* req, const void* k_pool,
+                                 const void* v_pool, const int32_t* block_table, int max_pages_per_req,
+                                 int page_size, int max_ctx, void* o, void* stream);
+
+/*
  * Backward-pass gradient scaling.  stage_train_bwd runs the whole backward on
  * dY * 2^e so that 16-bit gradient operands stay in the fp16 normal range (the
  * matrix cores flush fp16 subnormal inputs), and multiplies every fp32 result by

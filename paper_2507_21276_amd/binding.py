@@ -113,6 +113,7 @@ SIGNATURES = {
     "lsk_rope_kv_write": (_I, [_VP, _I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP, _VP, _I, _I, _VP]),
     "lsk_attn_paged": (_I, [_I, _VP, _I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP, _I, _I, _I, _VP, _VP, _VP]),
     "lsk_attn_paged_scratch_floats": (_SZ, [_I, _I, _I, _I, _I]),
+    "lsk_attn_paged_noalloc": (_I, [_VP, _I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP, _I, _I, _I, _VP, _VP]),
     "lsk_gemm_partials": (_I, [_I, _I, _I, _I, _VP, _L, _VP, _L, _VP, _SZ, C.POINTER(_I), _VP]),
     "lsk_finish_resid_norm": (_I, [_VP, _I, _I, _I, _VP, _VP, _VP, _I, _VP, _VP, _I, _F, _VP, _I, _VP]),
     "lsk_finish_act": (_I, [_VP, _I, _I, _I, _I, _VP, _I, _VP, _I, _VP]),
@@ -453,6 +454,13 @@ def lsk_attn_paged(impl, qkv, n_heads, head_dim, pos, req, k_pool, v_pool, block
     _check(lib().lsk_attn_paged(impl, _p(qkv), CODE_OF_TORCH[qkv.dtype], T, n_heads, head_dim, _p(pos),
                                 _p(req), _p(k_pool), _p(v_pool), _p(block_table), block_table.shape[1],
                                 page_size, max_ctx, _p(o), _p(scratch), _stream(stream)))
+
+
+def lsk_attn_paged_noalloc(qkv, n_heads, head_dim, pos, req, k_pool, v_pool, block_table, page_size, max_ctx, o,
+                           stream=None):
+    _check(lib().lsk_attn_paged_noalloc(_p(qkv), CODE_OF_TORCH[qkv.dtype], qkv.shape[0], n_heads, head_dim, _p(pos),
+                                        _p(req), _p(k_pool), _p(v_pool), _p(block_table), block_table.shape[1],
+                                        page_size, max_ctx, _p(o), _stream(stream)))
 
 
 def _opt(t):

@@ -10,9 +10,18 @@
 // Softmax is online per wavefront; the four partial (max, sum, output) triples
 // are merged in LDS, and when the context was split across workgroups a second
 // kernel merges the per-split partials (deterministic, no atomics).
+#include <mutex>
+
 #include "common.h"
 
 namespace {
+
+// Scratch of the entry point that allocates nothing (lsk_attn_paged_noalloc): the per-split partial results
+// (output, maximum, sum) of a context split over workgroups.  A launch splits only below 2048 (row, head)
+// pairs and then has fewer than 4096 (row, head, split) items of head_dim + 2 floats, head_dim <= 128.
+// One copy per GPU, held until the process ends; every call on a GPU shares it.
+constexpr size_t kStaticScratchFloats = (size_t)4096 * (128 + 2);   // 2.03 MiB
+static __device__ __align__(256) float scratch[kStaticScratchFloats];
 
 template <class T, int DH>
 __global__ __launch_bounds__(256) void decode_attn_kernel(
@@ -179,6 +188,27 @@ ls_status launch(const void* qkv, int T_, int h, const int32_t* pos, const int32
   return LS_OK;
 }
 
+// Device address of `scratch` on the current GPU.  The array's name is a host-side stand-in, not a device
+// address: the address comes from hipGetSymbolAddress, once per device with that device current (each GPU has
+// its own copy at its own address), and only that pointer is handed to kernels.
+ls_status static_scratch(float** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static float* ptrs[kMaxDevices] = {};
+  int dev = -1;
+  LS_CHECK_HIP(hipGetDevice(&dev));
+  LS_REQUIRE(dev >= 0 && dev < kMaxDevices, "attn_paged_noalloc: device index %d outside 0..%d", dev, kMaxDevices - 1);
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptrs[dev]) {
+    float* p = nullptr;
+    LS_CHECK_HIP(hipGetSymbolAddress((void**)&p, HIP_SYMBOL(scratch)));
+    LS_REQUIRE(p != nullptr, "attn_paged_noalloc: the scratch array has no device address");
+    ptrs[dev] = p;
+  }
+  *out = ptrs[dev];
+  return LS_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -204,6 +234,23 @@ ls_status lsk_attn_decode(const void* qkv, int dt, int T, int h, int dh, const i
                     : launch<bf16_t, 128>(qkv, T, h, pos, req, k_pool, v_pool, block_table, max_pages, page, max_ctx, o, scratch, st);
   return dh == 64 ? launch<f16_t, 64>(qkv, T, h, pos, req, k_pool, v_pool, block_table, max_pages, page, max_ctx, o, scratch, st)
                   : launch<f16_t, 128>(qkv, T, h, pos, req, k_pool, v_pool, block_table, max_pages, page, max_ctx, o, scratch, st);
+}
+
+// lsk_attn_paged with impl 1 for callers that cannot allocate: the split partials go to the library's static
+// per-GPU scratch instead of a caller buffer.  No allocation of any kind happens in this call.
+ls_status lsk_attn_paged_noalloc(const void* qkv, int dt, int T, int h, int dh, const int32_t* pos, const int32_t* req,
+                                 const void* k_pool, const void* v_pool, const int32_t* block_table, int max_pages,
+                                 int page, int max_ctx, void* o, void* stream) {
+  LS_REQUIRE(T > 0 && h > 0 && max_ctx > 0 && page > 0, "attn_paged_noalloc: non-positive size");
+  LS_REQUIRE(dh == 64 || dh == 128, "attn_paged_noalloc: head_dim must be 64 or 128");
+  const size_t need = lsk_attn_decode_scratch_floats(T, h, dh, max_ctx, page);
+  LS_REQUIRE(need <= kStaticScratchFloats,
+             "attn_paged_noalloc: this launch needs %zu scratch floats, the static scratch holds %zu", need,
+             kStaticScratchFloats);
+  float* sp = nullptr;
+  LS_TRY(static_scratch(&sp));
+  return lsk_attn_decode(qkv, dt, T, h, dh, pos, req, k_pool, v_pool, block_table, max_pages, page, max_ctx, o, sp,
+                         stream);
 }
 
 }  // extern "C"
