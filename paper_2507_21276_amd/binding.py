@@ -138,6 +138,11 @@ SIGNATURES = {
     "ls_batcher_finish": (_I, [_VP, C.POINTER(C.c_int64), _I]),
     "ls_batcher_queued": (_I, [_VP]),
     "ls_batcher_batch_size": (_I, [_VP]),
+    # lemix_profile.h (wrappers and structures in profiler.py)
+    "ls_profile_reduce": (_I, [_VP, _I, _VP]),
+    "ls_profile_memory_threshold": (_I, [_D, _DP, _I, _DP, _DP]),
+    "ls_profile_time_train": (_I, [_VP, _VP, _I, _I, _VP, _VP, _VP, _VP, _VP, _VP, _VP, _I, _DP, _DP]),
+    "ls_profile_time_prefill": (_I, [_VP, _VP, C.POINTER(C.c_int32), _I, _VP, _VP, _VP, _VP, _I, _DP]),
     # lemix_serve.h (wrappers in sched.py)
     "ls_server_create": (_I, [_VP, _VP, _VP, _VP, C.POINTER(_VP)]),
     "ls_server_destroy": (None, [_VP]),

@@ -14,7 +14,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def declared_symbols():
     names = set()
-    for hdr in ("lemix_stage.h", "lemix_kernels.h", "lemix_sched.h", "lemix_serve.h"):
+    for hdr in ("lemix_stage.h", "lemix_kernels.h", "lemix_sched.h", "lemix_serve.h", "lemix_profile.h"):
         txt = open(os.path.join(ROOT, "include", hdr)).read()
         txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
         names |= set(re.findall(r"\b((?:ls|lsk|stage)_[a-z0-9_]+)\s*\(", txt))

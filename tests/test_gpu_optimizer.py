@@ -119,6 +119,12 @@ def test_offline_profiler_sweep_runs_the_stage_and_reduces_its_timings():
         assert r["train_fwd_s"] > 0 and r["train_bwd_s"] > r["train_fwd_s"] * 0.8 and r["prefill_s"] > 0
     assert rows[-1]["saved_bytes"] > rows[0]["saved_bytes"]
     s = PR.summarise(rows, kappa=0.9)
-    for k in ("eta_F_train", "eta_F_prefill", "eta_B"):
-        assert s[k]["eta_s_per_token_sq"] > 0
-    assert s["M_threshold_bytes"] == pytest.approx(0.9 * s["M_peak_bytes"])
+    # the library's reduction of the samples it measured itself, against the oracle's plain loops
+    from oracle import profile_oracle as PO
+    for key, name in (("train_fwd_s", "eta_F_train"), ("prefill_s", "eta_F_prefill"), ("train_bwd_s", "eta_B")):
+        samples = [(r["C"], r["l"], r[key]) for r in rows]
+        assert s[name]["eta_s_per_token_sq"] == pytest.approx(PO.eta(samples), rel=1e-12)
+        assert s[name]["worst_rel_err"] == pytest.approx(PO.worst_relative_error(PO.eta(samples), samples), rel=1e-9)
+    demand = [r["saved_bytes"] + r["workspace_bytes"] for r in rows]
+    assert s["M_peak_bytes"] == max(demand)
+    assert s["M_threshold_bytes"] == pytest.approx(PO.memory_threshold(0.9, demand), rel=1e-15)

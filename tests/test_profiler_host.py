@@ -1,4 +1,5 @@
-"""Offline profiler: the oracle's pins and the host-side reduction against the oracle (CPU only)."""
+"""Offline profiler: the oracle's pins and the library's reduction (include/lemix_profile.h, host code) against
+the oracle (CPU only)."""
 import math
 
 import pytest
@@ -43,23 +44,33 @@ def test_oracle_memory_threshold():
         PO.eta([])
 
 
-def test_host_reduction_matches_the_oracle():
+def test_library_reduction_matches_the_oracle():
     s = make(7e-10, SHAPES, noise=[1.3, 0.7, 1.0, 1.05, 0.95])
-    assert PR.fit_eta(s) == pytest.approx(PO.eta(s), rel=1e-14)
-    errs = PR.relative_errors(PR.fit_eta(s), s)
-    assert max(errs) == pytest.approx(PO.worst_relative_error(PO.eta(s), s), rel=1e-12)
-    assert PR.memory_threshold(0.8, [1e9, 5e9]) == PO.memory_threshold(0.8, [1e9, 5e9])
-    with pytest.raises(ValueError):
-        PR.fit_eta([])
+    f = PR.ls_profile_reduce(s)
+    assert f["eta"] == pytest.approx(PO.eta(s), rel=1e-14)
+    assert f["worst_rel_err"] == pytest.approx(PO.worst_relative_error(PO.eta(s), s), rel=1e-12)
+    mean = sum(abs(PO.predicted(PO.eta(s), C, l) - t) / t for C, l, t in s) / len(s)
+    assert f["mean_rel_err"] == pytest.approx(mean, rel=1e-12)
+    assert PR.ls_profile_memory_threshold(0.8, [1e9, 5e9]) == (5e9, PO.memory_threshold(0.8, [1e9, 5e9]))
+    # the average of the normalised times, not a least-squares fit (the oracle's own pin, through the library)
+    assert PR.ls_profile_reduce([(1, 10, 1.0 * 100), (1, 1000, 3.0 * 1e6)])["eta"] == pytest.approx(2.0)
+    from paper_2507_21276_amd import binding as Bd
+    for bad in ([], [(0, 10, 1.0)], [(1, 10, 0.0)], [(1, 0, 1.0)]):
+        with pytest.raises(Bd.LsError):
+            PR.ls_profile_reduce(bad)
+    for kappa, demands in ((0.9, []), (0.0, [1.0]), (1.5, [1.0])):
+        with pytest.raises(Bd.LsError):
+            PR.ls_profile_memory_threshold(kappa, demands)
 
 
 def test_two_term_fit_recovers_linear_and_quadratic_parts():
     a, b = 4e-7, 2e-10
     s = [(C, l, a * C * l + b * C * l * l) for C, l in SHAPES]
-    fa, fb = PR.fit_linear_quadratic(s)
-    assert fa == pytest.approx(a, rel=1e-9) and fb == pytest.approx(b, rel=1e-9)
-    with pytest.raises(ValueError):
-        PR.fit_linear_quadratic([(1, 100, 1.0)])   # one length cannot separate l from l^2
+    f = PR.ls_profile_reduce(s)
+    assert f["has_two_term"] == 1 and f["a2"] == pytest.approx(a, rel=1e-9) and f["b2"] == pytest.approx(b, rel=1e-9)
+    assert f["two_term_worst_rel_err"] < 1e-9
+    one = PR.ls_profile_reduce([(1, 100, 1.0)])     # one length cannot separate l from l^2
+    assert one["has_two_term"] == 0 and math.isnan(one["a2"])
 
 
 def test_summary_shape():
@@ -78,7 +89,7 @@ def test_three_term_fit_recovers_a_floor():
     c0, a, b = 2e-3, 4e-7, 2e-10
     shapes = SHAPES + [(4, 256), (1, 2048)]
     s = [(C, l, c0 + a * C * l + b * C * l * l) for C, l in shapes]
-    f0, fa, fb = PR.fit_floor_linear_quadratic(s)
-    assert f0 == pytest.approx(c0, rel=1e-6) and fa == pytest.approx(a, rel=1e-6) and fb == pytest.approx(b, rel=1e-6)
-    with pytest.raises(ValueError):
-        PR.fit_floor_linear_quadratic([(1, 100, 1.0), (2, 100, 2.0)])
+    f = PR.ls_profile_reduce(s)
+    assert f["has_three_term"] == 1 and f["three_term_worst_rel_err"] < 1e-6
+    assert f["c3"] == pytest.approx(c0, rel=1e-6) and f["a3"] == pytest.approx(a, rel=1e-6) and f["b3"] == pytest.approx(b, rel=1e-6)
+    assert PR.ls_profile_reduce([(1, 100, 1.0), (2, 100, 2.0)])["has_three_term"] == 0
