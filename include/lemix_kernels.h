@@ -226,10 +226,11 @@ size_t lsk_attn_paged_scratch_floats(int T, int n_heads, int head_dim, int max_c
  * lsk_attn_paged (impl 1: 16-bit pools, head_dim 64 or 128, page_size * head_dim a multiple of 512) for callers
  * that cannot allocate device memory: code under HIP graph capture, tight serving loops, harnesses that
  * forbid it.  Same arguments without `scratch`, same kernels, same result bit for bit; the per-split partial
- * results go to a static array inside the library (2.03 MiB per GPU, held until the process ends) and the call
+ * results go to a static array inside the library (8 MiB per GPU, held until the process ends) and the call
  * allocates nothing, on the device or through any library.  LS_EINVAL when the launch would need more than the
- * array holds (it cannot for the head sizes above: a launch splits only below 2048 (row, head) pairs), or on the
- * argument errors of lsk_attn_paged.  Every call on one GPU shares that GPU's array: calls that overlap in time
+ * array holds - lsk_attn_paged_scratch_floats(...) above 2 097 152 floats: batches of 2048 or more (row, head)
+ * pairs whose longest context takes many 512-token chunks, e.g. 128 rows x 40 heads with 4096-token contexts;
+ * every smaller launch fits - or on the argument errors of lsk_attn_paged.  Every call on one GPU shares that GPU's array: calls that overlap in time
  * on the same GPU (two streams, two threads) race on it and must be serialised by the caller.  Nothing in the
  * array needs clearing between calls: every launch writes each partial it later reads.
  */

@@ -17,17 +17,18 @@
 namespace {
 
 // Scratch of the entry point that allocates nothing (lsk_attn_paged_noalloc): the per-split partial results
-// (output, maximum, sum) of a context split over workgroups.  A launch splits only below 2048 (row, head)
-// pairs and then has fewer than 4096 (row, head, split) items of head_dim + 2 floats, head_dim <= 128.
-// One copy per GPU, held until the process ends; every call on a GPU shares it.
-constexpr size_t kStaticScratchFloats = (size_t)4096 * (128 + 2);   // 2.03 MiB
+// (output, maximum, sum; head_dim + 2 floats) of contexts split over workgroups.  8 MiB hold 16 131 (row, head,
+// split) items at head_dim 128: every launch below 2048 (row, head) pairs (fewer than 4096 items), and e.g. 64
+// rows x 32 heads with contexts up to 3584 tokens.  One copy per GPU, held until the process ends; every call
+// on a GPU shares it.
+constexpr size_t kStaticScratchFloats = (size_t)2 << 20;   // 8 MiB
 static __device__ __align__(256) float scratch[kStaticScratchFloats];
 
 template <class T, int DH>
 __global__ __launch_bounds__(256) void decode_attn_kernel(
     const T* __restrict__ qkv, const int32_t* __restrict__ pos_arr, const int32_t* __restrict__ req_arr,
     const T* __restrict__ k_pool, const T* __restrict__ v_pool, const int32_t* __restrict__ block_table,
-    int max_pages, int page, int h, int nsplit, float scale_log2, T* __restrict__ o,
+    int max_pages, int page, int h, int nsplit, int chunk_pages, float scale_log2, T* __restrict__ o,
     float* __restrict__ partial) {
   constexpr int LPT = DH / 8;        // lanes per token
   constexpr int TPL = 64 / LPT;      // tokens per wave-wide load (1 KB)
@@ -43,8 +44,19 @@ __global__ __launch_bounds__(256) void decode_attn_kernel(
   const int nkeys = pos_arr[t] + 1;
   const int req = req_arr[t];
   const int npages = (nkeys + page - 1) / page;
-  const int per = (npages + nsplit - 1) / nsplit;
+  // chunk_pages > 0: every split covers that many pages whatever the request's length (splits past its end
+  // are empty), so that the work items of a ragged batch are all about the same size; otherwise the
+  // request's own pages are divided evenly over the splits
+  const int per = chunk_pages > 0 ? chunk_pages : (npages + nsplit - 1) / nsplit;
   const int p_lo = split * per, p_hi = min(npages, p_lo + per);
+  if (p_lo >= p_hi && nsplit > 1) {   // an empty split: only its marker is read by the merge
+    if (threadIdx.x == 0) {
+      float* pp = partial + (((long)t * h + head) * nsplit + split) * (DH + 2);
+      pp[DH] = -INFINITY;
+      pp[DH + 1] = 0.f;
+    }
+    return;
+  }
   const int loads_per_page = page / TPL;   // page * DH * 2 bytes / 1 KB
   const int32_t* bt = block_table + (long)req * max_pages;
 
@@ -159,10 +171,25 @@ __global__ void decode_merge_kernel(const float* __restrict__ partial, int nspli
   o[t * (long)h * DH + head * DH + threadIdx.x] = from_f<T>(oo / ll);
 }
 
-int pick_nsplit(long items, int max_ctx, int page) {
+// Pages per split when the batch alone fills the chip (2048 or more (row, head) pairs): contexts of a ragged
+// batch differ by an order of magnitude, and with one workgroup per pair the compute units that drew the
+// long ones are still streaming when the others have finished.  Chunks of 512 tokens make every work item
+// about the same size; the partial results cost (dh + 2) floats per chunk against 512 * dh * 4 bytes read.
+constexpr int kChunkTokens = 512;
+
+int pick_nsplit(long items, int max_ctx, int page, int* chunk_pages) {
   // enough workgroups to fill 256 compute units a few times over, but never
   // fewer than 8 pages per split
   const int max_pages = (max_ctx + page - 1) / page;
+  *chunk_pages = 0;
+  if (items >= 2048) {
+    const int cp = kChunkTokens / page > 0 ? kChunkTokens / page : 1;
+    if (max_pages <= cp + cp / 2) return 1;
+    const int ns = (max_pages + cp - 1) / cp;
+    if (ns > 32) return 1;
+    *chunk_pages = cp;
+    return ns;
+  }
   int ns = (int)((2048 + items - 1) / items);
   const int cap = max_pages / 8 > 1 ? max_pages / 8 : 1;
   if (ns > cap) ns = cap;
@@ -175,11 +202,12 @@ ls_status launch(const void* qkv, int T_, int h, const int32_t* pos, const int32
                  const void* vp, const int32_t* bt, int max_pages, int page, int max_ctx, void* o,
                  float* scratch, hipStream_t st) {
   const long items = (long)T_ * h;
-  const int ns = scratch ? pick_nsplit(items, max_ctx, page) : 1;
+  int chunk_pages = 0;
+  const int ns = scratch ? pick_nsplit(items, max_ctx, page, &chunk_pages) : 1;
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
   decode_attn_kernel<T, DH><<<dim3((unsigned)items, ns), 256, 0, st>>>(
-      (const T*)qkv, pos, req, (const T*)kp, (const T*)vp, bt, max_pages, page, h, ns, scale_log2, (T*)o,
-      scratch);
+      (const T*)qkv, pos, req, (const T*)kp, (const T*)vp, bt, max_pages, page, h, ns, chunk_pages, scale_log2,
+      (T*)o, scratch);
   LS_CHECK_LAUNCH();
   if (ns > 1) {
     decode_merge_kernel<T, DH><<<(unsigned)items, DH, 0, st>>>(scratch, ns, h, (T*)o);
@@ -214,7 +242,8 @@ ls_status static_scratch(float** out) {
 extern "C" {
 
 size_t lsk_attn_decode_scratch_floats(int T, int h, int dh, int max_ctx, int page) {
-  const int ns = pick_nsplit((long)T * h, max_ctx, page);
+  int chunk_pages = 0;
+  const int ns = pick_nsplit((long)T * h, max_ctx, page, &chunk_pages);
   return ns > 1 ? (size_t)T * h * ns * (dh + 2) : 0;
 }
 

@@ -262,6 +262,14 @@ ls_status linear(const ls_stage* s, int T, int N, int K, const void* X, const vo
 }
 
 // attention of a serving call over the pages of layer-local pools kp / vp (the new rows are already in them)
+// the caller's scratch for the decode-attention kernel's split partials, when it is large enough for this launch
+float* attn_scratch(const ls_stage* s, int rows, int max_ctx, float* scratch) {
+  const ls_config& c = s->cfg;
+  if (!scratch) return nullptr;
+  return lsk_attn_paged_scratch_floats(rows, c.n_heads, c.head_dim, max_ctx, c.page_size) <= serve_scratch_floats(s)
+             ? scratch : nullptr;
+}
+
 ls_status serve_attention(const ls_stage* s, int T, const FwdBufs& f, const int32_t* pos, const int32_t* req, int B,
                           const ls_kv* kv, void* kp, void* vp, int max_ctx, const int32_t* chunk_start, int n_decode,
                           hipStream_t st) {
@@ -272,7 +280,7 @@ ls_status serve_attention(const ls_stage* s, int T, const FwdBufs& f, const int3
     if (n_decode > 0)
       LS_TRY(lsk_attn_paged(1, f.qkv, mt, n_decode, c.n_heads, c.head_dim, pos, req, kp, vp, kv->block_table,
                             kv->max_pages_per_req, c.page_size, max_ctx, f.o,
-                            (long)n_decode * c.n_heads < 2048 ? f.scratch : nullptr, st));
+                            attn_scratch(s, n_decode, max_ctx, f.scratch), st));
     // prompt chunks: matrix-core attention over the pages (queries of a chunk share the K/V tiles)
     const size_t e = osz(s);
     if (B > n_decode)
@@ -285,7 +293,7 @@ ls_status serve_attention(const ls_stage* s, int T, const FwdBufs& f, const int3
   }
   return lsk_attn_paged(mt == LS_F32 ? 0 : 1, f.qkv, mt, T, c.n_heads, c.head_dim, pos, req, kp, vp,
                         kv->block_table, kv->max_pages_per_req, c.page_size, max_ctx, f.o,
-                        (long)T * c.n_heads < 2048 ? f.scratch : nullptr, st);
+                        attn_scratch(s, T, max_ctx, f.scratch), st);
 }
 
 // n_decode (serving with chunk_start only): the first n_decode rows are single-token decode rows of

@@ -73,5 +73,10 @@ def test_no_alloc_entry_point_rejects_what_it_cannot_hold():
                           o.data_ptr(), None)
     assert lib.lsk_attn_paged_noalloc(*args(32, 2)) == Bd.LS_EINVAL          # head size outside the kernel's
     assert lib.lsk_attn_paged_noalloc(*args(128, 0)) == Bd.LS_EINVAL         # no rows
+    # 128 rows x 40 heads with contexts up to 4096 tokens split into eight 512-token chunks: 21 MB of partials
+    big = list(args(128, 128))
+    big[3], big[12] = 40, 4096
+    assert lib.lsk_attn_paged_scratch_floats(128, 40, 128, 4096, 16) > (2 << 20)
+    assert lib.lsk_attn_paged_noalloc(*big) == Bd.LS_EINVAL and b"static scratch" in lib.ls_last_error()
     assert lib.lsk_attn_paged_noalloc(*args(128, 2)) == Bd.LS_OK
     torch.cuda.synchronize()
