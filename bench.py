@@ -10,8 +10,10 @@ stage (bf16 parameters, 16-bit matrix-core operands, fp32 accumulation):
   3. two 512-token prefill chunks of one 1024-token prompt (stage_prefill x 2).
 All inputs are seeded, synthetic and resident in HBM before the timed region.
 `value` is tokens processed per second over the whole step; the per-leg rates,
-the GEMM and decode rooflines, the two-stream interference probe and the CPU
-oracle baseline are reported beside it on the same JSON line.
+the GEMM roofline (from HIP events around the stage's own GEMM launches, recorded by the
+library in a pass of its own), the decode roofline, the same legs with the other operand
+format, the two-stream interference probe and the CPU oracle baseline are reported beside
+it on the same JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--mma f16|bf16]
 """
@@ -161,6 +163,7 @@ def main():
     ap.add_argument("--no-probe", action="store_true")
     ap.add_argument("--no-cfg5", action="store_true", help="skip the config-5 decode measurement")
     ap.add_argument("--no-serve-loop", action="store_true", help="skip the continuous-batching loop measurement")
+    ap.add_argument("--no-other-mode", action="store_true", help="skip the legs with the other operand format")
     ap.add_argument("--no-update", action="store_true", help="skip the model-update measurement (3 fp32 vectors of the stage's size)")
     ap.add_argument("--legs", default="train,decode,prefill",
                     help="comma list of the legs that make up a step (profiling aid; the default is the full "
@@ -318,31 +321,64 @@ def main():
     log(f"train {ms_train:.2f} ms, decode {ms_dec:.3f} ms, prefill {ms_pre:.2f} ms; hybrid 64 decode rows + one "
         f"512-token chunk in one call {ms_hyb:.2f} ms")
 
-    # ---- GEMM roofline ---------------------------------------------------------------------
+    # ---- GEMM roofline: the stage's own GEMM launches of the training leg, bracketed by HIP events inside the
+    #      library (a pass of its own: the events add a few microseconds between launches) -----------------
     traffic = {}
-    try:   # HBM bytes measured with rocprofv3 --pmc in an earlier run of this same command
+    try:   # HBM bytes from rocprofv3 --pmc runs of this same command (see the file for command, date, commit)
         with open(os.path.join(ROOT, "profiles", "hbm_traffic.json")) as fh:
             traffic = json.load(fh)
     except OSError:
         pass
-    ms_gemms = time_events(torch, gemms, 5)
-    flop_block = 3.0 * T * (8.0 * d * d + 6.0 * d * F)       # fwd + dX + dW of one block
-    gemm_tflops = flop_block / (ms_gemms * 1e-3) / 1e12
-    roofline = {"bound": "mfma", "kernel": "gemm_dma16_kernel (4 fwd, 4 dX) + gemm_dma_kernel<256,256> (4 dW): 12 launches per block",
+    n_trace = 3
+    train()
+    torch.cuda.synchronize()
+    Bd.lsk_timing_begin()
+    for _ in range(n_trace):
+        train()
+    torch.cuda.synchronize()
+    tr = Bd.lsk_timing_end()
+    ms_g, n_g = tr["gemm"][0] / n_trace, tr["gemm"][1] // n_trace
+    flop_gemm = 3.0 * T * nL * (8.0 * d * d + 6.0 * d * F)      # fwd + dX + dW of every block
+    gemm_tflops = flop_gemm / (ms_g * 1e-3) / 1e12
+    ms_gemms = time_events(torch, gemms, 5)                       # the same 12 shapes as bare lsk_gemm calls
+    roofline = {"bound": "mfma", "kernel": "gemm_dma16_kernel (forward and input-gradient layouts) + gemm_dma_kernel<256,256> "
+                "(weight gradients): the %d GEMM launches of stage_train_fwd + stage_train_bwd" % n_g,
                 "achieved": gemm_tflops, "peak": PEAK_MFMA_TFLOPS, "unit": "TFLOP/s",
-                "frac": gemm_tflops / PEAK_MFMA_TFLOPS, "avg_launch_ms": ms_gemms / 12,
-                "flop_per_launch": flop_block / 12,
-                "traffic": traffic.get("gemm_dma_kernel_bytes_per_launch"),
-                "peak_measured_gaussian_operands": 1650.0}
-    log(f"GEMMs of one block: {ms_gemms:.2f} ms -> {gemm_tflops:.0f} TFLOP/s")
+                "frac": gemm_tflops / PEAK_MFMA_TFLOPS, "avg_launch_ms": ms_g / n_g, "launches_per_step": n_g,
+                "flop_per_launch": flop_gemm / n_g, "measured": "HIP events around every GEMM launch of %d traced "
+                "training steps (lsk_timing_begin / lsk_timing_end)" % n_trace,
+                "traffic": traffic.get("gemm_bytes_per_launch", traffic.get("gemm_dma_kernel_bytes_per_launch")), "traffic_source": traffic.get("source"),
+                "bare_gemm_calls_tflops": 3.0 * T * (8.0 * d * d + 6.0 * d * F) / (ms_gemms * 1e-3) / 1e12}
+    train_kinds = {"gemm_ms": ms_g, "attention_fwd_ms": tr["attn_fwd"][0] / n_trace,
+                   "attention_bwd_ms": tr["attn_bwd"][0] / n_trace}
+    attn_flop_fwd = 2.0 * L * L * d * B * nL
+    train_kinds["attention_fwd_tflops"] = attn_flop_fwd / (train_kinds["attention_fwd_ms"] * 1e-3) / 1e12
+    train_kinds["attention_bwd_tflops"] = 2.0 * attn_flop_fwd / (train_kinds["attention_bwd_ms"] * 1e-3) / 1e12
+    log(f"GEMMs of the training leg: {n_g} launches, {ms_g:.2f} ms -> {gemm_tflops:.0f} TFLOP/s "
+        f"(bare calls of one block's 12 shapes: {roofline['bare_gemm_calls_tflops']:.0f}); attention fwd "
+        f"{train_kinds['attention_fwd_ms']:.2f} ms, bwd {train_kinds['attention_bwd_ms']:.2f} ms")
 
     # ---- decode roofline: weights once + the KV of every cached token ---------------------------
     w_bytes = 2.0 * nL * (4.0 * d * d + 3.0 * d * F)
     kv_bytes = float((ctx + 1).sum()) * nL * 2 * d * 2
     dec_gbs = (w_bytes + kv_bytes) / (ms_dec * 1e-3) / 1e9
+    decode()
+    torch.cuda.synchronize()
+    Bd.lsk_timing_begin()
+    for _ in range(n_trace):
+        decode()
+    torch.cuda.synchronize()
+    td = Bd.lsk_timing_end()
+    dec_kinds = {k + "_ms": td[k][0] / n_trace for k in ("decode_attn", "decode_gemm", "finish")}
+    dec_kinds["decode_attn_gbs"] = kv_bytes / (dec_kinds["decode_attn_ms"] * 1e-3) / 1e9
+    dec_kinds["decode_gemm_gbs"] = w_bytes / (dec_kinds["decode_gemm_ms"] * 1e-3) / 1e9
     roofline_decode = {"bound": "hbm", "kernel": "stage_decode (whole call)", "achieved": dec_gbs,
                        "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": dec_gbs / PEAK_HBM_GBS,
-                       "bytes_per_step": w_bytes + kv_bytes, "traffic": traffic.get("decode_step_bytes")}
+                       "bytes_per_step": w_bytes + kv_bytes, "traffic": traffic.get("decode_step_bytes"),
+                       "traffic_source": traffic.get("source"), "by_kind": dec_kinds}
+    log(f"decode by kind: attention {dec_kinds['decode_attn_ms']:.3f} ms ({dec_kinds['decode_attn_gbs']:.0f} GB/s), "
+        f"projections {dec_kinds['decode_gemm_ms']:.3f} ms ({dec_kinds['decode_gemm_gbs']:.0f} GB/s), "
+        f"finish kernels {dec_kinds['finish_ms']:.3f} ms")
 
     # ---- interference probe (BASELINE config 4: decode stream + 1 x 2048 training stream) --------
     probe = None
@@ -403,17 +439,18 @@ def main():
         serve_loop = {"requests": n_req, "prompt_tokens": p_len, "decode_steps": n_dec, "max_batch": Bq,
                       "passes": passes, "rows": rows, "wall_ms": wall * 1e3, "rows_per_s": rows / wall,
                       "requests_per_s": n_req / wall, "ms_per_pass": wall * 1e3 / passes,
-                      "host_us_per_pass": host_s * 1e6 / passes}
+                      "pass_call_us": host_s * 1e6 / passes,
+                      "pass_call_us_note": "wall time of one ls_server_pass call: host bookkeeping plus waiting for one "
+                                           "of the two staging slots, i.e. for the GPU (the loop is GPU-bound)"}
         log(f"serve loop: {n_req} requests ({p_len} + {n_dec} rows) in {passes} passes, {wall * 1e3:.0f} ms "
-            f"-> {rows / wall:.0f} rows/s, host {host_s * 1e6 / passes:.0f} us per pass")
+            f"-> {rows / wall:.0f} rows/s ({host_s * 1e6 / passes:.0f} us per pass call, GPU-bound)")
         srv.close()
         del kpl, vpl, Yr
 
-    # ---- BASELINE config 5 decode (LLaMA-13B-shaped blocks, 128 requests, lognormal contexts), four of
-    #      its ten blocks: bytes and time both scale with the block count ------------------------------
+    # ---- BASELINE config 5 decode (LLaMA-13B-shaped stage, all ten blocks, 128 requests, lognormal contexts) ----
     decode_cfg5 = None
     if not args.no_cfg5:
-        cfg5 = S.scaled(S.CONFIGS["llama13b_bf16"], n_layers=4)
+        cfg5 = S.CONFIGS["llama13b_bf16"]
         st5 = Bd.Stage(cfg5, io_dtype="bf16", mma_dtype=args.mma)
         p5 = S.make_params_torch(cfg5, seed=0, device=dev)
         st5.ls_bind_params(p5)
@@ -429,12 +466,40 @@ def main():
         ws5 = st5.new_workspace(B5)
         ms5 = time_events(torch, lambda: st5.stage_decode(X5, B5, kv5, Y5, ws5), 10, warm=2)
         by5 = 2.0 * nL5 * (4.0 * d5 * d5 + 3.0 * d5 * F5) + float((ctx5 + 1).sum()) * nL5 * 2 * d5 * 2
-        decode_cfg5 = {"workload": "cfg5 decode B=128 ctx~lognormal(median 1024) clipped [64, 4096], 4 of 10 blocks",
-                       "ms": ms5, "tok_s_4_blocks": B5 / ms5 * 1e3, "bytes": by5, "achieved_gbs": by5 / (ms5 * 1e-3) / 1e9,
+        decode_cfg5 = {"workload": "cfg5 decode B=128 ctx~lognormal(median 1024) clipped [64, 4096], 10 blocks",
+                       "ms": ms5, "tok_s": B5 / ms5 * 1e3, "bytes": by5, "achieved_gbs": by5 / (ms5 * 1e-3) / 1e9,
                        "frac_of_hbm_peak": by5 / (ms5 * 1e-3) / 1e9 / PEAK_HBM_GBS}
-        log(f"cfg5-shaped decode (4 blocks): {ms5:.2f} ms -> {decode_cfg5['achieved_gbs']:.0f} GB/s")
+        log(f"cfg5 decode (10 blocks): {ms5:.2f} ms -> {decode_cfg5['achieved_gbs']:.0f} GB/s")
         st5.close()
         del kv5, p5, X5, Y5, ws5
+
+    # ---- the other operand format: the same training and decode legs on a stage with bf16 (default fp16)
+    #      matrix-core operands, and the other way round under --mma bf16 -----------------------------------
+    other_mode = None
+    if not args.no_other_mode:
+        om = "bf16" if args.mma == "f16" else "f16"
+        st2 = Bd.Stage(cfg, io_dtype="bf16", mma_dtype=om)
+        st2.ls_bind_params(params)
+        kv2 = Bd.KV(st2, n_pages, table, ctx)
+        kv2.k_pool.copy_(kv.k_pool.to(kv2.k_pool.dtype))
+        kv2.v_pool.copy_(kv.v_pool.to(kv2.v_pool.dtype))
+
+        def train2():
+            st2.stage_train_fwd(X, B, L, Y, saved, ws)
+            st2.stage_train_bwd(dY, B, L, saved, dX, dP, 0, ws)
+
+        ms_t2 = time_events(torch, train2, 5)
+        ms_d2 = time_events(torch, lambda: st2.stage_decode(Xd, Bq, kv2, Yd, ws_a), 10)
+        Bd.lsk_timing_begin()
+        train2()
+        torch.cuda.synchronize()
+        t2 = Bd.lsk_timing_end()
+        other_mode = {"mma_operands": om, "train_ms": ms_t2, "train_tok_s": T / ms_t2 * 1e3, "decode_ms": ms_d2,
+                      "gemm_tflops": flop_gemm / (t2["gemm"][0] * 1e-3) / 1e12,
+                      "gemm_frac_of_mfma_peak": flop_gemm / (t2["gemm"][0] * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS}
+        log(f"{om} operands: train {ms_t2:.2f} ms, decode {ms_d2:.3f} ms, GEMMs {other_mode['gemm_tflops']:.0f} TFLOP/s")
+        st2.close()
+        del kv2
 
     # ---- model update (a row beyond the step: AdamW over the stage's parameters, last because it
     #      rewrites the weights) -------------------------------------------------------------------
@@ -479,6 +544,7 @@ def main():
                       "train_frac_of_mfma_peak": (3.0 * T * nL * (8.0 * d * d + 6.0 * d * F)
                                                   + 3.0 * 2.0 * L * L * d * B * nL) / (ms_train * 1e-3) / 1e12 / PEAK_MFMA_TFLOPS},
         "roofline": roofline, "roofline_decode": roofline_decode, "roofline_update": roofline_update,
+        "train_by_kind": train_kinds, "other_operand_format": other_mode,
         "probe": probe, "kv_offload": kv_move, "serve_loop": serve_loop, "decode_cfg5": decode_cfg5,
     }
     if not args.no_cpu_baseline:

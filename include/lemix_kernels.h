@@ -309,6 +309,28 @@ ls_status lsk_finish_qkv(const float* partial, int splits, int T, int h, int dh,
                          void* k_pool, void* v_pool, const int32_t* block_table, int max_pages, int page,
                          void* stream);
 
+/*
+ * Per-kind launch timing, for measurement inside a running program: between lsk_timing_begin and
+ * lsk_timing_end every kernel-level entry point of the kinds below brackets its launches with two HIP events on
+ * its stream (a nested entry point counts once, under the outermost kind).  lsk_timing_end waits for the
+ * events, writes the summed milliseconds and the number of bracketed entry-point calls per kind
+ * ([LSK_TIMED_KINDS] each, host) and switches the recording off.  Process-wide, one recording at a time, at most
+ * 65536 brackets (further ones are dropped and counted in *dropped when it is non-null).  The events add a few
+ * microseconds between launches, so a program records in a pass of its own, not in the one it reports as
+ * throughput.
+ */
+enum {
+  LSK_TIMED_GEMM = 0,        /* lsk_gemm / lsk_gemm_scaled / lsk_gemm_qkv_rope / lsk_gemm_ws with 256 rows or more */
+  LSK_TIMED_ATTN_FWD = 1,    /* matrix-core attention forward (training and prompt chunks) */
+  LSK_TIMED_ATTN_BWD = 2,    /* matrix-core attention backward (all its kernels) */
+  LSK_TIMED_DECODE_ATTN = 3, /* the paged decode-attention kernel and its merge */
+  LSK_TIMED_DECODE_GEMM = 4, /* weight-streaming projections of decode batches (lsk_gemm_partials, lsk_gemm_ws below 256 rows) */
+  LSK_TIMED_FINISH = 5,      /* lsk_finish_* */
+  LSK_TIMED_KINDS = 6
+};
+ls_status lsk_timing_begin(void);
+ls_status lsk_timing_end(double* ms_by_kind, int32_t* calls_by_kind, int32_t* dropped);
+
 #ifdef __cplusplus
 }
 #endif

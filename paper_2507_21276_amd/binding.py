@@ -79,6 +79,8 @@ SIGNATURES = {
                                       _VP, _VP, _VP, _VP, _VP, _VP, _I, C.POINTER(C.c_float)]),
     "stage_optimizer_step": (_I, [_VP, C.POINTER(ls_optim), _VP, _VP, _VP, _VP, _VP, _VP]),
     "ls_last_error": (C.c_char_p, []),
+    "lsk_timing_begin": (_I, []),
+    "lsk_timing_end": (_I, [_DP, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]),
     "lsk_gemm": (_I, [_I, _I, _I, _I, _VP, _L, _I, _VP, _L, _I, _VP, _L, _I, _VP, _I, _VP, _L, _I, _VP]),
     "lsk_gemm_ws": (_I, [_I, _I, _I, _I, _VP, _L, _VP, _L, _VP, _L, _I, _VP, _I, _VP, _L, _VP, _SZ, _VP]),
     "lsk_kv_packed_bytes": (_SZ, [C.POINTER(ls_config), _I]),
@@ -466,6 +468,22 @@ def lsk_attn_paged_noalloc(qkv, n_heads, head_dim, pos, req, k_pool, v_pool, blo
     _check(lib().lsk_attn_paged_noalloc(_p(qkv), CODE_OF_TORCH[qkv.dtype], qkv.shape[0], n_heads, head_dim, _p(pos),
                                         _p(req), _p(k_pool), _p(v_pool), _p(block_table), block_table.shape[1],
                                         page_size, max_ctx, _p(o), _stream(stream)))
+
+
+TIMED_KINDS = ("gemm", "attn_fwd", "attn_bwd", "decode_attn", "decode_gemm", "finish")
+
+
+def lsk_timing_begin():
+    _check(lib().lsk_timing_begin())
+
+
+def lsk_timing_end():
+    """{kind: (milliseconds, bracketed calls)} of the recording that lsk_timing_begin started, plus "dropped"."""
+    ms, calls, dropped = (C.c_double * len(TIMED_KINDS))(), (C.c_int32 * len(TIMED_KINDS))(), C.c_int32(0)
+    _check(lib().lsk_timing_end(ms, calls, C.byref(dropped)))
+    out = {k: (ms[i], calls[i]) for i, k in enumerate(TIMED_KINDS)}
+    out["dropped"] = dropped.value
+    return out
 
 
 def _opt(t):

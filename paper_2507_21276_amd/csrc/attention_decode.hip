@@ -251,6 +251,7 @@ ls_status lsk_attn_decode(const void* qkv, int dt, int T, int h, int dh, const i
                           const int32_t* req, const void* k_pool, const void* v_pool,
                           const int32_t* block_table, int max_pages, int page, int max_ctx, void* o,
                           float* scratch, void* stream) {
+  LsTimed timed(LSK_TIMED_DECODE_ATTN, stream);
   LS_REQUIRE(qkv && pos && req && k_pool && v_pool && block_table && o && T > 0 && max_ctx > 0,
              "attn_decode: bad argument");
   LS_REQUIRE(dt == LS_BF16 || dt == LS_F16, "attn_decode: 16-bit pools only");

@@ -1195,6 +1195,7 @@ ls_status launch_bwd(const void* qkv, const void* o, const void* dO, const float
 
 extern "C" ls_status lsk_attn_fwd_mfma(const void* qkv, int dt, int B, int L, int h, int dh, void* o,
                                        float* lse, void* stream) {
+  LsTimed timed(LSK_TIMED_ATTN_FWD, stream);
   LS_REQUIRE(qkv && o && B > 0 && L > 0 && h > 0, "attn_fwd: bad argument");
   LS_REQUIRE(dt == LS_BF16 || dt == LS_F16, "attn_fwd: the matrix-core kernel needs 16-bit operands");
   LS_REQUIRE(dh == 64 || dh == 128, "attn_fwd: the matrix-core kernel needs head_dim 64 or 128");
@@ -1212,6 +1213,7 @@ extern "C" ls_status lsk_attn_prefill_mfma(const void* qkv, int dt, int n_req, c
                                            int dh, const void* k_pool, const void* v_pool,
                                            const int32_t* block_table, const int32_t* ctx_len, int max_pages,
                                            int page, void* o, void* stream) {
+  LsTimed timed(LSK_TIMED_ATTN_FWD, stream);
   LS_REQUIRE(qkv && o && start_host && k_pool && v_pool && block_table && ctx_len, "attn_prefill: null argument");
   LS_REQUIRE(n_req > 0 && n_req <= 32, "attn_prefill: 1..32 requests per call");
   LS_REQUIRE(dt == LS_BF16 || dt == LS_F16, "attn_prefill: 16-bit operands only");
@@ -1233,6 +1235,7 @@ extern "C" ls_status lsk_attn_prefill_mfma(const void* qkv, int dt, int n_req, c
 extern "C" ls_status lsk_attn_bwd_mfma(const void* qkv, const void* o, const void* dO, const float* lse,
                                        int dt, int B, int L, int h, int dh, void* dqkv, float* dvec,
                                        const float* rope_table, void* stream) {
+  LsTimed timed(LSK_TIMED_ATTN_BWD, stream);
   LS_REQUIRE(qkv && o && dO && lse && dqkv && dvec && B > 0 && L > 0 && h > 0, "attn_bwd: bad argument");
   LS_REQUIRE(dt == LS_BF16 || dt == LS_F16, "attn_bwd: the matrix-core kernel needs 16-bit operands");
   LS_REQUIRE(dh == 64 || dh == 128, "attn_bwd: the matrix-core kernel needs head_dim 64 or 128");

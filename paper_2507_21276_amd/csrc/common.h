@@ -71,6 +71,16 @@ __device__ __forceinline__ float gelu_f(float u, int kind) {
 static inline size_t dtype_size(int dt) { return dt == LS_F32 ? 4 : 2; }
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+// Launch timing by kind of kernel (lsk_timing_begin / lsk_timing_end, defined in stage.hip): while it is on,
+// an LsTimed object at the top of an entry point records a HIP event on the stream before the entry point's
+// launches and one after them; nested entry points count once, under the outermost kind.
+struct LsTimed {
+  LsTimed(int kind, void* stream);
+  ~LsTimed();
+  bool armed;
+  void* stream;
+};
+
 // host-side error plumbing (defined in stage.hip)
 void ls_set_error(const char* fmt, ...);
 #define LS_CHECK_HIP(expr)                                                         \

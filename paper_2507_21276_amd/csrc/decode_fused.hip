@@ -168,6 +168,7 @@ extern "C" {
 
 ls_status lsk_gemm_partials(int op_dtype, int M, int N, int K, const void* X, long ldx, const void* W, long ldw,
                             float* partial, size_t partial_floats, int* splits, void* stream) {
+  LsTimed timed(LSK_TIMED_DECODE_GEMM, stream);
   LS_REQUIRE(X && W && partial && splits, "gemm_partials: null argument");
   LS_REQUIRE(half_type(op_dtype), "gemm_partials: 16-bit operands only");
   LS_REQUIRE(M >= 1 && M <= 128 && N >= 64 && N % 4 == 0 && K >= 64 && K % 64 == 0,
@@ -186,6 +187,7 @@ ls_status lsk_gemm_partials(int op_dtype, int M, int N, int K, const void* X, lo
 ls_status lsk_finish_resid_norm(const float* partial, int splits, int T, int d, const void* bias, const float* resid,
                                 float* x_out, int kind, const void* gamma, const void* beta, int pdt, float eps,
                                 void* h, int hdt, void* stream) {
+  LsTimed timed(LSK_TIMED_FINISH, stream);
   LS_REQUIRE(partial && x_out && splits >= 1 && T > 0 && d > 0, "finish_resid_norm: bad argument");
   LS_REQUIRE(d % 4 == 0 && d <= 4096 * FN_MAX, "finish_resid_norm: d_model %d must be a multiple of 4, at most %d", d,
              4096 * FN_MAX);
@@ -208,6 +210,7 @@ ls_status lsk_finish_resid_norm(const float* partial, int splits, int T, int d, 
 
 ls_status lsk_finish_act(const float* partial, int splits, int T, int F, int act, const void* bias, int pdt, void* out,
                          int odt, void* stream) {
+  LsTimed timed(LSK_TIMED_FINISH, stream);
   LS_REQUIRE(partial && out && splits >= 1 && T > 0 && F > 0, "finish_act: bad argument");
   LS_REQUIRE(F % 4 == 0, "finish_act: d_ff must be a multiple of 4");
   LS_REQUIRE(act == LS_ACT_GELU_TANH || act == LS_ACT_GELU_ERF || act == LS_ACT_SWIGLU, "finish_act: unknown activation %d", act);
@@ -224,6 +227,7 @@ ls_status lsk_finish_act(const float* partial, int splits, int T, int F, int act
 ls_status lsk_finish_qkv(const float* partial, int splits, int T, int h, int dh, const void* bias, int pdt,
                          const int32_t* pos, const int32_t* req, const float* table, void* qkv, int dt, void* k_pool,
                          void* v_pool, const int32_t* block_table, int max_pages, int page, void* stream) {
+  LsTimed timed(LSK_TIMED_FINISH, stream);
   LS_REQUIRE(partial && pos && req && qkv && k_pool && v_pool && block_table, "finish_qkv: null argument");
   LS_REQUIRE(splits >= 1 && T > 0 && h > 0 && dh > 0 && dh % 8 == 0 && max_pages > 0 && page > 0,
              "finish_qkv: bad size (head_dim must be a multiple of 8)");

@@ -303,6 +303,7 @@ extern "C" ls_status lsk_gemm_scaled(int op_dtype, int M, int N, int K, const vo
   LS_REQUIRE(M > 0 && N > 0 && K > 0, "gemm: non-positive size M=%d N=%d K=%d", M, N, K);
   LS_REQUIRE(A && B && C, "gemm: null operand");
   LS_REQUIRE(!accumulate || c_dtype == LS_F32, "gemm: accumulate needs an fp32 output");
+  LsTimed timed(M >= 256 ? LSK_TIMED_GEMM : LSK_TIMED_DECODE_GEMM, stream);
   GemmArgs g{M, N, K, A, lda, a_kmajor, B, ldb, b_kmajor, C, ldc, c_dtype,
              bias, bias_dtype, resid, ldr, accumulate, alpha_dev};
   hipStream_t st = (hipStream_t)stream;
@@ -348,6 +349,7 @@ extern "C" ls_status lsk_gemm_ws(int op_dtype, int M, int N, int K, const void* 
                                  void* stream) {
   LS_REQUIRE(M > 0 && N > 0 && K > 0, "gemm_ws: non-positive size M=%d N=%d K=%d", M, N, K);
   LS_REQUIRE(X && W && C, "gemm_ws: null operand");
+  LsTimed timed(M >= 256 ? LSK_TIMED_GEMM : LSK_TIMED_DECODE_GEMM, stream);
   // decode batches (M <= 128): weights stream through LDS in 64 x 128 or 128 x 128 tiles
   if (scratch && (op_dtype == LS_BF16 || op_dtype == LS_F16) && M <= 128 && K % 8 == 0 &&
       ldx % 8 == 0 && ldw % 8 == 0 && (uintptr_t)X % 16 == 0 && (uintptr_t)W % 16 == 0 &&
@@ -383,6 +385,7 @@ extern "C" ls_status lsk_gemm_qkv_rope(int op_dtype, int T, int d, const void* H
                                        int n_heads, int head_dim, const int32_t* pos, const float* table,
                                        void* stream) {
   LS_REQUIRE(H && Wqkv && qkv && pos && table && T > 0 && d == n_heads * head_dim, "gemm_qkv_rope: bad argument");
+  LsTimed timed(T >= 256 ? LSK_TIMED_GEMM : LSK_TIMED_DECODE_GEMM, stream);
   hipStream_t st = (hipStream_t)stream;
   if (gemm_qkv_rope_fuses(op_dtype, T, d, head_dim)) {
     const ls_status r = gemm_dma_try(op_dtype, T, 3 * d, d, H, d, 1, Wqkv, d, 1, qkv, 3 * d, op_dtype, nullptr, 0,

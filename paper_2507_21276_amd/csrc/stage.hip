@@ -22,6 +22,91 @@ void ls_set_error(const char* fmt, ...) {
 }
 extern "C" const char* ls_last_error(void) { return g_err; }
 
+// ------------------------------------------------------------ launch timing by kind
+#include <mutex>
+namespace {
+struct TimingRec { int kind; hipEvent_t e0, e1; };
+struct TimingState {
+  std::mutex mu;
+  bool on = false;
+  int dropped = 0;
+  std::vector<TimingRec> recs;
+};
+TimingState g_timing;
+thread_local int g_timed_depth = 0;
+thread_local int g_timed_slot = -1;
+constexpr size_t kMaxTimingRecs = 65536;
+}  // namespace
+
+LsTimed::LsTimed(int kind, void* st) : armed(false), stream(st) {
+  if (g_timed_depth++ > 0 || !g_timing.on) return;
+  std::lock_guard<std::mutex> lock(g_timing.mu);
+  if (!g_timing.on) return;
+  if (g_timing.recs.size() >= kMaxTimingRecs) { ++g_timing.dropped; return; }
+  TimingRec r{kind, nullptr, nullptr};
+  if (hipEventCreate(&r.e0) != hipSuccess || hipEventCreate(&r.e1) != hipSuccess ||
+      hipEventRecord(r.e0, (hipStream_t)st) != hipSuccess) {
+    if (r.e0) (void)hipEventDestroy(r.e0);
+    if (r.e1) (void)hipEventDestroy(r.e1);
+    (void)hipGetLastError();
+    ++g_timing.dropped;
+    return;
+  }
+  g_timing.recs.push_back(r);
+  g_timed_slot = (int)g_timing.recs.size() - 1;
+  armed = true;
+}
+LsTimed::~LsTimed() {
+  --g_timed_depth;
+  if (!armed) return;
+  std::lock_guard<std::mutex> lock(g_timing.mu);
+  if (g_timed_slot >= 0 && g_timed_slot < (int)g_timing.recs.size())
+    (void)hipEventRecord(g_timing.recs[g_timed_slot].e1, (hipStream_t)stream);
+  g_timed_slot = -1;
+}
+
+extern "C" ls_status lsk_timing_begin(void) {
+  std::lock_guard<std::mutex> lock(g_timing.mu);
+  if (g_timing.on) {
+    ls_set_error("timing_begin: a recording is already running");
+    return LS_ESTATE;
+  }
+  g_timing.on = true;
+  g_timing.dropped = 0;
+  return LS_OK;
+}
+
+extern "C" ls_status lsk_timing_end(double* ms_by_kind, int32_t* calls_by_kind, int32_t* dropped) {
+  LS_REQUIRE(ms_by_kind && calls_by_kind, "timing_end: null result");
+  std::vector<TimingRec> recs;
+  {
+    std::lock_guard<std::mutex> lock(g_timing.mu);
+    if (!g_timing.on) {
+      ls_set_error("timing_end: no recording is running");
+      return LS_ESTATE;
+    }
+    g_timing.on = false;
+    recs.swap(g_timing.recs);
+    if (dropped) *dropped = g_timing.dropped;
+  }
+  for (int k = 0; k < LSK_TIMED_KINDS; ++k) { ms_by_kind[k] = 0.0; calls_by_kind[k] = 0; }
+  ls_status rc = LS_OK;
+  for (const TimingRec& r : recs) {
+    float ms = 0.f;
+    if (hipEventSynchronize(r.e1) != hipSuccess || hipEventElapsedTime(&ms, r.e0, r.e1) != hipSuccess) {
+      (void)hipGetLastError();
+      rc = LS_EHIP;
+    } else if (r.kind >= 0 && r.kind < LSK_TIMED_KINDS) {
+      ms_by_kind[r.kind] += ms;
+      ++calls_by_kind[r.kind];
+    }
+    (void)hipEventDestroy(r.e0);
+    (void)hipEventDestroy(r.e1);
+  }
+  if (rc != LS_OK) ls_set_error("timing_end: an event of the recording could not be read");
+  return rc;
+}
+
 // internal kernel-level entry points that are not part of the public kernel header
 extern "C" {
 ls_status lsk_attn_fwd_simple(const void*, int, int, int, int, int, void*, float*, void*);
