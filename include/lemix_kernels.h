@@ -193,6 +193,22 @@ ls_status lsk_gemm_qkv_rope(int op_dtype, int T, int d, const void* H, const voi
                             const float* table, void* stream);
 
 /*
+ * Backward through the LLaMA block's FFN-down projection and its SwiGLU
+ * activation in one call (training backward of y = x1 + (SiLU(gate) * up) Wd^T):
+ *   da[T, F] = dY[T, d] Wd[d, F]            (the projection's input gradient)
+ *   dgate = da * up * s * (1 + gate * (1 - s)),  dup = da * gate * s,  s = sigmoid(gate)
+ * pre [dev] [T, 2F] holds the saved pre-activations (gate columns, then up
+ * columns), grad [dev] [T, 2F] receives (dgate | dup), both op_dtype (LS_F16 /
+ * LS_BF16); da is rounded to op_dtype before the activation's derivative is
+ * applied.  With enough 256 x 256 tiles the derivative runs in the product's
+ * epilogue and da never leaves the chip; otherwise the product is written to
+ * da_scratch [dev] [T, F] and lsk_swiglu_bwd follows - the same values either
+ * way.  F % 8 == 0; LS_EINVAL on null pointers or other operand types.
+ */
+ls_status lsk_gemm_swiglu_bwd(int op_dtype, int T, int F, int d, const void* dY, const void* Wd,
+                              const void* pre, void* grad, void* da_scratch, void* stream);
+
+/*
  * Serving attention over the paged pool.  Row t of qkv[T, 3d] belongs to
  * request req[t] and sits at absolute position pos[t]; its K and V are first
  * written to the request's page, then its query attends to keys 0..pos[t].

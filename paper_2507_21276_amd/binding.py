@@ -111,6 +111,7 @@ SIGNATURES = {
     "lsk_attn_bwd_scratch_floats": (_SZ, [_I, _I, _I]),
     "lsk_attn_bwd_rope": (_I, [_I, _VP, _VP, _VP, _VP, _I, _I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP]),
     "lsk_gemm_qkv_rope": (_I, [_I, _I, _I, _VP, _VP, _VP, _I, _I, _VP, _VP, _VP]),
+    "lsk_gemm_swiglu_bwd": (_I, [_I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP, _VP]),
     "lsk_kv_write": (_I, [_VP, _I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP, _I, _I, _VP]),
     "lsk_rope_kv_write": (_I, [_VP, _I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP, _VP, _I, _I, _VP]),
     "lsk_attn_paged": (_I, [_I, _VP, _I, _I, _I, _I, _VP, _VP, _VP, _VP, _VP, _I, _I, _I, _VP, _VP, _VP]),
@@ -439,6 +440,13 @@ def lsk_attn_bwd_rope(impl, qkv, o, dO, lse, B, L, n_heads, head_dim, dqkv, pos,
 def lsk_gemm_qkv_rope(h, w, qkv, n_heads, head_dim, pos, table, stream=None):
     _check(lib().lsk_gemm_qkv_rope(CODE_OF_TORCH[h.dtype], h.shape[0], h.shape[1], _p(h), _p(w), _p(qkv),
                                    n_heads, head_dim, _p(pos), _p(table), _stream(stream)))
+
+
+def lsk_gemm_swiglu_bwd(dY, Wd, pre, grad, da_scratch, stream=None):
+    T, d = dY.shape
+    F = Wd.shape[1]
+    _check(lib().lsk_gemm_swiglu_bwd(CODE_OF_TORCH[dY.dtype], T, F, d, _p(dY), _p(Wd), _p(pre), _p(grad), _p(da_scratch),
+                                     _stream(stream)))
 
 
 def lsk_rope_kv_write(qkv, n_heads, head_dim, pos, req, table, k_pool, v_pool, block_table, page_size, stream=None):

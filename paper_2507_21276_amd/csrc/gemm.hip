@@ -368,6 +368,28 @@ extern "C" ls_status lsk_gemm_ws(int op_dtype, int M, int N, int K, const void* 
   return lsk_gemm(op_dtype, M, N, K, X, ldx, 1, W, ldw, 1, C, ldc, c_dtype, bias, bias_dtype, resid, ldr, 0, stream);
 }
 
+ls_status gemm_dma16_swiglu_bwd_try(int, int, int, int, const void*, long, const void*, long, const void*, void*,
+                                    hipStream_t);
+
+// Backward through the FFN-down projection and the SwiGLU activation in one step: da = dY W_d (W_d stored
+// [d, F]: the input-gradient layout), then d(gate | up) from the saved pre-activations.  With enough
+// 256 x 256 tiles the activation's backward runs in the product's epilogue and da is never stored;
+// otherwise the product goes to `da_scratch` [T, F] and the element-wise kernel follows.  Same result
+// either way, bit for bit.
+extern "C" ls_status lsk_gemm_swiglu_bwd(int op_dtype, int T, int F, int d, const void* dY, const void* Wd,
+                                         const void* pre, void* grad, void* da_scratch, void* stream) {
+  LS_REQUIRE(dY && Wd && pre && grad && da_scratch && T > 0 && F > 0 && d > 0, "gemm_swiglu_bwd: bad argument");
+  LS_REQUIRE(op_dtype == LS_BF16 || op_dtype == LS_F16, "gemm_swiglu_bwd: 16-bit operands only");
+  LS_REQUIRE(F % 8 == 0, "gemm_swiglu_bwd: d_ff must be a multiple of 8");
+  {
+    LsTimed timed(T >= 256 ? LSK_TIMED_GEMM : LSK_TIMED_DECODE_GEMM, stream);
+    const ls_status r = gemm_dma16_swiglu_bwd_try(op_dtype, T, F, d, dY, d, Wd, F, pre, grad, (hipStream_t)stream);
+    if (r != LS_ESTATE) return r;
+  }
+  LS_TRY(lsk_gemm(op_dtype, T, F, d, dY, d, 1, Wd, F, 0, da_scratch, F, op_dtype, nullptr, 0, nullptr, 0, 0, stream));
+  return lsk_swiglu_bwd(da_scratch, pre, grad, op_dtype, T, F, stream);
+}
+
 // QKV projection with the rotary embedding of q and k fused into the epilogue
 // (head_dim 128, no bias): qkv[T, 3d] = h1 Wqkv^T, then the pairs (i, i + 64) of
 // every q and k head of row t rotated by pos[t] * theta^(-2i/128).  Falls back to

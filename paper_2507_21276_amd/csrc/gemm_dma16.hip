@@ -113,6 +113,11 @@ struct SpreadPlan {
 static_assert(32 * 3 / 4 >= 12, "one read per gap");
 
 // MODE 0: C (16-bit) = acc + bias;  1: C (fp32) = resid + acc + bias;  2: C (fp32) = acc;  4: C (fp32) += acc;
+// MODE 5: the product da[M, N] is not stored: it is the gradient of a = SiLU(gate) * up, and the rows written are
+//         those of the gradient of (gate | up) [M, 2 N], from the saved pre-activations:
+//         dgate = da up s (1 + gate (1 - s)), dup = da gate s, s = sigmoid(gate); da is rounded to the operand
+//         type first, as the staged 16-bit tile of MODE 0 is, so the result is that of MODE 0 followed by the
+//         element-wise kernel
 // MODE 3: as 0 without bias, and the half-split rotary embedding (head_dim 128) applied to the
 //         columns below rope_cols: a wavefront's 128 columns are one head, so the pair
 //         (c, c + 64) sits in accumulator blocks j and j + 4 of the same lane
@@ -255,7 +260,7 @@ __global__ __launch_bounds__(256) void gemm_dma16_kernel(DmaArgs g) {
   // stages its tile in its quarter of the (now idle) LDS, row-major with the 16-byte chunks of a row
   // XOR-permuted by the row number, and writes it out as full rows; residual and accumulation operands
   // are read with the same coalesced pattern.
-  constexpr int ESZ = (MODE == 0 || MODE == 3) ? 2 : 4;
+  constexpr int ESZ = (MODE == 0 || MODE == 3 || MODE == 5) ? 2 : 4;
   constexpr int REGION = (BM + BN) * 128 * 2 / 4;   // bytes of LDS per wavefront
   constexpr int ROWB = WN * ESZ;                    // bytes of a staged row
   constexpr int CPR = ROWB / 16;                    // 16-byte chunks per row
@@ -376,20 +381,61 @@ __global__ __launch_bounds__(256) void gemm_dma16_kernel(DmaArgs g) {
       }
     }
     // full rows out: 64 / CPR rows per instruction, 16 bytes per lane
+    if constexpr (MODE == 5) {
+      // the saved pre-activations of a group of rows are fetched together, before any of the group's results is
+      // stored (the buffers may alias as far as the compiler knows, so a load per store would wait for each in turn)
+      typedef typename Mf16<T>::V8 V8;
+      constexpr int NIT = ROWS_P * CPR / 64, GRP = 8;
+      static_assert(NIT % GRP == 0, "row groups of the activation epilogue");
+      const T* pre = (const T*)g.glu_pre;
+      T* grad = (T*)g.glu_grad;
+#pragma unroll 1
+      for (int it0 = 0; it0 < NIT; it0 += GRP) {
+        V8 gt[GRP], up[GRP], da[GRP];
+        long at[GRP];
 #pragma unroll
-    for (int it = 0; it < ROWS_P * CPR / 64; ++it) {
-      const int idx = it * 64 + lane;
-      const int r = idx / CPR, c = idx % CPR;
-      const int m = m0 + wm + pass * ROWS_P + r;
-      const int n = n0 + wn + c * (16 / ESZ);
-      if (m >= g.M || n >= g.N) continue;
-      const f32x4 v = *(const f32x4_a*)(stg + r * ROWB + ((c ^ (r & (CPR - 1))) * 16));
-      if constexpr (ESZ == 2) {
-        *(f32x4_a*)((T*)g.C + (long)m * g.ldc + n) = v;
-      } else if constexpr (MODE == 1) {
-        *(f32x4*)((float*)g.C + (long)m * g.ldc + n) = v + c_old[it];
-      } else {
-        *(f32x4*)((float*)g.C + (long)m * g.ldc + n) = MODE == 4 ? c_old[it] + v : v;
+        for (int u = 0; u < GRP; ++u) {
+          const int idx = (it0 + u) * 64 + lane;
+          const int r = idx / CPR, c = idx % CPR;
+          const int m = m0 + wm + pass * ROWS_P + r, n = n0 + wn + c * 8;
+          at[u] = m < g.M && n < g.N ? (long)m * 2 * g.N + n : -1;
+          const long a = at[u] < 0 ? 0 : at[u];
+          gt[u] = *(const V8*)(pre + a);
+          up[u] = *(const V8*)(pre + a + g.N);
+          da[u] = __builtin_bit_cast(V8, *(const f32x4_a*)(stg + r * ROWB + ((c ^ (r & (CPR - 1))) * 16)));
+        }
+#pragma unroll
+        for (int u = 0; u < GRP; ++u) {
+          V8 og, ou;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float a = to_f(da[u][e]), gf = to_f(gt[u][e]), uf = to_f(up[u][e]);
+            const float sg = 1.f / (1.f + __expf(-gf));
+            og[e] = from_f<T>(a * uf * sg * (1.f + gf * (1.f - sg)));
+            ou[e] = from_f<T>(a * gf * sg);
+          }
+          if (at[u] >= 0) {
+            *(V8*)(grad + at[u]) = og;
+            *(V8*)(grad + at[u] + g.N) = ou;
+          }
+        }
+      }
+    } else {
+#pragma unroll
+      for (int it = 0; it < ROWS_P * CPR / 64; ++it) {
+        const int idx = it * 64 + lane;
+        const int r = idx / CPR, c = idx % CPR;
+        const int m = m0 + wm + pass * ROWS_P + r;
+        const int n = n0 + wn + c * (16 / ESZ);
+        if (m >= g.M || n >= g.N) continue;
+        const f32x4 v = *(const f32x4_a*)(stg + r * ROWB + ((c ^ (r & (CPR - 1))) * 16));
+        if constexpr (ESZ == 2) {
+          *(f32x4_a*)((T*)g.C + (long)m * g.ldc + n) = v;
+        } else if constexpr (MODE == 1) {
+          *(f32x4*)((float*)g.C + (long)m * g.ldc + n) = v + c_old[it];
+        } else {
+          *(f32x4*)((float*)g.C + (long)m * g.ldc + n) = MODE == 4 ? c_old[it] + v : v;
+        }
       }
     }
   }
@@ -415,6 +461,11 @@ template <class T>
 ls_status dispatch16(const DmaArgs& g, hipStream_t st) {
   if (g.rope_table) {
     if (g.a_kmajor && g.b_kmajor && g.c_dtype != LS_F32 && !g.bias) return launch16<T, true, true, 3>(g, st);
+    return LS_ESTATE;
+  }
+  if (g.glu_pre) {
+    if (g.a_kmajor && !g.b_kmajor && g.c_dtype != LS_F32 && !g.bias && !g.alpha && g.N % 8 == 0)
+      return launch16<T, true, false, 5>(g, st);
     return LS_ESTATE;
   }
   const int mode = g.c_dtype != LS_F32 ? 0 : (g.resid ? 1 : (g.accumulate ? 4 : 2));
@@ -447,6 +498,27 @@ ls_status gemm_dma16_try(int op_dtype, int M, int N, int K, const void* A, long 
   if (big < 160) return LS_ESTATE;
   DmaArgs g{M, N, K, A, lda, a_kmajor, B, ldb, b_kmajor, C, ldc, c_dtype, bias, bias_dtype, resid, ldr,
             accumulate, alpha, 0, 0, 0, rope_pos, rope_table, rope_cols};
+  if (op_dtype == LS_BF16) return dispatch16<bf16_t>(g, st);
+  if (op_dtype == LS_F16) return dispatch16<f16_t>(g, st);
+  return LS_ESTATE;
+}
+
+// da[M, N] = dY[M, K] W[K, N] (W k-strided: the input-gradient layout of a linear map whose weight is stored
+// [K, N]) with the backward of SwiGLU in the epilogue: `pre` holds the saved (gate | up) pre-activations
+// [M, 2 N], `grad` receives their gradients [M, 2 N]; da itself is not stored.  LS_ESTATE when the shape is
+// outside what the large-tile kernel covers (the caller then runs the product and the element-wise kernel).
+ls_status gemm_dma16_swiglu_bwd_try(int op_dtype, int M, int N, int K, const void* dY, long ldy, const void* W, long ldw,
+                                    const void* pre, void* grad, hipStream_t st) {
+  if (K % TK != 0 || M < 64 || N < 64 || N % 8 != 0) return LS_ESTATE;
+  if (ldy % 8 != 0 || ldw % 8 != 0 || (uintptr_t)dY % 16 != 0 || (uintptr_t)W % 16 != 0 || (uintptr_t)pre % 16 != 0 ||
+      (uintptr_t)grad % 16 != 0)
+    return LS_ESTATE;
+  const long big = (long)((M + 255) / 256) * ((N + 255) / 256);
+  if (big < 160) return LS_ESTATE;
+  DmaArgs g{M, N, K, dY, ldy, 1, W, ldw, 0, grad, 2L * N, op_dtype, nullptr, 0, nullptr, 0, 0, nullptr, 0, 0, 0,
+            nullptr, nullptr, 0};
+  g.glu_pre = pre;
+  g.glu_grad = grad;
   if (op_dtype == LS_BF16) return dispatch16<bf16_t>(g, st);
   if (op_dtype == LS_F16) return dispatch16<f16_t>(g, st);
   return LS_ESTATE;

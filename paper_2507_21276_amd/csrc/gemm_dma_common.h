@@ -21,6 +21,9 @@ struct DmaArgs {
   long split_stride;   // split-K launches (gridDim.y > 1, MODE 2): elements between the partial results
   // MODE 3 only: rotary embedding of the columns below rope_cols (heads of 128)
   const int32_t* rope_pos; const float* rope_table; int rope_cols;
+  // MODE 5 only (16x16x32 kernel): the product is the gradient of a SwiGLU output; the saved (gate | up)
+  // pre-activations [M, 2 N] and the gradient buffer of the same shape that the epilogue fills
+  const void* glu_pre = nullptr; void* glu_grad = nullptr;
 };
 
 constexpr int TK = 64;  // k extent of a tile; a tile of ROWS rows is ROWS * 128 bytes = ROWS / 8 wave loads

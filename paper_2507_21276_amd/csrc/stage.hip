@@ -127,6 +127,7 @@ ls_status lsk_gemm_qkv_rope(int, int, int, const void*, const void*, void*, int,
 ls_status lsk_gemm_ws(int, int, int, int, const void*, long, const void*, long, void*, long, int, const void*, int,
                       const float*, long, float*, size_t, void*);
 ls_status lsk_gemm_partials(int, int, int, int, const void*, long, const void*, long, float*, size_t, int*, void*);
+ls_status lsk_gemm_swiglu_bwd(int, int, int, int, const void*, const void*, const void*, void*, void*, void*);
 }
 bool gemm_qkv_rope_fuses(int op_dtype, int T, int d, int head_dim);
 ls_status gemm_dma_splitk_partials(int, int, int, int, const void*, long, const void*, long, float*, size_t, int*,
@@ -780,13 +781,19 @@ ls_status stage_train_bwd(ls_stage* s, const void* dY, int B, int L, const void*
     const LayerOff& o = s->off[l];
     const Saved& v = sv[l];
     // y = x1 + act W_dn^T (+ b_dn)
-    LS_TRY(lsk_gemm(mt, T, F, d, w.g16, d, 1, wptr(s, o.w_dn), F, 0, w.dact, F, mt, nullptr, 0, nullptr, 0, 0, st));
+    if (gpt) {
+      LS_TRY(lsk_gemm(mt, T, F, d, w.g16, d, 1, wptr(s, o.w_dn), F, 0, w.dact, F, mt, nullptr, 0, nullptr, 0, 0, st));
+    } else if (mt == LS_F32) {
+      LS_TRY(lsk_gemm(mt, T, F, d, w.g16, d, 1, wptr(s, o.w_dn), F, 0, w.dact, F, mt, nullptr, 0, nullptr, 0, 0, st));
+      LS_TRY(lsk_swiglu_bwd(w.dact, v.up, w.dup, mt, T, F, st));
+    } else {
+      // the activation's backward in the epilogue of the product that feeds it (no dact round trip)
+      LS_TRY(lsk_gemm_swiglu_bwd(mt, T, F, d, w.g16, wptr(s, o.w_dn), v.up, w.dup, w.dact, st));
+    }
     LS_TRY(lsk_gemm_scaled(mt, d, F, T, w.g16, d, 0, v.act, F, 0, dParams + o.w_dn, F, LS_F32, nullptr, 0, nullptr, 0, acc, inv, st));
     if (gpt) {
       LS_TRY(lsk_colsum_scaled(w.g16, mt, T, d, d, dParams + o.b_dn, acc, w.partial, inv, st));
       LS_TRY(lsk_gelu_bwd(w.dact, v.up, w.dup, mt, (size_t)T * F, c.act, st));
-    } else {
-      LS_TRY(lsk_swiglu_bwd(w.dact, v.up, w.dup, mt, T, F, st));
     }
     // up = h2 W_up^T (+ b_up)
     LS_TRY(lsk_gemm(mt, T, d, U, w.dup, U, 1, wptr(s, o.w_up), d, 0, w.dh, d, mt, nullptr, 0, nullptr, 0, 0, st));

@@ -332,6 +332,31 @@ def test_grad_scale_is_a_power_of_two_that_brings_the_maximum_to_8_16():
         assert out[2].item() == x.float().abs().max().item()
 
 
+@pytest.mark.parametrize("name", ["f16", "bf16"])
+@pytest.mark.parametrize("T,F,d", [(4104, 2568, 192),     # 17 x 11 tiles of 256 with ragged edges: the fused epilogue
+                                    (300, 264, 128)])      # few tiles: product, then the element-wise kernel
+def test_ffn_down_input_gradient_with_swiglu_backward_in_one_call(name, T, F, d):
+    """d(gate | up) of a = SiLU(gate) * up from dY and W_d, against the chain rule in float64, and bit for bit
+    against the two-step route (product rounded to 16 bits, then lsk_swiglu_bwd)."""
+    dt = DT[name]
+    dY = q(S.normal(41, "dY", (T, d)), name)
+    Wd = q(S.normal(41, "Wd", (d, F), 0.05), name)
+    pre = q(S.normal(41, "pre", (T, 2 * F)), name)
+    dYd, Wdd, pred = dev(dY, dt), dev(Wd, dt), dev(pre, dt)
+    grad = torch.full((T, 2 * F), 7.0, dtype=dt, device="cuda")
+    scratch = torch.empty(T, F, dtype=dt, device="cuda")
+    Bd.lsk_gemm_swiglu_bwd(dYd, Wdd, pred, grad, scratch)
+    da = dY.astype(np.float64) @ Wd.astype(np.float64)
+    gate, up = pre[:, :F].astype(np.float64), pre[:, F:].astype(np.float64)
+    sg = O.sigmoid(gate)
+    ref = np.concatenate([da * up * sg * (1.0 + gate * (1.0 - sg)), da * gate * sg], axis=1)
+    assert_close(host(grad), ref, otol(name, ref), "d(gate | up)")
+    two = torch.empty_like(grad)
+    Bd.lsk_gemm(dYd, Wdd, scratch, M=T, N=F, K=d, a_kmajor=True, b_kmajor=False, lda=d, ldb=F)
+    Bd.lsk_swiglu_bwd(scratch, pred, two)
+    assert torch.equal(grad, two), "the fused epilogue and the two-step route differ"
+
+
 @pytest.mark.parametrize("name", ["f32", "f16"])
 def test_colsum(name):
     T, N = 333, 520
