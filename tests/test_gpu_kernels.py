@@ -72,11 +72,12 @@ def test_gemm_input_and_weight_gradient_layouts(name, T, N, K):
 
 @pytest.mark.parametrize("name", ["bf16", "f16"])
 @pytest.mark.parametrize("K", [64, 192])
-def test_gemm_large_tile_kernels_with_ragged_edges(name, K):
+@pytest.mark.parametrize("M,N", [(4104, 2568),    # 17 x 11 = 187 tiles of 256 x 256, 8 rows and 8 columns in the last ones
+                                  (2056, 8200)])   # 9 x 33 = 297 tiles: a second, nearly empty round of workgroups
+def test_gemm_large_tile_kernels_with_ragged_edges(name, K, M, N):
     """More than 160 tiles of 256 x 256 with partial tiles on both edges and one or three k tiles: the
     16x16x32 kernel (forward and input-gradient layouts) and the 32x32x16 kernel (weight gradient),
     every element against float64."""
-    M, N = 4104, 2568   # 17 x 11 = 187 tiles, 8 rows and 8 columns in the last ones
     A = q(S.normal(5, "A", (M, K)), name)
     W = q(S.normal(5, "W", (N, K), 0.05), name)
     bias = q(S.normal(5, "b", (N,)), "bf16")
@@ -334,6 +335,7 @@ def test_grad_scale_is_a_power_of_two_that_brings_the_maximum_to_8_16():
 
 @pytest.mark.parametrize("name", ["f16", "bf16"])
 @pytest.mark.parametrize("T,F,d", [(4104, 2568, 192),     # 17 x 11 tiles of 256 with ragged edges: the fused epilogue
+                                    (2056, 8200, 64),      # 297 tiles, two rounds of workgroups
                                     (300, 264, 128)])      # few tiles: product, then the element-wise kernel
 def test_ffn_down_input_gradient_with_swiglu_backward_in_one_call(name, T, F, d):
     """d(gate | up) of a = SiLU(gate) * up from dY and W_d, against the chain rule in float64, and bit for bit
@@ -350,7 +352,9 @@ def test_ffn_down_input_gradient_with_swiglu_backward_in_one_call(name, T, F, d)
     gate, up = pre[:, :F].astype(np.float64), pre[:, F:].astype(np.float64)
     sg = O.sigmoid(gate)
     ref = np.concatenate([da * up * sg * (1.0 + gate * (1.0 - sg)), da * gate * sg], axis=1)
-    assert_close(host(grad), ref, otol(name, ref), "d(gate | up)")
+    # two 16-bit roundings: da before the derivative, then the result (the products of three Gaussians have
+    # elements fifty times the tensor RMS, and half an ulp of those is the whole error)
+    assert_close(host(grad), ref, otol(name, ref) + out_rounding_bound(ref, name), "d(gate | up)")
     two = torch.empty_like(grad)
     Bd.lsk_gemm(dYd, Wdd, scratch, M=T, N=F, K=d, a_kmajor=True, b_kmajor=False, lda=d, ldb=F)
     Bd.lsk_swiglu_bwd(scratch, pred, two)
@@ -497,7 +501,7 @@ def test_attention_at_the_benchmarked_sizes_on_sampled_heads(name, B, L, h, head
 
 
 @pytest.mark.parametrize("name", ["f16", "bf16"])
-@pytest.mark.parametrize("T,h,dh", [(70, 2, 64), (300, 3, 128), (4096, 32, 128), (2304, 16, 128)])
+@pytest.mark.parametrize("T,h,dh", [(70, 2, 64), (300, 3, 128), (4096, 32, 128), (2304, 16, 128), (2048, 32, 128)])
 def test_qkv_projection_with_fused_rotary_embedding(name, T, h, dh):
     """(4096, 32, 128) is the training launch configuration with the rotation in the GEMM epilogue
     (checked on sampled rows); the small shapes take the GEMM + in-place rotation route."""
