@@ -1,0 +1,399 @@
+// Hand-scheduled attention backward for head_dim 128 (included by attention_mfma.hip, inside its
+// anonymous namespace).  Same tiles, layouts and arithmetic as flash_bwd_dkv_kernel; what differs is
+// who places the instructions:
+//   * every MFMA, LDS read and wait of the tile loop is issued from assembly, in source order, with
+//     scheduling barriers between the steps, so that the matrix pipe, the vector unit and the LDS
+//     work at the same time inside the one wavefront a SIMD holds;
+//   * S and dP accumulate in ordinary vector registers (the vector unit reads them directly), the
+//     dK / dV accumulators and the K / V operands of the workgroup live in the accumulator file;
+//   * LDS addresses are a per-lane register plus an immediate: one vector add per table entry and
+//     tile instead of address arithmetic per read;
+//   * fragments are fetched a fixed number of MFMAs ahead and waited for by count.
+//
+// A tile (64 queries in two blocks of 32, against the wavefront's 32 keys) is 64 MFMAs in four
+// phases of 16:  A: S, dP of block 0;  B: S, dP of block 1 beside the exponentials of block 0;
+// C: dV, dK of block 0 beside the exponentials of block 1;  D: dV, dK of block 1, the ring step
+// and the first fragments of the next tile.
+//
+// The compiler does not know what the assembly statements do, so the hazards it normally covers
+// are handled here: an MFMA result is read by vector instructions only after bwd_mfma_settle(),
+// and every LDS read is retired by a counted wait before its register is used (tests/isa_lint.py
+// checks the compiled code for that).
+#pragma once
+
+template <int I> using IC = std::integral_constant<int, I>;
+template <int B, int E, class F> __device__ __forceinline__ void static_for(F&& f) {
+  if constexpr (B < E) {
+    f(IC<B>{});
+    static_for<B + 1, E>(f);
+  }
+}
+
+// The MFMAs of this file.  An MFMA may read a register that a vector instruction wrote only two wait states
+// after it.  The compiler keeps that distance for its own MFMAs; here it cannot know that a statement is one (and
+// it does move the conversions that complete an operand down to the statement that first uses it), so operands
+// made by vector instructions go through operand_ready() at least one MFMA before they are used.
+template <class V> __device__ __forceinline__ void operand_ready(V& a, V& b) { asm volatile("" : "+v"(a), "+v"(b)); }
+// D (vector registers) = A (vector registers) x B (accumulator file) [+ D]
+template <class T, bool FIRST>
+__device__ __forceinline__ void mma_to_vgpr(f32x16& d, const typename Mma<T>::V8& a, const typename Mma<T>::V8& b) {
+  if constexpr (std::is_same<T, f16_t>::value) {
+    if constexpr (FIRST) asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+    else asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+  } else {
+    if constexpr (FIRST) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(a), "a"(b));
+    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(a), "a"(b));
+  }
+}
+// D (accumulator file) += A (vector registers) x B (vector registers)
+template <class T>
+__device__ __forceinline__ void mma_to_agpr(f32x16& d, const typename Mma<T>::V8& a, const typename Mma<T>::V8& b) {
+  if constexpr (std::is_same<T, f16_t>::value)
+    asm volatile("v_mfma_f32_32x32x16_f16 %0, %1, %2, %0" : "+a"(d) : "v"(a), "v"(b));
+  else
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(d) : "v"(a), "v"(b));
+}
+// Wait states between the last MFMA that wrote these registers and a vector instruction that reads
+// them (the longest case of the ISA's table is 19; the MFMA issued in between runs meanwhile).
+__device__ __forceinline__ void bwd_mfma_settle(f32x16& a, f32x16& b) {
+  asm volatile("s_nop 15\n\ts_nop 7" : "+v"(a), "+v"(b));
+}
+// The same for the eight accumulator blocks of a kernel, at the end of every tile: whatever the compiler places
+// after the tile's last MFMA (copies of an accumulator at a loop edge, the epilogue's reads) comes after it.
+__device__ __forceinline__ void bwd_mfma_settle_acc(f32x16 (&a)[4], f32x16 (&b)[4]) {
+  asm volatile("s_nop 15\n\ts_nop 7"
+               : "+a"(a[0]), "+a"(a[1]), "+a"(a[2]), "+a"(a[3]), "+a"(b[0]), "+a"(b[1]), "+a"(b[2]), "+a"(b[3]));
+}
+
+// From here on the value lives in the accumulator file (it is only ever an operand of the MFMAs above).
+template <class V> __device__ __forceinline__ void pin_agpr(V& v) { asm volatile("" : "+a"(v)); }
+
+template <int IMM, class V> __device__ __forceinline__ void lds_read16(V& d, uint32_t addr) {
+  asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(IMM) : "memory");
+}
+template <int IMM> __device__ __forceinline__ void lds_read_tr(s16x4_t& d, uint32_t addr) {
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(d) : "v"(addr), "n"(IMM) : "memory");
+}
+template <int N> __device__ __forceinline__ void lgkm_wait() {
+  static_assert(N >= 0 && N <= 15, "lgkmcnt holds 0 .. 15");
+  asm volatile("s_waitcnt lgkmcnt(%0)" ::"n"(N) : "memory");
+}
+
+// One direct-to-LDS wave load, 16 or 4 bytes per lane: address = uniform 64-bit base + per-lane 32-bit offset,
+// LDS destination = `lds` + 16 (or 4) x lane.  Issued from assembly, so the compiler neither counts these loads
+// nor forms a 64-bit address per lane; every wait for them in this file is an explicit s_waitcnt.
+__device__ __forceinline__ void dma16(const void* base, uint32_t off, uint32_t lds) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds), "v"(off), "s"(base) : "memory", "m0");
+}
+__device__ __forceinline__ void dma4(const void* base, uint32_t off, uint32_t lds) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(lds), "v"(off), "s"(base) : "memory", "m0");
+}
+
+// ---- the read schedule of a dK/dV tile, as a table the wait counts are derived from ----------
+// Time is counted in gaps (the slot after an MFMA); a cycle starts at the ring step, which leaves
+// no read outstanding: gaps 0..3 are the last four of phase D (first fragments of the next tile),
+// 4..19 phase A, 20..35 phase B, 36..51 phase C, 52..63 the first twelve of phase D.
+struct DkvPlan {
+  static constexpr int reads_in_gap(int g) {
+    if (g < 4) return 2;                  // two fragments of the next tile
+    if (g < 12) return 2;                 // fragment + one vector of log-sum-exp / D values of block 0
+    if (g < 20) return 1;                 // fragment
+    if (g < 28) return 2;                 // fragment + one vector of block 1's values
+    if (g < 36) return 1;                 // one half of a transposed fragment
+    return 2;                             // both halves of a transposed fragment
+  }
+  static constexpr int issued_through(int g) {   // reads issued in gaps 0 .. g
+    int n = 0;
+    for (int i = 0; i <= g; ++i) n += reads_in_gap(i);
+    return n;
+  }
+  // reads issued after read number `pos` of gap `gr` and before the MFMA that follows gap gc - 1
+  static constexpr int newer(int gc, int gr, int pos) { return issued_through(gc - 1) - issued_through(gr - 1) - pos - 1; }
+  // One wait serves two MFMAs: before MFMA f (even) the operands of f and f + 1 must have landed, i.e. the
+  // count is the number of reads issued after those of f + 1.
+  static constexpr int frag_gap(int f) { return f < 8 ? f / 2 : f - 4; }
+  static constexpr int frag_pos(int f) { return f < 8 ? f % 2 : 0; }
+  static constexpr int wait_AB(int f) { return newer(4 + f, frag_gap(f + 1), frag_pos(f + 1)); }   // f = 0, 2, .. 30
+  static constexpr int tr_gap(int M) { return M < 4 ? 29 + 2 * M : 32 + M; }                     // M = 16 c + m
+  static constexpr int tr_pos(int M) { return M < 4 ? 0 : 1; }
+  static constexpr int wait_CD(int M) { return newer(36 + M, tr_gap(M + 1), tr_pos(M + 1)); }    // M = 0, 2, .. 26
+};
+
+// dK, dV for head_dim 128.  Grid, LDS layout and arguments of flash_bwd_dkv_kernel, except that lse2 is the
+// log-sum-exp in base 2 (natural value times log2 e; dvec_kernel writes it beside D).
+template <class T>
+__global__ __launch_bounds__(256) void flash_bwd_dkv128_kernel(const T* __restrict__ qkv, const T* __restrict__ dO,
+                                                               const float* __restrict__ lse2,
+                                                               const float* __restrict__ dvec, T* __restrict__ dqkv,
+                                                               int L, int h, float scale,
+                                                               const float* __restrict__ rope) {
+  typedef typename Mma<T>::V8 V8;
+  constexpr int DH = 128, BKEY = 128, QR = 64, NS = 4, KS = DH / 16, DT = DH / 32;
+  constexpr int TILE_B = QR * DH * 2;            // bytes of a Q or dO tile
+  constexpr int STAGE_B = 2 * TILE_B + 512;      // Q, dO, 64 log-sum-exp, 64 D
+  constexpr int NLT = TILE_B / 1024 / 4;         // wave loads per wavefront and tile
+  constexpr int NLD = 2 * NLT + 2;               // loads per wavefront and stage
+  static_assert(NLD == 10, "the refill of a stage is spread as two loads over each of the last five gaps");
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+  const int ktile = blockIdx.y;
+  const int b = blockIdx.x / h, head = blockIdx.x % h;
+  const int d = h * DH;
+  const long ld = 3L * d;
+  const T* qb = qkv + (long)b * L * ld + (long)head * DH;
+  const T* kb = qb + d;
+  const T* vb = qb + 2 * d;
+  const T* dob = dO + (long)b * L * d + (long)head * DH;
+  const float* lseb = lse2 + (long)b * L * h + head;
+  const float* dvb = dvec + (long)b * L * h + head;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int col = lane & 31, hf = lane >> 5;
+  const int wk0 = ktile * BKEY + wave * 32;
+  const int key = wk0 + col;
+  const float scale_log2 = scale * 1.4426950408889634f;
+  const float gsc = do_scale(dvec + (long)gridDim.x * L + ((long)gridDim.x * L + 3) / 4);
+
+  // per-lane byte offsets inside a stage (see frag_rows / tr_read for the layouts)
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)smem;
+  uint32_t nat[KS], tr0[DT], tr1[DT], lsv;
+  {
+    const int row = pi_row(col);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) nat[s] = lds0 + row * (DH * 2) + (((2 * s + hf) ^ tile_swz<DH>(row)) * 16);
+    const int i16 = lane & 15, a = i16 >> 2, j4 = i16 & 3;
+    const int k = 8 * (lane >> 5) + a;
+#pragma unroll
+    for (int j = 0; j < DT; ++j) {
+      const int nb = j * 32 + 16 * ((lane >> 4) & 1) + 4 * j4;
+      tr0[j] = lds0 + k * (DH * 2) + (((nb >> 3) ^ tile_swz<DH>(k)) * 16) + ((nb >> 2) & 1) * 8;
+      tr1[j] = lds0 + (k + 4) * (DH * 2) + (((nb >> 3) ^ tile_swz<DH>(k + 4)) * 16) + ((nb >> 2) & 1) * 8;
+    }
+    lsv = lds0 + 2 * TILE_B + 32 * hf;
+  }
+
+  const int qt_first = (ktile * BKEY) / QR;   // first query tile that can see these keys
+  const int nt = (L + QR - 1) / QR - qt_first;
+  // Direct-to-LDS loads of a stage: load i = 0 .. NLD - 1 of this wavefront (Q rows, dO rows, then the 64
+  // log-sum-exp and the 64 D values, which every wavefront writes alike).  The per-lane offsets from the tile's
+  // first row are the same for every full tile (registers, set once); a tile cut off by the end of the sequence
+  // re-reads row L - 1 for the rows past it.  Tile t -> stage t % NS; tiles past the end re-fetch the last one (never used), so
+  // that every wavefront always has the same number of loads in flight.
+  constexpr int CPR = DH / 8, RPL = 64 / CPR;
+  uint32_t qoff[NLT], ooff[NLT], foff;
+  // offsets for a tile of `rows` valid rows (64 for all but a cut-off last tile)
+  auto set_offsets = [&](int rows) {
+#pragma unroll
+    for (int j = 0; j < NLT; ++j) {
+      const int row = (wave * NLT + j) * RPL + lane / CPR;
+      const int gch = (lane % CPR) ^ tile_swz<DH>(row);
+      const int r = min(row, rows - 1);
+      qoff[j] = (uint32_t)((r * ld + gch * 8) * 2);
+      ooff[j] = (uint32_t)(((long)r * d + gch * 8) * 2);
+    }
+    foff = (uint32_t)(min(lane, rows - 1) * h * 4);
+  };
+  set_offsets(QR);
+  const int last_rows = L - (qt_first + nt - 1) * QR;   // rows of the last tile, <= 64
+  // Called once per tile before its loads, in tile order: the last tile (which all fetches past the end repeat)
+  // switches the offsets to its row count, and nothing switches them back.
+  auto prepare_tile = [&](int t) {
+    if (t >= nt - 1 && last_rows < QR) set_offsets(last_rows);
+  };
+  auto issue_one = [&](int t, auto i_) {
+    constexpr int i = decltype(i_)::value;
+    const int q0 = (qt_first + min(t, nt - 1)) * QR;
+    const uint32_t st = lds0 + (t % NS) * STAGE_B;
+    if constexpr (i < 2 * NLT) {
+      constexpr int j = i % NLT;
+      if constexpr (i < NLT) dma16(qb + (long)q0 * ld, qoff[j], st + (wave * NLT + j) * 1024);
+      else dma16(dob + (long)q0 * d, ooff[j], st + TILE_B + (wave * NLT + j) * 1024);
+    } else {
+      dma4((i == 2 * NLT ? lseb : dvb) + (long)q0 * h, foff, st + 2 * TILE_B + (i == 2 * NLT ? 0 : 256));
+    }
+  };
+#pragma unroll
+  for (int t = 0; t < NS; ++t) {
+    prepare_tile(t);
+    static_for<0, NLD>([&](auto i_) { issue_one(t, i_); });
+  }
+
+  // this wavefront's 32 keys: K and V fragments, all requested before the first is used
+  V8 kf[KS], vf[KS];
+  {
+    u32x4 z0[KS], z1[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      z0[s] = z1[s] = u32x4{0u, 0u, 0u, 0u};
+      if (key < L) {
+        z0[s] = *(const u32x4*)(kb + (long)key * ld + s * 16 + hf * 8);
+        z1[s] = *(const u32x4*)(vb + (long)key * ld + s * 16 + hf * 8);
+      }
+    }
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      kf[s] = __builtin_bit_cast(V8, z0[s]);
+      vf[s] = __builtin_bit_cast(V8, z1[s]);
+      pin_agpr(kf[s]);
+      pin_agpr(vf[s]);
+    }
+  }
+  f32x16 dk[DT], dv[DT];
+#pragma unroll
+  for (int j = 0; j < DT; ++j) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) dk[j][e] = dv[j][e] = 0.f;
+    pin_agpr(dk[j]);
+    pin_agpr(dv[j]);
+  }
+  const unsigned vis = (unsigned)max(L - key, 0);   // queries key .. L - 1 see this lane's key
+  // the K / V fragments were requested after the four stages: when they are here, so are the stages
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+
+  // fragment F(i), i = 0 .. 31, of a tile's first products: block i / 16, k step (i % 16) / 2, Q (even) or dO (odd)
+  V8 nf[8];
+  auto read_frag = [&](auto i_) {
+    constexpr int i = decltype(i_)::value;
+    lds_read16<(i / 16) * 32 * (DH * 2) + (i % 2) * TILE_B>(nf[i % 8], nat[(i % 16) / 2]);
+  };
+  static_for<0, 8>([&](auto i_) { read_frag(i_); });
+
+  TrFrag tf[8];
+  f32x16 sacc0, pacc0, sacc1, pacc1;
+  f32x4 lv[2][8];        // per block: [g][lse lo, lse hi, D lo, D hi] of the lane's 8 queries of each 16-query step
+  u32x4 pw[2][2], dw[2][2];      // P and dS of a block, 16 bits each: per 16-query step the B operand of the second products
+
+  // transposed fragment for MFMA M = 16 c + m of the second products: step st4 = m / 4 (dO^T P, Q^T dS for the
+  // first 16 queries of the block, then for the second 16), head-dimension block j = m % 4
+  auto read_tr = [&](auto M_, auto half_) {
+    constexpr int M = decltype(M_)::value, half = decltype(half_)::value;
+    constexpr int c = M / 16, m = M % 16, st4 = m / 4, j = m % 4, g = st4 >> 1, which = st4 & 1;
+    constexpr int imm = (c * 32 + g * 16) * (DH * 2) + (which ? 0 : TILE_B);
+    if constexpr (half == 0) lds_read_tr<imm>(tf[M % 8].lo, tr0[j]);
+    else lds_read_tr<imm>(tf[M % 8].hi, tr1[j]);
+  };
+  auto read_lv = [&](auto c_, auto r_) {
+    constexpr int c = decltype(c_)::value, r = decltype(r_)::value, g = r / 4, k4 = r % 4;
+    lds_read16<128 * c + 64 * g + (k4 & 1) * 16 + (k4 >> 1) * 256>(lv[c][r], lsv);
+  };
+
+  auto tile = [&](auto masked_tag, int t) {
+    constexpr bool MASKED = decltype(masked_tag)::value;
+    const int q0 = (qt_first + t) * QR;
+    // the arithmetic between the products for element e of block c (query q0 + 32 c + 16 (e / 8) + 8 hf + e % 8)
+    float p_even = 0.f, d_even = 0.f;
+    auto element = [&](auto c_, auto e_, const f32x16& sacc, const f32x16& pacc) {
+      constexpr int c = decltype(c_)::value, e = decltype(e_)::value, g = e >> 3, i = e & 7;
+      const float lq = lv[c][g * 4 + (i >> 2)][i & 3];
+      const float dq = lv[c][g * 4 + 2 + (i >> 2)][i & 3];
+      float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[e], scale_log2, -lq));
+      if constexpr (MASKED) {
+        const int r0 = 32 * c + 16 * g + 8 * hf;
+        if ((unsigned)(q0 + r0 - key + i) >= vis) p = 0.f;   // key <= query < L, as one unsigned compare
+      }
+      const float ds = p * (pacc[e] - dq) * gsc;
+      if constexpr ((e & 1) == 0) {
+        p_even = p;
+        d_even = ds;
+      } else {
+        typedef T T2 __attribute__((ext_vector_type(2)));
+        T2 a, bb;
+        a[0] = from_f<T>(p_even); a[1] = from_f<T>(p);
+        bb[0] = from_f<T>(d_even); bb[1] = from_f<T>(ds);
+        pw[c][g][i >> 1] = __builtin_bit_cast(uint32_t, a);
+        dw[c][g][i >> 1] = __builtin_bit_cast(uint32_t, bb);
+        if constexpr (i == 7) operand_ready(pw[c][g], dw[c][g]);
+      }
+    };
+    auto operand = [&](const u32x4& w) { return __builtin_bit_cast(V8, w); };
+
+    // ---- phase A: S, dP of block 0
+    static_for<0, 16>([&](auto f_) {
+      constexpr int f = decltype(f_)::value, s = f / 2;
+      if constexpr (f % 2 == 0) lgkm_wait<DkvPlan::wait_AB(f)>();
+      if constexpr (f % 2 == 0) mma_to_vgpr<T, s == 0>(sacc0, nf[f % 8], kf[s]);
+      else mma_to_vgpr<T, s == 0>(pacc0, nf[f % 8], vf[s]);
+      read_frag(IC<f + 8>{});
+      if constexpr (f < 8) read_lv(IC<0>{}, f_);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    // ---- phase B: S, dP of block 1; exponentials of block 0
+    static_for<0, 16>([&](auto k_) {
+      constexpr int k = decltype(k_)::value, f = 16 + k, s = k / 2;
+      if constexpr (f % 2 == 0) lgkm_wait<DkvPlan::wait_AB(f)>();
+      if constexpr (f % 2 == 0) mma_to_vgpr<T, s == 0>(sacc1, nf[f % 8], kf[s]);
+      else mma_to_vgpr<T, s == 0>(pacc1, nf[f % 8], vf[s]);
+      if constexpr (k == 0) bwd_mfma_settle(sacc0, pacc0);
+      if constexpr (k < 8) {
+        read_frag(IC<f + 8>{});
+        read_lv(IC<1>{}, k_);
+      } else {
+        read_tr(IC<(k - 8) / 2>{}, IC<(k - 8) % 2>{});
+      }
+      element(IC<0>{}, k_, sacc0, pacc0);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    // ---- phase C: dV, dK of block 0; exponentials of block 1
+    static_for<0, 16>([&](auto m_) {
+      constexpr int m = decltype(m_)::value, st4 = m / 4, j = m % 4, g = st4 >> 1;
+      if constexpr (m % 2 == 0) lgkm_wait<DkvPlan::wait_CD(m)>();
+      if constexpr ((st4 & 1) == 0) mma_to_agpr<T>(dv[j], tr_value<T>(tf[m % 8]), operand(pw[0][g]));
+      else mma_to_agpr<T>(dk[j], tr_value<T>(tf[m % 8]), operand(dw[0][g]));
+      if constexpr (m == 0) bwd_mfma_settle(sacc1, pacc1);
+      read_tr(IC<m + 4>{}, IC<0>{});
+      read_tr(IC<m + 4>{}, IC<1>{});
+      element(IC<1>{}, m_, sacc1, pacc1);
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    // ---- phase D: dV, dK of block 1; ring step; first fragments of the next tile
+    static_for<0, 16>([&](auto m_) {
+      constexpr int m = decltype(m_)::value, st4 = m / 4, j = m % 4, g = st4 >> 1;
+      if constexpr (m < 12 && m % 2 == 0) lgkm_wait<DkvPlan::wait_CD(16 + m)>();
+      if constexpr ((st4 & 1) == 0) mma_to_agpr<T>(dv[j], tr_value<T>(tf[(16 + m) % 8]), operand(pw[1][g]));
+      else mma_to_agpr<T>(dk[j], tr_value<T>(tf[(16 + m) % 8]), operand(dw[1][g]));
+      if constexpr (m < 12) {
+        read_tr(IC<16 + m + 4>{}, IC<0>{});
+        read_tr(IC<16 + m + 4>{}, IC<1>{});
+      }
+      if constexpr (m == 11) {
+        // every read of this tile has been issued: when they have landed, and tile t + 1 too (only the loads
+        // of tiles t + 2 .. t + NS - 1 outstanding), the stage is handed back and refilled over the next gaps
+        // (the barrier is issued from assembly: before its own the compiler waits for every load in flight)
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NS - 2) * NLD) : "memory");
+        const int step = ((t + 1) % NS == 0) ? -(NS - 1) * STAGE_B : STAGE_B;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) nat[s] += step;
+#pragma unroll
+        for (int jj = 0; jj < DT; ++jj) {
+          tr0[jj] += step;
+          tr1[jj] += step;
+        }
+        lsv += step;
+      }
+      if constexpr (m == 11) prepare_tile(t + NS);
+      if constexpr (m >= 11) {
+        issue_one(t + NS, IC<2 * (m - 11)>{});
+        issue_one(t + NS, IC<2 * (m - 11) + 1>{});
+      }
+      if constexpr (m >= 12) {
+        read_frag(IC<2 * (m - 12)>{});
+        read_frag(IC<2 * (m - 12) + 1>{});
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    bwd_mfma_settle_acc(dk, dv);
+  };
+
+  // Tiles on the diagonal (the first two: 128 keys against 64-query tiles) and, when L is not a multiple of
+  // 64, the last one need the mask; with such an L every tile takes the masked path.
+  const int n_masked = (L % QR) ? nt : min(nt, BKEY / QR);
+  int t = 0;
+  for (; t < n_masked; ++t) tile(std::true_type{}, t);
+  for (; t < nt; ++t) tile(std::false_type{}, t);
+  // the fragments read ahead for a tile that does not exist; no direct-to-LDS write may outlive the workgroup
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+  if (key < L) {
+    T* rk = dqkv + ((long)b * L + key) * ld + d + (long)head * DH;
+    store_grad_row<T, DH>(rk, dk, scale / gsc, hf, rope ? rope + (long)key * DH : nullptr);
+    store_grad_row<T, DH>(rk + d, dv, 1.0f, hf, nullptr);
+  }
+}

@@ -46,7 +46,7 @@ ls_status lsk_attn_bwd_rope(int impl, const void* qkv, const void* o, const void
 
 size_t lsk_attn_bwd_scratch_floats(int B, int L, int n_heads) {
   const size_t items = (size_t)B * L * n_heads;
-  return items + (items + 3) / 4 + 1;
+  return 2 * items + (items + 3) / 4 + 1;   // D, per-workgroup maxima of |dO|, their maximum, log-sum-exp in base 2
 }
 
 size_t lsk_attn_decode_scratch_floats(int, int, int, int, int);

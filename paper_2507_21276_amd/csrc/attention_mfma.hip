@@ -1109,10 +1109,14 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const T* __restrict_
   }
 }
 
+#include "attention_bwd_sched.h"
+
 // also records max|dO| per workgroup in dvec[n_items + blockIdx.x]; amax_finish_kernel
 // folds those into dvec[n_items + gridDim.x] (no atomics: deterministic and contention-free)
+// lse2 (nullable): receives the log-sum-exp in base 2, lse * log2(e), which the head_dim-128 dK/dV kernel reads
 template <class T, int DH>
-__global__ __launch_bounds__(256) void dvec_kernel(const T* o, const T* dO, long n_items, float* dvec) {
+__global__ __launch_bounds__(256) void dvec_kernel(const T* o, const T* dO, long n_items, float* dvec,
+                                                   const float* lse, float* lse2) {
   typedef typename Mma<T>::V8 V8;
   constexpr int LPI = DH / 8, IPW = 64 / LPI;   // lanes per (row, head) item (16 bytes each), items per wavefront
   __shared__ float wmax[4];
@@ -1131,7 +1135,10 @@ __global__ __launch_bounds__(256) void dvec_kernel(const T* o, const T* dO, long
 #pragma unroll
   for (int off = 1; off < LPI; off <<= 1) s += __shfl_xor(s, off, 64);
   m = wave_max(m);
-  if (item < n_items && lane % LPI == 0) dvec[item] = s;
+  if (item < n_items && lane % LPI == 0) {
+    dvec[item] = s;
+    if (lse2) lse2[item] = lse[item] * 1.4426950408889634f;
+  }
   if (lane == 0) wmax[wave] = m;
   __syncthreads();
   if (threadIdx.x == 0) dvec[n_items + blockIdx.x] = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
@@ -1166,7 +1173,8 @@ ls_status launch_bwd(const void* qkv, const void* o, const void* dO, const float
   const long nb = (items + 3) / 4;
   // the scratch keeps room for one maximum per four items; the kernel fills one per 4 * (512 / head_dim)
   const long nwg = (items + 4 * (512 / DH) - 1) / (4 * (512 / DH));
-  dvec_kernel<T, DH><<<(unsigned)nwg, 256, 0, st>>>((const T*)o, (const T*)dO, items, dvec);
+  float* lse2 = DH == 128 ? dvec + items + nb + 1 : nullptr;   // after D, the per-workgroup maxima and their maximum
+  dvec_kernel<T, DH><<<(unsigned)nwg, 256, 0, st>>>((const T*)o, (const T*)dO, items, dvec, lse, lse2);
   amax_finish_kernel<<<1, 1024, 0, st>>>(dvec + items, nwg, nb);
   LS_CHECK_LAUNCH();
   dim3 gq(B * h, (L + 127) / 128), gk(B * h, (L + 127) / 128);
@@ -1181,6 +1189,16 @@ ls_status launch_bwd(const void* qkv, const void* o, const void* dO, const float
   LS_CHECK_LAUNCH();
   constexpr int dkv_lds = 4 * (2 * 64 * DH * 2 + 512);
   static bool dkv_attr = false;
+  if constexpr (DH == 128) {
+    if (!dkv_attr) {
+      LS_CHECK_HIP(hipFuncSetAttribute((const void*)flash_bwd_dkv128_kernel<T>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, dkv_lds));
+      dkv_attr = true;
+    }
+    flash_bwd_dkv128_kernel<T><<<gk, 256, dkv_lds, st>>>((const T*)qkv, (const T*)dO, lse2, dvec, (T*)dqkv, L, h, scale, rope);
+    LS_CHECK_LAUNCH();
+    return LS_OK;
+  }
   if (!dkv_attr) {
     LS_CHECK_HIP(hipFuncSetAttribute((const void*)flash_bwd_dkv_kernel<T, DH>,
                                      hipFuncAttributeMaxDynamicSharedMemorySize, dkv_lds));

@@ -148,6 +148,10 @@ def test_no_instruction_touches_a_register_with_an_assembly_issued_lds_read_in_f
     looped = ("_Zk:\n.LBB0_1:\n\tv_mov_b32_e32 v0, v4\n\ts_waitcnt lgkmcnt(0)\n\tds_read_b128 v[4:7], v9\n"
               "\ts_cbranch_scc0 .LBB0_1\n\ts_waitcnt lgkmcnt(0)\n\ts_endpgm\n")
     assert isa_lint.scan(looped) == {"_Zk": [(2, "v_mov_b32_e32 v0, v4")]}
+    # a scalar load in flight does not stop a counted wait from retiring the older LDS reads, and is never retired by one
+    mixed = ("_Zk:\n\tds_read_b128 v[4:7], v9\n\ts_load_dwordx2 s[0:1], s[2:3], 0x0\n\tds_read_b128 v[10:13], v9\n"
+             "\ts_waitcnt lgkmcnt(1)\n\tv_mov_b32_e32 v0, v4\n\tv_mov_b32_e32 v1, v10\n\ts_waitcnt lgkmcnt(0)\n\ts_endpgm\n")
+    assert isa_lint.scan(mixed) == {"_Zk": [(6, "v_mov_b32_e32 v1, v10")]}
     for src in ("gemm_dma.hip", "gemm_dma16.hip", "attention_mfma.hip"):
         out = tmp_path / (src + ".s")
         subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
