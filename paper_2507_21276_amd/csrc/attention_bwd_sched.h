@@ -10,10 +10,16 @@
 //     tile instead of address arithmetic per read;
 //   * fragments are fetched a fixed number of MFMAs ahead and waited for by count.
 //
-// A tile (64 queries in two blocks of 32, against the wavefront's 32 keys) is 64 MFMAs in four
-// phases of 16:  A: S, dP of block 0;  B: S, dP of block 1 beside the exponentials of block 0;
-// C: dV, dK of block 0 beside the exponentials of block 1;  D: dV, dK of block 1, the ring step
-// and the first fragments of the next tile.
+// A tile (64 queries in two blocks of 32, against the wavefront's 32 keys) is 64 MFMAs; "gap g" is the slot
+// after MFMA g, and everything else of the tile is placed into the gaps so that no gap holds much more than
+// the 32 cycles its MFMA runs:
+//   MFMA  0.. 7  S of block 0        8..15  dP of block 0      16..23  S of block 1     24..31  dP of block 1
+//        32..47  dV, dK of block 0  48..63  dV, dK of block 1
+//   exponentials of block 0 in gaps 8..23 (one element each), its dS in 24..31 (two each); exponentials of
+//   block 1 in 32..47, its dS in 48..59; fragment reads 8 MFMAs ahead (transposed ones 4 ahead), the
+//   log-sum-exp / D vectors a few gaps before their first use; the ten direct-to-LDS loads that refill the
+//   stage of the previous tile in every second gap of 5..15 and 25..31 (bunched after the barrier, the four
+//   wavefronts queue up at the compute unit's one load path: 450 ns per tile); the ring step after gap 59.
 //
 // The compiler does not know what the assembly statements do, so the hazards it normally covers
 // are handled here: an MFMA result is read by vector instructions only after bwd_mfma_settle(),
@@ -33,7 +39,7 @@ template <int B, int E, class F> __device__ __forceinline__ void static_for(F&& 
 // after it.  The compiler keeps that distance for its own MFMAs; here it cannot know that a statement is one (and
 // it does move the conversions that complete an operand down to the statement that first uses it), so operands
 // made by vector instructions go through operand_ready() at least one MFMA before they are used.
-template <class V> __device__ __forceinline__ void operand_ready(V& a, V& b) { asm volatile("" : "+v"(a), "+v"(b)); }
+template <class V> __device__ __forceinline__ void operand_ready(V& a) { asm volatile("" : "+v"(a)); }
 // D (vector registers) = A (vector registers) x B (accumulator file) [+ D]
 template <class T, bool FIRST>
 __device__ __forceinline__ void mma_to_vgpr(f32x16& d, const typename Mma<T>::V8& a, const typename Mma<T>::V8& b) {
@@ -53,13 +59,12 @@ __device__ __forceinline__ void mma_to_agpr(f32x16& d, const typename Mma<T>::V8
   else
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(d) : "v"(a), "v"(b));
 }
-// Wait states between the last MFMA that wrote these registers and a vector instruction that reads
-// them (the longest case of the ISA's table is 19; the MFMA issued in between runs meanwhile).
-__device__ __forceinline__ void bwd_mfma_settle(f32x16& a, f32x16& b) {
-  asm volatile("s_nop 15\n\ts_nop 7" : "+v"(a), "+v"(b));
-}
-// The same for the eight accumulator blocks of a kernel, at the end of every tile: whatever the compiler places
-// after the tile's last MFMA (copies of an accumulator at a loop edge, the epilogue's reads) comes after it.
+// Wait states between the last MFMA that wrote these registers and a vector instruction that reads them: 11
+// for this MFMA (its 8 passes + 3; the MFMA issued in between runs meanwhile).
+__device__ __forceinline__ void bwd_mfma_settle(f32x16& a) { asm volatile("s_nop 10" : "+v"(a)); }
+// The same, generously, for the eight accumulator blocks of a kernel at the end of every tile: whatever the
+// compiler places after the tile's last MFMA (copies of an accumulator at a loop edge, the epilogue's reads)
+// comes after it.
 __device__ __forceinline__ void bwd_mfma_settle_acc(f32x16 (&a)[4], f32x16 (&b)[4]) {
   asm volatile("s_nop 15\n\ts_nop 7"
                : "+a"(a[0]), "+a"(a[1]), "+a"(a[2]), "+a"(a[3]), "+a"(b[0]), "+a"(b[1]), "+a"(b[2]), "+a"(b[3]));
@@ -89,34 +94,39 @@ __device__ __forceinline__ void dma4(const void* base, uint32_t off, uint32_t ld
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(lds), "v"(off), "s"(base) : "memory", "m0");
 }
 
-// ---- the read schedule of a dK/dV tile, as a table the wait counts are derived from ----------
-// Time is counted in gaps (the slot after an MFMA); a cycle starts at the ring step, which leaves
-// no read outstanding: gaps 0..3 are the last four of phase D (first fragments of the next tile),
-// 4..19 phase A, 20..35 phase B, 36..51 phase C, 52..63 the first twelve of phase D.
+// ---- the LDS read schedule of a dK/dV tile, as a table the wait counts are derived from ----------
+// A cycle starts at the ring step (after gap 59), which leaves no read outstanding; position tau counts the
+// gaps from there: gaps 60..63 are tau 0..3, gaps 0..59 are tau 4..63.
 struct DkvPlan {
-  static constexpr int reads_in_gap(int g) {
-    if (g < 4) return 2;                  // two fragments of the next tile
-    if (g < 12) return 2;                 // fragment + one vector of log-sum-exp / D values of block 0
-    if (g < 20) return 1;                 // fragment
-    if (g < 28) return 2;                 // fragment + one vector of block 1's values
-    if (g < 36) return 1;                 // one half of a transposed fragment
-    return 2;                             // both halves of a transposed fragment
+  static constexpr int tau(int gap) { return gap >= 60 ? gap - 60 : gap + 4; }
+  static constexpr int reads_at(int t) {
+    const int gap = t < 4 ? 60 + t : t - 4;
+    if (gap >= 60) return 2;        // two fragments of the next tile
+    if (gap < 4) return 2;          // fragment, log-sum-exp of block 0
+    if (gap < 16) return 1;         // fragment
+    if (gap < 24) return 2;         // fragment, D of block 0 (16..19) or log-sum-exp of block 1 (20..23)
+    if (gap < 32) return 1;         // half a transposed fragment
+    if (gap < 40) return 2;         // transposed fragment
+    if (gap < 44) return 3;         // transposed fragment, D of block 1
+    return 2;                       // transposed fragment
   }
-  static constexpr int issued_through(int g) {   // reads issued in gaps 0 .. g
+  static constexpr int issued_through(int t) {   // reads issued at positions 0 .. t
     int n = 0;
-    for (int i = 0; i <= g; ++i) n += reads_in_gap(i);
+    for (int i = 0; i <= t; ++i) n += reads_at(i);
     return n;
   }
-  // reads issued after read number `pos` of gap `gr` and before the MFMA that follows gap gc - 1
-  static constexpr int newer(int gc, int gr, int pos) { return issued_through(gc - 1) - issued_through(gr - 1) - pos - 1; }
-  // One wait serves two MFMAs: before MFMA f (even) the operands of f and f + 1 must have landed, i.e. the
-  // count is the number of reads issued after those of f + 1.
-  static constexpr int frag_gap(int f) { return f < 8 ? f / 2 : f - 4; }
-  static constexpr int frag_pos(int f) { return f < 8 ? f % 2 : 0; }
-  static constexpr int wait_AB(int f) { return newer(4 + f, frag_gap(f + 1), frag_pos(f + 1)); }   // f = 0, 2, .. 30
-  static constexpr int tr_gap(int M) { return M < 4 ? 29 + 2 * M : 32 + M; }                     // M = 16 c + m
-  static constexpr int tr_pos(int M) { return M < 4 ? 0 : 1; }
-  static constexpr int wait_CD(int M) { return newer(36 + M, tr_gap(M + 1), tr_pos(M + 1)); }    // M = 0, 2, .. 26
+  // reads issued after read number `pos` of position tr and before the MFMA that precedes gap `gap`
+  static constexpr int newer(int gap, int tr, int pos) { return issued_through(tau(gap) - 1) - issued_through(tr - 1) - pos - 1; }
+  // position of the (last) read that MFMA g waits for
+  static constexpr int need_tau(int g) {
+    if (g < 8) return g / 2;
+    if (g < 32) return g - 4;                       // issued in gap g - 8
+    const int M = g - 32;
+    return M < 4 ? 29 + 2 * M : 32 + M;             // second half: gap 25 + 2 M, or gap 28 + M
+  }
+  static constexpr int need_pos(int g) { return g < 8 ? g % 2 : g < 32 ? 0 : (g - 32 < 4 ? 0 : 1); }
+  // One wait serves two MFMAs: before MFMA g (even) the operands of g and g + 1 must have landed.
+  static constexpr int wait(int g) { return newer(g, need_tau(g + 1), need_pos(g + 1)); }
 };
 
 // dK, dV for head_dim 128.  Grid, LDS layout and arguments of flash_bwd_dkv_kernel, except that lse2 is the
@@ -212,7 +222,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv128_kernel(const T* __restri
     }
   };
 #pragma unroll
-  for (int t = 0; t < NS; ++t) {
+  for (int t = 0; t < NS - 1; ++t) {   // the tile loop refills a stage one tile after it was used: tile 0 fetches tile NS - 1
     prepare_tile(t);
     static_for<0, NLD>([&](auto i_) { issue_one(t, i_); });
   }
@@ -249,21 +259,22 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv128_kernel(const T* __restri
   // the K / V fragments were requested after the four stages: when they are here, so are the stages
   asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
 
-  // fragment F(i), i = 0 .. 31, of a tile's first products: block i / 16, k step (i % 16) / 2, Q (even) or dO (odd)
+  // fragment n = 0 .. 31 of a tile's first products, in MFMA order: block n / 16, Q (S) or dO (dP) by (n % 16) / 8,
+  // k step n % 8
   V8 nf[8];
-  auto read_frag = [&](auto i_) {
-    constexpr int i = decltype(i_)::value;
-    lds_read16<(i / 16) * 32 * (DH * 2) + (i % 2) * TILE_B>(nf[i % 8], nat[(i % 16) / 2]);
+  auto read_frag = [&](auto n_) {
+    constexpr int n = decltype(n_)::value;
+    lds_read16<(n / 16) * 32 * (DH * 2) + ((n % 16) / 8) * TILE_B>(nf[n % 8], nat[n % 8]);
   };
   static_for<0, 8>([&](auto i_) { read_frag(i_); });
 
   TrFrag tf[8];
   f32x16 sacc0, pacc0, sacc1, pacc1;
-  f32x4 lv[2][8];        // per block: [g][lse lo, lse hi, D lo, D hi] of the lane's 8 queries of each 16-query step
+  f32x4 ls[2][4], dd[2][4];      // per block: log-sum-exp and D of the lane's queries, [16-query step][first / second four]
   u32x4 pw[2][2], dw[2][2];      // P and dS of a block, 16 bits each: per 16-query step the B operand of the second products
 
-  // transposed fragment for MFMA M = 16 c + m of the second products: step st4 = m / 4 (dO^T P, Q^T dS for the
-  // first 16 queries of the block, then for the second 16), head-dimension block j = m % 4
+  // transposed fragment for MFMA 32 + M of the second products, M = 16 c + m: step st4 = m / 4 (dO^T P, Q^T dS for
+  // the first 16 queries of the block, then for the second 16), head-dimension block j = m % 4
   auto read_tr = [&](auto M_, auto half_) {
     constexpr int M = decltype(M_)::value, half = decltype(half_)::value;
     constexpr int c = M / 16, m = M % 16, st4 = m / 4, j = m % 4, g = st4 >> 1, which = st4 & 1;
@@ -271,93 +282,99 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv128_kernel(const T* __restri
     if constexpr (half == 0) lds_read_tr<imm>(tf[M % 8].lo, tr0[j]);
     else lds_read_tr<imm>(tf[M % 8].hi, tr1[j]);
   };
-  auto read_lv = [&](auto c_, auto r_) {
-    constexpr int c = decltype(c_)::value, r = decltype(r_)::value, g = r / 4, k4 = r % 4;
-    lds_read16<128 * c + 64 * g + (k4 & 1) * 16 + (k4 >> 1) * 256>(lv[c][r], lsv);
+  // vector r = 0 .. 3 of a block's log-sum-exp (is_d = 0) or D (is_d = 1) values: 16-query step r / 2, half r % 2
+  auto read_lv = [&](auto c_, auto is_d_, auto r_) {
+    constexpr int c = decltype(c_)::value, is_d = decltype(is_d_)::value, r = decltype(r_)::value;
+    constexpr int imm = 128 * c + 64 * (r / 2) + (r % 2) * 16 + is_d * 256;
+    if constexpr (is_d) lds_read16<imm>(dd[c][r], lsv);
+    else lds_read16<imm>(ls[c][r], lsv);
   };
 
   auto tile = [&](auto masked_tag, int t) {
     constexpr bool MASKED = decltype(masked_tag)::value;
     const int q0 = (qt_first + t) * QR;
-    // the arithmetic between the products for element e of block c (query q0 + 32 c + 16 (e / 8) + 8 hf + e % 8)
-    float p_even = 0.f, d_even = 0.f;
-    auto element = [&](auto c_, auto e_, const f32x16& sacc, const f32x16& pacc) {
+    // element e of block c is query q0 + 32 c + 16 (e / 8) + 8 hf + e % 8.  First half of its arithmetic: the
+    // probability, which replaces the score in the accumulator register and goes into the P operand.
+    auto exp_part = [&](auto c_, auto e_, f32x16& sacc) {
       constexpr int c = decltype(c_)::value, e = decltype(e_)::value, g = e >> 3, i = e & 7;
-      const float lq = lv[c][g * 4 + (i >> 2)][i & 3];
-      const float dq = lv[c][g * 4 + 2 + (i >> 2)][i & 3];
-      float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[e], scale_log2, -lq));
+      float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[e], scale_log2, -ls[c][g * 2 + (i >> 2)][i & 3]));
       if constexpr (MASKED) {
         const int r0 = 32 * c + 16 * g + 8 * hf;
         if ((unsigned)(q0 + r0 - key + i) >= vis) p = 0.f;   // key <= query < L, as one unsigned compare
       }
-      const float ds = p * (pacc[e] - dq) * gsc;
-      if constexpr ((e & 1) == 0) {
-        p_even = p;
-        d_even = ds;
-      } else {
+      sacc[e] = p;
+      if constexpr (e & 1) {
         typedef T T2 __attribute__((ext_vector_type(2)));
-        T2 a, bb;
-        a[0] = from_f<T>(p_even); a[1] = from_f<T>(p);
-        bb[0] = from_f<T>(d_even); bb[1] = from_f<T>(ds);
+        T2 a;
+        a[0] = from_f<T>(sacc[e - 1]);
+        a[1] = from_f<T>(p);
         pw[c][g][i >> 1] = __builtin_bit_cast(uint32_t, a);
-        dw[c][g][i >> 1] = __builtin_bit_cast(uint32_t, bb);
-        if constexpr (i == 7) operand_ready(pw[c][g], dw[c][g]);
+        if constexpr (i == 7) operand_ready(pw[c][g]);
+      }
+    };
+    // second half: dS = P (dP - D), times the power of two that keeps it in the 16-bit format's range
+    auto ds_part = [&](auto c_, auto e_, f32x16& sacc, const f32x16& pacc) {
+      constexpr int c = decltype(c_)::value, e = decltype(e_)::value, g = e >> 3, i = e & 7;
+      sacc[e] = sacc[e] * (pacc[e] - dd[c][g * 2 + (i >> 2)][i & 3]) * gsc;
+      if constexpr (e & 1) {
+        typedef T T2 __attribute__((ext_vector_type(2)));
+        T2 a;
+        a[0] = from_f<T>(sacc[e - 1]);
+        a[1] = from_f<T>(sacc[e]);
+        dw[c][g][i >> 1] = __builtin_bit_cast(uint32_t, a);
+        if constexpr (i == 7) operand_ready(dw[c][g]);
       }
     };
     auto operand = [&](const u32x4& w) { return __builtin_bit_cast(V8, w); };
 
-    // ---- phase A: S, dP of block 0
-    static_for<0, 16>([&](auto f_) {
-      constexpr int f = decltype(f_)::value, s = f / 2;
-      if constexpr (f % 2 == 0) lgkm_wait<DkvPlan::wait_AB(f)>();
-      if constexpr (f % 2 == 0) mma_to_vgpr<T, s == 0>(sacc0, nf[f % 8], kf[s]);
-      else mma_to_vgpr<T, s == 0>(pacc0, nf[f % 8], vf[s]);
-      read_frag(IC<f + 8>{});
-      if constexpr (f < 8) read_lv(IC<0>{}, f_);
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    // ---- phase B: S, dP of block 1; exponentials of block 0
-    static_for<0, 16>([&](auto k_) {
-      constexpr int k = decltype(k_)::value, f = 16 + k, s = k / 2;
-      if constexpr (f % 2 == 0) lgkm_wait<DkvPlan::wait_AB(f)>();
-      if constexpr (f % 2 == 0) mma_to_vgpr<T, s == 0>(sacc1, nf[f % 8], kf[s]);
-      else mma_to_vgpr<T, s == 0>(pacc1, nf[f % 8], vf[s]);
-      if constexpr (k == 0) bwd_mfma_settle(sacc0, pacc0);
-      if constexpr (k < 8) {
-        read_frag(IC<f + 8>{});
-        read_lv(IC<1>{}, k_);
+    static_for<0, 64>([&](auto g_) {
+      constexpr int g = decltype(g_)::value;
+      // ---- the MFMA
+      if constexpr (g < 60 && g % 2 == 0) lgkm_wait<DkvPlan::wait(g)>();
+      if constexpr (g < 32) {
+        constexpr int s = g % 8;
+        if constexpr (g < 8) mma_to_vgpr<T, s == 0>(sacc0, nf[g % 8], kf[s]);
+        else if constexpr (g < 16) mma_to_vgpr<T, s == 0>(pacc0, nf[g % 8], vf[s]);
+        else if constexpr (g < 24) mma_to_vgpr<T, s == 0>(sacc1, nf[g % 8], kf[s]);
+        else mma_to_vgpr<T, s == 0>(pacc1, nf[g % 8], vf[s]);
       } else {
-        read_tr(IC<(k - 8) / 2>{}, IC<(k - 8) % 2>{});
+        constexpr int M = g - 32, c = M / 16, m = M % 16, st4 = m / 4, j = m % 4, gq = st4 >> 1;
+        if constexpr ((st4 & 1) == 0) mma_to_agpr<T>(dv[j], tr_value<T>(tf[M % 8]), operand(pw[c][gq]));
+        else mma_to_agpr<T>(dk[j], tr_value<T>(tf[M % 8]), operand(dw[c][gq]));
       }
-      element(IC<0>{}, k_, sacc0, pacc0);
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    // ---- phase C: dV, dK of block 0; exponentials of block 1
-    static_for<0, 16>([&](auto m_) {
-      constexpr int m = decltype(m_)::value, st4 = m / 4, j = m % 4, g = st4 >> 1;
-      if constexpr (m % 2 == 0) lgkm_wait<DkvPlan::wait_CD(m)>();
-      if constexpr ((st4 & 1) == 0) mma_to_agpr<T>(dv[j], tr_value<T>(tf[m % 8]), operand(pw[0][g]));
-      else mma_to_agpr<T>(dk[j], tr_value<T>(tf[m % 8]), operand(dw[0][g]));
-      if constexpr (m == 0) bwd_mfma_settle(sacc1, pacc1);
-      read_tr(IC<m + 4>{}, IC<0>{});
-      read_tr(IC<m + 4>{}, IC<1>{});
-      element(IC<1>{}, m_, sacc1, pacc1);
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    // ---- phase D: dV, dK of block 1; ring step; first fragments of the next tile
-    static_for<0, 16>([&](auto m_) {
-      constexpr int m = decltype(m_)::value, st4 = m / 4, j = m % 4, g = st4 >> 1;
-      if constexpr (m < 12 && m % 2 == 0) lgkm_wait<DkvPlan::wait_CD(16 + m)>();
-      if constexpr ((st4 & 1) == 0) mma_to_agpr<T>(dv[j], tr_value<T>(tf[(16 + m) % 8]), operand(pw[1][g]));
-      else mma_to_agpr<T>(dk[j], tr_value<T>(tf[(16 + m) % 8]), operand(dw[1][g]));
-      if constexpr (m < 12) {
-        read_tr(IC<16 + m + 4>{}, IC<0>{});
-        read_tr(IC<16 + m + 4>{}, IC<1>{});
+      // ---- LDS reads of this gap
+      if constexpr (g < 24) read_frag(IC<g + 8>{});
+      if constexpr (g < 4) read_lv(IC<0>{}, IC<0>{}, g_);
+      if constexpr (g >= 16 && g < 20) read_lv(IC<0>{}, IC<1>{}, IC<g - 16>{});
+      if constexpr (g >= 20 && g < 24) read_lv(IC<1>{}, IC<0>{}, IC<g - 20>{});
+      if constexpr (g >= 24 && g < 32) read_tr(IC<(g - 24) / 2>{}, IC<(g - 24) % 2>{});
+      if constexpr (g >= 32 && g < 60) {
+        read_tr(IC<g - 32 + 4>{}, IC<0>{});
+        read_tr(IC<g - 32 + 4>{}, IC<1>{});
       }
-      if constexpr (m == 11) {
+      if constexpr (g >= 40 && g < 44) read_lv(IC<1>{}, IC<1>{}, IC<g - 40>{});
+      // ---- direct-to-LDS loads of tile t + NS - 1 into the stage that tile t - 1 left
+      if constexpr (g == 4) prepare_tile(t + NS - 1);
+      if constexpr (g >= 5 && g < 16 && g % 2 == 1) issue_one(t + NS - 1, IC<(g - 5) / 2>{});
+      if constexpr (g >= 25 && g < 32 && g % 2 == 1) issue_one(t + NS - 1, IC<6 + (g - 25) / 2>{});
+      // ---- vector work of this gap
+      if constexpr (g == 8) bwd_mfma_settle(sacc0);
+      if constexpr (g >= 8 && g < 24) exp_part(IC<0>{}, IC<g - 8>{}, sacc0);
+      if constexpr (g >= 24 && g < 32) {
+        ds_part(IC<0>{}, IC<2 * (g - 24)>{}, sacc0, pacc0);
+        ds_part(IC<0>{}, IC<2 * (g - 24) + 1>{}, sacc0, pacc0);
+      }
+      if constexpr (g >= 32 && g < 48) exp_part(IC<1>{}, IC<g - 32>{}, sacc1);
+      if constexpr (g >= 48 && g < 52) {
+        ds_part(IC<1>{}, IC<2 * (g - 48)>{}, sacc1, pacc1);
+        ds_part(IC<1>{}, IC<2 * (g - 48) + 1>{}, sacc1, pacc1);
+      }
+      if constexpr (g >= 52 && g < 60) ds_part(IC<1>{}, IC<g - 44>{}, sacc1, pacc1);
+      // ---- ring step and the first fragments of the next tile
+      if constexpr (g == 59) {
         // every read of this tile has been issued: when they have landed, and tile t + 1 too (only the loads
-        // of tiles t + 2 .. t + NS - 1 outstanding), the stage is handed back and refilled over the next gaps
-        // (the barrier is issued from assembly: before its own the compiler waits for every load in flight)
+        // of tiles t + 2 and t + 3 outstanding), the stage is handed back.  (The barrier is issued from
+        // assembly: before its own the compiler waits for every load in flight.)
         asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NS - 2) * NLD) : "memory");
         const int step = ((t + 1) % NS == 0) ? -(NS - 1) * STAGE_B : STAGE_B;
 #pragma unroll
@@ -369,14 +386,9 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv128_kernel(const T* __restri
         }
         lsv += step;
       }
-      if constexpr (m == 11) prepare_tile(t + NS);
-      if constexpr (m >= 11) {
-        issue_one(t + NS, IC<2 * (m - 11)>{});
-        issue_one(t + NS, IC<2 * (m - 11) + 1>{});
-      }
-      if constexpr (m >= 12) {
-        read_frag(IC<2 * (m - 12)>{});
-        read_frag(IC<2 * (m - 12) + 1>{});
+      if constexpr (g >= 60) {
+        read_frag(IC<2 * (g - 60)>{});
+        read_frag(IC<2 * (g - 60) + 1>{});
       }
       __builtin_amdgcn_sched_barrier(0);
     });
