@@ -409,3 +409,261 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv128_kernel(const T* __restri
     store_grad_row<T, DH>(rk + d, dv, 1.0f, hf, nullptr);
   }
 }
+
+// ---- dQ ------------------------------------------------------------------------------------------
+// The same treatment for flash_bwd_dq_kernel at head_dim 128.  A workgroup owns 128 queries (32 per
+// wavefront, Q and dO fragments in the accumulator file) and walks the key tiles of 64 keys below its diagonal.
+// Both first products are formed transposed (S^T, dP^T: rows = keys, lane = query), so the softmax statistics are
+// per-lane scalars.  A tile is 48 MFMAs: 0..15 S^T and dP^T of keys 0..31 (alternating), 16..31 of keys
+// 32..63, 32..39 dQ^T += K^T dS^T of the first block, 40..47 of the second; the exponentials and dS of the first
+// block in gaps 16..31, of the second in 32..43; the eight direct-to-LDS loads in the odd gaps 1..15; the ring
+// step after gap 43.
+struct DqPlan {
+  static constexpr int tau(int gap) { return gap >= 44 ? gap - 44 : gap + 4; }
+  static constexpr int reads_at(int t) {
+    const int gap = t < 4 ? 44 + t : t - 4;
+    if (gap >= 44) return 2;        // two fragments of the next tile
+    if (gap < 24) return 1;         // fragment
+    if (gap < 32) return 1;         // half a transposed fragment
+    return 2;                       // transposed fragment (gaps 32..43)
+  }
+  static constexpr int issued_through(int t) {
+    int n = 0;
+    for (int i = 0; i <= t; ++i) n += reads_at(i);
+    return n;
+  }
+  static constexpr int newer(int gap, int tr, int pos) { return issued_through(tau(gap) - 1) - issued_through(tr - 1) - pos - 1; }
+  static constexpr int need_tau(int g) {
+    if (g < 8) return g / 2;
+    if (g < 32) return g - 4;                       // issued in gap g - 8
+    const int M = g - 32;
+    return M < 4 ? 29 + 2 * M : 32 + M;             // second half: gap 25 + 2 M, or gap 28 + M
+  }
+  static constexpr int need_pos(int g) { return g < 8 ? g % 2 : g < 32 ? 0 : (g - 32 < 4 ? 0 : 1); }
+  static constexpr int wait(int g) { return newer(g, need_tau(g + 1), need_pos(g + 1)); }
+};
+
+template <class T>
+__global__ __launch_bounds__(256) void flash_bwd_dq128_kernel(const T* __restrict__ qkv, const T* __restrict__ dO,
+                                                              const float* __restrict__ lse2v,
+                                                              const float* __restrict__ dvec, T* __restrict__ dqkv,
+                                                              int L, int h, float scale,
+                                                              const float* __restrict__ rope) {
+  typedef typename Mma<T>::V8 V8;
+  constexpr int DH = 128, BQ = 128, NS = 4, KS = DH / 16, DT = DH / 32;
+  constexpr int TILE_B = KT * DH * 2;            // bytes of a K or V tile
+  constexpr int STAGE_B = 2 * TILE_B;
+  constexpr int NLT = TILE_B / 1024 / 4;         // wave loads per wavefront and tile
+  constexpr int NLD = 2 * NLT;                   // loads per wavefront and stage
+  static_assert(NLD == 8, "the refill of a stage takes the eight odd gaps 1 .. 15");
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+  const int n_qt = (L + BQ - 1) / BQ;
+  const int qtile = n_qt - 1 - blockIdx.y;   // heaviest tiles of all heads first
+  const int b = blockIdx.x / h, head = blockIdx.x % h;
+  const int d = h * DH;
+  const long ld = 3L * d;
+  const T* qb = qkv + (long)b * L * ld + (long)head * DH;
+  const T* kb = qb + d;
+  const T* vb = qb + 2 * d;
+  const T* dob = dO + (long)b * L * d + (long)head * DH;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int col = lane & 31, hf = lane >> 5;
+  const int wq0 = qtile * BQ + wave * 32;
+  const int q = wq0 + col;
+  const float scale_log2 = scale * 1.4426950408889634f;
+  const float gsc = do_scale(dvec + (long)gridDim.x * L + ((long)gridDim.x * L + 3) / 4);   // after D and the per-workgroup maxima
+
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)smem;
+  uint32_t nat[KS], tr0[DT], tr1[DT];
+  {
+    const int row = pi_row(col);   // MFMA row r is key pi(r): a lane's 8 values per 16-key step are consecutive keys
+#pragma unroll
+    for (int s = 0; s < KS; ++s) nat[s] = lds0 + row * (DH * 2) + (((2 * s + hf) ^ tile_swz<DH>(row)) * 16);
+    const int i16 = lane & 15, a = i16 >> 2, j4 = i16 & 3;
+    const int k = 8 * (lane >> 5) + a;
+#pragma unroll
+    for (int j = 0; j < DT; ++j) {
+      const int nb = j * 32 + 16 * ((lane >> 4) & 1) + 4 * j4;
+      tr0[j] = lds0 + k * (DH * 2) + (((nb >> 3) ^ tile_swz<DH>(k)) * 16) + ((nb >> 2) & 1) * 8;
+      tr1[j] = lds0 + (k + 4) * (DH * 2) + (((nb >> 3) ^ tile_swz<DH>(k + 4)) * 16) + ((nb >> 2) & 1) * 8;
+    }
+  }
+
+  const int q_hi = min(L, qtile * BQ + BQ) - 1;
+  const int nt = q_hi / KT + 1;
+  // Direct-to-LDS loads of a stage: load i = 0 .. NLD - 1 of this wavefront (K rows, then V rows).  Per-lane offsets
+  // from the tile's first row, the same for every full tile; the last tile of the sequence, when cut off, re-reads
+  // row L - 1 for the rows past it (prepare_tile switches the offsets once; fetches past the end repeat that tile).
+  constexpr int CPR = DH / 8, RPL = 64 / CPR;
+  uint32_t koff[NLT];
+  auto set_offsets = [&](int rows) {
+#pragma unroll
+    for (int j = 0; j < NLT; ++j) {
+      const int row = (wave * NLT + j) * RPL + lane / CPR;
+      const int gch = (lane % CPR) ^ tile_swz<DH>(row);
+      koff[j] = (uint32_t)((min(row, rows - 1) * ld + gch * 8) * 2);
+    }
+  };
+  set_offsets(KT);
+  const int last_rows = min(L - (nt - 1) * KT, KT);
+  auto prepare_tile = [&](int t) {
+    if (t >= nt - 1 && last_rows < KT) set_offsets(last_rows);
+  };
+  auto issue_one = [&](int t, auto i_) {
+    constexpr int i = decltype(i_)::value, j = i % NLT;
+    const int key0 = min(t, nt - 1) * KT;
+    const uint32_t st = lds0 + (t % NS) * STAGE_B;
+    if constexpr (i < NLT) dma16(kb + (long)key0 * ld, koff[j], st + (wave * NLT + j) * 1024);
+    else dma16(vb + (long)key0 * ld, koff[j], st + TILE_B + (wave * NLT + j) * 1024);
+  };
+#pragma unroll
+  for (int t = 0; t < NS - 1; ++t) {   // the tile loop refills a stage one tile after it was used
+    prepare_tile(t);
+    static_for<0, NLD>([&](auto i_) { issue_one(t, i_); });
+  }
+
+  // this wavefront's 32 queries: Q and dO fragments, all requested before the first is used
+  V8 qf[KS], dof[KS];
+  {
+    u32x4 z0[KS], z1[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      z0[s] = z1[s] = u32x4{0u, 0u, 0u, 0u};
+      if (q < L) {
+        z0[s] = *(const u32x4*)(qb + (long)q * ld + s * 16 + hf * 8);
+        z1[s] = *(const u32x4*)(dob + (long)q * d + s * 16 + hf * 8);
+      }
+    }
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      qf[s] = __builtin_bit_cast(V8, z0[s]);
+      dof[s] = __builtin_bit_cast(V8, z1[s]);
+      pin_agpr(qf[s]);
+      pin_agpr(dof[s]);
+    }
+  }
+  float lse2 = INFINITY, dq_ = 0.f;
+  if (q < L) {
+    lse2 = lse2v[((long)b * L + q) * h + head];
+    dq_ = dvec[((long)b * L + q) * h + head];
+  }
+  f32x16 acc[DT];
+#pragma unroll
+  for (int j = 0; j < DT; ++j) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[j][e] = 0.f;
+    pin_agpr(acc[j]);
+  }
+  // the Q / dO fragments were requested after the three stages: when they are here, so are the stages
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+
+  // fragment n = 0 .. 31 of a tile's first products, in MFMA order: key block n / 16, k step (n % 16) / 2, K (S^T, even n)
+  // or V (dP^T, odd n)
+  V8 nf[8];
+  auto read_frag = [&](auto n_) {
+    constexpr int n = decltype(n_)::value;
+    lds_read16<(n / 16) * 32 * (DH * 2) + (n % 2) * TILE_B>(nf[n % 8], nat[(n % 16) / 2]);
+  };
+  static_for<0, 8>([&](auto i_) { read_frag(i_); });
+  TrFrag tf[8];
+  f32x16 sacc0, pacc0, sacc1, pacc1;
+  u32x4 dw[2][2];      // dS^T of a key block, 16 bits each: per 16-key step the B operand of the second product
+  // transposed fragment for MFMA 32 + M, M = 8 c + m: 16-key step m / 4 of block c, head-dimension block j = m % 4
+  auto read_tr = [&](auto M_, auto half_) {
+    constexpr int M = decltype(M_)::value, half = decltype(half_)::value;
+    constexpr int c = M / 8, m = M % 8, g = m / 4, j = m % 4;
+    constexpr int imm = (c * 32 + g * 16) * (DH * 2);
+    if constexpr (half == 0) lds_read_tr<imm>(tf[M % 8].lo, tr0[j]);
+    else lds_read_tr<imm>(tf[M % 8].hi, tr1[j]);
+  };
+
+  auto tile = [&](auto masked_tag, int t) {
+    constexpr bool MASKED = decltype(masked_tag)::value;
+    const int key0 = t * KT;
+    // element e of block c is key key0 + 32 c + 16 (e / 8) + 8 hf + e % 8, the lane's column is its query
+    auto element = [&](auto c_, auto e_, f32x16& sacc, const f32x16& pacc) {
+      constexpr int c = decltype(c_)::value, e = decltype(e_)::value, g = e >> 3, i = e & 7;
+      float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[e], scale_log2, -lse2));
+      if constexpr (MASKED) {
+        if (key0 + 32 * c + 16 * g + 8 * hf + i > q) p = 0.f;
+      }
+      sacc[e] = p * (pacc[e] - dq_) * gsc;
+      if constexpr (e & 1) {
+        typedef T T2 __attribute__((ext_vector_type(2)));
+        T2 a;
+        a[0] = from_f<T>(sacc[e - 1]);
+        a[1] = from_f<T>(sacc[e]);
+        dw[c][g][i >> 1] = __builtin_bit_cast(uint32_t, a);
+        if constexpr (i == 7) operand_ready(dw[c][g]);
+      }
+    };
+    auto operand = [&](const u32x4& w) { return __builtin_bit_cast(V8, w); };
+
+    static_for<0, 48>([&](auto g_) {
+      constexpr int g = decltype(g_)::value;
+      if constexpr (g < 44 && g % 2 == 0) lgkm_wait<DqPlan::wait(g)>();
+      if constexpr (g < 32) {
+        constexpr int s = (g % 16) / 2;
+        if constexpr (g < 16) {
+          if constexpr (g % 2 == 0) mma_to_vgpr<T, s == 0>(sacc0, nf[g % 8], qf[s]);
+          else mma_to_vgpr<T, s == 0>(pacc0, nf[g % 8], dof[s]);
+        } else {
+          if constexpr (g % 2 == 0) mma_to_vgpr<T, s == 0>(sacc1, nf[g % 8], qf[s]);
+          else mma_to_vgpr<T, s == 0>(pacc1, nf[g % 8], dof[s]);
+        }
+      } else {
+        constexpr int M = g - 32, c = M / 8, m = M % 8, gq = m / 4, j = m % 4;
+        mma_to_agpr<T>(acc[j], tr_value<T>(tf[M % 8]), operand(dw[c][gq]));
+      }
+      // LDS reads of this gap
+      if constexpr (g < 24) read_frag(IC<g + 8>{});
+      if constexpr (g >= 24 && g < 32) read_tr(IC<(g - 24) / 2>{}, IC<(g - 24) % 2>{});
+      if constexpr (g >= 32 && g < 44) {
+        read_tr(IC<g - 32 + 4>{}, IC<0>{});
+        read_tr(IC<g - 32 + 4>{}, IC<1>{});
+      }
+      // direct-to-LDS loads of tile t + NS - 1 into the stage that tile t - 1 left
+      if constexpr (g == 0) prepare_tile(t + NS - 1);
+      if constexpr (g < 16 && g % 2 == 1) issue_one(t + NS - 1, IC<g / 2>{});
+      // vector work of this gap
+      if constexpr (g == 16) bwd_mfma_settle(sacc0);
+      if constexpr (g == 32) bwd_mfma_settle(sacc1);
+      if constexpr (g >= 16 && g < 32) element(IC<0>{}, IC<g - 16>{}, sacc0, pacc0);
+      if constexpr (g >= 32 && g < 40) element(IC<1>{}, IC<g - 32>{}, sacc1, pacc1);
+      if constexpr (g >= 40 && g < 44) {
+        element(IC<1>{}, IC<8 + 2 * (g - 40)>{}, sacc1, pacc1);
+        element(IC<1>{}, IC<9 + 2 * (g - 40)>{}, sacc1, pacc1);
+      }
+      // ring step and the first fragments of the next tile
+      if constexpr (g == 43) {
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NS - 2) * NLD) : "memory");
+        const int step = ((t + 1) % NS == 0) ? -(NS - 1) * STAGE_B : STAGE_B;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) nat[s] += step;
+#pragma unroll
+        for (int jj = 0; jj < DT; ++jj) {
+          tr0[jj] += step;
+          tr1[jj] += step;
+        }
+      }
+      if constexpr (g >= 44) {
+        read_frag(IC<2 * (g - 44)>{});
+        read_frag(IC<2 * (g - 44) + 1>{});
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    asm volatile("s_nop 15\n\ts_nop 7" : "+a"(acc[0]), "+a"(acc[1]), "+a"(acc[2]), "+a"(acc[3]));
+  };
+
+  // The key tiles that reach the diagonal of some query of the workgroup (the last two) need the mask.
+  const int n_plain = max(0, min(nt, (qtile * BQ) / KT));
+  int t = 0;
+  for (; t < n_plain; ++t) tile(std::false_type{}, t);
+  for (; t < nt; ++t) tile(std::true_type{}, t);
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+  if (q < L) {
+    T* row = dqkv + ((long)b * L + q) * ld + (long)head * DH;
+    store_grad_row<T, DH>(row, acc, scale / gsc, hf, rope ? rope + (long)q * DH : nullptr);
+  }
+}

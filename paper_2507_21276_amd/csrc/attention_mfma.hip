@@ -1180,12 +1180,21 @@ ls_status launch_bwd(const void* qkv, const void* o, const void* dO, const float
   dim3 gq(B * h, (L + 127) / 128), gk(B * h, (L + 127) / 128);
   constexpr int dq_lds = 4 * (2 * KT * DH * 2);
   static bool dq_attr = false;
-  if (!dq_attr) {
-    LS_CHECK_HIP(hipFuncSetAttribute((const void*)flash_bwd_dq_kernel<T, DH>,
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, dq_lds));
-    dq_attr = true;
+  if constexpr (DH == 128) {
+    if (!dq_attr) {
+      LS_CHECK_HIP(hipFuncSetAttribute((const void*)flash_bwd_dq128_kernel<T>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, dq_lds));
+      dq_attr = true;
+    }
+    flash_bwd_dq128_kernel<T><<<gq, 256, dq_lds, st>>>((const T*)qkv, (const T*)dO, lse2, dvec, (T*)dqkv, L, h, scale, rope);
+  } else {
+    if (!dq_attr) {
+      LS_CHECK_HIP(hipFuncSetAttribute((const void*)flash_bwd_dq_kernel<T, DH>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, dq_lds));
+      dq_attr = true;
+    }
+    flash_bwd_dq_kernel<T, DH><<<gq, 256, dq_lds, st>>>((const T*)qkv, (const T*)dO, lse, dvec, (T*)dqkv, L, h, scale, rope);
   }
-  flash_bwd_dq_kernel<T, DH><<<gq, 256, dq_lds, st>>>((const T*)qkv, (const T*)dO, lse, dvec, (T*)dqkv, L, h, scale, rope);
   LS_CHECK_LAUNCH();
   constexpr int dkv_lds = 4 * (2 * 64 * DH * 2 + 512);
   static bool dkv_attr = false;
