@@ -94,6 +94,57 @@ __device__ __forceinline__ void dma4(const void* base, uint32_t off, uint32_t ld
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" : : "s"(lds), "v"(off), "s"(base) : "memory", "m0");
 }
 
+// Store a wavefront's 32 gradient rows (O^T-style accumulators: lane = row, registers = head dimension
+// j * 32 + 8 g + 4 hf + i, as store_grad_row takes them) through LDS: each lane puts its 8-byte pieces into a
+// [32][128] tile of 16-bit values (rows padded to 272 bytes: two-way bank conflicts at most), then the tile is
+// written out as whole rows, 16 bytes per lane, four rows per store instruction - instead of 64 instructions
+// that each touch 32 rows with 8 bytes.  `tile` is this wavefront's own 8704 bytes of LDS; row r of the tile goes
+// to out + r * ld if r < rows.  With a rotary table (this lane's row of it) the row is rotated back first.
+template <class T>
+__device__ __forceinline__ void store_grad_rows_staged(T* out, long ld, int rows, const f32x16 (&acc)[4], float mul,
+                                                       int lane, const float* tab, char* tile) {
+  typedef typename Mma<T>::V4 V4;
+  constexpr int DH = 128, DT = 4, RS = DH * 2 + 16;
+  const int col = lane & 31, hf = lane >> 5;
+  char* my = tile + col * RS;
+  if (tab == nullptr) {
+#pragma unroll
+    for (int j = 0; j < DT; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        V4 v;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) v[i] = from_f<T>(acc[j][g * 4 + i] * mul);
+        *(V4*)(my + (j * 32 + 8 * g + 4 * hf) * 2) = v;
+      }
+  } else {
+#pragma unroll
+    for (int j = 0; j < DT / 2; ++j)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const int i0 = j * 32 + 8 * g + 4 * hf;
+        const f32x4 cs0 = *(const f32x4*)(tab + i0 * 2), cs1 = *(const f32x4*)(tab + i0 * 2 + 4);
+        V4 lo, hi;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          const float c = i < 2 ? cs0[2 * i] : cs1[2 * (i - 2)], sn = i < 2 ? cs0[2 * i + 1] : cs1[2 * (i - 2) + 1];
+          const float a = acc[j][g * 4 + i] * mul, b = acc[j + DT / 2][g * 4 + i] * mul;
+          lo[i] = from_f<T>(a * c + b * sn);
+          hi[i] = from_f<T>(b * c - a * sn);
+        }
+        *(V4*)(my + i0 * 2) = lo;
+        *(V4*)(my + (i0 + DH / 2) * 2) = hi;
+      }
+  }
+  // the LDS executes one wavefront's operations in order: the reads below see the writes above
+#pragma unroll
+  for (int it = 0; it < 8; ++it) {
+    const int r = it * 4 + (lane >> 4);
+    const u32x4 v = *(const u32x4*)(tile + r * RS + (lane & 15) * 16);
+    if (r < rows) *(u32x4*)(out + (long)r * ld + (lane & 15) * 8) = v;
+  }
+}
+
 // ---- the LDS read schedule of a dK/dV tile, as a table the wait counts are derived from ----------
 // A cycle starts at the ring step (after gap 59), which leaves no read outstanding; position tau counts the
 // gaps from there: gaps 60..63 are tau 0..3, gaps 0..59 are tau 4..63.
@@ -401,12 +452,15 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv128_kernel(const T* __restri
   int t = 0;
   for (; t < n_masked; ++t) tile(std::true_type{}, t);
   for (; t < nt; ++t) tile(std::false_type{}, t);
-  // the fragments read ahead for a tile that does not exist; no direct-to-LDS write may outlive the workgroup
-  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-  if (key < L) {
-    T* rk = dqkv + ((long)b * L + key) * ld + d + (long)head * DH;
-    store_grad_row<T, DH>(rk, dk, scale / gsc, hf, rope ? rope + (long)key * DH : nullptr);
-    store_grad_row<T, DH>(rk + d, dv, 1.0f, hf, nullptr);
+  // The fragments read ahead for a tile that does not exist are dropped; when every wavefront's loads have landed
+  // (no direct-to-LDS write may outlive the workgroup, or hit the tiles staged below) the ring is free.
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  {
+    char* stage_k = smem + wave * (2 * 8704);
+    T* rk = dqkv + ((long)b * L + wk0) * ld + d + (long)head * DH;
+    store_grad_rows_staged<T>(rk, ld, L - wk0, dk, scale / gsc, lane, (rope && key < L) ? rope + (long)key * DH : nullptr,
+                              stage_k);
+    store_grad_rows_staged<T>(rk + d, ld, L - wk0, dv, 1.0f, lane, nullptr, stage_k + 8704);
   }
 }
 
@@ -661,9 +715,7 @@ __global__ __launch_bounds__(256) void flash_bwd_dq128_kernel(const T* __restric
   int t = 0;
   for (; t < n_plain; ++t) tile(std::false_type{}, t);
   for (; t < nt; ++t) tile(std::true_type{}, t);
-  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-  if (q < L) {
-    T* row = dqkv + ((long)b * L + q) * ld + (long)head * DH;
-    store_grad_row<T, DH>(row, acc, scale / gsc, hf, rope ? rope + (long)q * DH : nullptr);
-  }
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // see the dK / dV kernel
+  store_grad_rows_staged<T>(dqkv + ((long)b * L + wq0) * ld + (long)head * DH, ld, L - wq0, acc, scale / gsc, lane,
+                            (rope && q < L) ? rope + (long)q * DH : nullptr, smem + wave * 8704);
 }
