@@ -719,3 +719,266 @@ __global__ __launch_bounds__(256) void flash_bwd_dq128_kernel(const T* __restric
   store_grad_rows_staged<T>(dqkv + ((long)b * L + wq0) * ld + (long)head * DH, ld, L - wq0, acc, scale / gsc, lane,
                             (rope && q < L) ? rope + (long)q * DH : nullptr, smem + wave * 8704);
 }
+
+// ---- forward (training layout) ---------------------------------------------------------------------
+// flash_fwd_ring_kernel at head_dim 128 on the same scheme.  A workgroup owns 128 queries (32 per wavefront, Q
+// fragments in the accumulator file), K / V tiles of 64 keys come through the ring.  A tile is 32 MFMAs:
+// 0..15 S^T = K Q^T (the two 32-key blocks alternating), then - with no MFMA to run beside it - the running
+// maximum and the exponentials of the first block, 16..23 O^T += V^T P^T for the first 32 keys beside the
+// exponentials of the second block, 24..31 for the second 32 keys; the eight direct-to-LDS loads in the odd gaps
+// 1..15, the ring step after gap 27.
+struct FwdPlan {
+  static constexpr int tau(int gap) { return gap >= 28 ? gap - 28 : gap + 4; }
+  static constexpr int reads_at(int t) {
+    const int gap = t < 4 ? 28 + t : t - 4;
+    if (gap >= 28) return 2;        // two fragments of the next tile
+    if (gap < 8) return 1;          // fragment
+    if (gap < 12) return 0;
+    return 2;                       // transposed fragment (gaps 12..27)
+  }
+  static constexpr int issued_through(int t) {
+    int n = 0;
+    for (int i = 0; i <= t; ++i) n += reads_at(i);
+    return n;
+  }
+  static constexpr int newer(int gap, int tr, int pos) { return issued_through(tau(gap) - 1) - issued_through(tr - 1) - pos - 1; }
+  static constexpr int need_tau(int g) {
+    if (g < 8) return g / 2;
+    if (g < 16) return g - 4;                       // issued in gap g - 8
+    return g;                                       // transposed fragment of MFMA 16 + M: gap 12 + M
+  }
+  static constexpr int need_pos(int g) { return g < 8 ? g % 2 : g < 16 ? 0 : 1; }
+  static constexpr int wait(int g) { return newer(g, need_tau(g + 1), need_pos(g + 1)); }
+};
+
+template <class T>
+__global__ __launch_bounds__(256) void flash_fwd128_kernel(const T* __restrict__ qkv, T* __restrict__ o,
+                                                           float* __restrict__ lse, int L, int h, float scale_log2) {
+  typedef typename Mma<T>::V8 V8;
+  constexpr int DH = 128, BQ = 128, NS = 4, KS = DH / 16, DT = DH / 32;
+  constexpr int TILE_B = KT * DH * 2;            // bytes of a K or V tile
+  constexpr int STAGE_B = 2 * TILE_B;
+  constexpr int NLT = TILE_B / 1024 / 4;         // wave loads per wavefront and tile
+  constexpr int NLD = 2 * NLT;                   // loads per wavefront and stage
+  static_assert(NLD == 8, "the refill of a stage takes the eight odd gaps 1 .. 15");
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+
+  const int b = blockIdx.x / h, head = blockIdx.x % h;
+  const int d = h * DH;
+  const long ld = 3L * d;
+  const int n_qt = (L + BQ - 1) / BQ;
+  const int qtile = n_qt - 1 - blockIdx.y;   // heaviest tiles of all heads first
+  const T* qb = qkv + (long)b * L * ld + (long)head * DH;
+  const T* kb = qb + d;
+  const T* vb = qb + 2 * d;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  const int col = lane & 31, hf = lane >> 5;
+  const int wq0 = qtile * BQ + wave * 32;
+  const int q = wq0 + col;
+
+  const uint32_t lds0 = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)smem;
+  uint32_t nat[KS], tr0[DT], tr1[DT];
+  {
+    const int row = pi_row(col);   // MFMA row r is key pi(r): a lane's 8 values per 16-key step are consecutive keys
+#pragma unroll
+    for (int s = 0; s < KS; ++s) nat[s] = lds0 + row * (DH * 2) + (((2 * s + hf) ^ tile_swz<DH>(row)) * 16);
+    const int i16 = lane & 15, a = i16 >> 2, j4 = i16 & 3;
+    const int k = 8 * (lane >> 5) + a;
+#pragma unroll
+    for (int j = 0; j < DT; ++j) {
+      const int nb = j * 32 + 16 * ((lane >> 4) & 1) + 4 * j4;
+      tr0[j] = lds0 + TILE_B + k * (DH * 2) + (((nb >> 3) ^ tile_swz<DH>(k)) * 16) + ((nb >> 2) & 1) * 8;
+      tr1[j] = lds0 + TILE_B + (k + 4) * (DH * 2) + (((nb >> 3) ^ tile_swz<DH>(k + 4)) * 16) + ((nb >> 2) & 1) * 8;
+    }
+  }
+
+  const int q_hi = min(L, qtile * BQ + BQ) - 1;
+  const int nt = q_hi / KT + 1;
+  constexpr int CPR = DH / 8, RPL = 64 / CPR;
+  uint32_t koff[NLT];
+  auto set_offsets = [&](int rows) {
+#pragma unroll
+    for (int j = 0; j < NLT; ++j) {
+      const int row = (wave * NLT + j) * RPL + lane / CPR;
+      const int gch = (lane % CPR) ^ tile_swz<DH>(row);
+      koff[j] = (uint32_t)((min(row, rows - 1) * ld + gch * 8) * 2);
+    }
+  };
+  set_offsets(KT);
+  const int last_rows = min(L - (nt - 1) * KT, KT);
+  auto prepare_tile = [&](int t) {
+    if (t >= nt - 1 && last_rows < KT) set_offsets(last_rows);
+  };
+  auto issue_one = [&](int t, auto i_) {
+    constexpr int i = decltype(i_)::value, j = i % NLT;
+    const int key0 = min(t, nt - 1) * KT;
+    const uint32_t st = lds0 + (t % NS) * STAGE_B;
+    if constexpr (i < NLT) dma16(kb + (long)key0 * ld, koff[j], st + (wave * NLT + j) * 1024);
+    else dma16(vb + (long)key0 * ld, koff[j], st + TILE_B + (wave * NLT + j) * 1024);
+  };
+#pragma unroll
+  for (int t = 0; t < NS - 1; ++t) {   // the tile loop refills a stage one tile after it was used
+    prepare_tile(t);
+    static_for<0, NLD>([&](auto i_) { issue_one(t, i_); });
+  }
+
+  V8 qf[KS];
+  {
+    u32x4 z[KS];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      z[s] = u32x4{0u, 0u, 0u, 0u};
+      if (q < L) z[s] = *(const u32x4*)(qb + (long)q * ld + s * 16 + hf * 8);
+    }
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      qf[s] = __builtin_bit_cast(V8, z[s]);
+      pin_agpr(qf[s]);
+    }
+  }
+  f32x16 oacc[DT];
+#pragma unroll
+  for (int j = 0; j < DT; ++j) {
+#pragma unroll
+    for (int e = 0; e < 16; ++e) oacc[j][e] = 0.f;
+    pin_agpr(oacc[j]);
+  }
+  float m_run = -INFINITY, l_run = 0.f;
+  asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+
+  // fragment n = 0 .. 15 of S^T, in MFMA order: k step n / 2, key block n % 2
+  V8 nf[8];
+  auto read_frag = [&](auto n_) {
+    constexpr int n = decltype(n_)::value;
+    lds_read16<(n % 2) * 32 * (DH * 2)>(nf[n % 8], nat[n / 2]);
+  };
+  static_for<0, 8>([&](auto i_) { read_frag(i_); });
+  TrFrag tf[8];
+  f32x16 sacc[2];
+  u32x4 pw[4];      // P^T of the tile, 16 bits each: the B operand of each 16-key step of the second product
+  // transposed fragment of V for MFMA 16 + M, M = 4 kk + j: 16-key step kk, head-dimension block j
+  auto read_tr = [&](auto M_, auto half_) {
+    constexpr int M = decltype(M_)::value, half = decltype(half_)::value;
+    constexpr int kk = M / 4, j = M % 4;
+    if constexpr (half == 0) lds_read_tr<kk * 16 * (DH * 2)>(tf[M % 8].lo, tr0[j]);
+    else lds_read_tr<kk * 16 * (DH * 2)>(tf[M % 8].hi, tr1[j]);
+  };
+
+  auto tile = [&](auto masked_tag, int t) {
+    constexpr bool MASKED = decltype(masked_tag)::value;
+    const int key0 = t * KT;
+    float m_ref = 0.f, rs = 0.f;
+    // element e of block c <-> key key0 + 32 c + 16 (e / 8) + 8 hf + e % 8
+    auto exponential = [&](auto c_, auto e_) {
+      constexpr int c = decltype(c_)::value, e = decltype(e_)::value, g = e >> 3, i = e & 7;
+      const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[c][e], scale_log2, -m_ref));
+      rs += p;
+      sacc[c][e] = p;
+      if constexpr (e & 1) {
+        typedef T T2 __attribute__((ext_vector_type(2)));
+        T2 a;
+        a[0] = from_f<T>(sacc[c][e - 1]);
+        a[1] = from_f<T>(p);
+        pw[c * 2 + g][i >> 1] = __builtin_bit_cast(uint32_t, a);
+        if constexpr (i == 7) operand_ready(pw[c * 2 + g]);
+      }
+    };
+    auto operand = [&](const u32x4& w) { return __builtin_bit_cast(V8, w); };
+
+    // ---- S^T = K Q^T
+    static_for<0, 16>([&](auto g_) {
+      constexpr int g = decltype(g_)::value;
+      if constexpr (g % 2 == 0) lgkm_wait<FwdPlan::wait(g)>();
+      mma_to_vgpr<T, (g / 2 == 0)>(sacc[g % 2], nf[g % 8], qf[g / 2]);
+      if constexpr (g < 8) read_frag(IC<g + 8>{});
+      if constexpr (g >= 12) {
+        read_tr(IC<g - 12>{}, IC<0>{});
+        read_tr(IC<g - 12>{}, IC<1>{});
+      }
+      if constexpr (g == 0) prepare_tile(t + NS - 1);
+      if constexpr (g % 2 == 1) issue_one(t + NS - 1, IC<g / 2>{});
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    // ---- running maximum (m_run is the reference the exponentials are taken against; it follows the maximum
+    // lazily: only when some query of the wavefront exceeds it by more than 2^8 are the sum and the accumulators
+    // rescaled - exact either way) and the exponentials of the first 32 keys
+    asm volatile("s_nop 10" : "+v"(sacc[0]), "+v"(sacc[1]));
+    {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int c = 0; c < 2; ++c)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          if constexpr (MASKED) {
+            const int key = key0 + c * 32 + 16 * (e >> 3) + 8 * hf + (e & 7);
+            if (key > q) sacc[c][e] = -INFINITY;
+          }
+          mx = fmaxf(mx, sacc[c][e]);
+        }
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
+      if (__builtin_amdgcn_ballot_w64(mx > m_run + 8.f) != 0) {
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
+        l_run *= alpha;
+        m_run = m_new;
+#pragma unroll
+        for (int j = 0; j < DT; ++j) {
+#pragma unroll
+          for (int e = 0; e < 16; ++e) oacc[j][e] *= alpha;
+          pin_agpr(oacc[j]);
+        }
+      }
+      m_ref = m_run == -INFINITY ? 0.f : m_run;   // a row with no visible key yet
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<0, 16>([&](auto e_) { exponential(IC<0>{}, e_); });
+    __builtin_amdgcn_sched_barrier(0);
+    // ---- O^T += V^T P^T; the exponentials of the second 32 keys beside the first eight MFMAs
+    static_for<0, 16>([&](auto M_) {
+      constexpr int M = decltype(M_)::value, g = 16 + M, kk = M / 4, j = M % 4;
+      if constexpr (g < 28 && g % 2 == 0) lgkm_wait<FwdPlan::wait(g)>();
+      mma_to_agpr<T>(oacc[j], tr_value<T>(tf[M % 8]), operand(pw[kk]));
+      if constexpr (M + 4 < 16) {
+        read_tr(IC<M + 4>{}, IC<0>{});
+        read_tr(IC<M + 4>{}, IC<1>{});
+      }
+      if constexpr (M < 8) {
+        exponential(IC<1>{}, IC<2 * M>{});
+        exponential(IC<1>{}, IC<2 * M + 1>{});
+      }
+      if constexpr (M == 11) {
+        // every read of this tile has been issued: when they have landed, and tile t + 1 too, the stage is handed back
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NS - 2) * NLD) : "memory");
+        const int step = ((t + 1) % NS == 0) ? -(NS - 1) * STAGE_B : STAGE_B;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) nat[s] += step;
+#pragma unroll
+        for (int jj = 0; jj < DT; ++jj) {
+          tr0[jj] += step;
+          tr1[jj] += step;
+        }
+      }
+      if constexpr (M >= 12) {
+        read_frag(IC<2 * (M - 12)>{});
+        read_frag(IC<2 * (M - 12) + 1>{});
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    l_run += rs;
+    asm volatile("s_nop 15\n\ts_nop 7" : "+a"(oacc[0]), "+a"(oacc[1]), "+a"(oacc[2]), "+a"(oacc[3]));
+  };
+
+  // Tiles entirely below the diagonal of the wavefront's first row need no mask; the rest are masked (a tile
+  // entirely above the last row's diagonal adds zeros: all wavefronts make the same nt trips, so the barriers match).
+  const int t_plain = min(nt, max(0, (wq0 + 1) / KT));
+  int t = 0;
+  for (; t < t_plain; ++t) tile(std::false_type{}, t);
+  for (; t < nt; ++t) tile(std::true_type{}, t);
+  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // see the dK / dV kernel
+
+  const float l = l_run + __shfl_xor(l_run, 32, 64);
+  store_grad_rows_staged<T>(o + ((long)b * L + wq0) * d + (long)head * DH, d, L - wq0, oacc, 1.0f / l, lane, nullptr,
+                            smem + wave * 8704);
+  if (lse && hf == 0 && q < L)
+    lse[((long)b * L + q) * h + head] = (m_run + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+}

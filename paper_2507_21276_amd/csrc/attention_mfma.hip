@@ -758,6 +758,8 @@ __global__ __launch_bounds__(256, OCC) void flash_fwd_ring_kernel(const T* __res
   }
 }
 
+#include "attention_bwd_sched.h"
+
 // Four stages.  With head_dim 64 (64 KB of ring, under 256 registers) two workgroups share a compute
 // unit and cover each other's waits; with head_dim 128 one does (two stages and two workgroups were
 // measured slower: 227 against 164 us at 2 x 2048 x 32 heads, the registers no longer fit).
@@ -783,7 +785,18 @@ template <class T, int DH>
 ls_status launch_fwd(const void* qkv, int B, int L, int h, void* o, float* lse, hipStream_t st) {
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
   PagedGeom pg{};
-  if constexpr (DH >= 64) {
+  if constexpr (DH == 128) {
+    // the hand-scheduled kernel
+    constexpr int lds = 4 * 2 * KT * DH * 2;
+    static bool attr_set = false;
+    if (!attr_set) {
+      LS_CHECK_HIP(hipFuncSetAttribute((const void*)flash_fwd128_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+      attr_set = true;
+    }
+    flash_fwd128_kernel<T><<<dim3(B * h, (L + 127) / 128), 256, lds, st>>>((const T*)qkv, (T*)o, lse, L, h, scale_log2);
+    LS_CHECK_LAUNCH();
+    return LS_OK;
+  } else if constexpr (DH >= 64) {
     // the tile-ring kernel.  128 queries per workgroup: with 256 the two code paths of a tile (masked /
     // unmasked, rescaling or not) no longer fit the register file for head_dim 128
     return launch_ring<T, DH, 1, false>(qkv, o, lse, L, h, scale_log2, pg, dim3(B * h, (L + 127) / 128), 0, st);
@@ -1108,8 +1121,6 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv_kernel(const T* __restrict_
     store_grad_row<T, DH>(rk + d, dv, 1.0f, hf, nullptr);
   }
 }
-
-#include "attention_bwd_sched.h"
 
 // also records max|dO| per workgroup in dvec[n_items + blockIdx.x]; amax_finish_kernel
 // folds those into dvec[n_items + gridDim.x] (no atomics: deterministic and contention-free)
