@@ -721,20 +721,24 @@ __global__ __launch_bounds__(256) void flash_bwd_dq128_kernel(const T* __restric
 }
 
 // ---- forward (training layout) ---------------------------------------------------------------------
-// flash_fwd_ring_kernel at head_dim 128 on the same scheme.  A workgroup owns 128 queries (32 per wavefront, Q
-// fragments in the accumulator file), K / V tiles of 64 keys come through the ring.  A tile is 32 MFMAs:
-// 0..15 S^T = K Q^T (the two 32-key blocks alternating), then - with no MFMA to run beside it - the running
-// maximum and the exponentials of the first block, 16..23 O^T += V^T P^T for the first 32 keys beside the
-// exponentials of the second block, 24..31 for the second 32 keys; the eight direct-to-LDS loads in the odd gaps
-// 1..15, the ring step after gap 27.
+// flash_fwd_ring_kernel at head_dim 128 on the same scheme, software-pipelined over the key tiles.  A workgroup
+// owns 128 queries (32 per wavefront, Q fragments in the accumulator file), K / V tiles of 64 keys come through
+// the ring.  Iteration t holds the scores S^T(t) complete in registers and runs 32 MFMAs:
+//   0..15  S^T(t + 1) = K(t + 1) Q^T (the two 32-key blocks alternating) beside the exponentials of the first 32
+//          keys of tile t;
+//   16..31 O^T += V(t)^T P(t)^T beside the exponentials of the second 32 keys (gaps 16..27) and the maximum of
+//          S^T(t + 1) (gaps 28..31);
+// then the running maximum moves if it has to (rarely: see below) - so neither product waits for the vector unit
+// and the exponentials run in the shadow of MFMAs.  The eight direct-to-LDS loads of tile t + 3 go into the odd
+// gaps 1..15, the ring step comes after gap 27 (it waits for tile t + 2, whose K the next iteration reads).
 struct FwdPlan {
   static constexpr int tau(int gap) { return gap >= 28 ? gap - 28 : gap + 4; }
   static constexpr int reads_at(int t) {
     const int gap = t < 4 ? 28 + t : t - 4;
-    if (gap >= 28) return 2;        // two fragments of the next tile
-    if (gap < 8) return 1;          // fragment
+    if (gap >= 28) return 2;        // two K fragments of the tile after the next
+    if (gap < 8) return 1;          // K fragment
     if (gap < 12) return 0;
-    return 2;                       // transposed fragment (gaps 12..27)
+    return 2;                       // transposed V fragment (gaps 12..27)
   }
   static constexpr int issued_through(int t) {
     int n = 0;
@@ -777,7 +781,7 @@ __global__ __launch_bounds__(256) void flash_fwd128_kernel(const T* __restrict__
   const int q = wq0 + col;
 
   const uint32_t lds0 = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)smem;
-  uint32_t nat[KS], tr0[DT], tr1[DT];
+  uint32_t nat[KS], tr0[DT], tr1[DT];   // K fragments (stage of the tile being multiplied), V^T fragments (stage of tile t)
   {
     const int row = pi_row(col);   // MFMA row r is key pi(r): a lane's 8 values per 16-key step are consecutive keys
 #pragma unroll
@@ -817,7 +821,7 @@ __global__ __launch_bounds__(256) void flash_fwd128_kernel(const T* __restrict__
     else dma16(vb + (long)key0 * ld, koff[j], st + TILE_B + (wave * NLT + j) * 1024);
   };
 #pragma unroll
-  for (int t = 0; t < NS - 1; ++t) {   // the tile loop refills a stage one tile after it was used
+  for (int t = 0; t < NS - 1; ++t) {   // the tile loop refills a stage one tile after it was last used
     prepare_tile(t);
     static_for<0, NLD>([&](auto i_) { issue_one(t, i_); });
   }
@@ -843,19 +847,18 @@ __global__ __launch_bounds__(256) void flash_fwd128_kernel(const T* __restrict__
     for (int e = 0; e < 16; ++e) oacc[j][e] = 0.f;
     pin_agpr(oacc[j]);
   }
-  float m_run = -INFINITY, l_run = 0.f;
+  float m_run = -INFINITY, l_run = 0.f, m_ref = 0.f;
   asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
 
-  // fragment n = 0 .. 15 of S^T, in MFMA order: k step n / 2, key block n % 2
+  // K fragment n = 0 .. 15 of a tile, in MFMA order: k step n / 2, key block n % 2
   V8 nf[8];
   auto read_frag = [&](auto n_) {
     constexpr int n = decltype(n_)::value;
     lds_read16<(n % 2) * 32 * (DH * 2)>(nf[n % 8], nat[n / 2]);
   };
-  static_for<0, 8>([&](auto i_) { read_frag(i_); });
   TrFrag tf[8];
-  f32x16 sacc[2];
-  u32x4 pw[4];      // P^T of the tile, 16 bits each: the B operand of each 16-key step of the second product
+  f32x16 sa[2], sb[2];   // the scores of the tile being normalised and of the tile being multiplied, alternately
+  u32x4 pw[4];           // P^T of the tile, 16 bits each: the B operand of each 16-key step of the second product
   // transposed fragment of V for MFMA 16 + M, M = 4 kk + j: 16-key step kk, head-dimension block j
   auto read_tr = [&](auto M_, auto half_) {
     constexpr int M = decltype(M_)::value, half = decltype(half_)::value;
@@ -863,117 +866,144 @@ __global__ __launch_bounds__(256) void flash_fwd128_kernel(const T* __restrict__
     if constexpr (half == 0) lds_read_tr<kk * 16 * (DH * 2)>(tf[M % 8].lo, tr0[j]);
     else lds_read_tr<kk * 16 * (DH * 2)>(tf[M % 8].hi, tr1[j]);
   };
+  // Mask and maximum of the scores of tile `tile` (element e of block c <-> key 64 tile + 32 c + 16 (e / 8) + 8 hf + e % 8),
+  // then the reference of the exponentials: m_run follows the running maximum lazily - only when some query of the
+  // wavefront exceeds it by more than 2^8 are the sum and the accumulators rescaled (exact either way; until then
+  // p <= 256, far inside every format involved), which takes the rescaling out of all but the first tiles of a row.
+  auto part_max = [&](bool masked, f32x16 (&sc)[2], int tile, auto c_, auto quarter_, float& mx) {
+    constexpr int c = decltype(c_)::value, e0 = decltype(quarter_)::value * 8;
+    if (masked) {   // uniform: the tile reaches the diagonal of some query of the wavefront
+#pragma unroll
+      for (int e = e0; e < e0 + 8; ++e) {
+        const int key = tile * KT + c * 32 + 16 * (e >> 3) + 8 * hf + (e & 7);
+        if (key > q) sc[c][e] = -INFINITY;
+      }
+    }
+#pragma unroll
+    for (int e = e0; e < e0 + 8; ++e) mx = fmaxf(mx, sc[c][e]);
+  };
+  auto new_reference = [&](float mx) {
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
+    if (__builtin_amdgcn_ballot_w64(mx > m_run + 8.f) != 0) {
+      const float m_new = fmaxf(m_run, mx);
+      const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
+      l_run *= alpha;
+      m_run = m_new;
+#pragma unroll
+      for (int j = 0; j < DT; ++j) {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[j][e] *= alpha;
+        pin_agpr(oacc[j]);
+      }
+    }
+    m_ref = m_run == -INFINITY ? 0.f : m_run;   // a row with no visible key yet
+  };
 
-  auto tile = [&](auto masked_tag, int t) {
-    constexpr bool MASKED = decltype(masked_tag)::value;
-    const int key0 = t * KT;
-    float m_ref = 0.f, rs = 0.f;
-    // element e of block c <-> key key0 + 32 c + 16 (e / 8) + 8 hf + e % 8
+  // ---- before the loop: the scores of tile 0, their maximum, and the first K fragments of tile 1
+  static_for<0, 8>([&](auto i_) { read_frag(i_); });
+  static_for<0, 16>([&](auto g_) {
+    constexpr int g = decltype(g_)::value;
+    lgkm_wait<0>();
+    mma_to_vgpr<T, (g / 2 == 0)>(sa[g % 2], nf[g % 8], qf[g / 2]);
+    if constexpr (g < 8) read_frag(IC<g + 8>{});
+  });
+  {
+#pragma unroll
+    for (int s = 0; s < KS; ++s) nat[s] += STAGE_B;
+    static_for<0, 8>([&](auto i_) { read_frag(i_); });
+    asm volatile("s_nop 10" : "+v"(sa[0]), "+v"(sa[1]));
+    float mx = -INFINITY;
+    static_for<0, 4>([&](auto k_) { part_max(true, sa, 0, IC<decltype(k_)::value / 2>{}, IC<decltype(k_)::value % 2>{}, mx); });
+    new_reference(mx);
+  }
+
+  // Tiles entirely below the diagonal of the wavefront's first row need no mask; the rest are masked, and so is the
+  // tile past the last one, whose scores the last iteration forms and nobody uses (a tile entirely above the last
+  // row's diagonal adds zeros: all wavefronts make the same nt trips, so the barriers match).
+  const int t_plain = min(nt, max(0, (wq0 + 1) / KT));
+  // Iteration t: `cur` holds the scores of tile t, `nxt` receives those of tile t + 1.
+  auto iteration = [&](int t, f32x16 (&cur)[2], f32x16 (&nxt)[2]) {
+    const bool masked = t + 1 >= t_plain;
+    float rs = 0.f, mx = -INFINITY;
     auto exponential = [&](auto c_, auto e_) {
       constexpr int c = decltype(c_)::value, e = decltype(e_)::value, g = e >> 3, i = e & 7;
-      const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[c][e], scale_log2, -m_ref));
+      const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[c][e], scale_log2, -m_ref));
       rs += p;
-      sacc[c][e] = p;
+      cur[c][e] = p;
       if constexpr (e & 1) {
         typedef T T2 __attribute__((ext_vector_type(2)));
         T2 a;
-        a[0] = from_f<T>(sacc[c][e - 1]);
+        a[0] = from_f<T>(cur[c][e - 1]);
         a[1] = from_f<T>(p);
         pw[c * 2 + g][i >> 1] = __builtin_bit_cast(uint32_t, a);
         if constexpr (i == 7) operand_ready(pw[c * 2 + g]);
       }
     };
     auto operand = [&](const u32x4& w) { return __builtin_bit_cast(V8, w); };
-
-    // ---- S^T = K Q^T
-    static_for<0, 16>([&](auto g_) {
+    static_for<0, 32>([&](auto g_) {
       constexpr int g = decltype(g_)::value;
-      if constexpr (g % 2 == 0) lgkm_wait<FwdPlan::wait(g)>();
-      mma_to_vgpr<T, (g / 2 == 0)>(sacc[g % 2], nf[g % 8], qf[g / 2]);
+      if constexpr (g < 28 && g % 2 == 0) lgkm_wait<FwdPlan::wait(g)>();
+      if constexpr (g < 16) {
+        mma_to_vgpr<T, (g / 2 == 0)>(nxt[g % 2], nf[g % 8], qf[g / 2]);
+      } else {
+        constexpr int M = g - 16, kk = M / 4, j = M % 4;
+        mma_to_agpr<T>(oacc[j], tr_value<T>(tf[M % 8]), operand(pw[kk]));
+      }
+      // LDS reads
       if constexpr (g < 8) read_frag(IC<g + 8>{});
-      if constexpr (g >= 12) {
+      if constexpr (g >= 12 && g < 16) {
         read_tr(IC<g - 12>{}, IC<0>{});
         read_tr(IC<g - 12>{}, IC<1>{});
       }
+      if constexpr (g >= 16 && g < 28) {
+        read_tr(IC<g - 16 + 4>{}, IC<0>{});
+        read_tr(IC<g - 16 + 4>{}, IC<1>{});
+      }
+      // direct-to-LDS loads of tile t + 3 into the stage that tile t - 1 left
       if constexpr (g == 0) prepare_tile(t + NS - 1);
-      if constexpr (g % 2 == 1) issue_one(t + NS - 1, IC<g / 2>{});
-      __builtin_amdgcn_sched_barrier(0);
-    });
-    // ---- running maximum (m_run is the reference the exponentials are taken against; it follows the maximum
-    // lazily: only when some query of the wavefront exceeds it by more than 2^8 are the sum and the accumulators
-    // rescaled - exact either way) and the exponentials of the first 32 keys
-    asm volatile("s_nop 10" : "+v"(sacc[0]), "+v"(sacc[1]));
-    {
-      float mx = -INFINITY;
-#pragma unroll
-      for (int c = 0; c < 2; ++c)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          if constexpr (MASKED) {
-            const int key = key0 + c * 32 + 16 * (e >> 3) + 8 * hf + (e & 7);
-            if (key > q) sacc[c][e] = -INFINITY;
-          }
-          mx = fmaxf(mx, sacc[c][e]);
-        }
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64)) * scale_log2;
-      if (__builtin_amdgcn_ballot_w64(mx > m_run + 8.f) != 0) {
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = m_new == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(m_run - m_new);
-        l_run *= alpha;
-        m_run = m_new;
-#pragma unroll
-        for (int j = 0; j < DT; ++j) {
-#pragma unroll
-          for (int e = 0; e < 16; ++e) oacc[j][e] *= alpha;
-          pin_agpr(oacc[j]);
-        }
+      if constexpr (g < 16 && g % 2 == 1) issue_one(t + NS - 1, IC<g / 2>{});
+      // vector work
+      if constexpr (g < 16) exponential(IC<0>{}, g_);
+      if constexpr (g >= 16 && g < 24) exponential(IC<1>{}, IC<g - 16>{});
+      if constexpr (g >= 24 && g < 28) {
+        exponential(IC<1>{}, IC<8 + 2 * (g - 24)>{});
+        exponential(IC<1>{}, IC<9 + 2 * (g - 24)>{});
       }
-      m_ref = m_run == -INFINITY ? 0.f : m_run;   // a row with no visible key yet
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    static_for<0, 16>([&](auto e_) { exponential(IC<0>{}, e_); });
-    __builtin_amdgcn_sched_barrier(0);
-    // ---- O^T += V^T P^T; the exponentials of the second 32 keys beside the first eight MFMAs
-    static_for<0, 16>([&](auto M_) {
-      constexpr int M = decltype(M_)::value, g = 16 + M, kk = M / 4, j = M % 4;
-      if constexpr (g < 28 && g % 2 == 0) lgkm_wait<FwdPlan::wait(g)>();
-      mma_to_agpr<T>(oacc[j], tr_value<T>(tf[M % 8]), operand(pw[kk]));
-      if constexpr (M + 4 < 16) {
-        read_tr(IC<M + 4>{}, IC<0>{});
-        read_tr(IC<M + 4>{}, IC<1>{});
-      }
-      if constexpr (M < 8) {
-        exponential(IC<1>{}, IC<2 * M>{});
-        exponential(IC<1>{}, IC<2 * M + 1>{});
-      }
-      if constexpr (M == 11) {
-        // every read of this tile has been issued: when they have landed, and tile t + 1 too, the stage is handed back
-        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"((NS - 2) * NLD) : "memory");
-        const int step = ((t + 1) % NS == 0) ? -(NS - 1) * STAGE_B : STAGE_B;
+      if constexpr (g >= 28) part_max(masked, nxt, t + 1, IC<(g - 28) / 2>{}, IC<(g - 28) % 2>{}, mx);
+      if constexpr (g == 27) {
+        // every read of this iteration has been issued: when they have landed, and tile t + 2 too (only the loads of
+        // tile t + 3 outstanding), the stage of tile t is handed back; K moves on to tile t + 2, V to tile t + 1
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(NLD) : "memory");
+        const int step_k = ((t + 2) % NS == 0) ? -(NS - 1) * STAGE_B : STAGE_B;
+        const int step_v = ((t + 1) % NS == 0) ? -(NS - 1) * STAGE_B : STAGE_B;
 #pragma unroll
-        for (int s = 0; s < KS; ++s) nat[s] += step;
+        for (int s = 0; s < KS; ++s) nat[s] += step_k;
 #pragma unroll
         for (int jj = 0; jj < DT; ++jj) {
-          tr0[jj] += step;
-          tr1[jj] += step;
+          tr0[jj] += step_v;
+          tr1[jj] += step_v;
         }
       }
-      if constexpr (M >= 12) {
-        read_frag(IC<2 * (M - 12)>{});
-        read_frag(IC<2 * (M - 12) + 1>{});
+      if constexpr (g >= 28) {
+        read_frag(IC<2 * (g - 28)>{});
+        read_frag(IC<2 * (g - 28) + 1>{});
       }
       __builtin_amdgcn_sched_barrier(0);
     });
     l_run += rs;
     asm volatile("s_nop 15\n\ts_nop 7" : "+a"(oacc[0]), "+a"(oacc[1]), "+a"(oacc[2]), "+a"(oacc[3]));
+    new_reference(mx);
   };
 
-  // Tiles entirely below the diagonal of the wavefront's first row need no mask; the rest are masked (a tile
-  // entirely above the last row's diagonal adds zeros: all wavefronts make the same nt trips, so the barriers match).
-  const int t_plain = min(nt, max(0, (wq0 + 1) / KT));
-  int t = 0;
-  for (; t < t_plain; ++t) tile(std::false_type{}, t);
-  for (; t < nt; ++t) tile(std::true_type{}, t);
+  // The two score buffers change roles every iteration: one loop, two iterations per trip, so that every fragment
+  // in flight across an iteration boundary is in the registers the next iteration expects (another loop would be
+  // another register assignment, and the compiler would copy registers whose reads have not landed).  An odd
+  // number of tiles (only when L is not a multiple of 128) is rounded up: the extra iteration works on scores
+  // that are all masked, i.e. adds P = 0.
+  for (int t = 0; t < nt; t += 2) {
+    iteration(t, sa, sb);
+    iteration(t + 1, sb, sa);
+  }
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // see the dK / dV kernel
 
   const float l = l_run + __shfl_xor(l_run, 32, 64);
