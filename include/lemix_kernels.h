@@ -97,7 +97,8 @@ ls_status lsk_attn_fwd(int impl, const void* qkv, int dtype, int B, int L, int n
                        int head_dim, void* o, float* lse, void* stream);
 /* Backward of the above: dqkv[B*L, 3d] from dO[B*L, d], the forward's qkv, o
  * and lse.  dvec: fp32 scratch of lsk_attn_bwd_scratch_floats(B, L, n_heads)
- * floats (rowsum(dO*O) per (row, head), then per-workgroup and global max|dO|). */
+ * floats (rowsum(dO*O) per (row, head), then per-workgroup and global max|dO|,
+ * then the log-sum-exp in base 2 per (row, head) for the head_dim-128 kernels). */
 size_t lsk_attn_bwd_scratch_floats(int B, int L, int n_heads);
 ls_status lsk_attn_bwd(int impl, const void* qkv, const void* o, const void* dO,
                        const float* lse, int dtype, int B, int L, int n_heads, int head_dim,
