@@ -758,7 +758,7 @@ __global__ __launch_bounds__(256, OCC) void flash_fwd_ring_kernel(const T* __res
   }
 }
 
-#include "attention_bwd_sched.h"
+#include "attention_sched.h"
 
 // Four stages.  With head_dim 64 (64 KB of ring, under 256 registers) two workgroups share a compute
 // unit and cover each other's waits; with head_dim 128 one does (two stages and two workgroups were

@@ -1,6 +1,7 @@
-// Hand-scheduled attention backward for head_dim 128 (included by attention_mfma.hip, inside its
-// anonymous namespace).  Same tiles, layouts and arithmetic as flash_bwd_dkv_kernel; what differs is
-// who places the instructions:
+// Hand-scheduled attention kernels for head_dim 128: dK/dV, dQ and the training forward (included by
+// attention_mfma.hip, inside its anonymous namespace).  Same tiles, layouts and arithmetic as the
+// compiler-scheduled kernels of that file (flash_bwd_dkv_kernel, flash_bwd_dq_kernel, flash_fwd_ring_kernel,
+// which stay for head_dim 64 and for prompt chunks over pages); what differs is who places the instructions:
 //   * every MFMA, LDS read and wait of the tile loop is issued from assembly, in source order, with
 //     scheduling barriers between the steps, so that the matrix pipe, the vector unit and the LDS
 //     work at the same time inside the one wavefront a SIMD holds;

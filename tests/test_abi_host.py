@@ -130,7 +130,7 @@ def test_probe_validates_its_arguments_before_any_launch():
 
 
 def test_no_instruction_touches_a_register_with_an_assembly_issued_lds_read_in_flight(tmp_path):
-    """Compiles the two sources that use transposing LDS reads to ISA and lints them."""
+    """Compiles the sources that issue LDS reads or MFMAs from assembly to ISA and lints them."""
     import shutil
     import subprocess
     import isa_lint
@@ -152,6 +152,22 @@ def test_no_instruction_touches_a_register_with_an_assembly_issued_lds_read_in_f
     mixed = ("_Zk:\n\tds_read_b128 v[4:7], v9\n\ts_load_dwordx2 s[0:1], s[2:3], 0x0\n\tds_read_b128 v[10:13], v9\n"
              "\ts_waitcnt lgkmcnt(1)\n\tv_mov_b32_e32 v0, v4\n\tv_mov_b32_e32 v1, v10\n\ts_waitcnt lgkmcnt(0)\n\ts_endpgm\n")
     assert isa_lint.scan(mixed) == {"_Zk": [(6, "v_mov_b32_e32 v1, v10")]}
+    # an MFMA result named by another kind of instruction before the MFMA's passes + 3 wait states are over
+    early = ("_Zk:\n\tv_mfma_f32_32x32x16_f16 a[0:15], v[0:3], v[4:7], a[0:15]\n\tv_add_u32_e32 v9, 1, v9\n"
+             "\tv_accvgpr_read_b32 v8, a3\n\ts_endpgm\n")
+    assert isa_lint.scan(early) == {"_Zk": [(3, "v_accvgpr_read_b32 v8, a3")]}
+    settled = ("_Zk:\n\tv_mfma_f32_32x32x16_f16 a[0:15], v[0:3], v[4:7], a[0:15]\n\tv_mfma_f32_32x32x16_f16 a[0:15], v[0:3], v[4:7], a[0:15]\n"
+               "\ts_nop 10\n\tv_accvgpr_read_b32 v8, a3\n\ts_endpgm\n")
+    assert isa_lint.scan(settled) == {}
+    # an MFMA reading a register that a vector instruction wrote less than two wait states before
+    close = "_Zk:\n\tv_cvt_pk_f16_f32 v4, v8, v9\n\ts_nop 0\n\tv_mfma_f32_32x32x16_f16 a[0:15], v[0:3], v[4:7], a[0:15]\n\ts_endpgm\n"
+    assert isa_lint.scan(close) == {"_Zk": [(3, "v_mfma_f32_32x32x16_f16 a[0:15], v[0:3], v[4:7], a[0:15]")]}
+    apart = "_Zk:\n\tv_cvt_pk_f16_f32 v4, v8, v9\n\ts_nop 1\n\tv_mfma_f32_32x32x16_f16 a[0:15], v[0:3], v[4:7], a[0:15]\n\ts_endpgm\n"
+    assert isa_lint.scan(apart) == {}
+    # both sides of a branch are walked: the read is in flight on the path that skips the wait
+    forked = ("_Zk:\n\tds_read_b128 v[4:7], v9\n\ts_cbranch_scc1 .LBB0_2\n\ts_waitcnt lgkmcnt(0)\n.LBB0_2:\n"
+              "\tv_mov_b32_e32 v0, v4\n\ts_waitcnt lgkmcnt(0)\n\ts_endpgm\n")
+    assert isa_lint.scan(forked) == {"_Zk": [(5, "v_mov_b32_e32 v0, v4")]}
     for src in ("gemm_dma.hip", "gemm_dma16.hip", "attention_mfma.hip"):
         out = tmp_path / (src + ".s")
         subprocess.run(["hipcc", "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
