@@ -282,14 +282,19 @@ __global__ __launch_bounds__(256) void flash_bwd_dkv128_kernel(const T* __restri
   // this wavefront's 32 keys: K and V fragments, all requested before the first is used
   V8 kf[KS], vf[KS];
   {
+    // every lane loads (rows past the end read the last row and are cleared afterwards): loads under a per-lane
+    // condition compile to one branch and one full wait each, sixteen round trips in a row
     u32x4 z0[KS], z1[KS];
+    const long row_off = (long)min(key, L - 1) * ld + hf * 8;
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-      z0[s] = z1[s] = u32x4{0u, 0u, 0u, 0u};
-      if (key < L) {
-        z0[s] = *(const u32x4*)(kb + (long)key * ld + s * 16 + hf * 8);
-        z1[s] = *(const u32x4*)(vb + (long)key * ld + s * 16 + hf * 8);
-      }
+      z0[s] = *(const u32x4*)(kb + row_off + s * 16);
+      z1[s] = *(const u32x4*)(vb + row_off + s * 16);
+    }
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      z0[s] = key < L ? z0[s] : u32x4{0u, 0u, 0u, 0u};
+      z1[s] = key < L ? z1[s] : u32x4{0u, 0u, 0u, 0u};
     }
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
@@ -581,14 +586,17 @@ __global__ __launch_bounds__(256) void flash_bwd_dq128_kernel(const T* __restric
   // this wavefront's 32 queries: Q and dO fragments, all requested before the first is used
   V8 qf[KS], dof[KS];
   {
-    u32x4 z0[KS], z1[KS];
+    u32x4 z0[KS], z1[KS];   // loaded by every lane, then cleared past the end: see the dK / dV kernel
+    const int qc = min(q, L - 1);
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-      z0[s] = z1[s] = u32x4{0u, 0u, 0u, 0u};
-      if (q < L) {
-        z0[s] = *(const u32x4*)(qb + (long)q * ld + s * 16 + hf * 8);
-        z1[s] = *(const u32x4*)(dob + (long)q * d + s * 16 + hf * 8);
-      }
+      z0[s] = *(const u32x4*)(qb + (long)qc * ld + s * 16 + hf * 8);
+      z1[s] = *(const u32x4*)(dob + (long)qc * d + s * 16 + hf * 8);
+    }
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      z0[s] = q < L ? z0[s] : u32x4{0u, 0u, 0u, 0u};
+      z1[s] = q < L ? z1[s] : u32x4{0u, 0u, 0u, 0u};
     }
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
@@ -829,12 +837,12 @@ __global__ __launch_bounds__(256) void flash_fwd128_kernel(const T* __restrict__
 
   V8 qf[KS];
   {
-    u32x4 z[KS];
+    u32x4 z[KS];   // loaded by every lane, then cleared past the end: see the dK / dV kernel
+    const int qc = min(q, L - 1);
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      z[s] = u32x4{0u, 0u, 0u, 0u};
-      if (q < L) z[s] = *(const u32x4*)(qb + (long)q * ld + s * 16 + hf * 8);
-    }
+    for (int s = 0; s < KS; ++s) z[s] = *(const u32x4*)(qb + (long)qc * ld + s * 16 + hf * 8);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) z[s] = q < L ? z[s] : u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
       qf[s] = __builtin_bit_cast(V8, z[s]);
