@@ -17,6 +17,9 @@
 // Backward (dQ, dK, dV) follows the same scheme; see flash_bwd_kernel.
 #include <cstdlib>
 #include <cstring>
+#include <map>
+#include <mutex>
+#include <queue>
 #include <type_traits>
 
 #include "common.h"
@@ -781,19 +784,62 @@ ls_status launch_ring(const void* qkv, void* o, float* lse, int L, int h, float 
   return LS_OK;
 }
 
+// How many 128-row tiles of a (sequence, head) one workgroup of a hand-scheduled kernel takes in a row (it keeps
+// its ring of key tiles running from one to the next, which saves most of a workgroup's start-up per tile): the
+// count that makes the launch shortest under a simple model, if that is a tenth shorter than with one tile per
+// workgroup (the model is rough where the launch does not fill the chip).  A workgroup costs 3 units, a query
+// tile its key tiles (tile i has i + 1) plus 6 units (measured: a key tile takes about 1 us, a workgroup's first
+// query tile 8.8 us more than its key tiles, a further one 5.9); the workgroups start in launch order (all heads'
+// workgroup 0, then all heads' workgroup 1, ...), each on the compute unit that is free first.
+inline int tiles_per_workgroup(int bh, int n_tiles) {
+  static std::mutex mu;
+  static std::map<std::pair<int, int>, int> known;
+  std::lock_guard<std::mutex> lock(mu);
+  const auto hit = known.find({bh, n_tiles});
+  if (hit != known.end()) return hit->second;
+  constexpr int CUS = 256;
+  int best = 1;
+  double best_cost = 0;
+  for (int ipw = 1; ipw <= 16 && ipw <= n_tiles; ++ipw) {
+    const int G = (n_tiles + ipw - 1) / ipw;
+    std::priority_queue<double, std::vector<double>, std::greater<double>> free_at;
+    for (int i = 0; i < CUS; ++i) free_at.push(0.0);
+    double cost = 0;
+    for (int y = 0; y < G; ++y) {
+      double w = 3;
+      for (int k = 0; k < ipw; ++k) {
+        const int tile = snake_tile(k, y, G, n_tiles);
+        if (tile >= 0) w += tile + 1 + 6;
+      }
+      for (int i = 0; i < bh; ++i) {
+        const double end = free_at.top() + w;
+        free_at.pop();
+        free_at.push(end);
+        cost = end > cost ? end : cost;
+      }
+    }
+    if (ipw == 1) best_cost = 0.9 * cost;
+    else if (cost < best_cost) best = ipw, best_cost = cost;
+  }
+  known[{bh, n_tiles}] = best;
+  return best;
+}
+
 template <class T, int DH>
 ls_status launch_fwd(const void* qkv, int B, int L, int h, void* o, float* lse, hipStream_t st) {
   const float scale_log2 = 1.4426950408889634f / sqrtf((float)DH);
   PagedGeom pg{};
   if constexpr (DH == 128) {
     // the hand-scheduled kernel
-    constexpr int lds = 4 * 2 * KT * DH * 2;
+    constexpr int lds = FWD128_LDS;
     static bool attr_set = false;
     if (!attr_set) {
       LS_CHECK_HIP(hipFuncSetAttribute((const void*)flash_fwd128_kernel<T>, hipFuncAttributeMaxDynamicSharedMemorySize, lds));
       attr_set = true;
     }
-    flash_fwd128_kernel<T><<<dim3(B * h, (L + 127) / 128), 256, lds, st>>>((const T*)qkv, (T*)o, lse, L, h, scale_log2);
+    const int n_qt = (L + 127) / 128;
+    const int ipw = tiles_per_workgroup(B * h, n_qt);
+    flash_fwd128_kernel<T><<<dim3(B * h, (n_qt + ipw - 1) / ipw), 256, lds, st>>>((const T*)qkv, (T*)o, lse, L, h, scale_log2, ipw);
     LS_CHECK_LAUNCH();
     return LS_OK;
   } else if constexpr (DH >= 64) {

@@ -764,9 +764,74 @@ struct FwdPlan {
   static constexpr int wait(int g) { return newer(g, need_tau(g + 1), need_pos(g + 1)); }
 };
 
+// The queries a workgroup owns: `ipw` tiles of 128 of one (sequence, head), taken in order, heaviest first.  The
+// G = gridDim.y workgroups of a head deal the tiles out in a snake (workgroup y takes places y, 2G - 1 - y,
+// 2G + y, ... of the list of tiles by decreasing weight), which gives every workgroup the same number of key
+// tiles when the count divides; place k of workgroup y, or a negative number when the list has ended.
+__host__ __device__ __forceinline__ int snake_tile(int k, int y, int G, int n_tiles) {
+  return n_tiles - 1 - (k * G + ((k & 1) ? G - 1 - y : y));
+}
+
+// A wavefront's 32 rows (as store_grad_rows_staged takes them) through 4352 bytes of LDS of its own, sixteen rows
+// at a time - for the kernels whose ring stays live under the store.
+template <class T>
+__device__ __forceinline__ void store_rows_staged16(T* out, long ld, int rows, const f32x16 (&acc)[4], float mul,
+                                                    int lane, const float* tab, char* tile) {
+  typedef typename Mma<T>::V4 V4;
+  constexpr int DH = 128, DT = 4, RS = DH * 2 + 16;
+  const int col = lane & 31, hf = lane >> 5;
+  char* my = tile + (col & 15) * RS;
+#pragma unroll
+  for (int pass = 0; pass < 2; ++pass) {
+    if ((col >> 4) == pass) {
+      if (tab == nullptr) {
+#pragma unroll
+        for (int j = 0; j < DT; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            V4 v;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) v[i] = from_f<T>(acc[j][g * 4 + i] * mul);
+            *(V4*)(my + (j * 32 + 8 * g + 4 * hf) * 2) = v;
+          }
+      } else {
+#pragma unroll
+        for (int j = 0; j < DT / 2; ++j)
+#pragma unroll
+          for (int g = 0; g < 4; ++g) {
+            const int i0 = j * 32 + 8 * g + 4 * hf;
+            const f32x4 cs0 = *(const f32x4*)(tab + i0 * 2), cs1 = *(const f32x4*)(tab + i0 * 2 + 4);
+            V4 lo, hi;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const float c = i < 2 ? cs0[2 * i] : cs1[2 * (i - 2)], sn = i < 2 ? cs0[2 * i + 1] : cs1[2 * (i - 2) + 1];
+              const float a = acc[j][g * 4 + i] * mul, b = acc[j + DT / 2][g * 4 + i] * mul;
+              lo[i] = from_f<T>(a * c + b * sn);
+              hi[i] = from_f<T>(b * c - a * sn);
+            }
+            *(V4*)(my + i0 * 2) = lo;
+            *(V4*)(my + (i0 + DH / 2) * 2) = hi;
+          }
+      }
+    }
+    // the LDS executes one wavefront's operations in order: the reads see the writes above, and the writes of the
+    // second pass come after the reads of the first
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+      const int r16 = it * 4 + (lane >> 4), r = pass * 16 + r16;
+      const u32x4 v = *(const u32x4*)(tile + r16 * RS + (lane & 15) * 16);
+      if (r < rows) *(u32x4*)(out + (long)r * ld + (lane & 15) * 8) = v;
+    }
+  }
+}
+
+// LDS of the kernel below: the ring, then the four wavefronts' row staging
+constexpr int FWD128_LDS = 4 * 2 * KT * 128 * 2 + 4 * 4352;
+
 template <class T>
 __global__ __launch_bounds__(256) void flash_fwd128_kernel(const T* __restrict__ qkv, T* __restrict__ o,
-                                                           float* __restrict__ lse, int L, int h, float scale_log2) {
+                                                           float* __restrict__ lse, int L, int h, float scale_log2,
+                                                           int ipw) {
   typedef typename Mma<T>::V8 V8;
   constexpr int DH = 128, BQ = 128, NS = 4, KS = DH / 16, DT = DH / 32;
   constexpr int TILE_B = KT * DH * 2;            // bytes of a K or V tile
@@ -780,17 +845,16 @@ __global__ __launch_bounds__(256) void flash_fwd128_kernel(const T* __restrict__
   const int d = h * DH;
   const long ld = 3L * d;
   const int n_qt = (L + BQ - 1) / BQ;
-  const int qtile = n_qt - 1 - blockIdx.y;   // heaviest tiles of all heads first
   const T* qb = qkv + (long)b * L * ld + (long)head * DH;
   const T* kb = qb + d;
   const T* vb = qb + 2 * d;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
   const int col = lane & 31, hf = lane >> 5;
-  const int wq0 = qtile * BQ + wave * 32;
-  const int q = wq0 + col;
 
   const uint32_t lds0 = (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char*)smem;
-  uint32_t nat[KS], tr0[DT], tr1[DT];   // K fragments (stage of the tile being multiplied), V^T fragments (stage of tile t)
+  // K fragments and V^T fragments: the addresses below are those of ring stage pk and pv
+  uint32_t nat[KS], tr0[DT], tr1[DT];
+  int pk = 0, pv = 0;
   {
     const int row = pi_row(col);   // MFMA row r is key pi(r): a lane's 8 values per 16-key step are consecutive keys
 #pragma unroll
@@ -804,70 +868,91 @@ __global__ __launch_bounds__(256) void flash_fwd128_kernel(const T* __restrict__
       tr1[j] = lds0 + TILE_B + (k + 4) * (DH * 2) + (((nb >> 3) ^ tile_swz<DH>(k + 4)) * 16) + ((nb >> 2) & 1) * 8;
     }
   }
+  auto step_k = [&]() {   // K fragments: on to the next stage of the ring
+    const int step = pk == NS - 1 ? -(NS - 1) * STAGE_B : STAGE_B;
+    pk = pk == NS - 1 ? 0 : pk + 1;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) nat[s] += step;
+  };
+  auto step_v = [&]() {
+    const int step = pv == NS - 1 ? -(NS - 1) * STAGE_B : STAGE_B;
+    pv = pv == NS - 1 ? 0 : pv + 1;
+#pragma unroll
+    for (int jj = 0; jj < DT; ++jj) {
+      tr0[jj] += step;
+      tr1[jj] += step;
+    }
+  };
 
-  const int q_hi = min(L, qtile * BQ + BQ) - 1;
-  const int nt = q_hi / KT + 1;
+  // ---- the direct-to-LDS loads of a key tile (K and V rows 64 kt ..) into a ring stage
   constexpr int CPR = DH / 8, RPL = 64 / CPR;
   uint32_t koff[NLT];
-  auto set_offsets = [&](int rows) {
+  int off_rows = 0;   // the row count koff was made for
+  auto prepare_tile = [&](int kt) {
+    const int rows = min(L - kt * KT, KT);
+    if (rows != off_rows) {   // uniform; after the first tile only where a sequence ends inside a tile
+      off_rows = rows;
 #pragma unroll
-    for (int j = 0; j < NLT; ++j) {
-      const int row = (wave * NLT + j) * RPL + lane / CPR;
-      const int gch = (lane % CPR) ^ tile_swz<DH>(row);
-      koff[j] = (uint32_t)((min(row, rows - 1) * ld + gch * 8) * 2);
+      for (int j = 0; j < NLT; ++j) {
+        const int row = (wave * NLT + j) * RPL + lane / CPR;
+        const int gch = (lane % CPR) ^ tile_swz<DH>(row);
+        koff[j] = (uint32_t)((min(row, rows - 1) * ld + gch * 8) * 2);
+      }
     }
   };
-  set_offsets(KT);
-  const int last_rows = min(L - (nt - 1) * KT, KT);
-  auto prepare_tile = [&](int t) {
-    if (t >= nt - 1 && last_rows < KT) set_offsets(last_rows);
-  };
-  auto issue_one = [&](int t, auto i_) {
+  auto issue_one = [&](int stage, int kt, auto i_) {
     constexpr int i = decltype(i_)::value, j = i % NLT;
-    const int key0 = min(t, nt - 1) * KT;
-    const uint32_t st = lds0 + (t % NS) * STAGE_B;
-    if constexpr (i < NLT) dma16(kb + (long)key0 * ld, koff[j], st + (wave * NLT + j) * 1024);
-    else dma16(vb + (long)key0 * ld, koff[j], st + TILE_B + (wave * NLT + j) * 1024);
+    const uint32_t st = lds0 + stage * STAGE_B;
+    if constexpr (i < NLT) dma16(kb + (long)kt * KT * ld, koff[j], st + (wave * NLT + j) * 1024);
+    else dma16(vb + (long)kt * KT * ld, koff[j], st + TILE_B + (wave * NLT + j) * 1024);
   };
-#pragma unroll
-  for (int t = 0; t < NS - 1; ++t) {   // the tile loop refills a stage one tile after it was last used
-    prepare_tile(t);
-    static_for<0, NLD>([&](auto i_) { issue_one(t, i_); });
-  }
 
-  V8 qf[KS];
-  {
-    u32x4 z[KS];   // loaded by every lane, then cleared past the end: see the dK / dV kernel
-    const int qc = min(q, L - 1);
+  // ---- the workgroup's query tiles
+  const int G = gridDim.y, y = blockIdx.y;
+  struct Item {
+    int qtile, nt, n_iter;
+  };
+  auto make_item = [&](int k) {
+    Item it;
+    it.qtile = k < ipw ? snake_tile(k, y, G, n_qt) : -1;
+    const int q_hi = min(L, it.qtile * BQ + BQ) - 1;
+    it.nt = q_hi / KT + 1;
+    // an odd number of tiles (only when L is not a multiple of 128) is rounded up: see the loop below
+    it.n_iter = it.nt + (it.nt & 1);
+    return it;
+  };
+  auto load_q = [&](u32x4 (&z)[KS], int qtile) {   // by every lane, cleared past the end afterwards: see the dK / dV kernel
+    const int qc = min(qtile * BQ + wave * 32 + col, L - 1);
 #pragma unroll
     for (int s = 0; s < KS; ++s) z[s] = *(const u32x4*)(qb + (long)qc * ld + s * 16 + hf * 8);
+  };
+
+  int k_item = 0;
+  Item cur = make_item(0);
+  int gs = 0;   // ring stage of tile 0 of the current item
 #pragma unroll
-    for (int s = 0; s < KS; ++s) z[s] = q < L ? z[s] : u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      qf[s] = __builtin_bit_cast(V8, z[s]);
-      pin_agpr(qf[s]);
-    }
+  for (int u = 0; u < NS - 1; ++u) {   // the tile loop refills a stage one tile after it was last used
+    const int kt = min(u, cur.nt - 1);
+    prepare_tile(kt);
+    static_for<0, NLD>([&](auto i_) { issue_one(u, kt, i_); });
   }
+  u32x4 z[KS];
+  load_q(z, cur.qtile);
+
+  V8 qf[KS];
   f32x16 oacc[DT];
-#pragma unroll
-  for (int j = 0; j < DT; ++j) {
-#pragma unroll
-    for (int e = 0; e < 16; ++e) oacc[j][e] = 0.f;
-    pin_agpr(oacc[j]);
-  }
-  float m_run = -INFINITY, l_run = 0.f, m_ref = 0.f;
-  asm volatile("s_waitcnt vmcnt(0)\n\ts_barrier" ::: "memory");
+  V8 nf[8];
+  TrFrag tf[8];
+  f32x16 sa[2], sb[2];   // the scores of the tile being normalised and of the tile being multiplied, alternately
+  u32x4 pw[4];           // P^T of the tile, 16 bits each: the B operand of each 16-key step of the second product
+  float m_run, l_run, m_ref;
+  int wq0, q, t_plain;
 
   // K fragment n = 0 .. 15 of a tile, in MFMA order: k step n / 2, key block n % 2
-  V8 nf[8];
   auto read_frag = [&](auto n_) {
     constexpr int n = decltype(n_)::value;
     lds_read16<(n % 2) * 32 * (DH * 2)>(nf[n % 8], nat[n / 2]);
   };
-  TrFrag tf[8];
-  f32x16 sa[2], sb[2];   // the scores of the tile being normalised and of the tile being multiplied, alternately
-  u32x4 pw[4];           // P^T of the tile, 16 bits each: the B operand of each 16-key step of the second product
   // transposed fragment of V for MFMA 16 + M, M = 4 kk + j: 16-key step kk, head-dimension block j
   auto read_tr = [&](auto M_, auto half_) {
     constexpr int M = decltype(M_)::value, half = decltype(half_)::value;
@@ -908,41 +993,25 @@ __global__ __launch_bounds__(256) void flash_fwd128_kernel(const T* __restrict__
     m_ref = m_run == -INFINITY ? 0.f : m_run;   // a row with no visible key yet
   };
 
-  // ---- before the loop: the scores of tile 0, their maximum, and the first K fragments of tile 1
-  static_for<0, 8>([&](auto i_) { read_frag(i_); });
-  static_for<0, 16>([&](auto g_) {
-    constexpr int g = decltype(g_)::value;
-    lgkm_wait<0>();
-    mma_to_vgpr<T, (g / 2 == 0)>(sa[g % 2], nf[g % 8], qf[g / 2]);
-    if constexpr (g < 8) read_frag(IC<g + 8>{});
-  });
-  {
-#pragma unroll
-    for (int s = 0; s < KS; ++s) nat[s] += STAGE_B;
-    static_for<0, 8>([&](auto i_) { read_frag(i_); });
-    asm volatile("s_nop 10" : "+v"(sa[0]), "+v"(sa[1]));
-    float mx = -INFINITY;
-    static_for<0, 4>([&](auto k_) { part_max(true, sa, 0, IC<decltype(k_)::value / 2>{}, IC<decltype(k_)::value % 2>{}, mx); });
-    new_reference(mx);
-  }
-
-  // Tiles entirely below the diagonal of the wavefront's first row need no mask; the rest are masked, and so is the
-  // tile past the last one, whose scores the last iteration forms and nobody uses (a tile entirely above the last
-  // row's diagonal adds zeros: all wavefronts make the same nt trips, so the barriers match).
-  const int t_plain = min(nt, max(0, (wq0 + 1) / KT));
-  // Iteration t: `cur` holds the scores of tile t, `nxt` receives those of tile t + 1.
-  auto iteration = [&](int t, f32x16 (&cur)[2], f32x16 (&nxt)[2]) {
+  Item nxt_item = make_item(1);
+  // Iteration t of the current item: `cur_s` holds the scores of tile t, `nxt_s` receives those of tile t + 1.
+  auto iteration = [&](int t, f32x16 (&cur_s)[2], f32x16 (&nxt_s)[2]) {
     const bool masked = t + 1 >= t_plain;
     float rs = 0.f, mx = -INFINITY;
+    // the tile that goes into the stage tile t - 1 left: tile t + 3 of this item (its last tile again once it has
+    // run out), and past its last iteration the first tiles of the workgroup's next item
+    const int u = t + NS - 1;
+    const int stage = (gs + u) % NS;
+    const int kt = u < cur.n_iter ? min(u, cur.nt - 1) : nxt_item.qtile >= 0 ? min(u - cur.n_iter, nxt_item.nt - 1) : cur.nt - 1;
     auto exponential = [&](auto c_, auto e_) {
       constexpr int c = decltype(c_)::value, e = decltype(e_)::value, g = e >> 3, i = e & 7;
-      const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(cur[c][e], scale_log2, -m_ref));
+      const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(cur_s[c][e], scale_log2, -m_ref));
       rs += p;
-      cur[c][e] = p;
+      cur_s[c][e] = p;
       if constexpr (e & 1) {
         typedef T T2 __attribute__((ext_vector_type(2)));
         T2 a;
-        a[0] = from_f<T>(cur[c][e - 1]);
+        a[0] = from_f<T>(cur_s[c][e - 1]);
         a[1] = from_f<T>(p);
         pw[c * 2 + g][i >> 1] = __builtin_bit_cast(uint32_t, a);
         if constexpr (i == 7) operand_ready(pw[c * 2 + g]);
@@ -953,7 +1022,7 @@ __global__ __launch_bounds__(256) void flash_fwd128_kernel(const T* __restrict__
       constexpr int g = decltype(g_)::value;
       if constexpr (g < 28 && g % 2 == 0) lgkm_wait<FwdPlan::wait(g)>();
       if constexpr (g < 16) {
-        mma_to_vgpr<T, (g / 2 == 0)>(nxt[g % 2], nf[g % 8], qf[g / 2]);
+        mma_to_vgpr<T, (g / 2 == 0)>(nxt_s[g % 2], nf[g % 8], qf[g / 2]);
       } else {
         constexpr int M = g - 16, kk = M / 4, j = M % 4;
         mma_to_agpr<T>(oacc[j], tr_value<T>(tf[M % 8]), operand(pw[kk]));
@@ -968,9 +1037,9 @@ __global__ __launch_bounds__(256) void flash_fwd128_kernel(const T* __restrict__
         read_tr(IC<g - 16 + 4>{}, IC<0>{});
         read_tr(IC<g - 16 + 4>{}, IC<1>{});
       }
-      // direct-to-LDS loads of tile t + 3 into the stage that tile t - 1 left
-      if constexpr (g == 0) prepare_tile(t + NS - 1);
-      if constexpr (g < 16 && g % 2 == 1) issue_one(t + NS - 1, IC<g / 2>{});
+      // direct-to-LDS loads
+      if constexpr (g == 0) prepare_tile(kt);
+      if constexpr (g < 16 && g % 2 == 1) issue_one(stage, kt, IC<g / 2>{});
       // vector work
       if constexpr (g < 16) exponential(IC<0>{}, g_);
       if constexpr (g >= 16 && g < 24) exponential(IC<1>{}, IC<g - 16>{});
@@ -978,20 +1047,13 @@ __global__ __launch_bounds__(256) void flash_fwd128_kernel(const T* __restrict__
         exponential(IC<1>{}, IC<8 + 2 * (g - 24)>{});
         exponential(IC<1>{}, IC<9 + 2 * (g - 24)>{});
       }
-      if constexpr (g >= 28) part_max(masked, nxt, t + 1, IC<(g - 28) / 2>{}, IC<(g - 28) % 2>{}, mx);
+      if constexpr (g >= 28) part_max(masked, nxt_s, t + 1, IC<(g - 28) / 2>{}, IC<(g - 28) % 2>{}, mx);
       if constexpr (g == 27) {
         // every read of this iteration has been issued: when they have landed, and tile t + 2 too (only the loads of
-        // tile t + 3 outstanding), the stage of tile t is handed back; K moves on to tile t + 2, V to tile t + 1
+        // this iteration outstanding), the stage of tile t is handed back; K moves on to tile t + 2, V to tile t + 1
         asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(NLD) : "memory");
-        const int step_k = ((t + 2) % NS == 0) ? -(NS - 1) * STAGE_B : STAGE_B;
-        const int step_v = ((t + 1) % NS == 0) ? -(NS - 1) * STAGE_B : STAGE_B;
-#pragma unroll
-        for (int s = 0; s < KS; ++s) nat[s] += step_k;
-#pragma unroll
-        for (int jj = 0; jj < DT; ++jj) {
-          tr0[jj] += step_v;
-          tr1[jj] += step_v;
-        }
+        step_k();
+        step_v();
       }
       if constexpr (g >= 28) {
         read_frag(IC<2 * (g - 28)>{});
@@ -1004,20 +1066,81 @@ __global__ __launch_bounds__(256) void flash_fwd128_kernel(const T* __restrict__
     new_reference(mx);
   };
 
-  // The two score buffers change roles every iteration: one loop, two iterations per trip, so that every fragment
-  // in flight across an iteration boundary is in the registers the next iteration expects (another loop would be
-  // another register assignment, and the compiler would copy registers whose reads have not landed).  An odd
-  // number of tiles (only when L is not a multiple of 128) is rounded up: the extra iteration works on scores
-  // that are all masked, i.e. adds P = 0.
-  for (int t = 0; t < nt; t += 2) {
-    iteration(t, sa, sb);
-    iteration(t + 1, sb, sa);
-  }
-  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");   // see the dK / dV kernel
+  while (true) {
+    // ---- start of an item: its Q fragments (loaded a while ago), empty accumulators
+    wq0 = cur.qtile * BQ + wave * 32;
+    q = wq0 + col;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+      qf[s] = __builtin_bit_cast(V8, q < L ? z[s] : u32x4{0u, 0u, 0u, 0u});
+      pin_agpr(qf[s]);
+    }
+#pragma unroll
+    for (int j = 0; j < DT; ++j) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[j][e] = 0.f;
+      pin_agpr(oacc[j]);
+    }
+    m_run = -INFINITY, l_run = 0.f, m_ref = 0.f;
+    // The Q loads were issued after every direct-to-LDS load so far, with none in between, and loads return in
+    // order: the compiler's own wait for them (it sits before the selects above) has also waited for the item's
+    // first three tiles - while the stores of the previous item's rows, which came later, may still be on their way.
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
 
-  const float l = l_run + __shfl_xor(l_run, 32, 64);
-  store_grad_rows_staged<T>(o + ((long)b * L + wq0) * d + (long)head * DH, d, L - wq0, oacc, 1.0f / l, lane, nullptr,
-                            smem + wave * 8704);
-  if (lse && hf == 0 && q < L)
-    lse[((long)b * L + q) * h + head] = (m_run + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+    // ---- the scores of tile 0, their maximum, and the first K fragments of tile 1.  K fragments stand one stage
+    // past the item's first after the previous item (or at it, for the first item); V fragments stand at it.
+    if (pk != gs) {
+      const int back = pk == 0 ? (NS - 1) * STAGE_B : -STAGE_B;
+      pk = gs;
+#pragma unroll
+      for (int s = 0; s < KS; ++s) nat[s] += back;
+    }
+    static_for<0, 8>([&](auto i_) { read_frag(i_); });
+    static_for<0, 16>([&](auto g_) {
+      constexpr int g = decltype(g_)::value;
+      lgkm_wait<0>();
+      mma_to_vgpr<T, (g / 2 == 0)>(sa[g % 2], nf[g % 8], qf[g / 2]);
+      if constexpr (g < 8) read_frag(IC<g + 8>{});
+    });
+    {
+      step_k();
+      static_for<0, 8>([&](auto i_) { read_frag(i_); });
+      asm volatile("s_nop 10" : "+v"(sa[0]), "+v"(sa[1]));
+      float mx = -INFINITY;
+      static_for<0, 4>([&](auto k_) { part_max(true, sa, 0, IC<decltype(k_)::value / 2>{}, IC<decltype(k_)::value % 2>{}, mx); });
+      new_reference(mx);
+    }
+
+    // Tiles entirely below the diagonal of the wavefront's first row need no mask; the rest are masked, and so is the
+    // tile past the last one, whose scores the last iteration forms and nobody uses (a tile entirely above the last
+    // row's diagonal adds zeros: all wavefronts make the same trips, so the barriers match).
+    t_plain = min(cur.nt, max(0, (wq0 + 1) / KT));
+    // The two score buffers change roles every iteration: one loop, two iterations per trip, so that every fragment
+    // in flight across an iteration boundary is in the registers the next iteration expects (another loop would be
+    // another register assignment, and the compiler would copy registers whose reads have not landed).  The extra
+    // iteration of an odd tile count works on scores that are all masked, i.e. adds P = 0.
+    for (int t = 0; t < cur.n_iter; t += 2) {
+      iteration(t, sa, sb);
+      iteration(t + 1, sb, sa);
+    }
+    // the fragments read ahead for a tile nobody multiplies land before their registers get another use
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+
+    // ---- end of the item: ask for the next item's Q, store this item's rows (the ring stays live: its stages hold
+    // or await the next item's first tiles)
+    const bool more = nxt_item.qtile >= 0;
+    if (more) load_q(z, nxt_item.qtile);
+    const float l = l_run + __shfl_xor(l_run, 32, 64);
+    store_rows_staged16<T>(o + ((long)b * L + wq0) * d + (long)head * DH, d, L - wq0, oacc, 1.0f / l, lane, nullptr,
+                           smem + NS * STAGE_B + wave * 4352);
+    if (lse && hf == 0 && q < L)
+      lse[((long)b * L + q) * h + head] = (m_run + __builtin_amdgcn_logf(l)) * 0.6931471805599453f;
+    if (!more) break;
+    gs = (gs + cur.n_iter) % NS;
+    cur = nxt_item;
+    ++k_item;
+    nxt_item = make_item(k_item + 1);
+  }
+  // no direct-to-LDS write may outlive the workgroup
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 }

@@ -457,11 +457,15 @@ def test_attention_backward_with_rotary_backward(impl, name, B, L, h, dh):
     ("bf16", 1, 2048, 32, [(0, 5)]),                       # config 4's training stream, bf16 operands
     ("f16", 1, 4096, 40, [(0, 0), (0, 39)]),               # LLaMA-13B-shaped stage, one sequence of 4096
     ("f16", 1, 4096, 2, [(0, 0), (0, 1)]),                 # few heads: every (sequence, head) pair checked
+    # launches in which a forward workgroup takes several query tiles of a head in a row: three of nine (the last
+    # tile short, with an odd number of key tiles), all four (sequence end inside a key tile)
+    ("f16", 5, 1064, 32, [(0, 3), (2, 16), (4, 31)]),
+    ("f16", 8, 500, 32, [(0, 0), (7, 31)]),
 ])
 def test_attention_at_the_benchmarked_sizes_on_sampled_heads(name, B, L, h, heads):
     """The launches bench.py times (head_dim 128, all heads, L = 2048 and 4096: 16 and 32 query tiles
-    per head, dispatched heaviest first over every head), forward and both backward kernels, with and
-    without the fused rotary backward.  The float64 definition is formed for the sampled (sequence,
+    per head, dispatched heaviest first over every head, one or several to a workgroup), forward and both backward
+    kernels, with and without the fused rotary backward.  The float64 definition is formed for the sampled (sequence,
     head) pairs only: heads do not interact, and one head's 4096 x 4096 probability matrix is 134 MB."""
     dh = 128
     d = h * dh
@@ -498,6 +502,34 @@ def test_attention_at_the_benchmarked_sizes_on_sampled_heads(name, B, L, h, head
             if i < 2:
                 r_ = O.rope(r_.reshape(L, 1, dh), np.arange(L), 1e4, -1.0).reshape(L, dh)
             assert_close(host(dqkv_r[rows, col(i)]), r_, otol(name, r_, 1e-4), what + nm + " (rotary backward)")
+
+
+@pytest.mark.parametrize("name", ["f16", "bf16"])
+@pytest.mark.parametrize("B,L,h,heads", [(5, 1064, 32, [(0, 3), (2, 16), (4, 31)]), (8, 500, 32, [(0, 0), (3, 9), (7, 31)]),
+                                         (16, 2048, 32, [(0, 0), (9, 20), (15, 31)])])
+def test_attention_forward_over_several_query_tiles_per_workgroup(name, B, L, h, heads):
+    """Forward launches (head_dim 128) whose workgroups take 3, 4 and all 16 query tiles of a head in a row, the key
+    tiles of one flowing into the next: o and the log-sum-exp of sampled (sequence, head) pairs against the
+    definition, in both 16-bit formats."""
+    dh = 128
+    d = h * dh
+    dt = DT[name]
+    qd = S.normal_torch(29, "qkv", (B * L, 3 * d), 1.0, "cuda", dt)
+    o = torch.empty(B * L, d, dtype=dt, device="cuda")
+    lse = torch.empty(B * L, h, dtype=torch.float32, device="cuda")
+    Bd.lsk_attn_fwd(1, qd, B, L, h, dh, o, lse)
+    torch.cuda.synchronize()
+    assert torch.isfinite(o.float()).all() and torch.isfinite(lse).all()
+    for b, j in heads:
+        rows = slice(b * L, (b + 1) * L)
+        qq, kk, vv = (host(qd[rows, i * d + j * dh:i * d + (j + 1) * dh]).reshape(L, 1, dh) for i in range(3))
+        o_ref, _ = O.attention(qq, kk, vv, 0)
+        what = f"{name} B={B} L={L} sequence {b} head {j}: "
+        assert_close(host(o[rows, j * dh:(j + 1) * dh]), o_ref.reshape(L, dh), otol(name, o_ref, 1e-4), what + "o")
+        sc = (qq[:, 0] @ kk[:, 0].T) / math.sqrt(dh)
+        sc = np.where(np.tril(np.ones((L, L), bool)), sc, -np.inf)
+        m = sc.max(1)
+        assert np.abs(host(lse[rows, j]) - (m + np.log(np.exp(sc - m[:, None]).sum(1)))).max() < 2e-2, what + "lse"
 
 
 @pytest.mark.parametrize("name", ["f16", "bf16"])
