@@ -1098,7 +1098,7 @@ __global__ __launch_bounds__(256) void flash_fwd128_kernel(const T* __restrict__
     static_for<0, 8>([&](auto i_) { read_frag(i_); });
     static_for<0, 16>([&](auto g_) {
       constexpr int g = decltype(g_)::value;
-      lgkm_wait<0>();
+      lgkm_wait<(g < 8 ? 7 : 15 - g)>();   // fragments g + 1 .. g + 7 (up to the sixteenth) may still be on their way
       mma_to_vgpr<T, (g / 2 == 0)>(sa[g % 2], nf[g % 8], qf[g / 2]);
       if constexpr (g < 8) read_frag(IC<g + 8>{});
     });
