@@ -731,7 +731,8 @@ __global__ __launch_bounds__(256) void flash_bwd_dq128_kernel(const T* __restric
 
 // ---- forward (training layout) ---------------------------------------------------------------------
 // flash_fwd_ring_kernel at head_dim 128 on the same scheme, software-pipelined over the key tiles.  A workgroup
-// owns 128 queries (32 per wavefront, Q fragments in the accumulator file), K / V tiles of 64 keys come through
+// works on 128 queries at a time (32 per wavefront, Q fragments in the accumulator file) and takes one or several
+// such query tiles of a head in a row (snake_tile, tiles_per_workgroup); K / V tiles of 64 keys come through
 // the ring.  Iteration t holds the scores S^T(t) complete in registers and runs 32 MFMAs:
 //   0..15  S^T(t + 1) = K(t + 1) Q^T (the two 32-key blocks alternating) beside the exponentials of the first 32
 //          keys of tile t;
