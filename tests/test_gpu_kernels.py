@@ -506,9 +506,9 @@ def test_attention_at_the_benchmarked_sizes_on_sampled_heads(name, B, L, h, head
 
 @pytest.mark.parametrize("name", ["f16", "bf16"])
 @pytest.mark.parametrize("B,L,h,heads", [(5, 1064, 32, [(0, 3), (2, 16), (4, 31)]), (8, 500, 32, [(0, 0), (3, 9), (7, 31)]),
-                                         (16, 2048, 32, [(0, 0), (9, 20), (15, 31)])])
+                                         (4, 2048, 32, [(0, 0), (3, 31)]), (16, 2048, 32, [(0, 0), (9, 20), (15, 31)])])
 def test_attention_forward_over_several_query_tiles_per_workgroup(name, B, L, h, heads):
-    """Forward launches (head_dim 128) whose workgroups take 3, 4 and all 16 query tiles of a head in a row, the key
+    """Forward launches (head_dim 128) whose workgroups take 3, 4, 8 and all 16 query tiles of a head in a row, the key
     tiles of one flowing into the next: o and the log-sum-exp of sampled (sequence, head) pairs against the
     definition, in both 16-bit formats."""
     dh = 128
