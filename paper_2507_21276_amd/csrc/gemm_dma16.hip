@@ -421,20 +421,45 @@ __global__ __launch_bounds__(256) void gemm_dma16_kernel(DmaArgs g) {
         }
       }
     } else {
-#pragma unroll
-      for (int it = 0; it < ROWS_P * CPR / 64; ++it) {
-        const int idx = it * 64 + lane;
-        const int r = idx / CPR, c = idx % CPR;
-        const int m = m0 + wm + pass * ROWS_P + r;
-        const int n = n0 + wn + c * (16 / ESZ);
-        if (m >= g.M || n >= g.N) continue;
-        const f32x4 v = *(const f32x4_a*)(stg + r * ROWB + ((c ^ (r & (CPR - 1))) * 16));
+      constexpr int NIT = ROWS_P * CPR / 64, GRP = 8;
+      static_assert(NIT % GRP == 0, "row groups of the store loop");
+      auto put = [&](int it, int m, int n, const f32x4& v) {
         if constexpr (ESZ == 2) {
           *(f32x4_a*)((T*)g.C + (long)m * g.ldc + n) = v;
         } else if constexpr (MODE == 1) {
           *(f32x4*)((float*)g.C + (long)m * g.ldc + n) = v + c_old[it];
         } else {
           *(f32x4*)((float*)g.C + (long)m * g.ldc + n) = MODE == 4 ? c_old[it] + v : v;
+        }
+      };
+      if (m0 + wm + pass * ROWS_P + ROWS_P <= g.M && n0 + wn + WN <= g.N) {
+        // uniform: every row and column of the pass exists, so nothing depends on the lane and eight staged
+        // pieces are read before eight are stored (under the per-lane bounds check below the compiler moves each
+        // read to its store and waits for it there: 32 or 64 LDS round trips in a row per tile)
+#pragma unroll
+        for (int it0 = 0; it0 < NIT; it0 += GRP) {
+          f32x4 v[GRP];
+#pragma unroll
+          for (int u = 0; u < GRP; ++u) {
+            const int idx = (it0 + u) * 64 + lane;
+            const int r = idx / CPR, c = idx % CPR;
+            v[u] = *(const f32x4_a*)(stg + r * ROWB + ((c ^ (r & (CPR - 1))) * 16));
+          }
+#pragma unroll
+          for (int u = 0; u < GRP; ++u) {
+            const int idx = (it0 + u) * 64 + lane;
+            put(it0 + u, m0 + wm + pass * ROWS_P + idx / CPR, n0 + wn + (idx % CPR) * (16 / ESZ), v[u]);
+          }
+        }
+      } else {
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+          const int idx = it * 64 + lane;
+          const int r = idx / CPR, c = idx % CPR;
+          const int m = m0 + wm + pass * ROWS_P + r;
+          const int n = n0 + wn + c * (16 / ESZ);
+          if (m >= g.M || n >= g.N) continue;
+          put(it, m, n, *(const f32x4_a*)(stg + r * ROWB + ((c ^ (r & (CPR - 1))) * 16)));
         }
       }
     }
